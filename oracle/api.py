@@ -1,0 +1,206 @@
+"""numpy front end of the C oracle (oracle/sylvie_oracle.c).
+
+Each wrapper only checks shapes/dtypes and forwards pointers; all arithmetic is
+in the C file.  Arrays are C-contiguous numpy arrays; float data is float32.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sylvie_oracle.c")
+_SO = os.path.join(_HERE, "libsylvie_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+__all__ = [
+    "build", "words_per_row", "uniform24", "quantize_1bit", "dequantize_1bit_fwd",
+    "dequantize_1bit_bwd", "gcn_operator", "mean_weights", "aggregate_fwd", "aggregate_bwd",
+    "aggregate_bwd_rows", "transform_fwd", "transform_bwd", "num_threads",
+]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no contraction, OpenMP over rows)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC",
+               "-shared", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+def _L():
+    global _lib
+    with _lock:
+        if _lib is None:
+            build()
+            lib = C.CDLL(_SO)
+            lib.orc_uniform24.restype = C.c_uint32
+            lib.orc_uniform24.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
+            lib.orc_words_per_row.restype = C.c_int64
+            lib.orc_words_per_row.argtypes = [C.c_int32]
+            lib.orc_aggregate_bwd.restype = C.c_int
+            lib.orc_num_threads.restype = C.c_int
+            _lib = lib
+    return _lib
+
+
+def _p(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def _f32(a, name):
+    if a.dtype != np.float32 or not a.flags.c_contiguous:
+        raise TypeError(f"{name}: need C-contiguous float32")
+    return a
+
+
+def _chk(a, dtype, name):
+    if a.dtype != dtype or not a.flags.c_contiguous:
+        raise TypeError(f"{name}: need C-contiguous {np.dtype(dtype).name}")
+    return a
+
+
+def num_threads() -> int:
+    return int(_L().orc_num_threads())
+
+
+def words_per_row(d: int) -> int:
+    return int(_L().orc_words_per_row(int(d)))
+
+
+def uniform24(seed: int, stream: int, row: int, col: int) -> int:
+    return int(_L().orc_uniform24(C.c_uint64(seed), C.c_uint32(stream), C.c_uint32(row),
+                                  C.c_uint32(col)))
+
+
+def quantize_1bit(src, d, n_rows, seed, stream, idx=None, row_offset=0):
+    """-> (packed uint64 [n_rows, W], scale f32 [n_rows], zero f32 [n_rows])."""
+    _f32(src, "src")
+    ld = src.shape[1]
+    W = words_per_row(d)
+    packed = np.empty((n_rows, W), np.uint64)
+    scale = np.empty(n_rows, np.float32)
+    zero = np.empty(n_rows, np.float32)
+    if idx is not None:
+        _chk(idx, np.int32, "idx")
+    _L().orc_quantize_1bit(_p(src), C.c_int64(ld), C.c_int32(d), _p(idx), C.c_int64(row_offset),
+                           C.c_int64(n_rows), C.c_uint64(seed), C.c_uint32(stream), _p(packed),
+                           _p(scale), _p(zero))
+    return packed, scale, zero
+
+
+def dequantize_1bit_fwd(packed, scale, zero, d, dst, row_offset):
+    """dst[row_offset + i, :d] = dequantised wire row i (in place)."""
+    _chk(packed, np.uint64, "packed"); _f32(scale, "scale"); _f32(zero, "zero"); _f32(dst, "dst")
+    n = packed.shape[0]
+    _L().orc_dequantize_1bit_fwd(_p(packed), _p(scale), _p(zero), C.c_int64(n), C.c_int32(d),
+                                 _p(dst), C.c_int64(dst.shape[1]), C.c_int64(row_offset))
+
+
+def dequantize_1bit_bwd(packed, scale, zero, d, J, dst_row):
+    """J[dst_row[i], :d] += dequantised wire row i, ascending i (in place)."""
+    _chk(packed, np.uint64, "packed"); _f32(scale, "scale"); _f32(zero, "zero"); _f32(J, "J")
+    _chk(dst_row, np.int32, "dst_row")
+    n = packed.shape[0]
+    _L().orc_dequantize_1bit_bwd(_p(packed), _p(scale), _p(zero), C.c_int64(n), C.c_int32(d),
+                                 _p(J), C.c_int64(J.shape[1]), _p(dst_row))
+
+
+def gcn_operator(rowptr, col, deg, n_in):
+    """-> (rowptr', col', w) of D^-1/2 (A + I) D^-1/2 restricted to the inner rows."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _chk(deg, np.int32, "deg")
+    nnz = int(rowptr[n_in])
+    orp = np.empty(n_in + 1, np.int64)
+    ocol = np.empty(nnz + n_in, np.int32)
+    ow = np.empty(nnz + n_in, np.float32)
+    _L().orc_gcn_operator(_p(rowptr), _p(col), _p(deg), C.c_int64(n_in), _p(orp), _p(ocol),
+                          _p(ow))
+    return orp, ocol, ow
+
+
+def mean_weights(rowptr, n_in):
+    _chk(rowptr, np.int64, "rowptr")
+    w = np.empty(int(rowptr[n_in]), np.float32)
+    _L().orc_mean_weights(_p(rowptr), C.c_int64(n_in), _p(w))
+    return w
+
+
+def aggregate_fwd(rowptr, col, w, X, d, want_S=False):
+    """-> Z [n_rows, d] (and S, the sum of |terms|, if want_S)."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(w, "w"); _f32(X, "X")
+    n = rowptr.shape[0] - 1
+    Z = np.empty((n, d), np.float32)
+    S = np.empty((n, d), np.float32) if want_S else None
+    _L().orc_aggregate_fwd(_p(rowptr), _p(col), _p(w), C.c_int64(n), _p(X),
+                           C.c_int64(X.shape[1]), C.c_int32(d), _p(Z), C.c_int64(d), _p(S),
+                           C.c_int64(d))
+    return (Z, S) if want_S else Z
+
+
+def aggregate_bwd(rowptr, col, w, n_cols, dZ, d, want_S=False):
+    """-> dX [n_cols, d] = A^T dZ (and S if want_S)."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(w, "w"); _f32(dZ, "dZ")
+    n = rowptr.shape[0] - 1
+    dX = np.empty((n_cols, d), np.float32)
+    S = np.empty((n_cols, d), np.float32) if want_S else None
+    rc = _L().orc_aggregate_bwd(_p(rowptr), _p(col), _p(w), C.c_int64(n), C.c_int64(n_cols),
+                                _p(dZ), C.c_int64(dZ.shape[1]), C.c_int32(d), _p(dX),
+                                C.c_int64(d), _p(S), C.c_int64(d))
+    if rc != 0:
+        raise MemoryError("oracle aggregate_bwd: out of memory")
+    return (dX, S) if want_S else dX
+
+
+def aggregate_bwd_rows(rowptr, col, w, dZ, d, sel):
+    """Rows sel (ascending, distinct) of A^T dZ -> (out [n_sel, d], S [n_sel, d])."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(w, "w"); _f32(dZ, "dZ")
+    _chk(sel, np.int32, "sel")
+    n = rowptr.shape[0] - 1
+    out = np.empty((sel.shape[0], d), np.float32)
+    S = np.empty((sel.shape[0], d), np.float32)
+    _L().orc_aggregate_bwd_rows(_p(rowptr), _p(col), _p(w), C.c_int64(n), _p(dZ),
+                                C.c_int64(dZ.shape[1]), C.c_int32(d), _p(sel),
+                                C.c_int64(sel.shape[0]), _p(out), _p(S))
+    return out, S
+
+
+def transform_fwd(A1, Wm, relu, A2=None, want_S=False):
+    """H = relu?(max([A1|A2] W, 0)) -> H [n, h] (and S if want_S)."""
+    _f32(A1, "A1"); _f32(Wm, "W")
+    n, k1 = A1.shape
+    k2 = 0 if A2 is None else _f32(A2, "A2").shape[1]
+    h = Wm.shape[1]
+    assert Wm.shape[0] == k1 + k2
+    H = np.empty((n, h), np.float32)
+    S = np.empty((n, h), np.float32) if want_S else None
+    _L().orc_transform_fwd(_p(A1), C.c_int64(k1), C.c_int32(k1), _p(A2), C.c_int64(k2),
+                           C.c_int32(k2), _p(Wm), C.c_int32(h), C.c_int64(n), C.c_int(int(relu)),
+                           _p(H), C.c_int64(h), None, _p(S))
+    return (H, S) if want_S else H
+
+
+def transform_bwd(A1, Wm, relu, H, J, A2=None, want_G=True, want_dA=True, want_S=False):
+    """-> dict with G [(k1+k2), h], dA1 [n, k1], dA2 [n, k2] (and SG, SdA1, SdA2)."""
+    _f32(A1, "A1"); _f32(Wm, "W"); _f32(H, "H"); _f32(J, "J")
+    n, k1 = A1.shape
+    k2 = 0 if A2 is None else _f32(A2, "A2").shape[1]
+    h = Wm.shape[1]
+    out = {}
+    G = np.empty((k1 + k2, h), np.float32) if want_G else None
+    dA1 = np.empty((n, k1), np.float32) if want_dA else None
+    dA2 = np.empty((n, k2), np.float32) if (want_dA and k2) else None
+    SG = np.empty((k1 + k2, h), np.float32) if (want_S and want_G) else None
+    S1 = np.empty((n, k1), np.float32) if (want_S and want_dA) else None
+    S2 = np.empty((n, k2), np.float32) if (want_S and want_dA and k2) else None
+    _L().orc_transform_bwd(_p(A1), C.c_int64(k1), C.c_int32(k1), _p(A2), C.c_int64(k2),
+                           C.c_int32(k2), _p(Wm), C.c_int32(h), C.c_int64(n), C.c_int(int(relu)),
+                           _p(H), C.c_int64(h), _p(J), C.c_int64(J.shape[1]), _p(G), _p(SG),
+                           _p(dA1), C.c_int64(k1), _p(dA2), C.c_int64(k2), _p(S1), _p(S2))
+    out.update(G=G, dA1=dA1, dA2=dA2, SG=SG, SdA1=S1, SdA2=S2)
+    return out

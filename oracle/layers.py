@@ -1,0 +1,157 @@
+"""Oracle layer loop: Alg. 1 (forward) and Alg. 2 (backward) of Sylvie-S on the
+partitions of one graph, all partitions stepped in one process and the send /
+receive replaced by handing the wire arrays over (test infrastructure only).
+
+A partition is described by plain numpy arrays (see `PartData`).  Every halo row
+j of partition p names its owner partition `halo_part[j]` and the owner's inner
+row `halo_row[j]`; halo rows are grouped by owner in ascending order.  A single
+partition whose halo rows all name itself is the "loopback" stand-in for absent
+peers.
+
+wire = "1bit": quantize -> (packed, scale, zero) -> dequantize (Sec. 3.2).
+wire = "fp32": the rows are copied unchanged (vanilla full-precision exchange,
+Sec. 2.2), used where a check must not depend on the rounding randomness.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+from . import api as O
+
+
+@dataclass
+class PartData:
+    n_in: int
+    n_halo: int
+    rowptr: np.ndarray          # int64 [n_in+1], adjacency without self loops
+    col: np.ndarray             # int32 [nnz]
+    deg: np.ndarray             # int32 [n_in+n_halo], global degrees
+    halo_part: np.ndarray       # int32 [n_halo]
+    halo_row: np.ndarray        # int32 [n_halo]
+    X: np.ndarray               # f32 [n_in, d_0]
+    J: np.ndarray               # f32 [n_in, d_L] upstream gradient
+    # filled by the loop
+    op: tuple = None            # (rowptr, col, w) of the normalised operator
+    Htil: List[np.ndarray] = field(default_factory=list)   # Htil[l-1]: input of layer l
+    Z: List[np.ndarray] = field(default_factory=list)
+    H: List[np.ndarray] = field(default_factory=list)      # H[l]: output of layer l (H[0] = X)
+    G: List[Optional[np.ndarray]] = field(default_factory=list)
+    Jin: List[Optional[np.ndarray]] = field(default_factory=list)  # Jin[l] = J^(l)
+
+
+def pair_seed(seed: int, sender: int, receiver: int) -> int:
+    """One seed per ordered (sender, receiver) pair so no two wires share randomness."""
+    return (int(seed) + 0x9E3779B97F4A7C15 * (sender * 4096 + receiver + 1)) & (2**64 - 1)
+
+
+def owner_blocks(p: PartData):
+    """[(owner, j0, j1)]: maximal runs of halo rows with the same owner."""
+    out = []
+    j = 0
+    while j < p.n_halo:
+        q = int(p.halo_part[j])
+        k = j
+        while k < p.n_halo and int(p.halo_part[k]) == q:
+            k += 1
+        out.append((q, j, k))
+        j = k
+    return out
+
+
+def build_operator(p: PartData, model: str):
+    if model == "gcn":
+        p.op = O.gcn_operator(p.rowptr, p.col, p.deg, p.n_in)
+    elif model == "sage":
+        p.op = (p.rowptr, p.col, O.mean_weights(p.rowptr, p.n_in))
+    else:
+        raise ValueError(model)
+
+
+def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, wire="1bit"):
+    """Alg. 1 lines 8-17 for one epoch."""
+    L = len(W)
+    for me, p in enumerate(parts):
+        if p.op is None:
+            build_operator(p, model)
+        p.H = [p.X]
+        p.Htil, p.Z = [], []
+    for l in range(1, L + 1):
+        d = parts[0].H[l - 1].shape[1]
+        for me, p in enumerate(parts):
+            ht = np.zeros((p.n_in + p.n_halo, d), np.float32)
+            ht[: p.n_in] = p.H[l - 1]
+            # quantize at the owner, hand over, dequantize into the halo block
+            for (q, j0, j1) in owner_blocks(p):
+                src = parts[q].H[l - 1]
+                idx = np.ascontiguousarray(p.halo_row[j0:j1])
+                if wire == "1bit":
+                    pk, sc, zp = O.quantize_1bit(src, d, j1 - j0, pair_seed(seed, q, me),
+                                                 2 * l + 0, idx=idx)
+                    O.dequantize_1bit_fwd(pk, sc, zp, d, ht, p.n_in + j0)
+                else:
+                    ht[p.n_in + j0: p.n_in + j1] = src[idx]
+            p.Htil.append(ht)
+        for p in parts:
+            rp, cl, w = p.op
+            Z = O.aggregate_fwd(rp, cl, w, p.Htil[l - 1], d)
+            p.Z.append(Z)
+            relu = l != L
+            if model == "gcn":
+                H = O.transform_fwd(Z, W[l - 1], relu)
+            else:
+                H = O.transform_fwd(np.ascontiguousarray(p.H[l - 1]), W[l - 1], relu, A2=Z)
+            p.H.append(H)
+
+
+def backward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, wire="1bit",
+             exchange_first_layer=False):
+    """Alg. 2 for one epoch (weight gradients stay per partition: no all-reduce).
+
+    exchange_first_layer=True also computes and exchanges J^(0), as if another
+    layer sat below layer 1.
+    """
+    L = len(W)
+    for p in parts:
+        p.Jin = [None] * (L + 1)
+        p.G = [None] * (L + 1)
+        p.Jin[L] = p.J
+    for l in range(L, 0, -1):
+        need_dx = l > 1 or exchange_first_layer
+        dHt = []
+        for p in parts:
+            relu = l != L
+            Z = p.Z[l - 1]
+            if model == "gcn":
+                r = O.transform_bwd(Z, W[l - 1], relu, p.H[l], p.Jin[l], want_dA=need_dx)
+                dZ, dself = r["dA1"], None
+            else:
+                r = O.transform_bwd(np.ascontiguousarray(p.H[l - 1]), W[l - 1], relu, p.H[l],
+                                    p.Jin[l], A2=Z, want_dA=need_dx)
+                dself, dZ = r["dA1"], r["dA2"]
+            p.G[l] = r["G"]
+            if not need_dx:
+                dHt.append(None)
+                continue
+            rp, cl, w = p.op
+            d = dZ.shape[1]
+            g = O.aggregate_bwd(rp, cl, w, p.n_in + p.n_halo, dZ, d)
+            if dself is not None:
+                g[: p.n_in] = g[: p.n_in] + dself
+            dHt.append(g)
+        if not need_dx:
+            continue
+        for p, g in zip(parts, dHt):
+            p.Jin[l - 1] = np.ascontiguousarray(g[: p.n_in]).copy()
+        for me, (p, g) in enumerate(zip(parts, dHt)):
+            d = g.shape[1]
+            for (q, j0, j1) in owner_blocks(p):
+                dst = np.ascontiguousarray(p.halo_row[j0:j1])
+                if wire == "1bit":
+                    pk, sc, zp = O.quantize_1bit(g, d, j1 - j0, pair_seed(seed, me, q), 2 * l + 1,
+                                                 row_offset=p.n_in + j0)
+                    O.dequantize_1bit_bwd(pk, sc, zp, d, parts[q].Jin[l - 1], dst)
+                else:
+                    np.add.at(parts[q].Jin[l - 1], dst, g[p.n_in + j0: p.n_in + j1])

@@ -1,0 +1,424 @@
+/*
+ * CPU oracle for the Low-bit Module and the partition-local GNN layer of
+ * "Sylvie" (arXiv 2303.01277).  TEST INFRASTRUCTURE ONLY: the tests, the smoke
+ * check and the benchmark's cpu_baseline leg are the only callers.  The product
+ * (the HIP library) shares no code with this file and never calls it.
+ *
+ * Everything is written as the plain definition: scalar loops, one element at a
+ * time, no blocking, no fusion.  Sums that the method defines over real numbers
+ * (aggregation, dense transform) are accumulated in double and rounded to float
+ * once; steps whose single-precision arithmetic decides an integer (the
+ * stochastic-rounding comparison) or whose order is part of the definition (the
+ * backward "integrate" accumulation) are done in float exactly as stated below.
+ * Build with -O2 -ffp-contract=off (no fast-math) so every float operation is
+ * one IEEE-754 binary32 operation.
+ *
+ * "parity unpinned": the constants of the counter hash below.  The paper only
+ * says "with probability"; any hash that passes the uniformity / independence /
+ * unbiasedness tests is a correct reading, so no external value pins them.
+ *
+ * OpenMP `parallel for` over independent rows only; results do not depend on
+ * the thread count.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* Counter-based random bits for the stochastic rounding of Sec. 3.2, Eq. 4. */
+/* Keyed on (seed, stream, wire row, column); 24 uniform bits per element.   */
+/* ------------------------------------------------------------------------- */
+
+#define ORC_M1 0xce6e1acdu
+#define ORC_M2 0x6d3cb3a7u
+#define ORC_COL_STRIDE 0x9e3779b9u /* odd: floor(2^32 / golden ratio) */
+#define ORC_DOMAIN 0x53594c56u     /* "SYLV" */
+
+static uint32_t orc_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= ORC_M1;
+    x ^= x >> 15;
+    x *= ORC_M2;
+    x ^= x >> 16;
+    return x;
+}
+
+/* Key of one call: folds the 64-bit seed and the 32-bit stream id. */
+uint32_t orc_call_key(uint64_t seed, uint32_t stream)
+{
+    uint32_t k = orc_mix((uint32_t)(seed & 0xffffffffu) ^ ORC_DOMAIN);
+    k = orc_mix(k ^ (uint32_t)(seed >> 32));
+    k = orc_mix(k ^ stream);
+    return k;
+}
+
+/* Key of one wire row. */
+static uint32_t orc_row_key(uint32_t call_key, uint32_t row)
+{
+    return orc_mix(call_key ^ row);
+}
+
+/* 24 random bits of element (row, col): the top 24 bits of the second product. */
+static uint32_t orc_elem_u24(uint32_t row_key, uint32_t col)
+{
+    uint32_t x = row_key + col * ORC_COL_STRIDE;
+    x ^= x >> 16;
+    x *= ORC_M1;
+    x ^= x >> 15;
+    x *= ORC_M2;
+    return x >> 8;
+}
+
+/* Exposed for the statistical tests: the 24-bit integer behind u = k * 2^-24. */
+uint32_t orc_uniform24(uint64_t seed, uint32_t stream, uint32_t row, uint32_t col)
+{
+    return orc_elem_u24(orc_row_key(orc_call_key(seed, stream), row), col);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Quantizer (Sec. 3.2 "Quantizer", Eq. 3 and Eq. 4 with b = 1, B = 1) and     */
+/* the scale / zero-point side channel (Sec. 3.2 "Communicator").              */
+/* ------------------------------------------------------------------------- */
+
+int64_t orc_words_per_row(int32_t d) { return ((int64_t)d + 63) / 64; }
+
+/*
+ * For wire row i = 0..n_rows-1 the source row is idx[i] (idx != NULL) or
+ * row_offset + i (idx == NULL) of the row-major matrix src (leading dim ld).
+ *
+ *   mn = min_c r_c, mx = max_c r_c, each then "+ 0.0f" (turns -0 into +0)
+ *   zero = mn,  scale = mx - mn            (B = 1, so (max-min)/B is the range)
+ *   u    = k * 2^-24, k the 24 random bits of (seed, stream, i, c)
+ *   bit  = [ fl(u * scale) < fl(r_c - mn) ]
+ *
+ * Eq. 3 normalises h to hbar = (h - min)/(max - min) in [0, 1]; Eq. 4 rounds hbar
+ * up with probability hbar - floor(hbar), i.e. to 1 with probability hbar.  With
+ * u uniform on [0,1), "u < hbar" has exactly that probability; multiplying both
+ * sides by the range avoids the division and leaves a constant row (range 0)
+ * with all bits 0 and no special case.
+ *
+ * Packing: bit j (least significant = 0) of word k of a row is column 64k + j;
+ * ceil(d/64) words per row; bits of columns >= d are 0.
+ */
+void orc_quantize_1bit(const float *src, int64_t ld, int32_t d, const int32_t *idx,
+                       int64_t row_offset, int64_t n_rows, uint64_t seed, uint32_t stream,
+                       uint64_t *packed, float *scale, float *zero)
+{
+    const int64_t W = orc_words_per_row(d);
+    const uint32_t ck = orc_call_key(seed, stream);
+    const float two_m24 = 1.0f / 16777216.0f;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t srow = idx ? (int64_t)idx[i] : row_offset + i;
+        const float *r = src + srow * ld;
+        float mn = r[0], mx = r[0];
+        for (int32_t c = 1; c < d; ++c) {
+            if (r[c] < mn) mn = r[c];
+            if (r[c] > mx) mx = r[c];
+        }
+        mn = mn + 0.0f;
+        mx = mx + 0.0f;
+        const float sc = mx - mn;
+        zero[i] = mn;
+        scale[i] = sc;
+        const uint32_t rk = orc_row_key(ck, (uint32_t)i);
+        for (int64_t k = 0; k < W; ++k) packed[i * W + k] = 0;
+        for (int32_t c = 0; c < d; ++c) {
+            const float u = (float)orc_elem_u24(rk, (uint32_t)c) * two_m24;
+            const float lhs = u * sc;
+            const float rhs = r[c] - mn;
+            if (lhs < rhs) packed[i * W + (c >> 6)] |= (uint64_t)1 << (c & 63);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Dequantizer (Sec. 3.2 "Dequantizer", Eq. 5 with B = 1).                     */
+/* ------------------------------------------------------------------------- */
+
+static float orc_deq(const uint64_t *prow, float sc, float zp, int32_t c)
+{
+    const int bit = (int)((prow[c >> 6] >> (c & 63)) & 1u);
+    /* (max-min) * hhat / B + min: hhat is 0 or 1, so one float addition at most */
+    return bit ? zp + sc : zp;
+}
+
+/* Forward: received row i overwrites row row_offset + i of dst (Alg. 1: the
+ * recovered rows are appended below the inner rows, "concatenate"). */
+void orc_dequantize_1bit_fwd(const uint64_t *packed, const float *scale, const float *zero,
+                             int64_t n_rows, int32_t d, float *dst, int64_t ld,
+                             int64_t row_offset)
+{
+    const int64_t W = orc_words_per_row(d);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        float *o = dst + (row_offset + i) * ld;
+        for (int32_t c = 0; c < d; ++c) o[c] = orc_deq(packed + i * W, scale[i], zero[i], c);
+    }
+}
+
+/* Backward: J[dst_row[i]] += dequantized row i (Alg. 2 "integrate feature
+ * gradients").  Several wire rows may name one destination; the additions are
+ * single-precision and happen in ascending wire-row order. */
+void orc_dequantize_1bit_bwd(const uint64_t *packed, const float *scale, const float *zero,
+                             int64_t n_rows, int32_t d, float *J, int64_t ld,
+                             const int32_t *dst_row)
+{
+    const int64_t W = orc_words_per_row(d);
+    for (int64_t i = 0; i < n_rows; ++i) {
+        float *o = J + (int64_t)dst_row[i] * ld;
+        for (int32_t c = 0; c < d; ++c) {
+            const float v = orc_deq(packed + i * W, scale[i], zero[i], c);
+            o[c] = o[c] + v;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Normalised operators (Sec. 3.4: A_hat = D^-1/2 (A + I) D^-1/2 for GCN;       */
+/* mean over neighbours for GraphSAGE, Eq. 1 with rho = mean).                  */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * GCN rows of one partition.  Input: adjacency (rowptr, col) of the n_in inner
+ * rows without self loops, columns ascending; deg[r] = degree of local row r in
+ * the whole graph (self loop not counted).  Output CSR has the self loop (r, r)
+ * inserted in column order and weights 1/sqrt((deg_r+1)(deg_c+1)), evaluated in
+ * double and rounded to float.  out_rowptr has n_in+1 entries; out_col/out_w
+ * need nnz + n_in entries.
+ */
+void orc_gcn_operator(const int64_t *rowptr, const int32_t *col, const int32_t *deg,
+                      int64_t n_in, int64_t *out_rowptr, int32_t *out_col, float *out_w)
+{
+    for (int64_t r = 0; r <= n_in; ++r) out_rowptr[r] = rowptr[r] + r;
+#pragma omp parallel for schedule(dynamic, 1024)
+    for (int64_t r = 0; r < n_in; ++r) {
+        int64_t o = out_rowptr[r];
+        const double dr = (double)deg[r] + 1.0;
+        int placed = 0;
+        for (int64_t e = rowptr[r]; e < rowptr[r + 1]; ++e) {
+            if (!placed && (int64_t)col[e] > r) {
+                out_col[o] = (int32_t)r;
+                out_w[o] = (float)(1.0 / sqrt(dr * dr));
+                ++o;
+                placed = 1;
+            }
+            out_col[o] = col[e];
+            out_w[o] = (float)(1.0 / sqrt(dr * ((double)deg[col[e]] + 1.0)));
+            ++o;
+        }
+        if (!placed) {
+            out_col[o] = (int32_t)r;
+            out_w[o] = (float)(1.0 / sqrt(dr * dr));
+        }
+    }
+}
+
+/* GraphSAGE mean: weight of every entry of row r is 1/len(r) (in double, rounded). */
+void orc_mean_weights(const int64_t *rowptr, int64_t n_in, float *out_w)
+{
+#pragma omp parallel for schedule(dynamic, 1024)
+    for (int64_t r = 0; r < n_in; ++r) {
+        const int64_t len = rowptr[r + 1] - rowptr[r];
+        for (int64_t e = rowptr[r]; e < rowptr[r + 1]; ++e) out_w[e] = (float)(1.0 / (double)len);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Neighbour aggregation (Eq. 1; Alg. 1 "update embeddings", the A * Htilde     */
+/* product) and its transpose (Alg. 2 "compute feature gradients").             */
+/* ------------------------------------------------------------------------- */
+
+/* Z[v][c] = sum_e w_e * X[col_e][c] over the entries e of row v; double sum,
+ * one rounding.  If S != NULL also S[v][c] = sum_e |w_e * X[col_e][c]| (the
+ * magnitude the tolerance of a float re-implementation is measured against). */
+void orc_aggregate_fwd(const int64_t *rowptr, const int32_t *col, const float *w,
+                       int64_t n_rows, const float *X, int64_t ldx, int32_t d, float *Z,
+                       int64_t ldz, float *S, int64_t lds)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        for (int32_t c = 0; c < d; ++c) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+                const double t = (double)w[e] * (double)X[(int64_t)col[e] * ldx + c];
+                acc += t;
+                mag += fabs(t);
+            }
+            Z[v * ldz + c] = (float)acc;
+            if (S) S[v * lds + c] = (float)mag;
+        }
+    }
+}
+
+/* dX[u][c] = sum over entries (v, u) of w_vu * dZ[v][c], for every local row
+ * u in [0, n_cols): scattered straight from the forward CSR into a double
+ * buffer, rounded once at the end.  S as above (may be NULL). */
+int orc_aggregate_bwd(const int64_t *rowptr, const int32_t *col, const float *w, int64_t n_rows,
+                      int64_t n_cols, const float *dZ, int64_t ldz, int32_t d, float *dX,
+                      int64_t ldx, float *S, int64_t lds)
+{
+    double *acc = (double *)calloc((size_t)n_cols * (size_t)d, sizeof(double));
+    double *mag = S ? (double *)calloc((size_t)n_cols * (size_t)d, sizeof(double)) : NULL;
+    if (!acc || (S && !mag)) {
+        free(acc);
+        free(mag);
+        return -1;
+    }
+    for (int64_t v = 0; v < n_rows; ++v) {
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const int64_t u = col[e];
+            for (int32_t c = 0; c < d; ++c) {
+                const double t = (double)w[e] * (double)dZ[v * ldz + c];
+                acc[u * d + c] += t;
+                if (mag) mag[u * d + c] += fabs(t);
+            }
+        }
+    }
+    for (int64_t u = 0; u < n_cols; ++u)
+        for (int32_t c = 0; c < d; ++c) {
+            dX[u * ldx + c] = (float)acc[u * d + c];
+            if (S) S[u * lds + c] = (float)mag[u * d + c];
+        }
+    free(acc);
+    free(mag);
+    return 0;
+}
+
+/* The same transpose product, but only for the n_sel output rows listed in
+ * sel (ascending, distinct): one pass over the forward CSR, for checks at sizes
+ * where the full double buffer would not fit.  out / S are [n_sel][d]. */
+void orc_aggregate_bwd_rows(const int64_t *rowptr, const int32_t *col, const float *w,
+                            int64_t n_rows, const float *dZ, int64_t ldz, int32_t d,
+                            const int32_t *sel, int64_t n_sel, float *out, float *S)
+{
+    double *acc = (double *)calloc((size_t)n_sel * (size_t)d * 2, sizeof(double));
+    double *mag = acc + (size_t)n_sel * (size_t)d;
+    for (int64_t v = 0; v < n_rows; ++v) {
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            /* binary search for col[e] in sel */
+            int64_t lo = 0, hi = n_sel;
+            while (lo < hi) {
+                const int64_t mid = (lo + hi) / 2;
+                if (sel[mid] < col[e]) lo = mid + 1; else hi = mid;
+            }
+            if (lo == n_sel || sel[lo] != col[e]) continue;
+            for (int32_t c = 0; c < d; ++c) {
+                const double t = (double)w[e] * (double)dZ[v * ldz + c];
+                acc[lo * d + c] += t;
+                mag[lo * d + c] += fabs(t);
+            }
+        }
+    }
+    for (int64_t i = 0; i < n_sel * d; ++i) {
+        out[i] = (float)acc[i];
+        if (S) S[i] = (float)mag[i];
+    }
+    free(acc);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Dense transform (Eq. 2; Alg. 1 H = sigma(Z W); Alg. 2 weight and feature     */
+/* gradients).  sigma = ReLU.  The left operand may be two column blocks side   */
+/* by side, [A1 | A2] (GraphSAGE: own embedding next to the neighbour mean);    */
+/* pass k2 = 0 for a single block.  W is (k1+k2) x h row-major.                 */
+/* ------------------------------------------------------------------------- */
+
+/* P = [A1|A2] W (double sum, one rounding); H = relu ? max(P, 0) : P.
+ * P_out and S (sum of |terms|) may be NULL. */
+void orc_transform_fwd(const float *A1, int64_t ld1, int32_t k1, const float *A2, int64_t ld2,
+                       int32_t k2, const float *Wm, int32_t h, int64_t n, int relu, float *H,
+                       int64_t ldh, float *P_out, float *S)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        for (int32_t j = 0; j < h; ++j) {
+            double acc = 0.0, mag = 0.0;
+            for (int32_t k = 0; k < k1; ++k) {
+                const double t = (double)A1[i * ld1 + k] * (double)Wm[(int64_t)k * h + j];
+                acc += t;
+                mag += fabs(t);
+            }
+            for (int32_t k = 0; k < k2; ++k) {
+                const double t = (double)A2[i * ld2 + k] * (double)Wm[(int64_t)(k1 + k) * h + j];
+                acc += t;
+                mag += fabs(t);
+            }
+            const float p = (float)acc;
+            if (P_out) P_out[i * h + j] = p;
+            if (S) S[i * h + j] = (float)mag;
+            H[i * ldh + j] = (relu && !(p > 0.0f)) ? 0.0f : p;
+        }
+    }
+}
+
+/* Backward of the transform.  M = J o [H > 0] when relu (H is the forward
+ * output, so H > 0 exactly where the pre-activation was > 0), else M = J.
+ *   G  = [A1|A2]^T M          ((k1+k2) x h, double sums)          if G  != NULL
+ *   dA = M W^T                (n x (k1+k2), written as two blocks dA1 | dA2
+ *                              with leading dims ldd1, ldd2)       if dA1 != NULL
+ * SG / SdA1 / SdA2: sums of |terms|, dense ((k1+k2) x h, n x k1, n x k2; may be NULL). */
+void orc_transform_bwd(const float *A1, int64_t ld1, int32_t k1, const float *A2, int64_t ld2,
+                       int32_t k2, const float *Wm, int32_t h, int64_t n, int relu,
+                       const float *H, int64_t ldh, const float *J, int64_t ldj, float *G,
+                       float *SG, float *dA1, int64_t ldd1, float *dA2, int64_t ldd2,
+                       float *SdA1, float *SdA2)
+{
+    const int32_t K = k1 + k2;
+    if (G) {
+#pragma omp parallel for schedule(static)
+        for (int32_t k = 0; k < K; ++k) {
+            for (int32_t j = 0; j < h; ++j) {
+                double acc = 0.0, mag = 0.0;
+                for (int64_t i = 0; i < n; ++i) {
+                    const float m = (relu && !(H[i * ldh + j] > 0.0f)) ? 0.0f : J[i * ldj + j];
+                    const float a = k < k1 ? A1[i * ld1 + k] : A2[i * ld2 + (k - k1)];
+                    const double t = (double)a * (double)m;
+                    acc += t;
+                    mag += fabs(t);
+                }
+                G[(int64_t)k * h + j] = (float)acc;
+                if (SG) SG[(int64_t)k * h + j] = (float)mag;
+            }
+        }
+    }
+    if (dA1) {
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < n; ++i) {
+            for (int32_t k = 0; k < K; ++k) {
+                double acc = 0.0, mag = 0.0;
+                for (int32_t j = 0; j < h; ++j) {
+                    const float m = (relu && !(H[i * ldh + j] > 0.0f)) ? 0.0f : J[i * ldj + j];
+                    const double t = (double)m * (double)Wm[(int64_t)k * h + j];
+                    acc += t;
+                    mag += fabs(t);
+                }
+                if (k < k1) {
+                    dA1[i * ldd1 + k] = (float)acc;
+                    if (SdA1) SdA1[i * k1 + k] = (float)mag;
+                } else {
+                    dA2[i * ldd2 + (k - k1)] = (float)acc;
+                    if (SdA2) SdA2[i * k2 + (k - k1)] = (float)mag;
+                }
+            }
+        }
+    }
+}
+
+int orc_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}
