@@ -1,0 +1,296 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+One "step" is one forward + backward pass of the whole layer loop (Alg. 1 + Alg. 2)
+over one synthetic partition: per layer quantize -> dequantize -> aggregate ->
+transform, and the mirror-image backward.  All inputs are resident in HBM before
+the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "1-bit quant+dequant GB/s and aggregation edges/s (fwd+bwd), % of HBM peak"
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class OpTimer:
+    """Brackets every C-ABI call with HIP events on the stream the kernels run on and
+    books the call's algorithmic bytes / flops (formulas stated in the design doc)."""
+
+    def __init__(self, B, torch, op_info):
+        self.B, self.torch, self.op_info = B, torch, op_info
+        self.calls = []
+        self.orig = {}
+
+    def _wrap(self, name, cost):
+        fn = getattr(self.B, name)
+        self.orig[name] = fn
+        torch = self.torch
+
+        def wrapped(*a, **kw):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn(*a, **kw)
+            e1.record()
+            self.calls.append((name, e0, e1, cost(*a, **kw)))
+        setattr(self.B, name, wrapped)
+
+    def install(self):
+        W = lambda d: 8 * ((d + 63) // 64)
+
+        def q_cost(src, ld, d, idx, off, n, *rest):
+            return {"bytes": n * (4 * d + (4 if idx is not None else 0) + W(d) + 8), "rows": n}
+
+        def dqf_cost(pk, sc, zp, n, d, *rest):
+            return {"bytes": n * (W(d) + 8 + 4 * d), "rows": n}
+
+        def dqb_cost(pk, sc, zp, n, d, dst, ld, sp, sr, n_dst, di):
+            return {"bytes": n * (W(d) + 8 + 4) + n_dst * (8 * d + 12), "rows": n}
+
+        def ag_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, Y, ldy, **kw):
+            info = self.op_info[rp.data_ptr()]
+            b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched"] * 4 * d \
+                + n_rows * (4 * d + 8)
+            if kw.get("addend") is not None:
+                b += kw["addend_rows"] * 4 * d
+            return {"bytes": b, "edges": info["nnz"],
+                    "gather_bytes": info["nnz"] * (4 * d + 8) + n_rows * (4 * d + 8)}
+
+        def tf_cost(A1, ld1, k1, A2, ld2, k2, Wm, h, n, relu, H, ldh):
+            return {"flops": 2 * n * (k1 + k2) * h, "bytes": 4 * n * (k1 + k2 + h)}
+
+        def tb_cost(A1, ld1, k1, A2, ld2, k2, Wm, h, n, relu, H, ldh, J, ldj, G, dA1, *rest):
+            f = 2 * n * (k1 + k2) * h * ((1 if G is not None else 0) + (1 if dA1 is not None else 0))
+            return {"flops": f, "bytes": 4 * n * (2 * (k1 + k2) + 2 * h)}
+
+        self._wrap("sylvie_quantize_1bit_fwd", q_cost)
+        self._wrap("sylvie_quantize_1bit_bwd", q_cost)
+        self._wrap("sylvie_dequantize_1bit_fwd", dqf_cost)
+        self._wrap("sylvie_dequantize_1bit_bwd", dqb_cost)
+        self._wrap("sylvie_aggregate_csr_fwd", ag_cost)
+        self._wrap("sylvie_aggregate_csr_bwd", ag_cost)
+        self._wrap("sylvie_transform_fwd", tf_cost)
+        self._wrap("sylvie_transform_bwd", tb_cost)
+
+    def remove(self):
+        for k, v in self.orig.items():
+            setattr(self.B, k, v)
+
+    def summary(self, steps):
+        out = {}
+        for name, e0, e1, cost in self.calls:
+            ms = e0.elapsed_time(e1)
+            o = out.setdefault(name, {"calls": 0, "ms": 0.0, "bytes": 0, "flops": 0, "edges": 0,
+                                      "rows": 0, "gather_bytes": 0})
+            o["calls"] += 1
+            o["ms"] += ms
+            for k in ("bytes", "flops", "edges", "rows", "gather_bytes"):
+                o[k] += cost.get(k, 0)
+        for o in out.values():
+            o["avg_ms_per_call"] = o["ms"] / o["calls"]
+            o["ms_per_step"] = o["ms"] / steps
+            o["GBps"] = o["bytes"] / (o["ms"] * 1e-3) / 1e9 if o["ms"] > 0 else 0.0
+            o["frac_hbm_peak"] = o["GBps"] / HBM_PEAK_GBS
+            if o["flops"]:
+                o["TFLOPs"] = o["flops"] / (o["ms"] * 1e-3) / 1e12
+            if o["edges"]:
+                o["edges_per_s"] = o["edges"] / (o["ms"] * 1e-3)
+                o["gather_GBps"] = o["gather_bytes"] / (o["ms"] * 1e-3) / 1e9
+            if o["rows"]:
+                o["rows_per_s"] = o["rows"] / (o["ms"] * 1e-3)
+            for k in ("bytes", "flops", "edges", "rows", "gather_bytes", "ms"):
+                o[k] = o[k] / steps if k != "ms" else o[k]
+        return out
+
+
+def cpu_baseline(torch, loop, st, dims, budget_s=20.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: the first
+    rows of layer 1's aggregation and of its halo exchange, timed on the host cores."""
+    import numpy as np
+    import oracle
+    rp, cl, w = st.op
+    d = dims[0]
+    ht = st.Htil[0]
+    threads = oracle.num_threads()
+
+    def sample(n_rows):
+        n_rows = min(n_rows, st.n_in)
+        e1 = int(rp[n_rows])
+        cols = cl[:e1].long()
+        uniq, inv = torch.unique(cols, return_inverse=True)
+        Xs = np.ascontiguousarray(ht[uniq].cpu().numpy())
+        rps = np.ascontiguousarray(rp[: n_rows + 1].cpu().numpy())
+        cls = np.ascontiguousarray(inv.to(torch.int32).cpu().numpy())
+        ws = np.ascontiguousarray(w[:e1].cpu().numpy())
+        return n_rows, e1, rps, cls, ws, Xs
+
+    n_rows, e1, rps, cls, ws, Xs = sample(2000)
+    t0 = time.perf_counter()
+    oracle.aggregate_fwd(rps, cls, ws, Xs, d)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    want_rows = int(min(st.n_in, max(2000, n_rows * (budget_s * 0.6) / dt)))
+    if want_rows > n_rows * 2:
+        n_rows, e1, rps, cls, ws, Xs = sample(want_rows)
+        t0 = time.perf_counter()
+        oracle.aggregate_fwd(rps, cls, ws, Xs, d)
+        dt = time.perf_counter() - t0
+    edges_per_s = e1 / dt
+    # quantize + dequantize of a sample of the halo exchange
+    nq = int(min(st.n_halo, 200_000))
+    if nq > 0:
+        blk = st.blocks[0]
+        idx = np.ascontiguousarray(blk.rows[:nq].cpu().numpy())
+        nq = idx.shape[0]
+        uniq, inv = np.unique(idx, return_inverse=True)
+        src = np.ascontiguousarray(ht[torch.from_numpy(uniq).long().to(ht.device)].cpu().numpy())
+        t0 = time.perf_counter()
+        pk, sc, zp = oracle.quantize_1bit(src, d, nq, 1, 2, idx=inv.astype(np.int32))
+        out = np.empty((nq, d), np.float32)
+        oracle.dequantize_1bit_fwd(pk, sc, zp, d, out, 0)
+        dtq = time.perf_counter() - t0
+        Wb = 8 * ((d + 63) // 64)
+        qd_gbps = nq * ((4 * d + 4 + Wb + 8) + (Wb + 8 + 4 * d)) / dtq / 1e9
+    else:
+        qd_gbps, dtq = 0.0, 0.0
+    return {"value": edges_per_s, "unit": "edges/s", "cores": threads, "kind": "oracle",
+            "sample": f"oracle aggregate_fwd (float64 accumulate) on the first {n_rows} rows "
+                      f"({e1} edges, d={d}) of layer 1 in {dt:.2f} s; oracle quantize+dequantize "
+                      f"of {nq} halo rows in {dtq:.2f} s",
+            "quant_dequant_GBps": qd_gbps}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="stress")
+    ap.add_argument("--nodes", type=int, default=0, help="shrink the workload to this many nodes")
+    ap.add_argument("--chunk", type=int, default=1024)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+                 "use --gpus 1. value is the one GPU's throughput.")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU (there is no CPU path)")
+    from synth import CONFIGS, build_workload, scaled
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd.trainer import LayerLoop
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    spec = CONFIGS[args.workload]
+    if args.nodes:
+        spec = scaled(spec, args.nodes)
+    t0 = time.time()
+    wl = build_workload(spec, device=dev)
+    torch.cuda.synchronize()
+    p0 = wl.parts[0]
+    log(f"[bench] workload {spec.name}: n_in={p0.n_in} n_halo={p0.n_halo} nnz={p0.nnz} "
+        f"dims={spec.dims} model={spec.model} ({time.time() - t0:.1f} s to generate)")
+    if wl.mirror is not None:
+        owner = [torch.zeros(p0.n_halo, dtype=torch.int32, device=dev)]
+        rows = [wl.mirror]
+    else:
+        owner = [p.halo_part for p in wl.parts]
+        rows = [p.halo_row for p in wl.parts]
+    forced = spec.name.startswith("tiny")
+    t0 = time.time()
+    loop = LayerLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, spec.model, spec.dims,
+                     chunk=args.chunk, exchange_first_layer=forced)
+    torch.cuda.synchronize()
+    log(f"[bench] set-up (operators, transpose, plans, buffers): {time.time() - t0:.1f} s; "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
+
+    op_info = {}
+    for st in loop.parts:
+        for op in (st.op, st.opT):
+            op_info[op[0].data_ptr()] = {"nnz": int(op[0][-1]),
+                                         "touched": int(torch.unique(op[1]).numel())}
+    seed = 20230301
+    for i in range(args.warmup):
+        loop.forward(seed + i)
+        loop.backward(seed + i)
+    torch.cuda.synchronize()
+    log("[bench] warm-up done")
+
+    timer = OpTimer(B, torch, op_info)
+    timer.install()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        loop.forward(seed + 100 + i)
+        loop.backward(seed + 100 + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timer.remove()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ops = timer.summary(args.steps)
+
+    edges_per_step = sum(o["edges"] for o in ops.values())
+    value = edges_per_step / (ms_per_step * 1e-3)
+    q = [ops[k] for k in ops if "quantize" in k]            # quantize + dequantize, both directions
+    qd_bytes = sum(o["bytes"] for o in q)
+    qd_ms = sum(o["ms_per_step"] for o in q)
+    ag = [ops[k] for k in ops if "aggregate" in k]
+    ag_ms = sum(o["ms_per_step"] for o in ag)
+
+    dom_name = max(ops, key=lambda k: ops[k]["ms"])
+    dom = ops[dom_name]
+    if "transform" in dom_name:
+        roof = {"kernel": dom_name, "bound": "mfma", "achieved": dom["TFLOPs"],
+                "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom["TFLOPs"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None}
+    else:
+        roof = {"kernel": dom_name, "bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": dom["GBps"] / HBM_PEAK_GBS, "traffic": None}
+    roof["avg_launch_ms"] = dom["avg_ms_per_call"]
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": spec.name, "graph": spec.graph, "n_nodes": spec.n_nodes,
+                   "n_in": p0.n_in, "n_halo": p0.n_halo, "nnz_adjacency": p0.nnz,
+                   "layer_model": spec.model, "dims": list(spec.dims), "chunk": args.chunk,
+                   "value_is": "aggregated edges (fwd+bwd, all layers) per second of the whole "
+                               "step, every hot-path kernel inside the timed region"},
+        "roofline": roof,
+        "quant_dequant": {"GBps": qd_bytes / (qd_ms * 1e-3) / 1e9 if qd_ms else 0.0,
+                          "frac_hbm_peak": (qd_bytes / (qd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                          if qd_ms else 0.0, "ms_per_step": qd_ms},
+        "aggregation": {"edges_per_s": edges_per_step / (ag_ms * 1e-3) if ag_ms else 0.0,
+                        "ms_per_step": ag_ms},
+        "kernels": {k: {kk: (round(vv, 6) if isinstance(vv, float) else vv)
+                        for kk, vv in v.items()} for k, v in ops.items()},
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(torch, loop, loop.parts[0], spec.dims)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

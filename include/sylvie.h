@@ -1,0 +1,206 @@
+/*
+ * sylvie.h -- C ABI of the MI355X (gfx950) hot path of Sylvie's per-layer boundary
+ * exchange on one graph partition (arXiv 2303.01277): the Low-bit Module
+ * (1-bit quantizer / dequantizer, Sec. 3.2, Eq. 3-5) and the partition-local
+ * layer it feeds (CSR neighbour aggregation and dense transform, Alg. 1 / Alg. 2).
+ *
+ * Conventions (all entry points)
+ *   - Every pointer is DEVICE memory owned by the caller unless the parameter
+ *     says "host".  The library never allocates, frees or keeps a pointer.
+ *   - Matrices are row-major float32; `ld_*` is the distance between rows in
+ *     elements (>= the number of columns used).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.  Buffers must
+ *     stay valid and unaliased (except where stated) until that work is done.
+ *   - Return value: SYLVIE_OK or a negative SYLVIE_ERR_* code; nothing is
+ *     enqueued when an error is returned.  sylvie_last_error() gives a
+ *     thread-local text for the last failing call.
+ *   - Sizes of zero rows are valid no-ops.  Inputs must be finite with
+ *     |x| < 2^126; row indices must be in range (not checked on the device).
+ *
+ * Wire format of one exchange of n_rows rows of width d (Sec. 3.2, "1-bit
+ * integers" plus the scale / zero-point side channel):
+ *   packed : uint64 [n_rows][W], W = ceil(d/64); bit j (LSB = 0) of word k of a
+ *            row is column 64k + j; bits of columns >= d are 0.
+ *   scale  : float32 [n_rows], max - min of the row        (B = 2^1 - 1 = 1)
+ *   zero   : float32 [n_rows], min of the row (a -0 is stored as +0)
+ */
+#ifndef SYLVIE_H
+#define SYLVIE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SYLVIE_OK 0
+#define SYLVIE_ERR_INVALID_ARG (-1)
+#define SYLVIE_ERR_BAD_ALIGNMENT (-2)
+#define SYLVIE_ERR_HIP (-3)
+#define SYLVIE_ERR_UNIMPLEMENTED (-4)
+#define SYLVIE_ERR_WORKSPACE (-5)
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t sylvie_version(void);
+/* Static text for a status code. */
+const char *sylvie_status_string(int32_t status);
+/* Thread-local detail of the last error returned on this thread ("" if none). */
+const char *sylvie_last_error(void);
+
+/* Words per packed row: ceil(d / 64). */
+int64_t sylvie_words_per_row(int32_t d);
+
+/*
+ * Quantizer, forward direction (Alg. 1, "quantize([H(S_1), ..., H(S_N)])"; Eq. 3-4).
+ *
+ * Wire row i (0 <= i < n_rows) is source row idx[i] of `src` when idx != NULL,
+ * else source row row_offset + i.  Per row, in float32:
+ *     mn = min_c r_c, mx = max_c r_c (each + 0.0f);  zero = mn;  scale = mx - mn
+ *     u  = k / 2^24, k = 24 random bits of (seed, stream_id, i, c)
+ *     bit(i, c) = [ fl(u * scale) < fl(r_c - mn) ]
+ * which rounds the normalised value (r_c - mn)/(mx - mn) of Eq. 3 up to 1 with
+ * probability equal to that value (Eq. 4, b = 1) and gives all-zero bits for a
+ * constant row.  The random bits are a counter hash of the four keys; the same
+ * keys always give the same bits.  `stream_id` separates layers and directions
+ * (the callers here use 2*layer + direction).
+ *
+ *   src        [*, ld_src] float32, d <= ld_src, 1 <= d <= 65536
+ *   idx        int32 [n_rows] or NULL; duplicates allowed
+ *   n_rows     0 <= n_rows < 2^31
+ *   packed_out uint64 [n_rows][ceil(d/64)], 8-byte aligned
+ *   scale_out, zero_out  float32 [n_rows]
+ */
+int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
+                                 const int32_t *idx, int64_t row_offset, int64_t n_rows,
+                                 uint64_t seed, uint32_t stream_id, uint64_t *packed_out,
+                                 float *scale_out, float *zero_out, void *stream);
+
+/*
+ * Quantizer, backward direction (Alg. 2, "quantize([J(R_1), ..., J(R_N)])").
+ * Same operation and arguments; the rows are feature gradients.  The usual call
+ * passes the gradient of the halo block: idx = NULL, row_offset = number of
+ * inner rows.
+ */
+int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
+                                 const int32_t *idx, int64_t row_offset, int64_t n_rows,
+                                 uint64_t seed, uint32_t stream_id, uint64_t *packed_out,
+                                 float *scale_out, float *zero_out, void *stream);
+
+/*
+ * Dequantizer, forward direction (Eq. 5; Alg. 1 "dequantize" + "concatenate"):
+ *     dst[row_offset + i][c] = bit(i, c) ? fl(zero_i + scale_i) : zero_i,  c < d.
+ * Writing at row_offset = number of inner rows places the recovered rows directly
+ * below the inner rows, which is the concatenation.  Columns >= d of dst are not
+ * touched.
+ */
+int32_t sylvie_dequantize_1bit_fwd(const uint64_t *packed, const float *scale,
+                                   const float *zero, int64_t n_rows, int32_t d, float *dst,
+                                   int64_t ld_dst, int64_t row_offset, void *stream);
+
+/*
+ * Dequantizer, backward direction (Eq. 5; Alg. 2 "integrate feature gradients",
+ * J = J + R~): received gradient rows are added into the rows of `dst` they
+ * belong to.  Several wire rows may belong to one destination row, so the caller
+ * passes the wire rows grouped by destination:
+ *     for k in [0, n_dst_rows):  r = dst_ids[k]
+ *         acc = dst[r][:]
+ *         for j in [seg_ptr[k], seg_ptr[k+1]):  acc = fl(acc + deq(seg_rows[j])[:])
+ *         dst[r][:] = acc
+ * With seg_rows ascending inside each group this equals "for i ascending:
+ * dst[dst_row[i]] += deq(i)" bit for bit, with no atomics.
+ *
+ *   seg_ptr   int64 [n_dst_rows + 1], seg_ptr[0] = 0, seg_ptr[n_dst_rows] <= n_rows
+ *   seg_rows  int32 [seg_ptr[n_dst_rows]], wire row indices in [0, n_rows)
+ *   dst_ids   int32 [n_dst_rows], distinct rows of dst
+ */
+int32_t sylvie_dequantize_1bit_bwd(const uint64_t *packed, const float *scale,
+                                   const float *zero, int64_t n_rows, int32_t d, float *dst,
+                                   int64_t ld_dst, const int64_t *seg_ptr,
+                                   const int32_t *seg_rows, int64_t n_dst_rows,
+                                   const int32_t *dst_ids, void *stream);
+
+/*
+ * Neighbour aggregation, forward (Eq. 1; Alg. 1, the product A_n * H~ with A_n
+ * the normalised local adjacency, Sec. 3.4):
+ *     Y[v][c] = row_scale[v] * sum_{e in [rowptr[v], rowptr[v+1])}
+ *                                  w[e] * col_scale[col[e]] * X[col[e]][c]
+ * for v < n_rows, c < d; a NULL w / row_scale / col_scale counts as all ones.
+ * float32 accumulation in a fixed order (results are reproducible run to run).
+ * If `addend` != NULL, rows v < addend_rows get Y[v][c] += addend[v][c]
+ * (GraphSAGE backward: the gradient of a node's own embedding).
+ *
+ * Rows longer than `chunk` entries are split into ceil(len/chunk) tasks whose
+ * partial sums go through `workspace` and are added in task order.  The caller
+ * lists those rows (built once per graph from rowptr):
+ *   long_rows  int32 [n_long]   rows with len > chunk, ascending
+ *   long_ptr   int64 [n_long+1] prefix sum of ceil(len/chunk) over long_rows
+ *   n_tasks    = long_ptr[n_long] (host value)
+ *   workspace  float32 [n_tasks][d] (workspace_bytes >= n_tasks*d*4), 16-byte aligned
+ * With n_long = 0 these may be NULL / 0 and every row is summed by one wavefront.
+ * chunk must be a positive multiple of 64.
+ *
+ *   rowptr int64 [n_rows+1]; col int32 [nnz] in [0, rows of X)
+ */
+int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, const float *w,
+                                 const float *row_scale, const float *col_scale,
+                                 int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+                                 float *Y, int64_t ld_y, const float *addend,
+                                 int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                 const int32_t *long_rows, const int64_t *long_ptr,
+                                 int64_t n_long, int64_t n_tasks, float *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
+ * Neighbour aggregation, backward (Alg. 2, the product A_n^T * (J o sigma') W^T,
+ * here its sparse factor): the same operation applied to the CSR of the
+ * transposed operator, whose rows are ALL local rows (inner and halo) and whose
+ * columns are the inner rows, so that dX = A^T dY.  The halo block of dX is what
+ * the backward quantizer sends.  Arguments as in the forward call.
+ */
+int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_t *colT, const float *wT,
+                                 const float *row_scale, const float *col_scale,
+                                 int64_t n_rowsT, const float *dY, int64_t ld_dy, int32_t d,
+                                 float *dX, int64_t ld_dx, const float *addend,
+                                 int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                 const int32_t *long_rows, const int64_t *long_ptr,
+                                 int64_t n_long, int64_t n_tasks, float *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
+ * Dense transform, forward (Eq. 2; Alg. 1 "update embeddings", H = sigma(Z W)):
+ *     P = [A1 | A2] * W,   H = relu ? max(P, 0) : P
+ * A1 is n x k1 (ld_a1), A2 is n x k2 (ld_a2) or NULL with k2 = 0 (GraphSAGE puts a
+ * node's own embedding next to the neighbour mean); W is (k1+k2) x h, row-major,
+ * contiguous; H is n x h (ld_h).  float32 inputs, float32 MFMA accumulation.
+ * k1, k2 and h must be multiples of 4 and all pointers 16-byte aligned.
+ */
+int32_t sylvie_transform_fwd(const float *A1, int64_t ld_a1, int32_t k1, const float *A2,
+                             int64_t ld_a2, int32_t k2, const float *W, int32_t h, int64_t n,
+                             int32_t relu, float *H, int64_t ld_h, void *stream);
+
+/* Bytes of workspace sylvie_transform_bwd needs for the weight gradient. */
+size_t sylvie_transform_bwd_workspace_bytes(int32_t k1, int32_t k2, int32_t h, int64_t n);
+
+/*
+ * Dense transform, backward (Alg. 2 "compute weight gradients" and the dense
+ * factor of "compute feature gradients"):
+ *     M  = relu ? J o [H > 0] : J            (H is the forward output)
+ *     G  = [A1 | A2]^T * M     ((k1+k2) x h, contiguous)        if G   != NULL
+ *     dA = M * W^T             (n x (k1+k2), written as the two blocks
+ *                               dA1 (ld_da1) and dA2 (ld_da2))    if dA1 != NULL
+ * The weight gradient is summed over row slabs through `workspace`
+ * (sylvie_transform_bwd_workspace_bytes) in a fixed order.
+ */
+int32_t sylvie_transform_bwd(const float *A1, int64_t ld_a1, int32_t k1, const float *A2,
+                             int64_t ld_a2, int32_t k2, const float *W, int32_t h, int64_t n,
+                             int32_t relu, const float *H, int64_t ld_h, const float *J,
+                             int64_t ld_j, float *G, float *dA1, int64_t ld_da1, float *dA2,
+                             int64_t ld_da2, float *workspace, size_t workspace_bytes,
+                             void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SYLVIE_H */

@@ -1,0 +1,171 @@
+"""ctypes binding of libsylvie.so: one wrapper per entry point of include/sylvie.h.
+
+The wrappers take torch tensors that already live on the GPU, check nothing but
+device and dtype, and pass raw pointers, sizes and the current HIP stream.  There
+is no CPU path: if the library is not built, or a tensor is not on the GPU, the
+call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from .build import library_path
+
+_lib = None
+
+
+class SylvieError(RuntimeError):
+    pass
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise SylvieError(
+                f"{path} is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(path)
+        L.sylvie_version.restype = C.c_int32
+        L.sylvie_status_string.restype = C.c_char_p
+        L.sylvie_status_string.argtypes = [C.c_int32]
+        L.sylvie_last_error.restype = C.c_char_p
+        L.sylvie_words_per_row.restype = C.c_int64
+        L.sylvie_words_per_row.argtypes = [C.c_int32]
+        L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
+        L.sylvie_transform_bwd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32,
+                                                           C.c_int64]
+        for name in ("sylvie_quantize_1bit_fwd", "sylvie_quantize_1bit_bwd",
+                     "sylvie_dequantize_1bit_fwd", "sylvie_dequantize_1bit_bwd",
+                     "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
+                     "sylvie_transform_fwd", "sylvie_transform_bwd"):
+            getattr(L, name).restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise SylvieError(f"{name}: expected a GPU tensor (there is no CPU path)")
+    if dtype is not None and t.dtype != dtype:
+        raise SylvieError(f"{name}: expected {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc):
+    if rc != 0:
+        L = lib()
+        raise SylvieError(f"{L.sylvie_status_string(rc).decode()} ({rc}): "
+                          f"{L.sylvie_last_error().decode()}")
+
+
+def sylvie_version() -> int:
+    return int(lib().sylvie_version())
+
+
+def sylvie_words_per_row(d: int) -> int:
+    return int(lib().sylvie_words_per_row(int(d)))
+
+
+def _quantize(fn, src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, packed_out,
+              scale_out, zero_out):
+    _check(fn(_ptr(src, torch.float32, "src"), C.c_int64(ld_src), C.c_int32(d),
+              _ptr(idx, torch.int32, "idx"), C.c_int64(row_offset), C.c_int64(n_rows),
+              C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
+              _ptr(packed_out, torch.int64, "packed_out"), _ptr(scale_out, torch.float32, "scale"),
+              _ptr(zero_out, torch.float32, "zero"), _stream()))
+
+
+def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id,
+                             packed_out, scale_out, zero_out):
+    """packed_out is an int64 tensor viewed as uint64 words (torch has no uint64 kernels)."""
+    _quantize(lib().sylvie_quantize_1bit_fwd, src, ld_src, d, idx, row_offset, n_rows, seed,
+              stream_id, packed_out, scale_out, zero_out)
+
+
+def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id,
+                             packed_out, scale_out, zero_out):
+    _quantize(lib().sylvie_quantize_1bit_bwd, src, ld_src, d, idx, row_offset, n_rows, seed,
+              stream_id, packed_out, scale_out, zero_out)
+
+
+def sylvie_dequantize_1bit_fwd(packed, scale, zero, n_rows, d, dst, ld_dst, row_offset):
+    _check(lib().sylvie_dequantize_1bit_fwd(
+        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
+        _ptr(zero, torch.float32, "zero"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), C.c_int64(row_offset), _stream()))
+
+
+def sylvie_dequantize_1bit_bwd(packed, scale, zero, n_rows, d, dst, ld_dst, seg_ptr, seg_rows,
+                               n_dst_rows, dst_ids):
+    _check(lib().sylvie_dequantize_1bit_bwd(
+        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
+        _ptr(zero, torch.float32, "zero"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), _ptr(seg_ptr, torch.int64, "seg_ptr"),
+        _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int64(n_dst_rows),
+        _ptr(dst_ids, torch.int32, "dst_ids"), _stream()))
+
+
+def _aggregate(fn, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y, addend,
+               ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(fn(_ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
+              _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
+              _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
+              _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d),
+              _ptr(Y, torch.float32, "Y"), C.c_int64(ld_y), _ptr(addend, torch.float32, "addend"),
+              C.c_int64(ld_addend), C.c_int64(addend_rows), C.c_int32(chunk),
+              _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+              C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
+              C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y,
+                             addend=None, ld_addend=0, addend_rows=0, chunk=0, long_rows=None,
+                             long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    _aggregate(lib().sylvie_aggregate_csr_fwd, rowptr, col, w, row_scale, col_scale, n_rows, X,
+               ld_x, d, Y, ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
+               n_long, n_tasks, workspace)
+
+
+def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, dY, ld_dy, d, dX,
+                             ld_dx, addend=None, ld_addend=0, addend_rows=0, chunk=0,
+                             long_rows=None, long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    _aggregate(lib().sylvie_aggregate_csr_bwd, rowptrT, colT, wT, row_scale, col_scale, n_rowsT,
+               dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows, chunk, long_rows,
+               long_ptr, n_long, n_tasks, workspace)
+
+
+def sylvie_transform_fwd(A1, ld_a1, k1, A2, ld_a2, k2, W, h, n, relu, H, ld_h):
+    _check(lib().sylvie_transform_fwd(
+        _ptr(A1, torch.float32, "A1"), C.c_int64(ld_a1), C.c_int32(k1),
+        _ptr(A2, torch.float32, "A2"), C.c_int64(ld_a2), C.c_int32(k2),
+        _ptr(W, torch.float32, "W"), C.c_int32(h), C.c_int64(n), C.c_int32(int(relu)),
+        _ptr(H, torch.float32, "H"), C.c_int64(ld_h), _stream()))
+
+
+def sylvie_transform_bwd_workspace_bytes(k1, k2, h, n) -> int:
+    return int(lib().sylvie_transform_bwd_workspace_bytes(int(k1), int(k2), int(h), int(n)))
+
+
+def sylvie_transform_bwd(A1, ld_a1, k1, A2, ld_a2, k2, W, h, n, relu, H, ld_h, J, ld_j, G, dA1,
+                         ld_da1, dA2, ld_da2, workspace):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_transform_bwd(
+        _ptr(A1, torch.float32, "A1"), C.c_int64(ld_a1), C.c_int32(k1),
+        _ptr(A2, torch.float32, "A2"), C.c_int64(ld_a2), C.c_int32(k2),
+        _ptr(W, torch.float32, "W"), C.c_int32(h), C.c_int64(n), C.c_int32(int(relu)),
+        _ptr(H, torch.float32, "H"), C.c_int64(ld_h), _ptr(J, torch.float32, "J"),
+        C.c_int64(ld_j), _ptr(G, torch.float32, "G"), _ptr(dA1, torch.float32, "dA1"),
+        C.c_int64(ld_da1), _ptr(dA2, torch.float32, "dA2"), C.c_int64(ld_da2),
+        _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))

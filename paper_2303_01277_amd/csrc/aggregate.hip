@@ -1,0 +1,388 @@
+// CSR neighbour aggregation Y = diag(rs) * A * diag(cs) * X (Eq. 1; Alg. 1 the
+// product A_n * H~; Alg. 2 its transpose on the transposed CSR).
+//
+// The work is a gather of whole feature rows: every entry of A pulls one row of
+// X (d floats, contiguous) and adds it, weighted, into the output row.  It is
+// bound by memory, not arithmetic, so the layout goal is: every load a full
+// contiguous row segment, many rows in flight per wavefront, and no pass over
+// the data that does not have to happen.
+//
+//   * One wavefront sums one output row (or one <= `chunk`-entry piece of a long
+//     row).  G lanes cover one gathered row with VEC-wide loads and P passes
+//     (G*VEC*P >= d); when G < 64 the wave gathers 64/G rows at once and folds
+//     the lane groups together at the end.
+//   * Column indices and weights are read 64 at a time, one per lane, and handed
+//     to the gathering lanes through lane reads (scalar unit for G = 64), not
+//     through LDS: the values are needed exactly once.
+//   * U gathers are issued back to back before the first is consumed.
+//   * Long rows (hubs of a power-law graph) are cut into tasks so no wavefront
+//     runs away with the tail of the launch; the tasks share the launch with the
+//     ordinary rows and go first.  Partial sums are written to a workspace and
+//     added in task order by a second tiny kernel, so results do not depend on
+//     scheduling.
+#include "common.hpp"
+
+namespace sylvie {
+
+constexpr int kAgWavesPerBlock = 4;
+
+template <int VEC>
+struct Vec;
+template <>
+struct Vec<4> { using type = float4; };
+template <>
+struct Vec<2> { using type = float2; };
+template <>
+struct Vec<1> { using type = float; };
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float (&o)[VEC], const float *p)
+{
+    typename Vec<VEC>::type v = *reinterpret_cast<const typename Vec<VEC>::type *>(p);
+    __builtin_memcpy(o, &v, sizeof(v));
+}
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *p, const float (&o)[VEC])
+{
+    typename Vec<VEC>::type v;
+    __builtin_memcpy(&v, o, sizeof(v));
+    *reinterpret_cast<typename Vec<VEC>::type *>(p) = v;
+}
+
+struct AggArgs {
+    const int64_t *rowptr;
+    const int32_t *col;
+    const float *w;
+    const float *row_scale;
+    const float *col_scale;
+    int64_t n_rows;
+    const float *X;
+    int64_t ld_x;
+    int d;
+    float *Y;
+    int64_t ld_y;
+    const float *addend;
+    int64_t ld_addend;
+    int64_t addend_rows;
+    int chunk;          // 0: never split
+    const int32_t *long_rows;
+    const int64_t *long_ptr;
+    int64_t n_long;
+    float *workspace;
+};
+
+// acc[p][t] += sum over entries [e0, e1) of w_e * cs[col_e] * X[col_e][column(p, t)]
+template <int VEC, int G, int P>
+__device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int64_t e1,
+                                           const AggArgs &a, int lane)
+{
+    constexpr int EP = 64 / G;                 // rows gathered at once
+    constexpr int U = (P >= 4) ? 2 : (8 / P);  // gathers in flight per lane group
+    const int sub = EP == 1 ? 0 : lane / G;
+    const int gl = lane % G;
+    // column offsets of this lane; lanes past the row width re-read its last
+    // vector (never stored) so that no load needs a predicate
+    int coff[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int cc = (p * G + gl) * VEC;
+        coff[p] = cc < a.d ? cc : a.d - VEC;
+    }
+    for (int64_t base = e0; base < e1; base += 64) {
+        const int cnt = static_cast<int>(e1 - base < 64 ? e1 - base : 64);
+        int my_c = 0;
+        float my_w = 0.0f;
+        if (lane < cnt) {
+            my_c = a.col[base + lane];
+            my_w = a.w ? a.w[base + lane] : 1.0f;
+            if (a.col_scale) my_w *= a.col_scale[my_c];
+        }
+        int j = 0;
+        // full groups: U * EP valid entries, all gathers issued before any is used
+        for (; j + EP * U <= cnt; j += EP * U) {
+            float x[U][P][VEC];
+            float wv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int sl = j + u * EP + sub;
+                int c;
+                if constexpr (EP == 1) {
+                    c = __builtin_amdgcn_readlane(my_c, sl);
+                    wv[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), sl));
+                } else {
+                    c = __shfl(my_c, sl);
+                    wv[u] = __shfl(my_w, sl);
+                }
+                const float *xr = a.X + static_cast<int64_t>(c) * a.ld_x;
+#pragma unroll
+                for (int p = 0; p < P; ++p) load_vec<VEC>(x[u][p], xr + coff[p]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int p = 0; p < P; ++p)
+#pragma unroll
+                    for (int t = 0; t < VEC; ++t) acc[p][t] = fmaf(wv[u], x[u][p][t], acc[p][t]);
+        }
+        // remainder: one gather per lane group; groups past the end add w = 0 times
+        // a row they are allowed to read (lanes >= cnt hold column 0, weight 0)
+        for (; j < cnt; j += EP) {
+            const int sl = j + sub;
+            int c;
+            float wj;
+            if constexpr (EP == 1) {
+                c = __builtin_amdgcn_readlane(my_c, sl);
+                wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), sl));
+            } else {
+                c = __shfl(my_c, sl & 63);
+                wj = __shfl(my_w, sl & 63);
+                if (sl >= cnt) wj = 0.0f;
+            }
+            const float *xr = a.X + static_cast<int64_t>(c) * a.ld_x;
+            float x[P][VEC];
+#pragma unroll
+            for (int p = 0; p < P; ++p) load_vec<VEC>(x[p], xr + coff[p]);
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) acc[p][t] = fmaf(wj, x[p][t], acc[p][t]);
+        }
+    }
+    // fold the lane groups: afterwards every group holds the full sums
+    if constexpr (EP > 1) {
+#pragma unroll
+        for (int s = G; s < 64; s <<= 1)
+#pragma unroll
+            for (int p = 0; p < P; ++p)
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) acc[p][t] += __shfl_xor(acc[p][t], s);
+    }
+}
+
+// One launch covers everything that gathers.  The first ceil(n_tasks/4) workgroups
+// take the pieces of the long rows (they start first, so the heaviest rows never
+// trail the launch); every later wavefront takes one ordinary row and skips the
+// long ones.  Pieces write partial sums to workspace[task][0..d).
+template <int VEC, int G, int P>
+__global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kernel(AggArgs a,
+                                                                                    int64_t n_tasks)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t task_blocks = (n_tasks + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
+    float acc[P][VEC];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) acc[p][t] = 0.0f;
+
+    if (static_cast<int64_t>(blockIdx.x) < task_blocks) {
+        const int64_t t = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
+        if (t >= n_tasks) return;
+        // long row that owns task t: last i with long_ptr[i] <= t
+        int64_t lo = 0, hi = a.n_long;
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (a.long_ptr[mid] <= t) lo = mid; else hi = mid;
+        }
+        lo = uniform(lo);
+        const int64_t v = a.long_rows[lo];
+        const int64_t piece = t - a.long_ptr[lo];
+        const int64_t r0 = uniform(a.rowptr[v]);
+        const int64_t r1 = uniform(a.rowptr[v + 1]);
+        const int64_t e0 = r0 + piece * a.chunk;
+        const int64_t e1 = e0 + a.chunk < r1 ? e0 + a.chunk : r1;
+        gather_sum<VEC, G, P>(acc, e0, e1, a, lane);
+        if (lane >= G) return;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int cc = (p * G + lane) * VEC;
+            if (cc < a.d) store_vec<VEC>(a.workspace + t * a.d + cc, acc[p]);
+        }
+        return;
+    }
+
+    const int64_t v = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
+    if (v >= a.n_rows) return;
+    const int64_t e0 = uniform(a.rowptr[v]);
+    const int64_t e1 = uniform(a.rowptr[v + 1]);
+    if (a.chunk > 0 && e1 - e0 > a.chunk) return;
+    gather_sum<VEC, G, P>(acc, e0, e1, a, lane);
+    if (lane >= G) return;
+    const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
+    const bool add = a.addend && v < a.addend_rows;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int cc = (p * G + lane) * VEC;
+        if (cc < a.d) {
+            float o[VEC];
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) o[t] = rs * acc[p][t];
+            if (add) {
+                float ad[VEC];
+                load_vec<VEC>(ad, a.addend + v * a.ld_addend + cc);
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) o[t] += ad[t];
+            }
+            store_vec<VEC>(a.Y + v * a.ld_y + cc, o);
+        }
+    }
+}
+
+// One wavefront per long row: add its partial sums in task order, scale, store.
+template <int VEC>
+__global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kernel(AggArgs a)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
+    if (i >= a.n_long) return;
+    const int64_t v = a.long_rows[i];
+    const int64_t t0 = a.long_ptr[i], t1 = a.long_ptr[i + 1];
+    const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
+    const bool add = a.addend && v < a.addend_rows;
+    for (int cc = lane * VEC; cc < a.d; cc += 64 * VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
+        for (int64_t t = t0; t < t1; ++t) {
+            float part[VEC];
+            load_vec<VEC>(part, a.workspace + t * a.d + cc);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += part[q];
+        }
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) acc[q] *= rs;
+        if (add) {
+            float ad[VEC];
+            load_vec<VEC>(ad, a.addend + v * a.ld_addend + cc);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += ad[q];
+        }
+        store_vec<VEC>(a.Y + v * a.ld_y + cc, acc);
+    }
+}
+
+template <int VEC, int G, int P>
+static void launch_shape(const AggArgs &a, int64_t n_tasks, hipStream_t st)
+{
+    const dim3 block(kAgWavesPerBlock * kWave);
+    const int64_t nt = a.n_long > 0 ? n_tasks : 0;
+    const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
+                           (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
+    hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P>), dim3(static_cast<unsigned>(blocks)),
+                       block, 0, st, a, nt);
+    if (a.n_long > 0) {
+        const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
+        hipLaunchKernelGGL((aggregate_reduce_kernel<VEC>), rg, block, 0, st, a);
+    }
+}
+
+template <int VEC>
+static bool launch_vec(const AggArgs &a, int64_t n_tasks, hipStream_t st)
+{
+    const int lanes = (a.d + VEC - 1) / VEC;   // lanes needed for one row, one pass
+    if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, st);
+    else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, st);
+    else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, st);
+    else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, st);
+    else if (lanes <= 192) launch_shape<VEC, 64, 3>(a, n_tasks, st);
+    else if (lanes <= 256) launch_shape<VEC, 64, 4>(a, n_tasks, st);
+    else if (lanes <= 320) launch_shape<VEC, 64, 5>(a, n_tasks, st);
+    else if (lanes <= 384) launch_shape<VEC, 64, 6>(a, n_tasks, st);
+    else if (lanes <= 512) launch_shape<VEC, 64, 8>(a, n_tasks, st);
+    else return false;
+    return true;
+}
+
+static int32_t aggregate_common(const char *name, const int64_t *rowptr, const int32_t *col,
+                                const float *w, const float *row_scale, const float *col_scale,
+                                int64_t n_rows, const float *X, int64_t ld_x, int32_t d, float *Y,
+                                int64_t ld_y, const float *addend, int64_t ld_addend,
+                                int64_t addend_rows, int32_t chunk, const int32_t *long_rows,
+                                const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+                                float *workspace, size_t workspace_bytes, void *stream)
+{
+    if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
+    if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
+    if (ld_x < d || ld_y < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: leading dimension < d", name);
+    if (addend && (ld_addend < d || addend_rows < 0))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad addend shape", name);
+    if (n_long < 0 || n_tasks < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative count", name);
+    if (n_rows == 0) return SYLVIE_OK;
+    if (!rowptr || !col || !X || !Y) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!aligned(rowptr, 8) || !aligned(col, 4) || !aligned(X, 4) || !aligned(Y, 4) ||
+        (w && !aligned(w, 4)))
+        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned pointer", name);
+    if (n_long > 0) {
+        if (chunk <= 0 || chunk % 64 != 0)
+            return fail(SYLVIE_ERR_INVALID_ARG, "%s: chunk must be a positive multiple of 64", name);
+        if (!long_rows || !long_ptr || !workspace)
+            return fail(SYLVIE_ERR_INVALID_ARG, "%s: long-row plan has null pointers", name);
+        if (n_tasks < n_long || n_tasks >= (int64_t(1) << 31))
+            return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_tasks out of range", name);
+        if (workspace_bytes < static_cast<size_t>(n_tasks) * static_cast<size_t>(d) * 4)
+            return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace %zu B < %zu B", name, workspace_bytes,
+                        static_cast<size_t>(n_tasks) * static_cast<size_t>(d) * 4);
+        if (!aligned(workspace, 16))
+            return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: workspace needs 16-byte alignment", name);
+    }
+    AggArgs a;
+    a.rowptr = rowptr; a.col = col; a.w = w; a.row_scale = row_scale; a.col_scale = col_scale;
+    a.n_rows = n_rows; a.X = X; a.ld_x = ld_x; a.d = d; a.Y = Y; a.ld_y = ld_y;
+    a.addend = addend; a.ld_addend = ld_addend; a.addend_rows = addend_rows;
+    a.chunk = n_long > 0 ? chunk : 0;
+    a.long_rows = long_rows; a.long_ptr = long_ptr; a.n_long = n_long; a.workspace = workspace;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool a16 = aligned(X, 16) && aligned(Y, 16) && ld_x % 4 == 0 && ld_y % 4 == 0 &&
+                     d % 4 == 0 && (!addend || (aligned(addend, 16) && ld_addend % 4 == 0));
+    const bool a8 = aligned(X, 8) && aligned(Y, 8) && ld_x % 2 == 0 && ld_y % 2 == 0 &&
+                    d % 2 == 0 && (!addend || (aligned(addend, 8) && ld_addend % 2 == 0));
+    bool ok;
+    if (a16) ok = launch_vec<4>(a, n_tasks, st);
+    else if (a8) ok = launch_vec<2>(a, n_tasks, st);
+    else ok = launch_vec<1>(a, n_tasks, st);
+    if (!ok)
+        return fail(SYLVIE_ERR_UNIMPLEMENTED,
+                    "%s: d = %d is wider than one launch covers at this alignment "
+                    "(2048 / 1024 / 512 columns for 16 / 8 / 4-byte aligned rows); "
+                    "split the columns across calls", name, d);
+    SYLVIE_HIP_LAUNCH_CHECK(name);
+    return SYLVIE_OK;
+}
+
+}  // namespace sylvie
+
+extern "C" int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col,
+                                            const float *w, const float *row_scale,
+                                            const float *col_scale, int64_t n_rows,
+                                            const float *X, int64_t ld_x, int32_t d, float *Y,
+                                            int64_t ld_y, const float *addend, int64_t ld_addend,
+                                            int64_t addend_rows, int32_t chunk,
+                                            const int32_t *long_rows, const int64_t *long_ptr,
+                                            int64_t n_long, int64_t n_tasks, float *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    return sylvie::aggregate_common("sylvie_aggregate_csr_fwd", rowptr, col, w, row_scale,
+                                    col_scale, n_rows, X, ld_x, d, Y, ld_y, addend, ld_addend,
+                                    addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
+                                    workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_t *colT,
+                                            const float *wT, const float *row_scale,
+                                            const float *col_scale, int64_t n_rowsT,
+                                            const float *dY, int64_t ld_dy, int32_t d, float *dX,
+                                            int64_t ld_dx, const float *addend, int64_t ld_addend,
+                                            int64_t addend_rows, int32_t chunk,
+                                            const int32_t *long_rows, const int64_t *long_ptr,
+                                            int64_t n_long, int64_t n_tasks, float *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    return sylvie::aggregate_common("sylvie_aggregate_csr_bwd", rowptrT, colT, wT, row_scale,
+                                    col_scale, n_rowsT, dY, ld_dy, d, dX, ld_dx, addend, ld_addend,
+                                    addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
+                                    workspace, workspace_bytes, stream);
+}

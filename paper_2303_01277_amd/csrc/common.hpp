@@ -1,0 +1,88 @@
+// Shared host/device helpers of the gfx950 kernels (wave64 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/sylvie.h"
+
+namespace sylvie {
+
+constexpr int kWave = 64;
+
+// ---- host side -------------------------------------------------------------
+
+void set_error(const char *fmt, ...);  // api.hip
+int32_t fail(int32_t code, const char *fmt, ...);
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+#define SYLVIE_HIP_LAUNCH_CHECK(name)                                                   \
+    do {                                                                                \
+        hipError_t e_ = hipGetLastError();                                              \
+        if (e_ != hipSuccess)                                                           \
+            return ::sylvie::fail(SYLVIE_ERR_HIP, "%s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- device side -----------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & 63; }
+
+// Wave-uniform value of a quantity that is the same in every lane (lets the
+// compiler keep it, and everything derived from it, on the scalar unit).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ uint32_t uniform(uint32_t v)
+{
+    return static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+}
+__device__ __forceinline__ int64_t uniform(int64_t v)
+{
+    const uint32_t lo = uniform(static_cast<uint32_t>(v));
+    const uint32_t hi = uniform(static_cast<uint32_t>(static_cast<uint64_t>(v) >> 32));
+    return static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+__device__ __forceinline__ float uniform(float v)
+{
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+
+// Plain compare-select minimum / maximum (inputs are finite by contract).
+__device__ __forceinline__ float fmin_sel(float a, float b) { return b < a ? b : a; }
+__device__ __forceinline__ float fmax_sel(float a, float b) { return b > a ? b : a; }
+
+// Minimum and maximum over the 64 lanes, returned wave-uniform.  DPP butterfly
+// inside each row of 16 lanes (quad swaps, half-row mirror, row mirror), then
+// row broadcasts 15 -> rows 1,3 and 31 -> rows 2,3; lane 63 ends with the full
+// result.  Each step is one VALU op with the lane permutation fused in.  The
+// min and max chains alternate and an s_nop separates dependent steps: a DPP
+// operand needs two wait states after the VALU write that produced it, and the
+// compiler does not schedule inside an asm block.
+__device__ __forceinline__ void wave_minmax(float &mn, float &mx)
+{
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "v_max_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(mn), "+v"(mx));
+    mn = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mn), 63));
+    mx = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 63));
+}
+
+}  // namespace sylvie

@@ -1,0 +1,296 @@
+// 1-bit stochastic-rounding quantizer with fused row gather, row extrema and bit
+// packing (Sec. 3.2 "Quantizer" / "Communicator", Eq. 3-4 with b = 1).
+//
+// One wavefront owns one wire row at a time.  Lane L holds columns L, L+64,
+// L+128, ... of the row in registers, so a single wave-wide compare produces a
+// 64-bit lane mask that IS packed word k of the row (bit j = column 64k + j): the
+// packing costs no instructions.  Row minimum and maximum are a DPP reduction;
+// the per-row hash key lives on the scalar unit.
+#include "common.hpp"
+
+namespace sylvie {
+
+// Counter hash behind the rounding draws.  Keys: (seed, stream) -> call key on
+// the host; (call key, wire row) -> row key, scalar unit; (row key, column) ->
+// 24 uniform bits per element.
+constexpr uint32_t kM1 = 0xce6e1acdu;
+constexpr uint32_t kM2 = 0x6d3cb3a7u;
+constexpr uint32_t kColStride = 0x9e3779b9u;
+constexpr uint32_t kDomain = 0x53594c56u;
+
+__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= kM1;
+    x ^= x >> 15;
+    x *= kM2;
+    x ^= x >> 16;
+    return x;
+}
+
+static uint32_t call_key(uint64_t seed, uint32_t stream_id)
+{
+    uint32_t k = mix32(static_cast<uint32_t>(seed) ^ kDomain);
+    k = mix32(k ^ static_cast<uint32_t>(seed >> 32));
+    return mix32(k ^ stream_id);
+}
+
+// Top 24 bits of the second product: the draw for one element.
+__device__ __forceinline__ uint32_t draw24(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= kM1;
+    x ^= x >> 15;
+    x *= kM2;
+    return x >> 8;
+}
+
+constexpr int kRowsPerWave = 4;
+constexpr int kWavesPerBlock = 4;
+
+// P = number of 64-column chunks held in registers (64 (P-1) < d <= 64 P);
+// FULL = (d == 64 P): no ragged last chunk.
+//
+// A wave owns kRowsPerWave consecutive wire rows.  The loads of row r+1 are issued
+// before row r is processed.  Columns past d re-read column d-1, which leaves
+// the extrema unchanged and needs no predicate; their bits are masked off.  The
+// words of all the wave's rows are collected into lanes r*W + k and leave in one
+// contiguous store, as do the scales and zero-points.
+template <int P, bool FULL>
+__global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
+    const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ packed,
+    float *__restrict__ scale, float *__restrict__ zero)
+{
+    constexpr int R = kRowsPerWave;
+    static_assert(R * P <= 64, "one store must hold all words of a wave");
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t first = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave) * R;
+    if (first >= n_rows) return;
+    const int nrows = static_cast<int>(n_rows - first < R ? n_rows - first : R);
+    constexpr int W = P;
+    constexpr float kTwoM24 = 1.0f / 16777216.0f;
+
+    int my_src = 0;
+    if (idx && lane < nrows) my_src = idx[first + lane];
+
+    int coff[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int c = p * 64 + lane;
+        coff[p] = FULL ? c : (c < d ? c : d - 1);
+    }
+    const uint64_t tail_mask =
+        FULL ? ~uint64_t(0) : (~uint64_t(0) >> (63 - ((d - 1) & 63)));
+
+    auto row_base = [&](int r) -> const float * {
+        const int64_t srow = idx ? static_cast<int64_t>(__builtin_amdgcn_readlane(my_src, r))
+                                 : row_offset + first + r;
+        return src + srow * ld;
+    };
+
+    float cur[P], nxt[P];
+    {
+        const float *row = row_base(0);
+#pragma unroll
+        for (int p = 0; p < P; ++p) cur[p] = row[coff[p]];
+    }
+    uint64_t my_word = 0;
+    float my_scale = 0.0f, my_zero = 0.0f;
+    const uint32_t lane_ctr = static_cast<uint32_t>(lane) * kColStride;
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r < nrows) {
+            if (r + 1 < nrows) {
+                const float *row = row_base(r + 1);
+#pragma unroll
+                for (int p = 0; p < P; ++p) nxt[p] = row[coff[p]];
+            }
+            float mn = cur[0], mx = cur[0];
+#pragma unroll
+            for (int p = 1; p < P; ++p) {
+                mn = fmin_sel(mn, cur[p]);
+                mx = fmax_sel(mx, cur[p]);
+            }
+            wave_minmax(mn, mx);
+            mn = mn + 0.0f;
+            mx = mx + 0.0f;
+            const float sc = mx - mn;
+            const uint32_t rkey = mix32(ckey ^ static_cast<uint32_t>(first + r));
+            uint32_t ctr = rkey + lane_ctr;
+            // u * scale with u = k * 2^-24: folding the exact power of two into the
+            // scale gives the same single rounding unless scale * 2^-24 is subnormal.
+            const bool fold = sc >= 0x1p-102f || sc == 0.0f;
+            if (__builtin_expect(fold, 1)) {
+                const float sc24 = sc * kTwoM24;
+#pragma unroll
+                for (int p = 0; p < P; ++p) {
+                    const float lhs = static_cast<float>(draw24(ctr)) * sc24;
+                    const float rhs = cur[p] - mn;
+                    uint64_t word = __ballot(lhs < rhs);
+                    if (!FULL && p == P - 1) word &= tail_mask;
+                    if (lane == r * W + p) my_word = word;
+                    ctr += 64u * kColStride;
+                }
+            } else {
+#pragma unroll 1
+                for (int p = 0; p < P; ++p) {
+                    const float lhs = (static_cast<float>(draw24(ctr)) * kTwoM24) * sc;
+                    const float rhs = cur[p] - mn;
+                    uint64_t word = __ballot(lhs < rhs);
+                    if (!FULL && p == P - 1) word &= tail_mask;
+                    if (lane == r * W + p) my_word = word;
+                    ctr += 64u * kColStride;
+                }
+            }
+            if (lane == r) {
+                my_scale = sc;
+                my_zero = mn;
+            }
+#pragma unroll
+            for (int p = 0; p < P; ++p) cur[p] = nxt[p];
+        }
+    }
+    if (lane < nrows * W) packed[first * W + lane] = my_word;
+    if (lane < nrows) {
+        scale[first + lane] = my_scale;
+        zero[first + lane] = my_zero;
+    }
+}
+
+// Any width: the row is read twice (the second read hits the cache).
+__global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kernel(
+    const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ packed,
+    float *__restrict__ scale, float *__restrict__ zero)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
+    if (i >= n_rows) return;
+    const int W = (d + 63) >> 6;
+    constexpr float kTwoM24 = 1.0f / 16777216.0f;
+    const int64_t srow = idx ? static_cast<int64_t>(uniform(idx[i])) : row_offset + i;
+    const float *row = src + srow * ld;
+    float mn = __builtin_inff(), mx = -__builtin_inff();
+    for (int c = lane; c < d; c += 64) {
+        const float x = row[c];
+        mn = fmin_sel(mn, x);
+        mx = fmax_sel(mx, x);
+    }
+    wave_minmax(mn, mx);
+    mn = mn + 0.0f;
+    mx = mx + 0.0f;
+    const float sc = mx - mn;
+    const uint32_t rkey = mix32(ckey ^ static_cast<uint32_t>(i));
+    uint32_t ctr = rkey + static_cast<uint32_t>(lane) * kColStride;
+    uint64_t *out = packed + i * W;
+    for (int k = 0; k < W; ++k) {
+        const int c = k * 64 + lane;
+        const float x = c < d ? row[c] : 0.0f;
+        const float u = static_cast<float>(draw24(ctr)) * kTwoM24;
+        const bool on = (c < d) && (u * sc < x - mn);
+        const uint64_t word = __ballot(on);
+        if (lane == 0) out[k] = word;
+        ctr += 64u * kColStride;
+    }
+    if (lane == 0) {
+        scale[i] = sc;
+        zero[i] = mn;
+    }
+}
+
+template <int P, bool FULL>
+static void launch_rows(const float *src, int64_t ld, int d, const int32_t *idx,
+                        int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *packed,
+                        float *scale, float *zero, hipStream_t st)
+{
+    const int64_t rows_per_block = kRowsPerWave * kWavesPerBlock;
+    const int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL((quantize_rows_kernel<P, FULL>), dim3(static_cast<unsigned>(blocks)),
+                       dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset, n_rows,
+                       ckey, packed, scale, zero);
+}
+
+static int32_t quantize_common(const char *name, const float *src, int64_t ld, int32_t d,
+                               const int32_t *idx, int64_t row_offset, int64_t n_rows,
+                               uint64_t seed, uint32_t stream_id, uint64_t *packed, float *scale,
+                               float *zero, void *stream)
+{
+    if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
+    if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
+    if (ld < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_src %lld < d %d", name, (long long)ld, d);
+    if (!idx && row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
+    if (n_rows == 0) return SYLVIE_OK;
+    if (!src || !packed || !scale || !zero)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!aligned(src, 4) || !aligned(scale, 4) || !aligned(zero, 4) || (idx && !aligned(idx, 4)))
+        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: float/int arrays need 4-byte alignment", name);
+    if (!aligned(packed, 8))
+        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: packed_out needs 8-byte alignment", name);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint32_t ckey = call_key(seed, stream_id);
+    const int P = (d + 63) / 64;
+#define SYLVIE_Q_CASE(p)                                                                       \
+    case p:                                                                                    \
+        if (d == 64 * p)                                                                       \
+            launch_rows<p, true>(src, ld, d, idx, row_offset, n_rows, ckey, packed, scale, zero, st);  \
+        else                                                                                   \
+            launch_rows<p, false>(src, ld, d, idx, row_offset, n_rows, ckey, packed, scale, zero, st); \
+        break;
+    switch (P) {
+        SYLVIE_Q_CASE(1)
+        SYLVIE_Q_CASE(2)
+        SYLVIE_Q_CASE(3)
+        SYLVIE_Q_CASE(4)
+        SYLVIE_Q_CASE(5)
+        SYLVIE_Q_CASE(6)
+        SYLVIE_Q_CASE(7)
+        SYLVIE_Q_CASE(8)
+        SYLVIE_Q_CASE(9)
+        SYLVIE_Q_CASE(10)
+        SYLVIE_Q_CASE(11)
+        SYLVIE_Q_CASE(12)
+        SYLVIE_Q_CASE(13)
+        SYLVIE_Q_CASE(14)
+        SYLVIE_Q_CASE(15)
+        SYLVIE_Q_CASE(16)
+    default: {
+        const int64_t blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
+        hipLaunchKernelGGL(quantize_rows_wide_kernel, dim3(static_cast<unsigned>(blocks)),
+                           dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset,
+                           n_rows, ckey, packed, scale, zero);
+    }
+    }
+#undef SYLVIE_Q_CASE
+    SYLVIE_HIP_LAUNCH_CHECK(name);
+    return SYLVIE_OK;
+}
+
+}  // namespace sylvie
+
+extern "C" int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
+                                            const int32_t *idx, int64_t row_offset,
+                                            int64_t n_rows, uint64_t seed, uint32_t stream_id,
+                                            uint64_t *packed_out, float *scale_out,
+                                            float *zero_out, void *stream)
+{
+    return sylvie::quantize_common("sylvie_quantize_1bit_fwd", src, ld_src, d, idx, row_offset,
+                                   n_rows, seed, stream_id, packed_out, scale_out, zero_out,
+                                   stream);
+}
+
+extern "C" int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
+                                            const int32_t *idx, int64_t row_offset,
+                                            int64_t n_rows, uint64_t seed, uint32_t stream_id,
+                                            uint64_t *packed_out, float *scale_out,
+                                            float *zero_out, void *stream)
+{
+    return sylvie::quantize_common("sylvie_quantize_1bit_bwd", src, ld_src, d, idx, row_offset,
+                                   n_rows, seed, stream_id, packed_out, scale_out, zero_out,
+                                   stream);
+}

@@ -1,0 +1,218 @@
+"""Per-layer call sequence of Sylvie-S on one GPU (Alg. 1 forward, Alg. 2 backward).
+
+Every partition handed in lives on the same GPU; "send / receive" is the wire
+arrays staying where the quantizer wrote them.  This module only allocates device
+buffers and calls the C-ABI entry points in order: all arithmetic happens in the
+HIP kernels.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Callable, List, Optional
+
+import torch
+
+from . import binding as B
+from . import graph_engine as GE
+
+
+def default_pair_seed(seed: int, sender: int, receiver: int) -> int:
+    return (int(seed) + 0x9E3779B97F4A7C15 * (sender * 4096 + receiver + 1)) & (2**64 - 1)
+
+
+@dataclass
+class Block:
+    """Halo rows [j0, j1) of a receiver, all owned by partition `owner`."""
+    owner: int
+    j0: int
+    j1: int
+    rows: torch.Tensor          # int32 [j1-j0] owner-local inner rows (send list / scatter targets)
+    seg_ptr: torch.Tensor
+    seg_rows: torch.Tensor
+    dst_ids: torch.Tensor
+
+
+@dataclass
+class PartState:
+    n_in: int
+    n_halo: int
+    op: tuple                   # (rowptr, col, w) forward operator
+    opT: tuple                  # transposed operator
+    plan: tuple                 # long-row plan of op
+    planT: tuple                # long-row plan of opT
+    blocks: List[Block]
+    X: torch.Tensor
+    J: torch.Tensor
+    Htil: List[torch.Tensor] = field(default_factory=list)   # Htil[l-1]: input of layer l
+    Z: List[torch.Tensor] = field(default_factory=list)      # Z[l-1]: aggregate of layer l
+    out: Optional[torch.Tensor] = None                        # H^(L)
+    G: List[Optional[torch.Tensor]] = field(default_factory=list)
+    dHtil: List[Optional[torch.Tensor]] = field(default_factory=list)  # dHtil[l-1]; J^(l-1) = its inner rows
+    dZ: Optional[torch.Tensor] = None
+    dself: Optional[torch.Tensor] = None
+    ws_agg: Optional[torch.Tensor] = None
+    ws_aggT: Optional[torch.Tensor] = None
+    ws_g: Optional[torch.Tensor] = None
+    packed: Optional[torch.Tensor] = None
+    scale: Optional[torch.Tensor] = None
+    zero: Optional[torch.Tensor] = None
+
+
+class LayerLoop:
+    """model: "gcn" (A_hat = D^-1/2 (A+I) D^-1/2, H = sigma(A_hat Htil W)) or "sage"
+    (mean aggregator, H = sigma([H_self | mean] W)).  ReLU on all layers but the last."""
+
+    def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
+                 exchange_first_layer: bool = False, wire: str = "1bit"):
+        """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
+        partition int32 tensors naming the owner partition and owner-local inner row of
+        each halo row (grouped by owner, ascending)."""
+        self.model, self.dims, self.W = model, tuple(dims), W
+        self.L = len(W)
+        self.chunk = chunk
+        self.exchange_first_layer = exchange_first_layer
+        self.wire = wire
+        self.record = None          # set to a dict to keep copies of every wire
+        dev = X[0].device
+        self.dev = dev
+        dmax = max(dims)
+        self.parts: List[PartState] = []
+        for p, part in enumerate(parts):
+            if model == "gcn":
+                op = GE.gcn_operator(part.rowptr, part.col, part.deg, part.n_in)
+            else:
+                op = GE.mean_operator(part.rowptr, part.col, part.n_in)
+            n_loc = part.n_in + part.n_halo
+            opT = GE.transpose_csr(op[0], op[1], op[2], n_loc)
+            plan = GE.long_row_plan(op[0], chunk)
+            planT = GE.long_row_plan(opT[0], chunk)
+            blocks = []
+            if part.n_halo:
+                own, cnt = torch.unique_consecutive(halo_owner[p], return_counts=True)
+                j = 0
+                for o, c in zip(own.tolist(), cnt.tolist()):
+                    rows = halo_row[p][j:j + c].contiguous()
+                    sp, sr, di = GE.scatter_segments(rows)
+                    blocks.append(Block(o, j, j + c, rows, sp, sr, di))
+                    j += c
+            st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
+            Wd = B.sylvie_words_per_row(dmax)
+            st.packed = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
+            st.scale = torch.empty(max(1, part.n_halo), dtype=torch.float32, device=dev)
+            st.zero = torch.empty(max(1, part.n_halo), dtype=torch.float32, device=dev)
+            st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
+            st.ws_aggT = torch.empty(max(1, planT[2]) * dmax, dtype=torch.float32, device=dev)
+            kmax = max(dims[l - 1] * (2 if model == "sage" else 1) for l in range(1, self.L + 1))
+            nbytes = B.sylvie_transform_bwd_workspace_bytes(kmax, 0, max(dims[1:]), part.n_in)
+            st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
+            for l in range(1, self.L + 1):
+                st.Htil.append(torch.empty(n_loc, dims[l - 1], dtype=torch.float32, device=dev))
+                st.Z.append(torch.empty(part.n_in, dims[l - 1], dtype=torch.float32, device=dev))
+            st.Htil[0][: part.n_in].copy_(X[p])
+            st.out = torch.empty(part.n_in, dims[-1], dtype=torch.float32, device=dev)
+            st.G = [None] + [torch.empty(W[l - 1].shape, dtype=torch.float32, device=dev)
+                             for l in range(1, self.L + 1)]
+            st.dHtil = [None] * self.L
+            lo = 0 if exchange_first_layer else 1
+            for l in range(lo, self.L):
+                st.dHtil[l] = torch.empty(n_loc, dims[l], dtype=torch.float32, device=dev)
+            st.dZ = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
+            if model == "sage":
+                st.dself = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
+            self.parts.append(st)
+
+    # -- helpers ---------------------------------------------------------------
+    def _keep(self, key, st, n, W):
+        if self.record is not None:
+            self.record[key] = (st.packed[: n * W].clone(), st.scale[:n].clone(),
+                                st.zero[:n].clone())
+
+    def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0):
+        rp, cl, w = op
+        lr, lp, nt = plan
+        fn(rp, cl, w, None, None, n_rows, X, X.stride(0), d, Y, Y.stride(0),
+           addend=addend, ld_addend=0 if addend is None else addend.stride(0),
+           addend_rows=addend_rows, chunk=self.chunk, long_rows=lr if nt else None,
+           long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+           workspace=ws if nt else None)
+
+    # -- Alg. 1 ------------------------------------------------------------------
+    def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+        for l in range(1, self.L + 1):
+            d = self.dims[l - 1]
+            Wd = B.sylvie_words_per_row(d)
+            for me, st in enumerate(self.parts):
+                ht = st.Htil[l - 1]
+                for b in st.blocks:
+                    n = b.j1 - b.j0
+                    src = self.parts[b.owner].Htil[l - 1]
+                    if self.wire == "1bit":
+                        B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
+                                                   pair_seed(seed, b.owner, me), 2 * l + 0,
+                                                   st.packed, st.scale, st.zero)
+                        self._keep(("fwd", l, me, b.j0), st, n, Wd)
+                        B.sylvie_dequantize_1bit_fwd(st.packed, st.scale, st.zero, n, d, ht,
+                                                     ht.stride(0), st.n_in + b.j0)
+                    else:   # full-precision exchange: plain device copy of the rows
+                        ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
+            for st in self.parts:
+                ht, Z = st.Htil[l - 1], st.Z[l - 1]
+                self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg, st.n_in,
+                                ht, d, Z)
+                relu = l != self.L
+                Hout = st.Htil[l] if l < self.L else st.out
+                h = self.dims[l]
+                if self.model == "gcn":
+                    B.sylvie_transform_fwd(Z, Z.stride(0), d, None, 0, 0, self.W[l - 1], h, st.n_in,
+                                           relu, Hout, Hout.stride(0))
+                else:
+                    B.sylvie_transform_fwd(ht, ht.stride(0), d, Z, Z.stride(0), d, self.W[l - 1], h,
+                                           st.n_in, relu, Hout, Hout.stride(0))
+
+    # -- Alg. 2 ------------------------------------------------------------------
+    def backward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+        for l in range(self.L, 0, -1):
+            d, h = self.dims[l - 1], self.dims[l]
+            need_dx = l > 1 or self.exchange_first_layer
+            Wd = B.sylvie_words_per_row(d)
+            for st in self.parts:
+                relu = l != self.L
+                Hout = st.Htil[l] if l < self.L else st.out
+                Jl = st.J if l == self.L else st.dHtil[l]
+                ht, Z = st.Htil[l - 1], st.Z[l - 1]
+                dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+                if self.model == "gcn":
+                    B.sylvie_transform_bwd(Z, Z.stride(0), d, None, 0, 0, self.W[l - 1], h, st.n_in,
+                                           relu, Hout, Hout.stride(0), Jl, Jl.stride(0), st.G[l],
+                                           dZ if need_dx else None, d, None, 0, st.ws_g)
+                    dself = None
+                else:
+                    dself = st.dself.view(-1)[: st.n_in * d].view(st.n_in, d)
+                    B.sylvie_transform_bwd(ht, ht.stride(0), d, Z, Z.stride(0), d, self.W[l - 1], h,
+                                           st.n_in, relu, Hout, Hout.stride(0), Jl, Jl.stride(0),
+                                           st.G[l], dself if need_dx else None, d,
+                                           dZ if need_dx else None, d, st.ws_g)
+                if need_dx:
+                    g = st.dHtil[l - 1]
+                    self._aggregate(B.sylvie_aggregate_csr_bwd, st.opT, st.planT, st.ws_aggT,
+                                    st.n_in + st.n_halo, dZ, d, g, addend=dself,
+                                    addend_rows=st.n_in)
+            if not need_dx:
+                continue
+            # exchange the halo gradients; all transposed aggregates above are complete
+            # before any partition's inner rows are touched (same stream, in order)
+            for me, st in enumerate(self.parts):
+                g = st.dHtil[l - 1]
+                for b in st.blocks:
+                    n = b.j1 - b.j0
+                    tgt = self.parts[b.owner].dHtil[l - 1]
+                    if self.wire == "1bit":
+                        B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
+                                                   pair_seed(seed, me, b.owner), 2 * l + 1,
+                                                   st.packed, st.scale, st.zero)
+                        self._keep(("bwd", l, me, b.j0), st, n, Wd)
+                        B.sylvie_dequantize_1bit_bwd(st.packed, st.scale, st.zero, n, d, tgt,
+                                                     tgt.stride(0), b.seg_ptr, b.seg_rows,
+                                                     int(b.dst_ids.numel()), b.dst_ids)
+                    else:
+                        tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())

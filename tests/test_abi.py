@@ -1,0 +1,122 @@
+"""CPU-side checks of the boundary: the library builds/loads, exports every symbol the
+header declares, and rejects bad arguments before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2303_01277_amd import build_library
+    path = build_library()
+    return C.CDLL(path)
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sylvie.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sylvie_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"sylvie_quantize_1bit_fwd", "sylvie_quantize_1bit_bwd", "sylvie_dequantize_1bit_fwd",
+            "sylvie_dequantize_1bit_bwd", "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
+            "sylvie_transform_fwd", "sylvie_transform_bwd"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_has_the_same_names():
+    from paper_2303_01277_amd import binding
+    for n in declared_symbols():
+        if n in ("sylvie_status_string", "sylvie_last_error"):
+            continue
+        assert hasattr(binding, n), n
+
+
+def test_version_and_strings(lib):
+    lib.sylvie_status_string.restype = C.c_char_p
+    assert lib.sylvie_version() >= 100
+    assert lib.sylvie_status_string(0) == b"ok"
+    assert b"argument" in lib.sylvie_status_string(-1)
+    lib.sylvie_words_per_row.restype = C.c_int64
+    assert [lib.sylvie_words_per_row(d) for d in (1, 64, 65, 100, 602)] == [1, 1, 2, 2, 10]
+
+
+def test_bad_arguments_are_rejected_without_gpu(lib):
+    """Validation happens on the host before any launch, so it runs without a GPU."""
+    lib.sylvie_last_error.restype = C.c_char_p
+    p = C.c_void_p(4096)           # never dereferenced: the call fails first
+    q = lib.sylvie_quantize_1bit_fwd
+    q.restype = C.c_int32
+    args = lambda **kw: [kw.get("src", p), C.c_int64(kw.get("ld", 64)), C.c_int32(kw.get("d", 64)),
+                         None, C.c_int64(0), C.c_int64(kw.get("n", 8)), C.c_uint64(1),
+                         C.c_uint32(0), kw.get("packed", p), p, p, None]
+    assert q(*args(d=0)) == -1
+    assert q(*args(d=65, ld=64)) == -1
+    assert q(*args(n=-1)) == -1
+    assert q(*args(n=2**31)) == -1
+    assert q(*args(src=None)) == -1
+    assert q(*args(packed=C.c_void_p(4100))) == -2
+    assert b"align" in lib.sylvie_last_error()
+    assert q(*args(n=0)) == 0                                  # empty exchange is a no-op
+    dq = lib.sylvie_dequantize_1bit_fwd
+    dq.restype = C.c_int32
+    assert dq(p, p, p, C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
+    assert dq(p, p, p, C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
+    ag = lib.sylvie_aggregate_csr_fwd
+    ag.restype = C.c_int32
+    base = [p, p, None, None, None, C.c_int64(4), p, C.c_int64(64), C.c_int32(64), p,
+            C.c_int64(64), None, C.c_int64(0), C.c_int64(0)]
+    # long rows announced but chunk not a multiple of 64
+    assert ag(*base, C.c_int32(100), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(1 << 20),
+              None) == -1
+    # workspace too small for the announced tasks
+    assert ag(*base, C.c_int32(128), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(16),
+              None) == -5
+    tf = lib.sylvie_transform_fwd
+    tf.restype = C.c_int32
+    assert tf(p, C.c_int64(8), C.c_int32(16), None, C.c_int64(0), C.c_int32(0), p, C.c_int32(16),
+              C.c_int64(4), C.c_int32(1), p, C.c_int64(16), None) == -1   # ld_a1 < k1
+
+
+def test_graph_engine_host_logic(oracle):
+    """Set-up code of the product against the oracle's operator and scipy's transpose."""
+    import numpy as np
+    import scipy.sparse as sp
+    import torch
+    from synth import CONFIGS, build_workload, scaled
+    from paper_2303_01277_amd import graph_engine as GE
+    wl = build_workload(scaled(CONFIGS["citation"], 4000))
+    p = wl.parts[0]
+    rp, cl, w = GE.gcn_operator(p.rowptr, p.col, p.deg, p.n_in)
+    orp, ocl, ow = oracle.gcn_operator(p.rowptr.numpy(), p.col.numpy(), p.deg.numpy(), p.n_in)
+    assert np.array_equal(rp.numpy(), orp) and np.array_equal(cl.numpy(), ocl)
+    assert np.array_equal(w.numpy().view(np.uint32), ow.view(np.uint32))
+    _, _, wm = GE.mean_operator(p.rowptr, p.col, p.n_in)
+    assert np.array_equal(wm.numpy().view(np.uint32),
+                          oracle.mean_weights(p.rowptr.numpy(), p.n_in).view(np.uint32))
+    n_loc = p.n_in + p.n_halo
+    rpT, clT, wT = GE.transpose_csr(rp, cl, w, n_loc)
+    A = sp.csr_matrix((w.numpy(), cl.numpy(), rp.numpy()), shape=(p.n_in, n_loc))
+    AT = sp.csr_matrix((wT.numpy(), clT.numpy(), rpT.numpy()), shape=(n_loc, p.n_in))
+    assert abs(A.T - AT).max() == 0
+    for r in range(0, n_loc, 97):                               # ascending original rows
+        seg = clT[rpT[r]:rpT[r + 1]].numpy()
+        assert (np.diff(seg) > 0).all()
+    lr, lp, nt = GE.long_row_plan(rp, 64)
+    cnt = np.diff(rp.numpy())
+    assert np.array_equal(lr.numpy(), np.nonzero(cnt > 64)[0])
+    assert nt == int(np.ceil(cnt[cnt > 64] / 64).sum()) and lp[0] == 0 and lp[-1] == nt
+    sp_, sr, di = GE.scatter_segments(wl.mirror)
+    m = wl.mirror.numpy()
+    assert np.array_equal(di.numpy(), np.unique(m))
+    for k in range(0, di.numel(), 53):
+        rows = sr[sp_[k]:sp_[k + 1]].numpy()
+        assert (np.diff(rows) > 0).all() and (m[rows] == di[k].item()).all()
+    assert sp_[-1] == m.size

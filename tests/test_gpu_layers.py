@@ -1,0 +1,217 @@
+"""GPU parity of the whole layer loop (Alg. 1 + Alg. 2) on the synthetic workloads.
+
+The loop runs on the GPU; then every step is replayed on the CPU oracle from the
+GPU's own inputs to that step (so a last-bit difference in a float sum cannot flip a
+rounding decision downstream and hide or fake an error): wires bit-exact, halo
+blocks bit-exact, backward accumulate bit-exact, aggregate / transform outputs within
+1e-5 * max(|ref|, S).  A second pass with a full-precision exchange compares the
+end-to-end outputs of the two loops directly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as OL
+from synth import CONFIGS, build_workload, scaled
+from util import np_c, to_partdata
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = 1e-5
+
+
+def bits32(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def close(got, ref, S, what):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = TOL * np.maximum(np.abs(ref), S).astype(np.float64)
+    bad = err > bound
+    assert not bad.any(), (what, int(bad.sum()), float((err / np.maximum(bound, 1e-300)).max()))
+
+
+def build_loop(wl, wire="1bit", chunk=256):
+    from paper_2303_01277_amd.trainer import LayerLoop
+    spec = wl.spec
+    parts = wl.parts
+    for p in parts:
+        for f in ("rowptr", "col", "deg", "halo_gid", "halo_part", "halo_row"):
+            setattr(p, f, getattr(p, f).to(DEV))
+    if wl.mirror is not None:
+        owner = [torch.zeros(parts[0].n_halo, dtype=torch.int32, device=DEV)]
+        rows = [wl.mirror.to(DEV)]
+    else:
+        owner = [p.halo_part for p in parts]
+        rows = [p.halo_row for p in parts]
+    return LayerLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
+                     [w.to(DEV) for w in wl.W], spec.model, spec.dims, chunk=chunk,
+                     exchange_first_layer=True, wire=wire)
+
+
+def replay(oracle, wl, loop, pdata, seed):
+    """Teacher-forced check of every step of one forward + backward pass."""
+    model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
+    W = [np_c(w) for w in wl.W]
+    ops = []
+    for pd in pdata:
+        OL.build_operator(pd, model)
+        ops.append(pd.op)
+    for l in range(1, L + 1):
+        d, h = dims[l - 1], dims[l]
+        for me, (st, pd) in enumerate(zip(loop.parts, pdata)):
+            ht = np_c(st.Htil[l - 1])
+            for b in st.blocks:
+                src = np_c(loop.parts[b.owner].Htil[l - 1])
+                idx = np_c(b.rows)
+                n = b.j1 - b.j0
+                ref = oracle.quantize_1bit(src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=idx)
+                pk, sc, zp = (np_c(t) for t in loop.record[("fwd", l, me, b.j0)])
+                assert np.array_equal(pk.view(np.uint64).reshape(n, -1), ref[0]), ("fwd wire", l)
+                assert np.array_equal(bits32(sc), bits32(ref[1]))
+                assert np.array_equal(bits32(zp), bits32(ref[2]))
+                want = np.empty((n, d), np.float32)
+                oracle.dequantize_1bit_fwd(ref[0], ref[1], ref[2], d, want, 0)
+                assert np.array_equal(bits32(ht[st.n_in + b.j0: st.n_in + b.j1]), bits32(want))
+            rp, cl, w = ops[me]
+            Z, S = oracle.aggregate_fwd(rp, cl, w, ht, d, want_S=True)
+            Zg = np_c(st.Z[l - 1])
+            close(Zg, Z, S, ("Z", l))
+            Hg = np_c(st.Htil[l][: st.n_in] if l < L else st.out)
+            if model == "gcn":
+                H, SH = oracle.transform_fwd(Zg, W[l - 1], l != L, want_S=True)
+            else:
+                H, SH = oracle.transform_fwd(np.ascontiguousarray(ht[: st.n_in]), W[l - 1], l != L, A2=Zg,
+                                             want_S=True)
+            close(Hg, H, SH, ("H", l))
+
+
+def replay_backward(oracle, wl, loop, pdata, seed, snaps):
+    model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
+    W = [np_c(w) for w in wl.W]
+    for l in range(L, 0, -1):
+        d, h = dims[l - 1], dims[l]
+        for me, (st, pd) in enumerate(zip(loop.parts, pdata)):
+            s = snaps[(l, me)]
+            Hg = np_c(st.Htil[l][: st.n_in] if l < L else st.out)
+            ht = np_c(st.Htil[l - 1])
+            Zg = np_c(st.Z[l - 1])
+            if model == "gcn":
+                r = oracle.transform_bwd(Zg, W[l - 1], l != L, Hg, s["J"], want_S=True)
+                dZ, SdZ, dself = r["dA1"], r["SdA1"], None
+            else:
+                r = oracle.transform_bwd(np.ascontiguousarray(ht[: st.n_in]), W[l - 1], l != L, Hg, s["J"], A2=Zg,
+                                         want_S=True)
+                dself, dZ, SdZ = r["dA1"], r["dA2"], r["SdA2"]
+                close(s["dself"], dself, r["SdA1"], ("dself", l))
+            close(np_c(st.G[l]), r["G"], r["SG"], ("G", l))
+            close(s["dZ"], dZ, SdZ, ("dZ", l))
+            rp, cl, w = pd.op
+            g, Sg = oracle.aggregate_bwd(rp, cl, w, st.n_in + st.n_halo, s["dZ"], d, want_S=True)
+            g = g.astype(np.float64)
+            if dself is not None:
+                g[: st.n_in] += s["dself"]
+                Sg[: st.n_in] += np.abs(s["dself"])
+            close(s["dHtil_pre"], g, Sg, ("dHtil", l))
+        # exchange: wires bit-exact from the GPU's halo gradients, accumulate bit-exact
+        for q, stq in enumerate(loop.parts):
+            want = snaps[(l, q)]["dHtil_pre"][: stq.n_in].copy()
+            for me, st in enumerate(loop.parts):
+                gpre = snaps[(l, me)]["dHtil_pre"]
+                for b in st.blocks:
+                    if b.owner != q:
+                        continue
+                    n = b.j1 - b.j0
+                    ref = oracle.quantize_1bit(gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
+                                               row_offset=st.n_in + b.j0)
+                    pk, sc, zp = (np_c(t) for t in loop.record[("bwd", l, me, b.j0)])
+                    assert np.array_equal(pk.view(np.uint64).reshape(n, -1), ref[0]), ("bwd wire", l)
+                    assert np.array_equal(bits32(sc), bits32(ref[1]))
+                    assert np.array_equal(bits32(zp), bits32(ref[2]))
+                    oracle.dequantize_1bit_bwd(ref[0], ref[1], ref[2], d, want, np_c(b.rows))
+            got = np_c(stq.dHtil[l - 1][: stq.n_in])
+            assert np.array_equal(bits32(got), bits32(want)), ("J after integrate", l, q)
+
+
+class SnapLoop:
+    """Runs the GPU backward layer by layer while copying out what each step consumed."""
+
+    @staticmethod
+    def run(loop, seed):
+        from paper_2303_01277_amd import binding as B
+        snaps = {}
+        orig_q = B.sylvie_quantize_1bit_bwd
+        state = {"l": None}
+
+        # snapshot J^(l), dZ, dself and the pre-exchange dHtil of every partition: hook the
+        # first backward quantize call of each layer (all aggregates of that layer are done)
+        def hook(src, ld, d, idx, off, n, sd, stream_id, pk, sc, zp):
+            l = (stream_id - 1) // 2
+            if state["l"] != l:
+                state["l"] = l
+                torch.cuda.synchronize()
+                for me, st in enumerate(loop.parts):
+                    dd = loop.dims[l - 1]
+                    Jl = st.J if l == loop.L else st.dHtil[l]
+                    snaps[(l, me)] = {
+                        "J": np_c(Jl[: st.n_in]) if l < loop.L else np_c(Jl),
+                        "dZ": np_c(st.dZ.view(-1)[: st.n_in * dd].view(st.n_in, dd)),
+                        "dself": None if st.dself is None else np_c(
+                            st.dself.view(-1)[: st.n_in * dd].view(st.n_in, dd)),
+                        "dHtil_pre": np_c(st.dHtil[l - 1]),
+                    }
+            return orig_q(src, ld, d, idx, off, n, sd, stream_id, pk, sc, zp)
+
+        B.sylvie_quantize_1bit_bwd = hook
+        try:
+            loop.backward(seed, OL.pair_seed)
+        finally:
+            B.sylvie_quantize_1bit_bwd = orig_q
+        torch.cuda.synchronize()
+        return snaps
+
+
+CASES = [
+    ("tiny", None),                       # full size: 2 real partitions, 10k nodes
+    ("dense_social", 6_000),
+    ("co_purchase", 20_000),
+    ("citation", 20_000),
+    ("stress", 24_000),
+]
+
+
+@pytest.mark.parametrize("cfg,n_nodes", CASES)
+def test_layer_loop_teacher_forced(oracle, cfg, n_nodes):
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    pdata = to_partdata(wl)
+    loop = build_loop(wl)
+    loop.record = {}
+    seed = 0x5EED0000 + len(cfg)
+    loop.forward(seed, OL.pair_seed)
+    torch.cuda.synchronize()
+    replay(oracle, wl, loop, pdata, seed)
+    snaps = SnapLoop.run(loop, seed)
+    replay_backward(oracle, wl, loop, pdata, seed, snaps)
+
+
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("co_purchase", 12_000)])
+def test_layer_loop_end_to_end_fp32_wire(oracle, cfg, n_nodes):
+    """No randomness, no teacher forcing: both loops run alone and must agree."""
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    pdata = to_partdata(wl)
+    W = [np_c(w) for w in wl.W]
+    OL.forward(pdata, spec.model, W, 1, "fp32")
+    OL.backward(pdata, spec.model, W, 1, "fp32", exchange_first_layer=True)
+    loop = build_loop(wl, wire="fp32")
+    loop.forward(1)
+    loop.backward(1)
+    torch.cuda.synchronize()
+    for st, pd in zip(loop.parts, pdata):
+        out = np_c(st.out)
+        assert np.abs(out - pd.H[-1]).max() <= 2e-5 * np.abs(pd.H[-1]).max()
+        j0 = np_c(st.dHtil[0][: st.n_in])
+        assert np.abs(j0 - pd.Jin[0]).max() <= 2e-5 * np.abs(pd.Jin[0]).max()
+        for l in range(1, len(W) + 1):
+            g = np_c(st.G[l])
+            assert np.abs(g - pd.G[l]).max() <= 2e-5 * np.abs(pd.G[l]).max()
