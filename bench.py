@@ -73,6 +73,14 @@ class OpTimer:
             return {"bytes": b, "edges": info["nnz"],
                     "gather_bytes": info["nnz"] * (4 * d + 8) + n_rows * (4 * d + 8)}
 
+        def agw_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, n_dense, pk, sc, zp, n_wire, Y, ldy, **kw):
+            info = self.op_info[rp.data_ptr()]
+            b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched_dense"] * 4 * d \
+                + info["touched_wire"] * (W(d) + 8) + n_rows * (4 * d + 8)
+            return {"bytes": b, "edges": info["nnz"],
+                    "gather_bytes": info["nnz_dense"] * (4 * d + 8)
+                    + (info["nnz"] - info["nnz_dense"]) * (W(d) + 16) + n_rows * (4 * d + 8)}
+
         def tf_cost(A1, ld1, k1, A2, ld2, k2, Wm, h, n, relu, H, ldh):
             return {"flops": 2 * n * (k1 + k2) * h, "bytes": 4 * n * (k1 + k2 + h)}
 
@@ -86,6 +94,7 @@ class OpTimer:
         self._wrap("sylvie_dequantize_1bit_bwd", dqb_cost)
         self._wrap("sylvie_aggregate_csr_fwd", ag_cost)
         self._wrap("sylvie_aggregate_csr_bwd", ag_cost)
+        self._wrap("sylvie_aggregate_csr_fwd_wire", agw_cost)
         self._wrap("sylvie_transform_fwd", tf_cost)
         self._wrap("sylvie_transform_bwd", tb_cost)
 
@@ -130,12 +139,33 @@ def cpu_baseline(torch, loop, st, dims, budget_s=20.0):
     ht = st.Htil[0]
     threads = oracle.num_threads()
 
+    from paper_2303_01277_amd import binding as B
+    halo = None
+    if ht.shape[0] < st.n_in + st.n_halo and st.n_halo:
+        # fused loop: the float halo rows were never materialised; recover them once
+        halo = torch.empty(st.n_halo, d, dtype=torch.float32, device=ht.device)
+        Wd = B.sylvie_words_per_row(d)
+        pk = torch.empty(st.n_halo * Wd, dtype=torch.int64, device=ht.device)
+        sc = torch.empty(st.n_halo, dtype=torch.float32, device=ht.device)
+        zp = torch.empty_like(sc)
+        for b in st.blocks:                      # layer 1's exchange, as the loop does it
+            src = loop.parts[b.owner].Htil[0]
+            B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, b.j1 - b.j0, 20230301, 2,
+                                       pk[b.j0 * Wd:], sc[b.j0:], zp[b.j0:])
+        B.sylvie_dequantize_1bit_fwd(pk, sc, zp, st.n_halo, d, halo, d, 0)
+        del pk, sc, zp
+
     def sample(n_rows):
         n_rows = min(n_rows, st.n_in)
         e1 = int(rp[n_rows])
         cols = cl[:e1].long()
         uniq, inv = torch.unique(cols, return_inverse=True)
-        Xs = np.ascontiguousarray(ht[uniq].cpu().numpy())
+        if halo is None:
+            Xd = ht[uniq]
+        else:
+            inner = uniq < st.n_in
+            Xd = torch.cat([ht[uniq[inner]], halo[uniq[~inner] - st.n_in]])
+        Xs = np.ascontiguousarray(Xd.cpu().numpy())
         rps = np.ascontiguousarray(rp[: n_rows + 1].cpu().numpy())
         cls = np.ascontiguousarray(inv.to(torch.int32).cpu().numpy())
         ws = np.ascontiguousarray(w[:e1].cpu().numpy())
@@ -185,6 +215,9 @@ def main():
     ap.add_argument("--nodes", type=int, default=0, help="shrink the workload to this many nodes")
     ap.add_argument("--chunk", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of known size (scales the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -199,6 +232,16 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 1 << 30                                   # 1 GiB read + 1 GiB written per copy
+        src = torch.ones(n // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 5}))
+        return
     spec = CONFIGS[args.workload]
     if args.nodes:
         spec = scaled(spec, args.nodes)
@@ -225,8 +268,11 @@ def main():
     op_info = {}
     for st in loop.parts:
         for op in (st.op, st.opT):
-            op_info[op[0].data_ptr()] = {"nnz": int(op[0][-1]),
-                                         "touched": int(torch.unique(op[1]).numel())}
+            uq = torch.unique(op[1])
+            nd = int((uq < st.n_in).sum())
+            op_info[op[0].data_ptr()] = {"nnz": int(op[0][-1]), "touched": int(uq.numel()),
+                                         "touched_dense": nd, "touched_wire": int(uq.numel()) - nd,
+                                         "nnz_dense": int((op[1] < st.n_in).sum())}
     seed = 20230301
     for i in range(args.warmup):
         loop.forward(seed + i)

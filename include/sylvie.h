@@ -153,6 +153,27 @@ int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, cons
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * Neighbour aggregation, forward, reading the halo rows straight from the wire
+ * (Alg. 1 "dequantize" + "concatenate" + the product A_n * H~ in one pass; Eq. 5
+ * is applied to each gathered element): the same result as
+ * sylvie_dequantize_1bit_fwd into rows n_dense.. of X followed by
+ * sylvie_aggregate_csr_fwd, without ever materialising the dequantized rows.
+ *     column c <  n_dense : row c of X (float32, as above)
+ *     column c >= n_dense : wire row c - n_dense of (packed, scale, zero), width d
+ * Inside every CSR row all columns < n_dense must precede all columns >= n_dense
+ * (true when columns are ascending).  n_wire = number of wire rows (0: plain X).
+ * Other arguments as in sylvie_aggregate_csr_fwd (no addend).
+ */
+int32_t sylvie_aggregate_csr_fwd_wire(const int64_t *rowptr, const int32_t *col, const float *w,
+                                      const float *row_scale, const float *col_scale,
+                                      int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+                                      int64_t n_dense, const uint64_t *packed, const float *scale,
+                                      const float *zero, int64_t n_wire, float *Y, int64_t ld_y,
+                                      int32_t chunk, const int32_t *long_rows,
+                                      const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+                                      float *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Neighbour aggregation, backward (Alg. 2, the product A_n^T * (J o sigma') W^T,
  * here its sparse factor): the same operation applied to the CSR of the
  * transposed operator, whose rows are ALL local rows (inner and halo) and whose

@@ -42,6 +42,7 @@ def lib():
         for name in ("sylvie_quantize_1bit_fwd", "sylvie_quantize_1bit_bwd",
                      "sylvie_dequantize_1bit_fwd", "sylvie_dequantize_1bit_bwd",
                      "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
+                     "sylvie_aggregate_csr_fwd_wire",
                      "sylvie_transform_fwd", "sylvie_transform_bwd"):
             getattr(L, name).restype = C.c_int32
         _lib = L
@@ -136,6 +137,22 @@ def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld
     _aggregate(lib().sylvie_aggregate_csr_fwd, rowptr, col, w, row_scale, col_scale, n_rows, X,
                ld_x, d, Y, ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
                n_long, n_tasks, workspace)
+
+
+def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,
+                                  packed, scale, zero, n_wire, Y, ld_y, chunk=0, long_rows=None,
+                                  long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_aggregate_csr_fwd_wire(
+        _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
+        _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
+        _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), C.c_int64(n_dense),
+        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
+        _ptr(zero, torch.float32, "zero"), C.c_int64(n_wire), _ptr(Y, torch.float32, "Y"),
+        C.c_int64(ld_y), C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"),
+        _ptr(long_ptr, torch.int64, "long_ptr"), C.c_int64(n_long), C.c_int64(n_tasks),
+        _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))
 
 
 def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, dY, ld_dy, d, dX,

@@ -69,10 +69,21 @@ struct AggArgs {
     const int64_t *long_ptr;
     int64_t n_long;
     float *workspace;
+    // optional packed tail of X: columns >= n_dense are rows of a 1-bit wire
+    int64_t n_dense;
+    const uint32_t *packed32;   // the uint64 words of the wire seen as dword pairs
+    const float *wscale;
+    const float *wzero;
 };
 
 // acc[p][t] += sum over entries [e0, e1) of w_e * cs[col_e] * X[col_e][column(p, t)]
-template <int VEC, int G, int P>
+//
+// WIRE: columns >= n_dense are not rows of X but rows of a packed 1-bit wire
+// (Eq. 5 applied on the fly: the element is zero or fl(zero + scale) by its bit), so a
+// halo row costs 8 W + 8 bytes instead of 4 d.  Inside a row all dense columns
+// precede all wire columns (columns ascending), so each 64-entry batch splits
+// at one point found with a ballot.
+template <int VEC, int G, int P, bool WIRE>
 __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int64_t e1,
                                            const AggArgs &a, int lane)
 {
@@ -88,6 +99,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         const int cc = (p * G + gl) * VEC;
         coff[p] = cc < a.d ? cc : a.d - VEC;
     }
+    const int W32 = ((a.d + 63) >> 6) * 2;     // dwords per wire row
     for (int64_t base = e0; base < e1; base += 64) {
         const int cnt = static_cast<int>(e1 - base < 64 ? e1 - base : 64);
         int my_c = 0;
@@ -97,9 +109,12 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
             my_w = a.w ? a.w[base + lane] : 1.0f;
             if (a.col_scale) my_w *= a.col_scale[my_c];
         }
+        int nd = cnt;                          // entries [0, nd) are dense, [nd, cnt) wire
+        if constexpr (WIRE)
+            nd = __builtin_popcountll(__ballot(lane < cnt && my_c < a.n_dense));
         int j = 0;
         // full groups: U * EP valid entries, all gathers issued before any is used
-        for (; j + EP * U <= cnt; j += EP * U) {
+        for (; j + EP * U <= nd; j += EP * U) {
             float x[U][P][VEC];
             float wv[U];
 #pragma unroll
@@ -125,8 +140,8 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                     for (int t = 0; t < VEC; ++t) acc[p][t] = fmaf(wv[u], x[u][p][t], acc[p][t]);
         }
         // remainder: one gather per lane group; groups past the end add w = 0 times
-        // a row they are allowed to read (lanes >= cnt hold column 0, weight 0)
-        for (; j < cnt; j += EP) {
+        // row 0 (lanes >= cnt hold column 0, weight 0)
+        for (; j < nd; j += EP) {
             const int sl = j + sub;
             int c;
             float wj;
@@ -136,7 +151,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
             } else {
                 c = __shfl(my_c, sl & 63);
                 wj = __shfl(my_w, sl & 63);
-                if (sl >= cnt) wj = 0.0f;
+                if (sl >= nd) { wj = 0.0f; c = 0; }
             }
             const float *xr = a.X + static_cast<int64_t>(c) * a.ld_x;
             float x[P][VEC];
@@ -146,6 +161,71 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
             for (int p = 0; p < P; ++p)
 #pragma unroll
                 for (int t = 0; t < VEC; ++t) acc[p][t] = fmaf(wj, x[p][t], acc[p][t]);
+        }
+        if constexpr (WIRE) {
+            if (nd < cnt) {
+                // Wire entries.  Each lane first fetches the two levels of ITS entry
+                // (zero and fl(zero + scale), Eq. 5) so that the per-entry loop has no
+                // dependent scalar fetch; then, entry by entry, the levels and the
+                // weight are broadcast, every lane loads the one dword that holds its
+                // VEC bits, and a bit-field insert picks the level.  Lane groups stay
+                // aligned with the dense loops; an entry before nd is masked with weight
+                // 0 and reads wire row 0.
+                const bool mine = lane >= nd && lane < cnt;
+                const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
+                const float my_zp = a.wzero[my_wr];
+                const float my_hi = my_zp + a.wscale[my_wr];
+                const float my_ww = mine ? my_w : 0.0f;
+                constexpr int UW = (P >= 4) ? 4 : (16 / P);
+                for (j = nd - nd % EP; j < cnt; j += EP * UW) {
+                    uint32_t dw[UW][P];
+                    float wv[UW], zp[UW], hi[UW];
+#pragma unroll
+                    for (int u = 0; u < UW; ++u) {
+                        const int sl = j + u * EP + sub;
+                        int64_t wr;
+                        if constexpr (EP == 1) {
+                            const int slc = sl < cnt ? sl : cnt - 1;   // wave-uniform, >= nd
+                            wr = static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, slc)) - a.n_dense;
+                            wv[u] = sl < cnt ? __int_as_float(__builtin_amdgcn_readlane(
+                                                   __float_as_int(my_ww), slc))
+                                             : 0.0f;
+                            zp[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_zp), slc));
+                            hi[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_hi), slc));
+                        } else {
+                            const int src = sl & 63;
+                            const bool ok = sl >= nd && sl < cnt;
+                            // every lane takes part in the lane reads; select afterwards
+                            const int cs = __shfl(my_c, src);
+                            wr = ok ? static_cast<int64_t>(cs) - a.n_dense : 0;
+                            wv[u] = __shfl(my_ww, src);
+                            if (!ok) wv[u] = 0.0f;
+                            zp[u] = __shfl(my_zp, src);
+                            hi[u] = __shfl(my_hi, src);
+                        }
+                        const uint32_t *pr = a.packed32 + wr * W32;
+#pragma unroll
+                        for (int p = 0; p < P; ++p) dw[u][p] = pr[coff[p] >> 5];
+                    }
+#pragma unroll
+                    for (int u = 0; u < UW; ++u)
+#pragma unroll
+                        for (int p = 0; p < P; ++p) {
+                            const int bits = static_cast<int>(dw[u][p] >> (coff[p] & 31));
+#pragma unroll
+                            for (int t = 0; t < VEC; ++t) {
+                                // all-ones where the bit is set, then (m & hi) | (~m & zp):
+                                // written as the two instructions meant, because the
+                                // compiler turns the C form into and + compare + select
+                                uint32_t m;
+                                float x;
+                                asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(m) : "v"(bits), "n"(t));
+                                asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(x) : "v"(m), "v"(hi[u]), "v"(zp[u]));
+                                acc[p][t] = fmaf(wv[u], x, acc[p][t]);
+                            }
+                        }
+                }
+            }
         }
     }
     // fold the lane groups: afterwards every group holds the full sums
@@ -163,7 +243,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
 // take the pieces of the long rows (they start first, so the heaviest rows never
 // trail the launch); every later wavefront takes one ordinary row and skips the
 // long ones.  Pieces write partial sums to workspace[task][0..d).
-template <int VEC, int G, int P>
+template <int VEC, int G, int P, bool WIRE>
 __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kernel(AggArgs a,
                                                                                     int64_t n_tasks)
 {
@@ -192,7 +272,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         const int64_t r1 = uniform(a.rowptr[v + 1]);
         const int64_t e0 = r0 + piece * a.chunk;
         const int64_t e1 = e0 + a.chunk < r1 ? e0 + a.chunk : r1;
-        gather_sum<VEC, G, P>(acc, e0, e1, a, lane);
+        gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane);
         if (lane >= G) return;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -207,7 +287,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
     const int64_t e0 = uniform(a.rowptr[v]);
     const int64_t e1 = uniform(a.rowptr[v + 1]);
     if (a.chunk > 0 && e1 - e0 > a.chunk) return;
-    gather_sum<VEC, G, P>(acc, e0, e1, a, lane);
+    gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane);
     if (lane >= G) return;
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
@@ -270,8 +350,12 @@ static void launch_shape(const AggArgs &a, int64_t n_tasks, hipStream_t st)
     const int64_t nt = a.n_long > 0 ? n_tasks : 0;
     const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
                            (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
-    hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P>), dim3(static_cast<unsigned>(blocks)),
-                       block, 0, st, a, nt);
+    if (a.packed32)
+        hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, true>),
+                           dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
+    else
+        hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, false>),
+                           dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
     if (a.n_long > 0) {
         const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
         hipLaunchKernelGGL((aggregate_reduce_kernel<VEC>), rg, block, 0, st, a);
@@ -301,7 +385,10 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
                                 int64_t ld_y, const float *addend, int64_t ld_addend,
                                 int64_t addend_rows, int32_t chunk, const int32_t *long_rows,
                                 const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
-                                float *workspace, size_t workspace_bytes, void *stream)
+                                float *workspace, size_t workspace_bytes, void *stream,
+                                int64_t n_dense = 0, const uint64_t *packed = nullptr,
+                                const float *wscale = nullptr, const float *wzero = nullptr,
+                                int64_t n_wire = 0)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
@@ -310,6 +397,11 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     if (addend && (ld_addend < d || addend_rows < 0))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad addend shape", name);
     if (n_long < 0 || n_tasks < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative count", name);
+    if (n_wire < 0 || n_dense < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative count", name);
+    if (n_wire > 0 && (!packed || !wscale || !wzero))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: wire has null pointers", name);
+    if (n_wire > 0 && (!aligned(packed, 8) || !aligned(wscale, 4) || !aligned(wzero, 4)))
+        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
     if (n_rows == 0) return SYLVIE_OK;
     if (!rowptr || !col || !X || !Y) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
     if (!aligned(rowptr, 8) || !aligned(col, 4) || !aligned(X, 4) || !aligned(Y, 4) ||
@@ -334,6 +426,9 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.addend = addend; a.ld_addend = ld_addend; a.addend_rows = addend_rows;
     a.chunk = n_long > 0 ? chunk : 0;
     a.long_rows = long_rows; a.long_ptr = long_ptr; a.n_long = n_long; a.workspace = workspace;
+    a.n_dense = n_dense;
+    a.packed32 = n_wire > 0 ? reinterpret_cast<const uint32_t *>(packed) : nullptr;
+    a.wscale = wscale; a.wzero = wzero;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool a16 = aligned(X, 16) && aligned(Y, 16) && ld_x % 4 == 0 && ld_y % 4 == 0 &&
@@ -385,4 +480,17 @@ extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_
                                     col_scale, n_rowsT, dY, ld_dy, d, dX, ld_dx, addend, ld_addend,
                                     addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
                                     workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
+    const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
+    const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+    int64_t n_dense, const uint64_t *packed, const float *scale, const float *zero, int64_t n_wire,
+    float *Y, int64_t ld_y, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+{
+    return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
+                                    col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
+                                    long_rows, long_ptr, n_long, n_tasks, workspace,
+                                    workspace_bytes, stream, n_dense, packed, scale, zero, n_wire);
 }

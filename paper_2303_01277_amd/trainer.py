@@ -63,7 +63,7 @@ class LayerLoop:
     (mean aggregator, H = sigma([H_self | mean] W)).  ReLU on all layers but the last."""
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
-                 exchange_first_layer: bool = False, wire: str = "1bit"):
+                 exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True):
         """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
         partition int32 tensors naming the owner partition and owner-local inner row of
         each halo row (grouped by owner, ascending)."""
@@ -72,6 +72,9 @@ class LayerLoop:
         self.chunk = chunk
         self.exchange_first_layer = exchange_first_layer
         self.wire = wire
+        # fused: the forward aggregation reads halo rows straight from the packed wire
+        # (no dequantize pass, no float halo block)
+        self.fused = fused and wire == "1bit"
         self.record = None          # set to a dict to keep copies of every wire
         dev = X[0].device
         self.dev = dev
@@ -106,7 +109,9 @@ class LayerLoop:
             nbytes = B.sylvie_transform_bwd_workspace_bytes(kmax, 0, max(dims[1:]), part.n_in)
             st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             for l in range(1, self.L + 1):
-                st.Htil.append(torch.empty(n_loc, dims[l - 1], dtype=torch.float32, device=dev))
+                # the float halo block below the inner rows exists only when it is written
+                rows = part.n_in if (fused and wire == "1bit") else n_loc
+                st.Htil.append(torch.empty(rows, dims[l - 1], dtype=torch.float32, device=dev))
                 st.Z.append(torch.empty(part.n_in, dims[l - 1], dtype=torch.float32, device=dev))
             st.Htil[0][: part.n_in].copy_(X[p])
             st.out = torch.empty(part.n_in, dims[-1], dtype=torch.float32, device=dev)
@@ -122,10 +127,9 @@ class LayerLoop:
             self.parts.append(st)
 
     # -- helpers ---------------------------------------------------------------
-    def _keep(self, key, st, n, W):
+    def _keep(self, key, pk, sc, zp, n, W):
         if self.record is not None:
-            self.record[key] = (st.packed[: n * W].clone(), st.scale[:n].clone(),
-                                st.zero[:n].clone())
+            self.record[key] = (pk[: n * W].clone(), sc[:n].clone(), zp[:n].clone())
 
     def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0):
         rp, cl, w = op
@@ -147,18 +151,32 @@ class LayerLoop:
                     n = b.j1 - b.j0
                     src = self.parts[b.owner].Htil[l - 1]
                     if self.wire == "1bit":
+                        # the wire of halo rows [j0, j1) sits at the same offset in the
+                        # receiver's wire arrays, so all blocks stay resident side by side
+                        pk, sc, zp = st.packed[b.j0 * Wd:], st.scale[b.j0:], st.zero[b.j0:]
                         B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
                                                    pair_seed(seed, b.owner, me), 2 * l + 0,
-                                                   st.packed, st.scale, st.zero)
-                        self._keep(("fwd", l, me, b.j0), st, n, Wd)
-                        B.sylvie_dequantize_1bit_fwd(st.packed, st.scale, st.zero, n, d, ht,
-                                                     ht.stride(0), st.n_in + b.j0)
+                                                   pk, sc, zp)
+                        self._keep(("fwd", l, me, b.j0), pk, sc, zp, n, Wd)
+                        if not self.fused:
+                            B.sylvie_dequantize_1bit_fwd(pk, sc, zp, n, d, ht, ht.stride(0),
+                                                         st.n_in + b.j0)
                     else:   # full-precision exchange: plain device copy of the rows
                         ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
             for st in self.parts:
                 ht, Z = st.Htil[l - 1], st.Z[l - 1]
-                self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg, st.n_in,
-                                ht, d, Z)
+                if self.fused:
+                    rp, cl, w = st.op
+                    lr, lp, nt = st.plan
+                    B.sylvie_aggregate_csr_fwd_wire(
+                        rp, cl, w, None, None, st.n_in, ht, ht.stride(0), d, st.n_in, st.packed,
+                        st.scale, st.zero, st.n_halo, Z, Z.stride(0), chunk=self.chunk,
+                        long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                        n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                        workspace=st.ws_agg if nt else None)
+                else:
+                    self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
+                                    st.n_in, ht, d, Z)
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
                 h = self.dims[l]
@@ -210,7 +228,7 @@ class LayerLoop:
                         B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
                                                    pair_seed(seed, me, b.owner), 2 * l + 1,
                                                    st.packed, st.scale, st.zero)
-                        self._keep(("bwd", l, me, b.j0), st, n, Wd)
+                        self._keep(("bwd", l, me, b.j0), st.packed, st.scale, st.zero, n, Wd)
                         B.sylvie_dequantize_1bit_bwd(st.packed, st.scale, st.zero, n, d, tgt,
                                                      tgt.stride(0), b.seg_ptr, b.seg_rows,
                                                      int(b.dst_ids.numel()), b.dst_ids)

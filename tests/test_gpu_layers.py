@@ -30,7 +30,7 @@ def close(got, ref, S, what):
     assert not bad.any(), (what, int(bad.sum()), float((err / np.maximum(bound, 1e-300)).max()))
 
 
-def build_loop(wl, wire="1bit", chunk=256):
+def build_loop(wl, wire="1bit", chunk=256, fused=True):
     from paper_2303_01277_amd.trainer import LayerLoop
     spec = wl.spec
     parts = wl.parts
@@ -45,7 +45,7 @@ def build_loop(wl, wire="1bit", chunk=256):
         rows = [p.halo_row for p in parts]
     return LayerLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
                      [w.to(DEV) for w in wl.W], spec.model, spec.dims, chunk=chunk,
-                     exchange_first_layer=True, wire=wire)
+                     exchange_first_layer=True, wire=wire, fused=fused)
 
 
 def replay(oracle, wl, loop, pdata, seed):
@@ -60,6 +60,8 @@ def replay(oracle, wl, loop, pdata, seed):
         d, h = dims[l - 1], dims[l]
         for me, (st, pd) in enumerate(zip(loop.parts, pdata)):
             ht = np_c(st.Htil[l - 1])
+            if loop.fused:      # no float halo block on the GPU: rebuild it from the checked wires
+                ht = np.concatenate([ht, np.full((st.n_halo, d), np.nan, np.float32)])
             for b in st.blocks:
                 src = np_c(loop.parts[b.owner].Htil[l - 1])
                 idx = np_c(b.rows)
@@ -71,7 +73,10 @@ def replay(oracle, wl, loop, pdata, seed):
                 assert np.array_equal(bits32(zp), bits32(ref[2]))
                 want = np.empty((n, d), np.float32)
                 oracle.dequantize_1bit_fwd(ref[0], ref[1], ref[2], d, want, 0)
-                assert np.array_equal(bits32(ht[st.n_in + b.j0: st.n_in + b.j1]), bits32(want))
+                if loop.fused:
+                    ht[st.n_in + b.j0: st.n_in + b.j1] = want
+                else:
+                    assert np.array_equal(bits32(ht[st.n_in + b.j0: st.n_in + b.j1]), bits32(want))
             rp, cl, w = ops[me]
             Z, S = oracle.aggregate_fwd(rp, cl, w, ht, d, want_S=True)
             Zg = np_c(st.Z[l - 1])
@@ -179,12 +184,13 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("cfg,n_nodes", CASES)
-def test_layer_loop_teacher_forced(oracle, cfg, n_nodes):
+def test_layer_loop_teacher_forced(oracle, cfg, n_nodes, fused):
     spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
     wl = build_workload(spec)
     pdata = to_partdata(wl)
-    loop = build_loop(wl)
+    loop = build_loop(wl, fused=fused)
     loop.record = {}
     seed = 0x5EED0000 + len(cfg)
     loop.forward(seed, OL.pair_seed)

@@ -238,3 +238,40 @@ def test_transform_parity(oracle, n, k1, k2, h):
         close(dA1.cpu().numpy(), r["dA1"], r["SdA1"], ("dA1", relu))
         if k2:
             close(dA2.cpu().numpy(), r["dA2"], r["SdA2"], ("dA2", relu))
+
+
+@pytest.mark.parametrize("d", [2, 64, 100, 128, 256, 602])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 40_000, "gcn"),
+                                               ("co_purchase", 30_000, "sage")])
+def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
+    """Fused dequantize + aggregate: against the oracle's dequantize followed by its
+    aggregate, and bit for bit against the GPU's own two-step path."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + 7)
+    X = make_rows(rng, n_loc, d, "heavy")
+    pk, sc, zp = oracle.quantize_1bit(X, d, p.n_halo, 77, 2, row_offset=p.n_in)
+    Xo = X.copy()
+    oracle.dequantize_1bit_fwd(pk, sc, zp, d, Xo, p.n_in)       # halo block := recovered rows
+    Z, S = oracle.aggregate_fwd(rp, cl, w, Xo, d, want_S=True)
+    rpd, cld, wd = dev(rp), dev(cl), dev(w)
+    Xin = dev(X[: p.n_in])
+    pkd, scd, zpd = dev(pk.view(np.int64)), dev(sc), dev(zp)
+    for chunk in (0, 128):
+        kw = {}
+        if chunk:
+            lr, lp, nt = GE.long_row_plan(rpd, chunk)
+            kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                      workspace=torch.empty(max(1, nt) * d, device=DEV))
+        Y = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, pkd,
+                                        scd, zpd, p.n_halo, Y, d, **kw)
+        Xfull = dev(X)
+        B.sylvie_dequantize_1bit_fwd(pkd, scd, zpd, p.n_halo, d, Xfull, d, p.n_in)
+        Y2 = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, Y2, d, **kw)
+        torch.cuda.synchronize()
+        close(Y.cpu().numpy(), Z, S, ("wire", chunk))
+        assert np.array_equal(bits32(Y.cpu().numpy()), bits32(Y2.cpu().numpy())), chunk
