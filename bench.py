@@ -53,15 +53,15 @@ class OpTimer:
         setattr(self.B, name, wrapped)
 
     def install(self):
-        W = lambda d: 8 * ((d + 63) // 64)
+        W = lambda d: 8 * ((d + 63) // 64)     # bytes of bit words per wire row (+ 8 metadata)
 
         def q_cost(src, ld, d, idx, off, n, *rest):
             return {"bytes": n * (4 * d + (4 if idx is not None else 0) + W(d) + 8), "rows": n}
 
-        def dqf_cost(pk, sc, zp, n, d, *rest):
+        def dqf_cost(wire, n, d, *rest):
             return {"bytes": n * (W(d) + 8 + 4 * d), "rows": n}
 
-        def dqb_cost(pk, sc, zp, n, d, dst, ld, sp, sr, n_dst, di):
+        def dqb_cost(wire, n, d, dst, ld, sp, sr, n_dst, di):
             return {"bytes": n * (W(d) + 8 + 4) + n_dst * (8 * d + 12), "rows": n}
 
         def ag_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, Y, ldy, **kw):
@@ -73,7 +73,7 @@ class OpTimer:
             return {"bytes": b, "edges": info["nnz"],
                     "gather_bytes": info["nnz"] * (4 * d + 8) + n_rows * (4 * d + 8)}
 
-        def agw_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, n_dense, pk, sc, zp, n_wire, Y, ldy, **kw):
+        def agw_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, n_dense, wire, n_wire, Y, ldy, **kw):
             info = self.op_info[rp.data_ptr()]
             b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched_dense"] * 4 * d \
                 + info["touched_wire"] * (W(d) + 8) + n_rows * (4 * d + 8)
@@ -144,16 +144,14 @@ def cpu_baseline(torch, loop, st, dims, budget_s=20.0):
     if ht.shape[0] < st.n_in + st.n_halo and st.n_halo:
         # fused loop: the float halo rows were never materialised; recover them once
         halo = torch.empty(st.n_halo, d, dtype=torch.float32, device=ht.device)
-        Wd = B.sylvie_words_per_row(d)
-        pk = torch.empty(st.n_halo * Wd, dtype=torch.int64, device=ht.device)
-        sc = torch.empty(st.n_halo, dtype=torch.float32, device=ht.device)
-        zp = torch.empty_like(sc)
+        Wd = B.sylvie_wire_row_words(d)
+        wire = torch.empty(st.n_halo * Wd, dtype=torch.int64, device=ht.device)
         for b in st.blocks:                      # layer 1's exchange, as the loop does it
             src = loop.parts[b.owner].Htil[0]
             B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, b.j1 - b.j0, 20230301, 2,
-                                       pk[b.j0 * Wd:], sc[b.j0:], zp[b.j0:])
-        B.sylvie_dequantize_1bit_fwd(pk, sc, zp, st.n_halo, d, halo, d, 0)
-        del pk, sc, zp
+                                       wire[b.j0 * Wd:])
+        B.sylvie_dequantize_1bit_fwd(wire, st.n_halo, d, halo, d, 0)
+        del wire
 
     def sample(n_rows):
         n_rows = min(n_rows, st.n_in)

@@ -19,11 +19,14 @@
  *     |x| < 2^126; row indices must be in range (not checked on the device).
  *
  * Wire format of one exchange of n_rows rows of width d (Sec. 3.2, "1-bit
- * integers" plus the scale / zero-point side channel):
- *   packed : uint64 [n_rows][W], W = ceil(d/64); bit j (LSB = 0) of word k of a
- *            row is column 64k + j; bits of columns >= d are 0.
- *   scale  : float32 [n_rows], max - min of the row        (B = 2^1 - 1 = 1)
- *   zero   : float32 [n_rows], min of the row (a -0 is stored as +0)
+ * integers" plus the scale / zero-point side channel): one contiguous array
+ *   wire : uint64 [n_rows][W + 1], W = ceil(d/64), little-endian
+ *     words 0..W-1 : the bits; bit j (LSB = 0) of word k is column 64k + j; bits of
+ *                    columns >= d are 0
+ *     word W       : the error-compensation pair of the row, scale in bits 0..31
+ *                    and zero-point in bits 32..63, both float32:
+ *                    scale = max - min (B = 2^1 - 1 = 1), zero = min (-0 stored as +0)
+ * so one row (and one message to a peer) is a single contiguous run of bytes.
  */
 #ifndef SYLVIE_H
 #define SYLVIE_H
@@ -49,8 +52,8 @@ const char *sylvie_status_string(int32_t status);
 /* Thread-local detail of the last error returned on this thread ("" if none). */
 const char *sylvie_last_error(void);
 
-/* Words per packed row: ceil(d / 64). */
-int64_t sylvie_words_per_row(int32_t d);
+/* uint64 words per wire row: ceil(d / 64) + 1. */
+int64_t sylvie_wire_row_words(int32_t d);
 
 /*
  * Quantizer, forward direction (Alg. 1, "quantize([H(S_1), ..., H(S_N)])"; Eq. 3-4).
@@ -69,13 +72,12 @@ int64_t sylvie_words_per_row(int32_t d);
  *   src        [*, ld_src] float32, d <= ld_src, 1 <= d <= 65536
  *   idx        int32 [n_rows] or NULL; duplicates allowed
  *   n_rows     0 <= n_rows < 2^31
- *   packed_out uint64 [n_rows][ceil(d/64)], 8-byte aligned
- *   scale_out, zero_out  float32 [n_rows]
+ *   wire_out   uint64 [n_rows][ceil(d/64) + 1], 8-byte aligned
  */
 int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
                                  const int32_t *idx, int64_t row_offset, int64_t n_rows,
-                                 uint64_t seed, uint32_t stream_id, uint64_t *packed_out,
-                                 float *scale_out, float *zero_out, void *stream);
+                                 uint64_t seed, uint32_t stream_id, uint64_t *wire_out,
+                                 void *stream);
 
 /*
  * Quantizer, backward direction (Alg. 2, "quantize([J(R_1), ..., J(R_N)])").
@@ -85,8 +87,8 @@ int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
  */
 int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
                                  const int32_t *idx, int64_t row_offset, int64_t n_rows,
-                                 uint64_t seed, uint32_t stream_id, uint64_t *packed_out,
-                                 float *scale_out, float *zero_out, void *stream);
+                                 uint64_t seed, uint32_t stream_id, uint64_t *wire_out,
+                                 void *stream);
 
 /*
  * Dequantizer, forward direction (Eq. 5; Alg. 1 "dequantize" + "concatenate"):
@@ -95,8 +97,7 @@ int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
  * below the inner rows, which is the concatenation.  Columns >= d of dst are not
  * touched.
  */
-int32_t sylvie_dequantize_1bit_fwd(const uint64_t *packed, const float *scale,
-                                   const float *zero, int64_t n_rows, int32_t d, float *dst,
+int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_rows, int32_t d, float *dst,
                                    int64_t ld_dst, int64_t row_offset, void *stream);
 
 /*
@@ -115,8 +116,7 @@ int32_t sylvie_dequantize_1bit_fwd(const uint64_t *packed, const float *scale,
  *   seg_rows  int32 [seg_ptr[n_dst_rows]], wire row indices in [0, n_rows)
  *   dst_ids   int32 [n_dst_rows], distinct rows of dst
  */
-int32_t sylvie_dequantize_1bit_bwd(const uint64_t *packed, const float *scale,
-                                   const float *zero, int64_t n_rows, int32_t d, float *dst,
+int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_rows, int32_t d, float *dst,
                                    int64_t ld_dst, const int64_t *seg_ptr,
                                    const int32_t *seg_rows, int64_t n_dst_rows,
                                    const int32_t *dst_ids, void *stream);
@@ -159,7 +159,7 @@ int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, cons
  * sylvie_dequantize_1bit_fwd into rows n_dense.. of X followed by
  * sylvie_aggregate_csr_fwd, without ever materialising the dequantized rows.
  *     column c <  n_dense : row c of X (float32, as above)
- *     column c >= n_dense : wire row c - n_dense of (packed, scale, zero), width d
+ *     column c >= n_dense : wire row c - n_dense of `wire`, width d
  * Inside every CSR row all columns < n_dense must precede all columns >= n_dense
  * (true when columns are ascending).  n_wire = number of wire rows (0: plain X).
  * Other arguments as in sylvie_aggregate_csr_fwd (no addend).
@@ -167,9 +167,9 @@ int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, cons
 int32_t sylvie_aggregate_csr_fwd_wire(const int64_t *rowptr, const int32_t *col, const float *w,
                                       const float *row_scale, const float *col_scale,
                                       int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
-                                      int64_t n_dense, const uint64_t *packed, const float *scale,
-                                      const float *zero, int64_t n_wire, float *Y, int64_t ld_y,
-                                      int32_t chunk, const int32_t *long_rows,
+                                      int64_t n_dense, const uint64_t *wire, int64_t n_wire,
+                                      float *Y, int64_t ld_y, int32_t chunk,
+                                      const int32_t *long_rows,
                                       const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
                                       float *workspace, size_t workspace_bytes, void *stream);
 

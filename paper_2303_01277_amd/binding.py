@@ -34,8 +34,8 @@ def lib():
         L.sylvie_status_string.restype = C.c_char_p
         L.sylvie_status_string.argtypes = [C.c_int32]
         L.sylvie_last_error.restype = C.c_char_p
-        L.sylvie_words_per_row.restype = C.c_int64
-        L.sylvie_words_per_row.argtypes = [C.c_int32]
+        L.sylvie_wire_row_words.restype = C.c_int64
+        L.sylvie_wire_row_words.argtypes = [C.c_int32]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
         L.sylvie_transform_bwd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32,
                                                            C.c_int64]
@@ -74,44 +74,38 @@ def sylvie_version() -> int:
     return int(lib().sylvie_version())
 
 
-def sylvie_words_per_row(d: int) -> int:
-    return int(lib().sylvie_words_per_row(int(d)))
+def sylvie_wire_row_words(d: int) -> int:
+    return int(lib().sylvie_wire_row_words(int(d)))
 
 
-def _quantize(fn, src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, packed_out,
-              scale_out, zero_out):
+def _quantize(fn, src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
     _check(fn(_ptr(src, torch.float32, "src"), C.c_int64(ld_src), C.c_int32(d),
               _ptr(idx, torch.int32, "idx"), C.c_int64(row_offset), C.c_int64(n_rows),
               C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
-              _ptr(packed_out, torch.int64, "packed_out"), _ptr(scale_out, torch.float32, "scale"),
-              _ptr(zero_out, torch.float32, "zero"), _stream()))
+              _ptr(wire_out, torch.int64, "wire_out"), _stream()))
 
 
-def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id,
-                             packed_out, scale_out, zero_out):
-    """packed_out is an int64 tensor viewed as uint64 words (torch has no uint64 kernels)."""
+def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
+    """wire_out is an int64 tensor holding the uint64 wire words (torch has no uint64 kernels)."""
     _quantize(lib().sylvie_quantize_1bit_fwd, src, ld_src, d, idx, row_offset, n_rows, seed,
-              stream_id, packed_out, scale_out, zero_out)
+              stream_id, wire_out)
 
 
-def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id,
-                             packed_out, scale_out, zero_out):
+def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
     _quantize(lib().sylvie_quantize_1bit_bwd, src, ld_src, d, idx, row_offset, n_rows, seed,
-              stream_id, packed_out, scale_out, zero_out)
+              stream_id, wire_out)
 
 
-def sylvie_dequantize_1bit_fwd(packed, scale, zero, n_rows, d, dst, ld_dst, row_offset):
+def sylvie_dequantize_1bit_fwd(wire, n_rows, d, dst, ld_dst, row_offset):
     _check(lib().sylvie_dequantize_1bit_fwd(
-        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
-        _ptr(zero, torch.float32, "zero"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d),
         _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), C.c_int64(row_offset), _stream()))
 
 
-def sylvie_dequantize_1bit_bwd(packed, scale, zero, n_rows, d, dst, ld_dst, seg_ptr, seg_rows,
-                               n_dst_rows, dst_ids):
+def sylvie_dequantize_1bit_bwd(wire, n_rows, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows,
+                               dst_ids):
     _check(lib().sylvie_dequantize_1bit_bwd(
-        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
-        _ptr(zero, torch.float32, "zero"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d),
         _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), _ptr(seg_ptr, torch.int64, "seg_ptr"),
         _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int64(n_dst_rows),
         _ptr(dst_ids, torch.int32, "dst_ids"), _stream()))
@@ -140,7 +134,7 @@ def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld
 
 
 def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,
-                                  packed, scale, zero, n_wire, Y, ld_y, chunk=0, long_rows=None,
+                                  wire, n_wire, Y, ld_y, chunk=0, long_rows=None,
                                   long_ptr=None, n_long=0, n_tasks=0, workspace=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_fwd_wire(
@@ -148,8 +142,7 @@ def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, 
         _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
         _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), C.c_int64(n_dense),
-        _ptr(packed, torch.int64, "packed"), _ptr(scale, torch.float32, "scale"),
-        _ptr(zero, torch.float32, "zero"), C.c_int64(n_wire), _ptr(Y, torch.float32, "Y"),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(n_wire), _ptr(Y, torch.float32, "Y"),
         C.c_int64(ld_y), C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"),
         _ptr(long_ptr, torch.int64, "long_ptr"), C.c_int64(n_long), C.c_int64(n_tasks),
         _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))

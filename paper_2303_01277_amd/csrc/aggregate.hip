@@ -71,9 +71,7 @@ struct AggArgs {
     float *workspace;
     // optional packed tail of X: columns >= n_dense are rows of a 1-bit wire
     int64_t n_dense;
-    const uint32_t *packed32;   // the uint64 words of the wire seen as dword pairs
-    const float *wscale;
-    const float *wzero;
+    const uint32_t *wire32;     // wire rows (W bit words + 1 metadata word) seen as dwords
 };
 
 // acc[p][t] += sum over entries [e0, e1) of w_e * cs[col_e] * X[col_e][column(p, t)]
@@ -99,7 +97,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         const int cc = (p * G + gl) * VEC;
         coff[p] = cc < a.d ? cc : a.d - VEC;
     }
-    const int W32 = ((a.d + 63) >> 6) * 2;     // dwords per wire row
+    const int W32 = ((a.d + 63) >> 6) * 2;     // bit dwords per wire row; 2 metadata dwords follow
     for (int64_t base = e0; base < e1; base += 64) {
         const int cnt = static_cast<int>(e1 - base < 64 ? e1 - base : 64);
         int my_c = 0;
@@ -173,8 +171,10 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 // 0 and reads wire row 0.
                 const bool mine = lane >= nd && lane < cnt;
                 const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
-                const float my_zp = a.wzero[my_wr];
-                const float my_hi = my_zp + a.wscale[my_wr];
+                const uint2 meta =
+                    *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (W32 + 2) + W32);
+                const float my_zp = __uint_as_float(meta.y);
+                const float my_hi = my_zp + __uint_as_float(meta.x);
                 const float my_ww = mine ? my_w : 0.0f;
                 constexpr int UW = (P >= 4) ? 4 : (16 / P);
                 for (j = nd - nd % EP; j < cnt; j += EP * UW) {
@@ -203,7 +203,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             zp[u] = __shfl(my_zp, src);
                             hi[u] = __shfl(my_hi, src);
                         }
-                        const uint32_t *pr = a.packed32 + wr * W32;
+                        const uint32_t *pr = a.wire32 + wr * (W32 + 2);
 #pragma unroll
                         for (int p = 0; p < P; ++p) dw[u][p] = pr[coff[p] >> 5];
                     }
@@ -350,7 +350,7 @@ static void launch_shape(const AggArgs &a, int64_t n_tasks, hipStream_t st)
     const int64_t nt = a.n_long > 0 ? n_tasks : 0;
     const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
                            (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
-    if (a.packed32)
+    if (a.wire32)
         hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, true>),
                            dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
     else
@@ -386,8 +386,7 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
                                 int64_t addend_rows, int32_t chunk, const int32_t *long_rows,
                                 const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
                                 float *workspace, size_t workspace_bytes, void *stream,
-                                int64_t n_dense = 0, const uint64_t *packed = nullptr,
-                                const float *wscale = nullptr, const float *wzero = nullptr,
+                                int64_t n_dense = 0, const uint64_t *wire = nullptr,
                                 int64_t n_wire = 0)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
@@ -398,9 +397,8 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad addend shape", name);
     if (n_long < 0 || n_tasks < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative count", name);
     if (n_wire < 0 || n_dense < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative count", name);
-    if (n_wire > 0 && (!packed || !wscale || !wzero))
-        return fail(SYLVIE_ERR_INVALID_ARG, "%s: wire has null pointers", name);
-    if (n_wire > 0 && (!aligned(packed, 8) || !aligned(wscale, 4) || !aligned(wzero, 4)))
+    if (n_wire > 0 && !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null wire", name);
+    if (n_wire > 0 && !aligned(wire, 8))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
     if (n_rows == 0) return SYLVIE_OK;
     if (!rowptr || !col || !X || !Y) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
@@ -427,8 +425,7 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.chunk = n_long > 0 ? chunk : 0;
     a.long_rows = long_rows; a.long_ptr = long_ptr; a.n_long = n_long; a.workspace = workspace;
     a.n_dense = n_dense;
-    a.packed32 = n_wire > 0 ? reinterpret_cast<const uint32_t *>(packed) : nullptr;
-    a.wscale = wscale; a.wzero = wzero;
+    a.wire32 = n_wire > 0 ? reinterpret_cast<const uint32_t *>(wire) : nullptr;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool a16 = aligned(X, 16) && aligned(Y, 16) && ld_x % 4 == 0 && ld_y % 4 == 0 &&
@@ -485,12 +482,11 @@ extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_
 extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
     const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
     const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
-    int64_t n_dense, const uint64_t *packed, const float *scale, const float *zero, int64_t n_wire,
-    float *Y, int64_t ld_y, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_dense, const uint64_t *wire, int64_t n_wire, float *Y, int64_t ld_y, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
     int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
 {
     return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
                                     col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
                                     long_rows, long_ptr, n_long, n_tasks, workspace,
-                                    workspace_bytes, stream, n_dense, packed, scale, zero, n_wire);
+                                    workspace_bytes, stream, n_dense, wire, n_wire);
 }

@@ -44,4 +44,4 @@ extern "C" const char *sylvie_status_string(int32_t status)
 
 extern "C" const char *sylvie_last_error(void) { return sylvie::g_err; }
 
-extern "C" int64_t sylvie_words_per_row(int32_t d) { return (static_cast<int64_t>(d) + 63) / 64; }
+extern "C" int64_t sylvie_wire_row_words(int32_t d) { return (static_cast<int64_t>(d) + 63) / 64 + 1; }

@@ -44,8 +44,7 @@ __device__ __forceinline__ void select_store(float *p, uint32_t bits, float lo, 
 
 template <int VEC>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel(
-    const uint64_t *__restrict__ packed, const float *__restrict__ scale,
-    const float *__restrict__ zero, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
+    const uint64_t *__restrict__ wire, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
     int64_t row_offset)
 {
     const int lane = lane_id();
@@ -57,9 +56,10 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel
     for (int r = 0; r < kDqRowsPerWave; ++r) {
         const int64_t i = first + r;
         if (i >= n_rows) break;
-        const float zp = zero[i];
-        const float hi = zp + scale[i];
-        const uint64_t *prow = packed + i * W;
+        const uint64_t *prow = wire + i * (W + 1);
+        const uint64_t meta = prow[W];                      // scale | zero << 32
+        const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
+        const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
         float *orow = dst + (row_offset + i) * ld;
         for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
             const uint64_t word = prow[c0 >> 6];
@@ -73,8 +73,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel
 // rows seg_rows[seg_ptr[k] .. seg_ptr[k+1]) in that order, float32.
 template <int VEC>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel(
-    const uint64_t *__restrict__ packed, const float *__restrict__ scale,
-    const float *__restrict__ zero, int d, float *__restrict__ dst, int64_t ld,
+    const uint64_t *__restrict__ wire, int d, float *__restrict__ dst, int64_t ld,
     const int64_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_rows,
     int64_t n_dst_rows, const int32_t *__restrict__ dst_ids)
 {
@@ -92,10 +91,11 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
         float acc[VEC];
         __builtin_memcpy(acc, &accv, sizeof(V));
         for (int64_t j = j0; j < j1; ++j) {
-            const int64_t i = seg_rows[j];
-            const float zp = zero[i];
-            const float hi = zp + scale[i];
-            const uint64_t word = packed[i * W + (c0 >> 6)];
+            const uint64_t *prow = wire + static_cast<int64_t>(seg_rows[j]) * (W + 1);
+            const uint64_t meta = prow[W];
+            const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
+            const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
+            const uint64_t word = prow[c0 >> 6];
             const uint32_t bits = static_cast<uint32_t>(word >> (c0 & 63));
 #pragma unroll
             for (int t = 0; t < VEC; ++t) acc[t] = acc[t] + (((bits >> t) & 1u) ? hi : zp);
@@ -112,31 +112,29 @@ static int pick_vec(int d, int64_t ld, const void *p)
     return 1;
 }
 
-static int32_t check_wire(const char *name, const uint64_t *packed, const float *scale,
-                          const float *zero, int64_t n_rows, int32_t d, const float *dst,
-                          int64_t ld)
+static int32_t check_wire(const char *name, const uint64_t *wire, int64_t n_rows, int32_t d,
+                          const float *dst, int64_t ld)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
     if (ld < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_dst %lld < d %d", name, (long long)ld, d);
     if (n_rows == 0) return SYLVIE_OK;
-    if (!packed || !scale || !zero || !dst) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
-    if (!aligned(packed, 8) || !aligned(scale, 4) || !aligned(zero, 4) || !aligned(dst, 4))
+    if (!wire || !dst) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!aligned(wire, 8) || !aligned(dst, 4))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned pointer", name);
     return SYLVIE_OK;
 }
 
 }  // namespace sylvie
 
-extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *packed, const float *scale,
-                                              const float *zero, int64_t n_rows, int32_t d,
+extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_rows, int32_t d,
                                               float *dst, int64_t ld_dst, int64_t row_offset,
                                               void *stream)
 {
     using namespace sylvie;
     const char *name = "sylvie_dequantize_1bit_fwd";
-    const int32_t rc = check_wire(name, packed, scale, zero, n_rows, d, dst, ld_dst);
+    const int32_t rc = check_wire(name, wire, n_rows, d, dst, ld_dst);
     if (rc != SYLVIE_OK) return rc;
     if (row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
     if (n_rows == 0) return SYLVIE_OK;
@@ -147,27 +145,26 @@ extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *packed, const floa
     // the vector width must also hold for the first written row
     const int vec = pick_vec(d, ld_dst, dst + row_offset * ld_dst);
     if (vec == 4)
-        hipLaunchKernelGGL(dequantize_fwd_kernel<4>, grid, block, 0, st, packed, scale, zero, n_rows,
+        hipLaunchKernelGGL(dequantize_fwd_kernel<4>, grid, block, 0, st, wire, n_rows,
                            d, dst, ld_dst, row_offset);
     else if (vec == 2)
-        hipLaunchKernelGGL(dequantize_fwd_kernel<2>, grid, block, 0, st, packed, scale, zero, n_rows,
+        hipLaunchKernelGGL(dequantize_fwd_kernel<2>, grid, block, 0, st, wire, n_rows,
                            d, dst, ld_dst, row_offset);
     else
-        hipLaunchKernelGGL(dequantize_fwd_kernel<1>, grid, block, 0, st, packed, scale, zero, n_rows,
+        hipLaunchKernelGGL(dequantize_fwd_kernel<1>, grid, block, 0, st, wire, n_rows,
                            d, dst, ld_dst, row_offset);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
 
-extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *packed, const float *scale,
-                                              const float *zero, int64_t n_rows, int32_t d,
+extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_rows, int32_t d,
                                               float *dst, int64_t ld_dst, const int64_t *seg_ptr,
                                               const int32_t *seg_rows, int64_t n_dst_rows,
                                               const int32_t *dst_ids, void *stream)
 {
     using namespace sylvie;
     const char *name = "sylvie_dequantize_1bit_bwd";
-    const int32_t rc = check_wire(name, packed, scale, zero, n_rows, d, dst, ld_dst);
+    const int32_t rc = check_wire(name, wire, n_rows, d, dst, ld_dst);
     if (rc != SYLVIE_OK) return rc;
     if (n_dst_rows < 0 || n_dst_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_dst_rows out of range", name);
@@ -180,13 +177,13 @@ extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *packed, const floa
     const dim3 block(kDqWavesPerBlock * kWave);
     const int vec = pick_vec(d, ld_dst, dst);
     if (vec == 4)
-        hipLaunchKernelGGL(dequantize_bwd_kernel<4>, grid, block, 0, st, packed, scale, zero, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<4>, grid, block, 0, st, wire, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     else if (vec == 2)
-        hipLaunchKernelGGL(dequantize_bwd_kernel<2>, grid, block, 0, st, packed, scale, zero, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<2>, grid, block, 0, st, wire, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     else
-        hipLaunchKernelGGL(dequantize_bwd_kernel<1>, grid, block, 0, st, packed, scale, zero, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<1>, grid, block, 0, st, wire, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;

@@ -45,31 +45,32 @@ __device__ __forceinline__ uint32_t draw24(uint32_t x)
     return x >> 8;
 }
 
-constexpr int kRowsPerWave = 4;
 constexpr int kWavesPerBlock = 4;
+// rows per wave: as many as fit one 64-lane store of (P + 1)-word wire rows, at most 4
+constexpr int rows_per_wave(int P) { return 64 / (P + 1) < 4 ? 64 / (P + 1) : 4; }
 
 // P = number of 64-column chunks held in registers (64 (P-1) < d <= 64 P);
 // FULL = (d == 64 P): no ragged last chunk.
 //
-// A wave owns kRowsPerWave consecutive wire rows.  The loads of row r+1 are issued
-// before row r is processed.  Columns past d re-read column d-1, which leaves
-// the extrema unchanged and needs no predicate; their bits are masked off.  The
-// words of all the wave's rows are collected into lanes r*W + k and leave in one
-// contiguous store, as do the scales and zero-points.
+// A wave owns R consecutive wire rows.  The loads of row r+1 are issued before
+// row r is processed.  Columns past d re-read column d-1, which leaves the
+// extrema unchanged and needs no predicate; their bits are masked off.  A wire
+// row is P bit words followed by one metadata word (scale in the low half, zero
+// in the high half); the words of all the wave's rows are collected into lanes
+// r*(P+1) + k and leave in one contiguous store.
 template <int P, bool FULL>
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ packed,
-    float *__restrict__ scale, float *__restrict__ zero)
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
 {
-    constexpr int R = kRowsPerWave;
-    static_assert(R * P <= 64, "one store must hold all words of a wave");
+    constexpr int R = rows_per_wave(P);
+    static_assert(R >= 1 && R * (P + 1) <= 64, "one store must hold all words of a wave");
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t first = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave) * R;
     if (first >= n_rows) return;
     const int nrows = static_cast<int>(n_rows - first < R ? n_rows - first : R);
-    constexpr int W = P;
+    constexpr int W1 = P + 1;       // words per wire row
     constexpr float kTwoM24 = 1.0f / 16777216.0f;
 
     int my_src = 0;
@@ -97,7 +98,6 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
         for (int p = 0; p < P; ++p) cur[p] = row[coff[p]];
     }
     uint64_t my_word = 0;
-    float my_scale = 0.0f, my_zero = 0.0f;
     const uint32_t lane_ctr = static_cast<uint32_t>(lane) * kColStride;
 
 #pragma unroll
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
                     const float rhs = cur[p] - mn;
                     uint64_t word = __ballot(lhs < rhs);
                     if (!FULL && p == P - 1) word &= tail_mask;
-                    if (lane == r * W + p) my_word = word;
+                    if (lane == r * W1 + p) my_word = word;
                     ctr += 64u * kColStride;
                 }
             } else {
@@ -141,30 +141,23 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
                     const float rhs = cur[p] - mn;
                     uint64_t word = __ballot(lhs < rhs);
                     if (!FULL && p == P - 1) word &= tail_mask;
-                    if (lane == r * W + p) my_word = word;
+                    if (lane == r * W1 + p) my_word = word;
                     ctr += 64u * kColStride;
                 }
             }
-            if (lane == r) {
-                my_scale = sc;
-                my_zero = mn;
-            }
+            if (lane == r * W1 + P)
+                my_word = (static_cast<uint64_t>(__float_as_uint(mn)) << 32) | __float_as_uint(sc);
 #pragma unroll
             for (int p = 0; p < P; ++p) cur[p] = nxt[p];
         }
     }
-    if (lane < nrows * W) packed[first * W + lane] = my_word;
-    if (lane < nrows) {
-        scale[first + lane] = my_scale;
-        zero[first + lane] = my_zero;
-    }
+    if (lane < nrows * W1) wire[first * W1 + lane] = my_word;
 }
 
 // Any width: the row is read twice (the second read hits the cache).
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ packed,
-    float *__restrict__ scale, float *__restrict__ zero)
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
 {
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
@@ -186,7 +179,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kern
     const float sc = mx - mn;
     const uint32_t rkey = mix32(ckey ^ static_cast<uint32_t>(i));
     uint32_t ctr = rkey + static_cast<uint32_t>(lane) * kColStride;
-    uint64_t *out = packed + i * W;
+    uint64_t *out = wire + i * (W + 1);
     for (int k = 0; k < W; ++k) {
         const int c = k * 64 + lane;
         const float x = c < d ? row[c] : 0.0f;
@@ -196,28 +189,24 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kern
         if (lane == 0) out[k] = word;
         ctr += 64u * kColStride;
     }
-    if (lane == 0) {
-        scale[i] = sc;
-        zero[i] = mn;
-    }
+    if (lane == 0) out[W] = (static_cast<uint64_t>(__float_as_uint(mn)) << 32) | __float_as_uint(sc);
 }
 
 template <int P, bool FULL>
 static void launch_rows(const float *src, int64_t ld, int d, const int32_t *idx,
-                        int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *packed,
-                        float *scale, float *zero, hipStream_t st)
+                        int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *wire,
+                        hipStream_t st)
 {
-    const int64_t rows_per_block = kRowsPerWave * kWavesPerBlock;
+    const int64_t rows_per_block = rows_per_wave(P) * kWavesPerBlock;
     const int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
     hipLaunchKernelGGL((quantize_rows_kernel<P, FULL>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset, n_rows,
-                       ckey, packed, scale, zero);
+                       ckey, wire);
 }
 
 static int32_t quantize_common(const char *name, const float *src, int64_t ld, int32_t d,
                                const int32_t *idx, int64_t row_offset, int64_t n_rows,
-                               uint64_t seed, uint32_t stream_id, uint64_t *packed, float *scale,
-                               float *zero, void *stream)
+                               uint64_t seed, uint32_t stream_id, uint64_t *wire, void *stream)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
@@ -225,12 +214,11 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
     if (ld < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_src %lld < d %d", name, (long long)ld, d);
     if (!idx && row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
     if (n_rows == 0) return SYLVIE_OK;
-    if (!src || !packed || !scale || !zero)
-        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
-    if (!aligned(src, 4) || !aligned(scale, 4) || !aligned(zero, 4) || (idx && !aligned(idx, 4)))
+    if (!src || !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!aligned(src, 4) || (idx && !aligned(idx, 4)))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: float/int arrays need 4-byte alignment", name);
-    if (!aligned(packed, 8))
-        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: packed_out needs 8-byte alignment", name);
+    if (!aligned(wire, 8))
+        return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: wire_out needs 8-byte alignment", name);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const uint32_t ckey = call_key(seed, stream_id);
@@ -238,9 +226,9 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
 #define SYLVIE_Q_CASE(p)                                                                       \
     case p:                                                                                    \
         if (d == 64 * p)                                                                       \
-            launch_rows<p, true>(src, ld, d, idx, row_offset, n_rows, ckey, packed, scale, zero, st);  \
+            launch_rows<p, true>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);                \
         else                                                                                   \
-            launch_rows<p, false>(src, ld, d, idx, row_offset, n_rows, ckey, packed, scale, zero, st); \
+            launch_rows<p, false>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);              \
         break;
     switch (P) {
         SYLVIE_Q_CASE(1)
@@ -263,7 +251,7 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
         const int64_t blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
         hipLaunchKernelGGL(quantize_rows_wide_kernel, dim3(static_cast<unsigned>(blocks)),
                            dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset,
-                           n_rows, ckey, packed, scale, zero);
+                           n_rows, ckey, wire);
     }
     }
 #undef SYLVIE_Q_CASE
@@ -276,21 +264,17 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
 extern "C" int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
                                             const int32_t *idx, int64_t row_offset,
                                             int64_t n_rows, uint64_t seed, uint32_t stream_id,
-                                            uint64_t *packed_out, float *scale_out,
-                                            float *zero_out, void *stream)
+                                            uint64_t *wire_out, void *stream)
 {
     return sylvie::quantize_common("sylvie_quantize_1bit_fwd", src, ld_src, d, idx, row_offset,
-                                   n_rows, seed, stream_id, packed_out, scale_out, zero_out,
-                                   stream);
+                                   n_rows, seed, stream_id, wire_out, stream);
 }
 
 extern "C" int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
                                             const int32_t *idx, int64_t row_offset,
                                             int64_t n_rows, uint64_t seed, uint32_t stream_id,
-                                            uint64_t *packed_out, float *scale_out,
-                                            float *zero_out, void *stream)
+                                            uint64_t *wire_out, void *stream)
 {
     return sylvie::quantize_common("sylvie_quantize_1bit_bwd", src, ld_src, d, idx, row_offset,
-                                   n_rows, seed, stream_id, packed_out, scale_out, zero_out,
-                                   stream);
+                                   n_rows, seed, stream_id, wire_out, stream);
 }

@@ -53,9 +53,7 @@ class PartState:
     ws_agg: Optional[torch.Tensor] = None
     ws_aggT: Optional[torch.Tensor] = None
     ws_g: Optional[torch.Tensor] = None
-    packed: Optional[torch.Tensor] = None
-    scale: Optional[torch.Tensor] = None
-    zero: Optional[torch.Tensor] = None
+    wire: Optional[torch.Tensor] = None                       # int64 words, n_halo wire rows
 
 
 class LayerLoop:
@@ -99,10 +97,8 @@ class LayerLoop:
                     blocks.append(Block(o, j, j + c, rows, sp, sr, di))
                     j += c
             st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
-            Wd = B.sylvie_words_per_row(dmax)
-            st.packed = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
-            st.scale = torch.empty(max(1, part.n_halo), dtype=torch.float32, device=dev)
-            st.zero = torch.empty(max(1, part.n_halo), dtype=torch.float32, device=dev)
+            Wd = B.sylvie_wire_row_words(dmax)
+            st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
             st.ws_aggT = torch.empty(max(1, planT[2]) * dmax, dtype=torch.float32, device=dev)
             kmax = max(dims[l - 1] * (2 if model == "sage" else 1) for l in range(1, self.L + 1))
@@ -127,9 +123,9 @@ class LayerLoop:
             self.parts.append(st)
 
     # -- helpers ---------------------------------------------------------------
-    def _keep(self, key, pk, sc, zp, n, W):
+    def _keep(self, key, wire, n, W):
         if self.record is not None:
-            self.record[key] = (pk[: n * W].clone(), sc[:n].clone(), zp[:n].clone())
+            self.record[key] = wire[: n * W].clone()
 
     def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0):
         rp, cl, w = op
@@ -144,7 +140,7 @@ class LayerLoop:
     def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
         for l in range(1, self.L + 1):
             d = self.dims[l - 1]
-            Wd = B.sylvie_words_per_row(d)
+            Wd = B.sylvie_wire_row_words(d)
             for me, st in enumerate(self.parts):
                 ht = st.Htil[l - 1]
                 for b in st.blocks:
@@ -153,13 +149,12 @@ class LayerLoop:
                     if self.wire == "1bit":
                         # the wire of halo rows [j0, j1) sits at the same offset in the
                         # receiver's wire arrays, so all blocks stay resident side by side
-                        pk, sc, zp = st.packed[b.j0 * Wd:], st.scale[b.j0:], st.zero[b.j0:]
+                        wire = st.wire[b.j0 * Wd:]
                         B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
-                                                   pair_seed(seed, b.owner, me), 2 * l + 0,
-                                                   pk, sc, zp)
-                        self._keep(("fwd", l, me, b.j0), pk, sc, zp, n, Wd)
+                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
+                        self._keep(("fwd", l, me, b.j0), wire, n, Wd)
                         if not self.fused:
-                            B.sylvie_dequantize_1bit_fwd(pk, sc, zp, n, d, ht, ht.stride(0),
+                            B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
                                                          st.n_in + b.j0)
                     else:   # full-precision exchange: plain device copy of the rows
                         ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
@@ -169,8 +164,8 @@ class LayerLoop:
                     rp, cl, w = st.op
                     lr, lp, nt = st.plan
                     B.sylvie_aggregate_csr_fwd_wire(
-                        rp, cl, w, None, None, st.n_in, ht, ht.stride(0), d, st.n_in, st.packed,
-                        st.scale, st.zero, st.n_halo, Z, Z.stride(0), chunk=self.chunk,
+                        rp, cl, w, None, None, st.n_in, ht, ht.stride(0), d, st.n_in, st.wire,
+                        st.n_halo, Z, Z.stride(0), chunk=self.chunk,
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
                         workspace=st.ws_agg if nt else None)
@@ -192,7 +187,7 @@ class LayerLoop:
         for l in range(self.L, 0, -1):
             d, h = self.dims[l - 1], self.dims[l]
             need_dx = l > 1 or self.exchange_first_layer
-            Wd = B.sylvie_words_per_row(d)
+            Wd = B.sylvie_wire_row_words(d)
             for st in self.parts:
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
@@ -227,10 +222,9 @@ class LayerLoop:
                     if self.wire == "1bit":
                         B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
                                                    pair_seed(seed, me, b.owner), 2 * l + 1,
-                                                   st.packed, st.scale, st.zero)
-                        self._keep(("bwd", l, me, b.j0), st.packed, st.scale, st.zero, n, Wd)
-                        B.sylvie_dequantize_1bit_bwd(st.packed, st.scale, st.zero, n, d, tgt,
-                                                     tgt.stride(0), b.seg_ptr, b.seg_rows,
-                                                     int(b.dst_ids.numel()), b.dst_ids)
+                                                   st.wire)
+                        self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
+                        B.sylvie_dequantize_1bit_bwd(st.wire, n, d, tgt, tgt.stride(0), b.seg_ptr,
+                                                     b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
                     else:
                         tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())

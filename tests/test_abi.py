@@ -44,8 +44,8 @@ def test_version_and_strings(lib):
     assert lib.sylvie_version() >= 100
     assert lib.sylvie_status_string(0) == b"ok"
     assert b"argument" in lib.sylvie_status_string(-1)
-    lib.sylvie_words_per_row.restype = C.c_int64
-    assert [lib.sylvie_words_per_row(d) for d in (1, 64, 65, 100, 602)] == [1, 1, 2, 2, 10]
+    lib.sylvie_wire_row_words.restype = C.c_int64
+    assert [lib.sylvie_wire_row_words(d) for d in (1, 64, 65, 100, 602)] == [2, 2, 3, 3, 11]
 
 
 def test_bad_arguments_are_rejected_without_gpu(lib):
@@ -56,7 +56,7 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     q.restype = C.c_int32
     args = lambda **kw: [kw.get("src", p), C.c_int64(kw.get("ld", 64)), C.c_int32(kw.get("d", 64)),
                          None, C.c_int64(0), C.c_int64(kw.get("n", 8)), C.c_uint64(1),
-                         C.c_uint32(0), kw.get("packed", p), p, p, None]
+                         C.c_uint32(0), kw.get("packed", p), None]
     assert q(*args(d=0)) == -1
     assert q(*args(d=65, ld=64)) == -1
     assert q(*args(n=-1)) == -1
@@ -67,8 +67,8 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     assert q(*args(n=0)) == 0                                  # empty exchange is a no-op
     dq = lib.sylvie_dequantize_1bit_fwd
     dq.restype = C.c_int32
-    assert dq(p, p, p, C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
-    assert dq(p, p, p, C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
+    assert dq(p, C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
+    assert dq(p, C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
     ag = lib.sylvie_aggregate_csr_fwd
     ag.restype = C.c_int32
     base = [p, p, None, None, None, C.c_int64(4), p, C.c_int64(64), C.c_int32(64), p,

@@ -12,7 +12,7 @@ import torch
 
 from oracle import layers as OL
 from synth import CONFIGS, build_workload, scaled
-from util import np_c, to_partdata
+from util import np_c, split_wire, to_partdata
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -67,8 +67,8 @@ def replay(oracle, wl, loop, pdata, seed):
                 idx = np_c(b.rows)
                 n = b.j1 - b.j0
                 ref = oracle.quantize_1bit(src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=idx)
-                pk, sc, zp = (np_c(t) for t in loop.record[("fwd", l, me, b.j0)])
-                assert np.array_equal(pk.view(np.uint64).reshape(n, -1), ref[0]), ("fwd wire", l)
+                pk, sc, zp = split_wire(np_c(loop.record[("fwd", l, me, b.j0)]), n, d)
+                assert np.array_equal(pk, ref[0]), ("fwd wire", l)
                 assert np.array_equal(bits32(sc), bits32(ref[1]))
                 assert np.array_equal(bits32(zp), bits32(ref[2]))
                 want = np.empty((n, d), np.float32)
@@ -128,8 +128,8 @@ def replay_backward(oracle, wl, loop, pdata, seed, snaps):
                     n = b.j1 - b.j0
                     ref = oracle.quantize_1bit(gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
                                                row_offset=st.n_in + b.j0)
-                    pk, sc, zp = (np_c(t) for t in loop.record[("bwd", l, me, b.j0)])
-                    assert np.array_equal(pk.view(np.uint64).reshape(n, -1), ref[0]), ("bwd wire", l)
+                    pk, sc, zp = split_wire(np_c(loop.record[("bwd", l, me, b.j0)]), n, d)
+                    assert np.array_equal(pk, ref[0]), ("bwd wire", l)
                     assert np.array_equal(bits32(sc), bits32(ref[1]))
                     assert np.array_equal(bits32(zp), bits32(ref[2]))
                     oracle.dequantize_1bit_bwd(ref[0], ref[1], ref[2], d, want, np_c(b.rows))
@@ -149,7 +149,7 @@ class SnapLoop:
 
         # snapshot J^(l), dZ, dself and the pre-exchange dHtil of every partition: hook the
         # first backward quantize call of each layer (all aggregates of that layer are done)
-        def hook(src, ld, d, idx, off, n, sd, stream_id, pk, sc, zp):
+        def hook(src, ld, d, idx, off, n, sd, stream_id, wire):
             l = (stream_id - 1) // 2
             if state["l"] != l:
                 state["l"] = l
@@ -164,7 +164,7 @@ class SnapLoop:
                             st.dself.view(-1)[: st.n_in * dd].view(st.n_in, dd)),
                         "dHtil_pre": np_c(st.dHtil[l - 1]),
                     }
-            return orig_q(src, ld, d, idx, off, n, sd, stream_id, pk, sc, zp)
+            return orig_q(src, ld, d, idx, off, n, sd, stream_id, wire)
 
         B.sylvie_quantize_1bit_bwd = hook
         try:

@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from synth import CONFIGS, build_workload, scaled
+from util import join_wire, split_wire
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -52,23 +53,19 @@ def make_rows(rng, n, ld, kind):
 
 
 def run_quantize(B, oracle, x, d, n, idx, row_offset, seed, stream, fn):
-    W = (d + 63) // 64
+    W1 = (d + 63) // 64 + 1
     xs = dev(x)
-    packed = torch.full((n * W + 3,), -1, dtype=torch.int64, device=DEV)
-    scale = torch.full((n + 3,), -7.0, device=DEV)
-    zero = torch.full((n + 3,), -7.0, device=DEV)
-    fn(xs, x.shape[1], d, None if idx is None else dev(idx), row_offset, n, seed, stream,
-       packed, scale, zero)
+    wire = torch.full((n * W1 + 3,), -1, dtype=torch.int64, device=DEV)
+    fn(xs, x.shape[1], d, None if idx is None else dev(idx), row_offset, n, seed, stream, wire)
     torch.cuda.synchronize()
     ref = oracle.quantize_1bit(x, d, n, seed, stream, idx=idx, row_offset=row_offset)
-    gp = packed.cpu().numpy().view(np.uint64)
-    assert np.array_equal(gp[: n * W].reshape(n, W), ref[0]), "packed words"
-    assert np.array_equal(bits32(scale.cpu().numpy()[:n]), bits32(ref[1])), "scale"
-    assert np.array_equal(bits32(zero.cpu().numpy()[:n]), bits32(ref[2])), "zero"
-    # nothing written past the end
-    assert (gp[n * W:] == np.uint64(2**64 - 1)).all()
-    assert (scale.cpu().numpy()[n:] == -7).all() and (zero.cpu().numpy()[n:] == -7).all()
-    return packed, scale, zero, ref
+    gw = wire.cpu().numpy()
+    pk, sc, zp = split_wire(gw, n, d)
+    assert np.array_equal(pk, ref[0]), "packed words"
+    assert np.array_equal(bits32(sc), bits32(ref[1])), "scale"
+    assert np.array_equal(bits32(zp), bits32(ref[2])), "zero"
+    assert (gw[n * W1:] == -1).all()                            # nothing written past the end
+    return wire, ref
 
 
 @pytest.mark.parametrize("d", [1, 2, 3, 63, 64, 65, 100, 128, 129, 256, 300, 602, 640, 1024, 1100])
@@ -94,9 +91,8 @@ def test_quantize_tiny_counts(oracle):
     for n in (1, 2, 3, 4, 5, 15, 16, 17):
         run_quantize(B, oracle, x, 256, n, None, 7, 99, 1, B.sylvie_quantize_1bit_fwd)
     # n = 0: nothing is written, nothing fails
-    p = torch.zeros(4, dtype=torch.int64, device=DEV)
-    s = torch.zeros(4, device=DEV)
-    B.sylvie_quantize_1bit_fwd(dev(x), 256, 256, None, 0, 0, 1, 1, p, s, s)
+    p = torch.zeros(8, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_1bit_fwd(dev(x), 256, 256, None, 0, 0, 1, 1, p)
 
 
 @pytest.mark.parametrize("d", [1, 2, 3, 64, 65, 100, 128, 256, 602, 1100])
@@ -110,7 +106,7 @@ def test_dequantize_fwd_parity(oracle, d):
         ref = rng.standard_normal((n + 20, ld)).astype(np.float32)
         out = dev(ref)
         oracle.dequantize_1bit_fwd(pk, sc, zp, d, ref, off)
-        B.sylvie_dequantize_1bit_fwd(dev(pk.view(np.int64)), dev(sc), dev(zp), n, d, out, ld, off)
+        B.sylvie_dequantize_1bit_fwd(dev(join_wire(pk, sc, zp)), n, d, out, ld, off)
         torch.cuda.synchronize()
         assert np.array_equal(bits32(out.cpu().numpy()), bits32(ref)), (ld, off)
 
@@ -130,7 +126,7 @@ def test_dequantize_bwd_parity(oracle, d):
     Jg = dev(J)
     oracle.dequantize_1bit_bwd(pk, sc, zp, d, J, dst)
     sp_, sr, di = GE.scatter_segments(dev(dst))
-    B.sylvie_dequantize_1bit_bwd(dev(pk.view(np.int64)), dev(sc), dev(zp), n, d, Jg, ld, sp_, sr,
+    B.sylvie_dequantize_1bit_bwd(dev(join_wire(pk, sc, zp)), n, d, Jg, ld, sp_, sr,
                                  int(di.numel()), di)
     torch.cuda.synchronize()
     assert np.array_equal(bits32(Jg.cpu().numpy()), bits32(J))
@@ -258,7 +254,7 @@ def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
     Z, S = oracle.aggregate_fwd(rp, cl, w, Xo, d, want_S=True)
     rpd, cld, wd = dev(rp), dev(cl), dev(w)
     Xin = dev(X[: p.n_in])
-    pkd, scd, zpd = dev(pk.view(np.int64)), dev(sc), dev(zp)
+    wired = dev(join_wire(pk, sc, zp))
     for chunk in (0, 128):
         kw = {}
         if chunk:
@@ -266,10 +262,10 @@ def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
             kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
                       workspace=torch.empty(max(1, nt) * d, device=DEV))
         Y = torch.full((p.n_in, d), float("nan"), device=DEV)
-        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, pkd,
-                                        scd, zpd, p.n_halo, Y, d, **kw)
+        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, wired,
+                                        p.n_halo, Y, d, **kw)
         Xfull = dev(X)
-        B.sylvie_dequantize_1bit_fwd(pkd, scd, zpd, p.n_halo, d, Xfull, d, p.n_in)
+        B.sylvie_dequantize_1bit_fwd(wired, p.n_halo, d, Xfull, d, p.n_in)
         Y2 = torch.full((p.n_in, d), float("nan"), device=DEV)
         B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, Y2, d, **kw)
         torch.cuda.synchronize()

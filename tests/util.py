@@ -32,3 +32,24 @@ def to_partdata(wl, loopback=None):
 def ulp32(x):
     x = np.abs(np.asarray(x, np.float32))
     return np.spacing(x)
+
+
+def split_wire(wire, n, d):
+    """GPU wire (uint64 [n][W+1], as an int64/uint64 array) -> the oracle's three arrays:
+    packed uint64 [n, W], scale f32 [n], zero f32 [n]."""
+    W = (d + 63) // 64
+    w = np.ascontiguousarray(wire).view(np.uint64)[: n * (W + 1)].reshape(n, W + 1)
+    meta = np.ascontiguousarray(w[:, W])
+    scale = (meta & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.float32)
+    zero = (meta >> np.uint64(32)).astype(np.uint32).view(np.float32)
+    return np.ascontiguousarray(w[:, :W]), scale, zero
+
+
+def join_wire(packed, scale, zero):
+    """The oracle's three arrays -> wire rows uint64 [n][W+1] (returned as int64 for torch)."""
+    n, W = packed.shape
+    w = np.empty((n, W + 1), np.uint64)
+    w[:, :W] = packed
+    w[:, W] = (zero.view(np.uint32).astype(np.uint64) << np.uint64(32)) | \
+        scale.view(np.uint32).astype(np.uint64)
+    return w.view(np.int64)
