@@ -79,8 +79,9 @@ def uniform24(seed: int, stream: int, row: int, col: int) -> int:
                                   C.c_uint32(col)))
 
 
-def quantize_1bit(src, d, n_rows, seed, stream, idx=None, row_offset=0):
-    """-> (packed uint64 [n_rows, W], scale f32 [n_rows], zero f32 [n_rows])."""
+def quantize_1bit(src, d, n_rows, seed, stream, idx=None, row_offset=0, wire_row0=0):
+    """-> (packed uint64 [n_rows, W], scale f32 [n_rows], zero f32 [n_rows]).
+    wire_row0: index of the first of these rows in the exchange they belong to."""
     _f32(src, "src")
     ld = src.shape[1]
     W = words_per_row(d)
@@ -90,8 +91,8 @@ def quantize_1bit(src, d, n_rows, seed, stream, idx=None, row_offset=0):
     if idx is not None:
         _chk(idx, np.int32, "idx")
     _L().orc_quantize_1bit(_p(src), C.c_int64(ld), C.c_int32(d), _p(idx), C.c_int64(row_offset),
-                           C.c_int64(n_rows), C.c_uint64(seed), C.c_uint32(stream), _p(packed),
-                           _p(scale), _p(zero))
+                           C.c_int64(n_rows), C.c_uint64(seed), C.c_uint32(stream),
+                           C.c_int64(wire_row0), _p(packed), _p(scale), _p(zero))
     return packed, scale, zero
 
 

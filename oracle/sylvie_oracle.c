@@ -69,7 +69,7 @@ static uint32_t orc_elem_u24(uint32_t row_key, uint32_t col)
     uint32_t x = row_key + col * ORC_COL_STRIDE;
     x ^= x >> 16;
     x *= ORC_M1;
-    x ^= x >> 15;
+    x ^= x >> 16;
     x *= ORC_M2;
     return x >> 8;
 }
@@ -90,6 +90,8 @@ int64_t orc_words_per_row(int32_t d) { return ((int64_t)d + 63) / 64; }
 /*
  * For wire row i = 0..n_rows-1 the source row is idx[i] (idx != NULL) or
  * row_offset + i (idx == NULL) of the row-major matrix src (leading dim ld).
+ * wire_row0 is added to i where i keys the random draws, so that a window of a
+ * longer exchange can be recomputed on its own (0 for a whole exchange).
  *
  *   mn = min_c r_c, mx = max_c r_c, each then "+ 0.0f" (turns -0 into +0)
  *   zero = mn,  scale = mx - mn            (B = 1, so (max-min)/B is the range)
@@ -107,7 +109,7 @@ int64_t orc_words_per_row(int32_t d) { return ((int64_t)d + 63) / 64; }
  */
 void orc_quantize_1bit(const float *src, int64_t ld, int32_t d, const int32_t *idx,
                        int64_t row_offset, int64_t n_rows, uint64_t seed, uint32_t stream,
-                       uint64_t *packed, float *scale, float *zero)
+                       int64_t wire_row0, uint64_t *packed, float *scale, float *zero)
 {
     const int64_t W = orc_words_per_row(d);
     const uint32_t ck = orc_call_key(seed, stream);
@@ -126,7 +128,7 @@ void orc_quantize_1bit(const float *src, int64_t ld, int32_t d, const int32_t *i
         const float sc = mx - mn;
         zero[i] = mn;
         scale[i] = sc;
-        const uint32_t rk = orc_row_key(ck, (uint32_t)i);
+        const uint32_t rk = orc_row_key(ck, (uint32_t)(wire_row0 + i));
         for (int64_t k = 0; k < W; ++k) packed[i * W + k] = 0;
         for (int32_t c = 0; c < d; ++c) {
             const float u = (float)orc_elem_u24(rk, (uint32_t)c) * two_m24;

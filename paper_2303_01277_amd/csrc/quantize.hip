@@ -6,6 +6,8 @@
 // 64-bit lane mask that IS packed word k of the row (bit j = column 64k + j): the
 // packing costs no instructions.  Row minimum and maximum are a DPP reduction;
 // the per-row hash key lives on the scalar unit.
+#include <utility>
+
 #include "common.hpp"
 
 namespace sylvie {
@@ -35,17 +37,50 @@ static uint32_t call_key(uint64_t seed, uint32_t stream_id)
     return mix32(k ^ stream_id);
 }
 
-// Top 24 bits of the second product: the draw for one element.
+// Top 24 bits of the second product: the draw for one element.  Both xor-shifts
+// are by 16 so that each is a single VALU op (the shifted operand is a sub-dword
+// select of the same register).
 __device__ __forceinline__ uint32_t draw24(uint32_t x)
 {
     x ^= x >> 16;
     x *= kM1;
-    x ^= x >> 15;
+    x ^= x >> 16;
     x *= kM2;
     return x >> 8;
 }
 
 constexpr int kWavesPerBlock = 4;
+
+// dst[lane LANE] = value (wave-uniform, taken from a scalar register); other lanes keep theirs.
+// lo[LANE] = low half, hi[LANE] = high half of a wave-uniform 64-bit value held in
+// scalar registers; other lanes keep theirs.  The lane select has to be an inline
+// constant (data and select may not both be scalar registers).  The value is
+// usually the result of the vector compare just before: a scalar register written
+// by the vector unit needs two wait states before the vector unit reads it back,
+// and the compiler does not look inside an asm block, hence the s_nop.
+template <int LANE>
+__device__ __forceinline__ void write_lane64(int &lo, int &hi, uint64_t value)
+{
+    asm volatile("s_nop 1\n\t"
+                 "v_writelane_b32 %0, %2, %4\n\t"
+                 "v_writelane_b32 %1, %3, %4"
+                 : "+v"(lo), "+v"(hi)
+                 : "s"(static_cast<int>(value)), "s"(static_cast<int>(value >> 32)), "n"(LANE));
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): loop indices that
+// are constant expressions inside the body
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 // rows per wave: as many as fit one 64-lane store of (P + 1)-word wire rows, at most 4
 constexpr int rows_per_wave(int P) { return 64 / (P + 1) < 4 ? 64 / (P + 1) : 4; }
 
@@ -97,11 +132,11 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
 #pragma unroll
         for (int p = 0; p < P; ++p) cur[p] = row[coff[p]];
     }
-    uint64_t my_word = 0;
+    int my_lo = 0, my_hi = 0;       // this lane's word of the wave's output run
     const uint32_t lane_ctr = static_cast<uint32_t>(lane) * kColStride;
 
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
+    static_for<R>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
         if (r < nrows) {
             if (r + 1 < nrows) {
                 const float *row = row_base(r + 1);
@@ -123,35 +158,36 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
             // u * scale with u = k * 2^-24: folding the exact power of two into the
             // scale gives the same single rounding unless scale * 2^-24 is subnormal.
             const bool fold = sc >= 0x1p-102f || sc == 0.0f;
+            const float sc24 = sc * kTwoM24;
+            auto emit = [&](auto pc, bool on) {
+                constexpr int p = decltype(pc)::value;
+                uint64_t word = __ballot(on);
+                if (!FULL && p == P - 1) word &= tail_mask;
+                write_lane64<r * W1 + p>(my_lo, my_hi, word);
+            };
             if (__builtin_expect(fold, 1)) {
-                const float sc24 = sc * kTwoM24;
-#pragma unroll
-                for (int p = 0; p < P; ++p) {
-                    const float lhs = static_cast<float>(draw24(ctr)) * sc24;
-                    const float rhs = cur[p] - mn;
-                    uint64_t word = __ballot(lhs < rhs);
-                    if (!FULL && p == P - 1) word &= tail_mask;
-                    if (lane == r * W1 + p) my_word = word;
-                    ctr += 64u * kColStride;
-                }
+                static_for<P>([&](auto pc) {
+                    constexpr int p = decltype(pc)::value;
+                    const float k = static_cast<float>(draw24(ctr + static_cast<uint32_t>(p) * 64u * kColStride));
+                    emit(pc, k * sc24 < cur[p] - mn);
+                });
             } else {
-#pragma unroll 1
-                for (int p = 0; p < P; ++p) {
-                    const float lhs = (static_cast<float>(draw24(ctr)) * kTwoM24) * sc;
-                    const float rhs = cur[p] - mn;
-                    uint64_t word = __ballot(lhs < rhs);
-                    if (!FULL && p == P - 1) word &= tail_mask;
-                    if (lane == r * W1 + p) my_word = word;
-                    ctr += 64u * kColStride;
-                }
+                static_for<P>([&](auto pc) {
+                    constexpr int p = decltype(pc)::value;
+                    const float k = static_cast<float>(draw24(ctr + static_cast<uint32_t>(p) * 64u * kColStride));
+                    emit(pc, (k * kTwoM24) * sc < cur[p] - mn);
+                });
             }
-            if (lane == r * W1 + P)
-                my_word = (static_cast<uint64_t>(__float_as_uint(mn)) << 32) | __float_as_uint(sc);
+            write_lane64<r * W1 + P>(my_lo, my_hi,
+                                     (static_cast<uint64_t>(uniform(__float_as_uint(mn))) << 32) |
+                                         uniform(__float_as_uint(sc)));
 #pragma unroll
             for (int p = 0; p < P; ++p) cur[p] = nxt[p];
         }
-    }
-    if (lane < nrows * W1) wire[first * W1 + lane] = my_word;
+    });
+    if (lane < nrows * W1)
+        wire[first * W1 + lane] = (static_cast<uint64_t>(static_cast<uint32_t>(my_hi)) << 32) |
+                                  static_cast<uint32_t>(my_lo);
 }
 
 // Any width: the row is read twice (the second read hits the cache).

@@ -104,24 +104,36 @@ __device__ __forceinline__ void put_kc(float *T, int i, const float (&v)[4])
     for (int q = 0; q < 4; ++q) p[q * kPadKC] = v[q];
 }
 
-// 64 x 64 quarter of the block tile: 8 k-steps of 2, 2 x 2 MFMA blocks each.
+// 64 x 64 quarter of the block tile: 8 k-steps of 2, 2 x 2 MFMA blocks each.  The
+// operands of step k+1 are read from LDS before the MFMAs of step k are issued, so
+// the LDS latency hides behind the matrix pipe.
 template <int PADA, int PADB>
 __device__ __forceinline__ void mma_tile(floatx16 (&acc)[2][2], const float *As, const float *Bs,
                                          int wm, int wn, int lane)
 {
     const int l32 = lane & 31, kh = lane >> 5;
+    const float *pa = As + kh * PADA + wm + l32;
+    const float *pb = Bs + kh * PADB + wn + l32;
+    float a[2][2], b[2][2];
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
-        float a[2], b[2];
+    for (int i = 0; i < 2; ++i) a[0][i] = pa[i * 32];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = As[(kk + kh) * PADA + wm + i * 32 + l32];
+    for (int j = 0; j < 2; ++j) b[0][j] = pb[j * 32];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) b[j] = Bs[(kk + kh) * PADB + wn + j * 32 + l32];
+    for (int s = 0; s < BK / 2; ++s) {
+        const int cur = s & 1, nxt = cur ^ 1;
+        if (s + 1 < BK / 2) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[nxt][i] = pa[(2 * s + 2) * PADA + i * 32];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[nxt][j] = pb[(2 * s + 2) * PADB + j * 32];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the reads above ahead of the MFMAs below
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][i], b[cur][j], acc[i][j], 0, 0, 0);
     }
 }
 

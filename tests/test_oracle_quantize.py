@@ -84,6 +84,10 @@ def test_gather_index_and_offset(oracle):
     e = oracle.quantize_1bit(np.ascontiguousarray(x[30:]), 70, 10, 77, 4)
     for u, v in zip(c, e):
         assert np.array_equal(u, v)
+    # a window of an exchange recomputed on its own gives the same rows
+    h = oracle.quantize_1bit(np.ascontiguousarray(x[idx[7:19]]), 70, 12, 77, 4, wire_row0=7)
+    for u, v in zip(a, h):
+        assert np.array_equal(u[7:19], v)
     # leading dimension larger than d: only the first d columns are read
     f = oracle.quantize_1bit(x, 33, 40, 77, 4)
     g = oracle.quantize_1bit(np.ascontiguousarray(x[:, :33]), 33, 40, 77, 4)
