@@ -81,6 +81,27 @@ class OpTimer:
                     "gather_bytes": info["nnz_dense"] * (4 * d + 8)
                     + (info["nnz"] - info["nnz_dense"]) * (W(d) + 16) + n_rows * (4 * d + 8)}
 
+        def range_info(rp, row_begin, n_rows):
+            return self.op_info[(rp.data_ptr(), int(row_begin), int(n_rows))]
+
+        def agq_cost(rp, cl, w, rs, cs, row_begin, n_rows, dY, ld, d, seed, sid, wire, **kw):
+            info = range_info(rp, row_begin, n_rows)
+            b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched"] * 4 * d \
+                + n_rows * (8 + W(d) + 8)
+            return {"bytes": b, "edges": info["nnz"], "rows": n_rows,
+                    "gather_bytes": info["nnz"] * (4 * d + 8) + n_rows * (8 + W(d) + 8)}
+
+        def agi_cost(rp, cl, w, rs, cs, row_begin, n_rows, dY, ld, d, dX, ldx, addend, lda, arows,
+                     wire, n_wire, sp, sr, **kw):
+            info = range_info(rp, row_begin, n_rows)
+            b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched"] * 4 * d \
+                + n_rows * (4 * d + 8 + 8) + n_wire * (W(d) + 8 + 4)
+            if addend is not None:
+                b += arows * 4 * d
+            return {"bytes": b, "edges": info["nnz"], "rows": n_wire,
+                    "gather_bytes": info["nnz"] * (4 * d + 8) + n_rows * (4 * d + 16)
+                    + n_wire * (W(d) + 12)}
+
         def tf_cost(A1, ld1, k1, A2, ld2, k2, Wm, h, n, relu, H, ldh):
             return {"flops": 2 * n * (k1 + k2) * h, "bytes": 4 * n * (k1 + k2 + h)}
 
@@ -95,6 +116,8 @@ class OpTimer:
         self._wrap("sylvie_aggregate_csr_fwd", ag_cost)
         self._wrap("sylvie_aggregate_csr_bwd", ag_cost)
         self._wrap("sylvie_aggregate_csr_fwd_wire", agw_cost)
+        self._wrap("sylvie_aggregate_csr_bwd_quantize", agq_cost)
+        self._wrap("sylvie_aggregate_csr_bwd_integrate", agi_cost)
         self._wrap("sylvie_transform_fwd", tf_cost)
         self._wrap("sylvie_transform_bwd", tb_cost)
 
@@ -271,6 +294,14 @@ def main():
             op_info[op[0].data_ptr()] = {"nnz": int(op[0][-1]), "touched": int(uq.numel()),
                                          "touched_dense": nd, "touched_wire": int(uq.numel()) - nd,
                                          "nnz_dense": int((op[1] < st.n_in).sum())}
+    if loop.fused_bwd:
+        for st in loop.parts:
+            rpT, clT = st.opT[0], st.opT[1]
+            ranges = [(0, st.n_in)] + [(st.n_in + b.j0, b.j1 - b.j0) for b in st.blocks]
+            for r0, n in ranges:
+                e0, e1 = int(rpT[r0]), int(rpT[r0 + n])
+                op_info[(rpT.data_ptr(), r0, n)] = {
+                    "nnz": e1 - e0, "touched": int(torch.unique(clT[e0:e1]).numel())}
     seed = 20230301
     for i in range(args.warmup):
         loop.forward(seed + i)
@@ -293,7 +324,9 @@ def main():
 
     edges_per_step = sum(o["edges"] for o in ops.values())
     value = edges_per_step / (ms_per_step * 1e-3)
-    q = [ops[k] for k in ops if "quantize" in k]            # quantize + dequantize, both directions
+    # stand-alone quantize / dequantize kernels (the epilogue-fused ones are booked with
+    # the aggregation they live in)
+    q = [ops[k] for k in ops if k.startswith(("sylvie_quantize", "sylvie_dequantize"))]
     qd_bytes = sum(o["bytes"] for o in q)
     qd_ms = sum(o["ms_per_step"] for o in q)
     ag = [ops[k] for k in ops if "aggregate" in k]

@@ -190,6 +190,51 @@ int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_t *colT, co
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * Neighbour aggregation, backward, halo block, quantized on the spot (Alg. 2 "compute
+ * feature gradients" restricted to the rows that are sent, fused with "quantize"):
+ * the same wire as sylvie_aggregate_csr_bwd into a float block followed by
+ * sylvie_quantize_1bit_bwd of that block (idx = NULL), bit for bit, but the float
+ * rows never reach memory.  Rows row_begin .. row_begin + n_rows - 1 of the
+ * transposed operator are computed; wire row i is row row_begin + i and takes the
+ * random draws of wire row i.  rowptrT is indexed by the absolute row; long_rows
+ * holds absolute rows inside the range.  d <= 2048.
+ *   wire_out uint64 [n_rows][ceil(d/64) + 1]
+ */
+int32_t sylvie_aggregate_csr_bwd_quantize(const int64_t *rowptrT, const int32_t *colT,
+                                          const float *wT, const float *row_scale,
+                                          const float *col_scale, int64_t row_begin,
+                                          int64_t n_rows, const float *dY, int64_t ld_dy,
+                                          int32_t d, uint64_t seed, uint32_t stream_id,
+                                          uint64_t *wire_out, int32_t chunk,
+                                          const int32_t *long_rows, const int64_t *long_ptr,
+                                          int64_t n_long, int64_t n_tasks, float *workspace,
+                                          size_t workspace_bytes, void *stream);
+
+/*
+ * Neighbour aggregation, backward, inner block, with the received gradients added
+ * (Alg. 2 "compute feature gradients" fused with "dequantize" and "integrate"):
+ *     dX[v] = (A^T dY)[v] (+ addend[v]) , then for j in [seg_ptr[v - row_begin],
+ *     seg_ptr[v - row_begin + 1]):  dX[v] = fl(dX[v] + deq(wire row seg_rows[j]))
+ * for rows v = row_begin .. row_begin + n_rows - 1: the same values as
+ * sylvie_aggregate_csr_bwd followed by sylvie_dequantize_1bit_bwd, bit for bit, with
+ * one store per row.
+ *   seg_ptr  int64 [n_rows + 1] (every row has an entry; empty segments allowed)
+ *   seg_rows int32 [seg_ptr[n_rows]] wire rows, ascending inside a segment
+ */
+int32_t sylvie_aggregate_csr_bwd_integrate(const int64_t *rowptrT, const int32_t *colT,
+                                           const float *wT, const float *row_scale,
+                                           const float *col_scale, int64_t row_begin,
+                                           int64_t n_rows, const float *dY, int64_t ld_dy,
+                                           int32_t d, float *dX, int64_t ld_dx,
+                                           const float *addend, int64_t ld_addend,
+                                           int64_t addend_rows, const uint64_t *wire,
+                                           int64_t n_wire, const int64_t *seg_ptr,
+                                           const int32_t *seg_rows, int32_t chunk,
+                                           const int32_t *long_rows, const int64_t *long_ptr,
+                                           int64_t n_long, int64_t n_tasks, float *workspace,
+                                           size_t workspace_bytes, void *stream);
+
+/*
  * Dense transform, forward (Eq. 2; Alg. 1 "update embeddings", H = sigma(Z W)):
  *     P = [A1 | A2] * W,   H = relu ? max(P, 0) : P
  * A1 is n x k1 (ld_a1), A2 is n x k2 (ld_a2) or NULL with k2 = 0 (GraphSAGE puts a

@@ -42,7 +42,8 @@ def lib():
         for name in ("sylvie_quantize_1bit_fwd", "sylvie_quantize_1bit_bwd",
                      "sylvie_dequantize_1bit_fwd", "sylvie_dequantize_1bit_bwd",
                      "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
-                     "sylvie_aggregate_csr_fwd_wire",
+                     "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
+                     "sylvie_aggregate_csr_bwd_integrate",
                      "sylvie_transform_fwd", "sylvie_transform_bwd"):
             getattr(L, name).restype = C.c_int32
         _lib = L
@@ -154,6 +155,41 @@ def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, d
     _aggregate(lib().sylvie_aggregate_csr_bwd, rowptrT, colT, wT, row_scale, col_scale, n_rowsT,
                dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows, chunk, long_rows,
                long_ptr, n_long, n_tasks, workspace)
+
+
+def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
+                                      ld_dy, d, seed, stream_id, wire_out, chunk=0, long_rows=None,
+                                      long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_aggregate_csr_bwd_quantize(
+        _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
+        _ptr(wT, torch.float32, "wT"), _ptr(row_scale, torch.float32, "row_scale"),
+        _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
+        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
+        C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
+        _ptr(wire_out, torch.int64, "wire_out"), C.c_int32(chunk),
+        _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+        C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
+        C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows,
+                                       dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows,
+                                       wire, n_wire, seg_ptr, seg_rows, chunk=0, long_rows=None,
+                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_aggregate_csr_bwd_integrate(
+        _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
+        _ptr(wT, torch.float32, "wT"), _ptr(row_scale, torch.float32, "row_scale"),
+        _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
+        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
+        _ptr(dX, torch.float32, "dX"), C.c_int64(ld_dx), _ptr(addend, torch.float32, "addend"),
+        C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(wire, torch.int64, "wire"),
+        C.c_int64(n_wire), _ptr(seg_ptr, torch.int64, "seg_ptr"),
+        _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int32(chunk),
+        _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+        C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
+        C.c_size_t(ws_bytes), _stream()))
 
 
 def sylvie_transform_fwd(A1, ld_a1, k1, A2, ld_a2, k2, W, h, n, relu, H, ld_h):

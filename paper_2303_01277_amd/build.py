@@ -19,7 +19,7 @@ _SOURCES = {
     "api.hip": [],
     "quantize.hip": ["-ffp-contract=off", "-fno-honor-nans"],
     "dequantize.hip": ["-ffp-contract=off"],
-    "aggregate.hip": [],
+    "aggregate.hip": ["-ffp-contract=off"],
     "transform.hip": [],
 }
 

@@ -20,7 +20,14 @@
 //     ordinary rows and go first.  Partial sums are written to a workspace and
 //     added in task order by a second tiny kernel, so results do not depend on
 //     scheduling.
+//   * What happens to a finished row is a template choice: store it; or, for the
+//     halo block of the backward pass, quantize it on the spot (the row goes
+//     through LDS once to change from "lane = 4 adjacent columns" to "lane =
+//     columns 64 apart", the layout in which a wave-wide compare is a packed word)
+//     and write only the wire row; or, for the inner block, add the dequantized
+//     wire rows that belong to it (Alg. 2 "integrate") before the one store.
 #include "common.hpp"
+#include "rounding.hpp"
 
 namespace sylvie {
 
@@ -72,7 +79,36 @@ struct AggArgs {
     // optional packed tail of X: columns >= n_dense are rows of a 1-bit wire
     int64_t n_dense;
     const uint32_t *wire32;     // wire rows (W bit words + 1 metadata word) seen as dwords
+    // rows handled by this launch are row_begin .. row_begin + n_rows - 1 (absolute
+    // indices into rowptr / Y / addend / row_scale)
+    int64_t row_begin;
+    // epilogue "quantize": wire row (v - row_begin) <- quantized row v
+    uint64_t *wire_out;
+    uint32_t ckey;
+    // epilogue "integrate": row v += dequantized wire rows seg_rows[seg_ptr[v - row_begin] ..)
+    const int64_t *seg_ptr;
+    const int32_t *seg_rows;
 };
+
+enum : int { kEpiStore = 0, kEpiQuantize = 1, kEpiIntegrate = 2 };
+
+// o[0..VEC) += the dequantized elements cc .. cc+VEC-1 of the wire rows of segment s,
+// in order (single-precision adds, Alg. 2 "integrate feature gradients")
+template <int VEC>
+__device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int cc, float (&o)[VEC])
+{
+    const int W32 = ((a.d + 63) >> 6) * 2;
+    const int64_t j0 = a.seg_ptr[s], j1 = a.seg_ptr[s + 1];
+    for (int64_t j = j0; j < j1; ++j) {
+        const uint32_t *pr = a.wire32 + static_cast<int64_t>(a.seg_rows[j]) * (W32 + 2);
+        const uint2 meta = *reinterpret_cast<const uint2 *>(pr + W32);
+        const float zp = __uint_as_float(meta.y);
+        const float hi = zp + __uint_as_float(meta.x);
+        const uint32_t bits = pr[cc >> 5] >> (cc & 31);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) o[t] = o[t] + (((bits >> t) & 1u) ? hi : zp);
+    }
+}
 
 // acc[p][t] += sum over entries [e0, e1) of w_e * cs[col_e] * X[col_e][column(p, t)]
 //
@@ -243,10 +279,12 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
 // take the pieces of the long rows (they start first, so the heaviest rows never
 // trail the launch); every later wavefront takes one ordinary row and skips the
 // long ones.  Pieces write partial sums to workspace[task][0..d).
-template <int VEC, int G, int P, bool WIRE>
+template <int VEC, int G, int P, bool WIRE, int EPI>
 __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kernel(AggArgs a,
                                                                                     int64_t n_tasks)
 {
+    constexpr int kStage = EPI == kEpiQuantize ? VEC * G * P : 1;
+    __shared__ float stage[kAgWavesPerBlock][kStage];
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t task_blocks = (n_tasks + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
@@ -282,45 +320,61 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         return;
     }
 
-    const int64_t v = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
-    if (v >= a.n_rows) return;
+    const int64_t local = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
+    if (local >= a.n_rows) return;
+    const int64_t v = a.row_begin + local;
     const int64_t e0 = uniform(a.rowptr[v]);
     const int64_t e1 = uniform(a.rowptr[v + 1]);
     if (a.chunk > 0 && e1 - e0 > a.chunk) return;
     gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane);
-    if (lane >= G) return;
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
+    if (lane < G) {
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        const int cc = (p * G + lane) * VEC;
-        if (cc < a.d) {
-            float o[VEC];
+        for (int p = 0; p < P; ++p) {
+            const int cc = (p * G + lane) * VEC;
+            if (cc < a.d) {
+                float o[VEC];
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) o[t] = rs * acc[p][t];
-            if (add) {
-                float ad[VEC];
-                load_vec<VEC>(ad, a.addend + v * a.ld_addend + cc);
+                for (int t = 0; t < VEC; ++t) o[t] = rs * acc[p][t];
+                if (add) {
+                    float ad[VEC];
+                    load_vec<VEC>(ad, a.addend + v * a.ld_addend + cc);
 #pragma unroll
-                for (int t = 0; t < VEC; ++t) o[t] += ad[t];
+                    for (int t = 0; t < VEC; ++t) o[t] += ad[t];
+                }
+                if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC>(a, local, cc, o);
+                if constexpr (EPI == kEpiQuantize) {
+#pragma unroll
+                    for (int t = 0; t < VEC; ++t) stage[wave][cc + t] = o[t];
+                } else {
+                    store_vec<VEC>(a.Y + v * a.ld_y + cc, o);
+                }
             }
-            store_vec<VEC>(a.Y + v * a.ld_y + cc, o);
         }
+    }
+    if constexpr (EPI == kEpiQuantize) {
+        const int W1 = ((a.d + 63) >> 6) + 1;
+        quantize_row_lds(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
+                         a.wire_out + local * W1, lane);
     }
 }
 
-// One wavefront per long row: add its partial sums in task order, scale, store.
-template <int VEC>
+// One wavefront per long row: add its partial sums in task order, scale, finish.
+template <int VEC, int EPI>
 __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kernel(AggArgs a)
 {
+    extern __shared__ float rstage[];      // EPI quantize: kAgWavesPerBlock rows of d floats
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
     if (i >= a.n_long) return;
     const int64_t v = a.long_rows[i];
+    const int64_t local = v - a.row_begin;
     const int64_t t0 = a.long_ptr[i], t1 = a.long_ptr[i + 1];
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
+    float *srow = rstage + wave * a.d;
     for (int cc = lane * VEC; cc < a.d; cc += 64 * VEC) {
         float acc[VEC];
 #pragma unroll
@@ -339,45 +393,75 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[q] += ad[q];
         }
-        store_vec<VEC>(a.Y + v * a.ld_y + cc, acc);
+        if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC>(a, local, cc, acc);
+        if constexpr (EPI == kEpiQuantize) {
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) srow[cc + q] = acc[q];
+        } else {
+            store_vec<VEC>(a.Y + v * a.ld_y + cc, acc);
+        }
+    }
+    if constexpr (EPI == kEpiQuantize) {
+        const int W1 = ((a.d + 63) >> 6) + 1;
+        quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local), a.wire_out + local * W1,
+                         lane);
+    }
+}
+
+template <int VEC, int G, int P, bool WIRE, int EPI>
+static void launch_kernels(const AggArgs &a, int64_t nt, hipStream_t st)
+{
+    const dim3 block(kAgWavesPerBlock * kWave);
+    const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
+                           (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
+    hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, WIRE, EPI>),
+                       dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
+    if (a.n_long > 0) {
+        const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
+        const size_t lds = EPI == kEpiQuantize ? sizeof(float) * kAgWavesPerBlock * a.d : 0;
+        hipLaunchKernelGGL((aggregate_reduce_kernel<VEC, EPI>), rg, block, lds, st, a);
     }
 }
 
 template <int VEC, int G, int P>
-static void launch_shape(const AggArgs &a, int64_t n_tasks, hipStream_t st)
+static void launch_shape(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t st)
 {
-    const dim3 block(kAgWavesPerBlock * kWave);
     const int64_t nt = a.n_long > 0 ? n_tasks : 0;
-    const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
-                           (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
-    if (a.wire32)
-        hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, true>),
-                           dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
-    else
-        hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, false>),
-                           dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
-    if (a.n_long > 0) {
-        const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
-        hipLaunchKernelGGL((aggregate_reduce_kernel<VEC>), rg, block, 0, st, a);
-    }
+    if (epi == kEpiQuantize) launch_kernels<VEC, G, P, false, kEpiQuantize>(a, nt, st);
+    else if (epi == kEpiIntegrate) launch_kernels<VEC, G, P, false, kEpiIntegrate>(a, nt, st);
+    else if (a.wire32) launch_kernels<VEC, G, P, true, kEpiStore>(a, nt, st);
+    else launch_kernels<VEC, G, P, false, kEpiStore>(a, nt, st);
 }
 
 template <int VEC>
-static bool launch_vec(const AggArgs &a, int64_t n_tasks, hipStream_t st)
+static bool launch_vec(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t st)
 {
     const int lanes = (a.d + VEC - 1) / VEC;   // lanes needed for one row, one pass
-    if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, st);
-    else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, st);
-    else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, st);
-    else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, st);
-    else if (lanes <= 192) launch_shape<VEC, 64, 3>(a, n_tasks, st);
-    else if (lanes <= 256) launch_shape<VEC, 64, 4>(a, n_tasks, st);
-    else if (lanes <= 320) launch_shape<VEC, 64, 5>(a, n_tasks, st);
-    else if (lanes <= 384) launch_shape<VEC, 64, 6>(a, n_tasks, st);
-    else if (lanes <= 512) launch_shape<VEC, 64, 8>(a, n_tasks, st);
+    if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, epi, st);
+    else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, epi, st);
+    else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, st);
+    else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, epi, st);
+    else if (lanes <= 192) launch_shape<VEC, 64, 3>(a, n_tasks, epi, st);
+    else if (lanes <= 256) launch_shape<VEC, 64, 4>(a, n_tasks, epi, st);
+    else if (lanes <= 320) launch_shape<VEC, 64, 5>(a, n_tasks, epi, st);
+    else if (lanes <= 384) launch_shape<VEC, 64, 6>(a, n_tasks, epi, st);
+    else if (lanes <= 512) launch_shape<VEC, 64, 8>(a, n_tasks, epi, st);
     else return false;
     return true;
 }
+
+// Everything an aggregation call may carry beyond the plain operands.
+struct AggExtra {
+    int64_t n_dense = 0;            // forward: columns >= n_dense are wire rows
+    const uint64_t *wire = nullptr; // forward: wire to read; integrate: wire to add
+    int64_t n_wire = 0;
+    int64_t row_begin = 0;
+    int epi = kEpiStore;
+    uint64_t *wire_out = nullptr;   // quantize epilogue
+    uint32_t ckey = 0;
+    const int64_t *seg_ptr = nullptr;
+    const int32_t *seg_rows = nullptr;
+};
 
 static int32_t aggregate_common(const char *name, const int64_t *rowptr, const int32_t *col,
                                 const float *w, const float *row_scale, const float *col_scale,
@@ -386,9 +470,10 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
                                 int64_t addend_rows, int32_t chunk, const int32_t *long_rows,
                                 const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
                                 float *workspace, size_t workspace_bytes, void *stream,
-                                int64_t n_dense = 0, const uint64_t *wire = nullptr,
-                                int64_t n_wire = 0)
+                                const AggExtra &x = AggExtra())
 {
+    const int64_t n_dense = x.n_dense, n_wire = x.n_wire;
+    const uint64_t *wire = x.wire;
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
@@ -401,7 +486,15 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     if (n_wire > 0 && !aligned(wire, 8))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
     if (n_rows == 0) return SYLVIE_OK;
-    if (!rowptr || !col || !X || !Y) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (x.row_begin < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_begin", name);
+    if (x.epi == kEpiQuantize && (!x.wire_out || !aligned(x.wire_out, 8)))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: wire_out null or misaligned", name);
+    if (x.epi == kEpiIntegrate && (!x.seg_ptr || (n_wire > 0 && !x.seg_rows)))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: segment table has null pointers", name);
+    if (x.epi == kEpiQuantize && d > 2048)
+        return fail(SYLVIE_ERR_UNIMPLEMENTED, "%s: fused quantize supports d <= 2048", name);
+    if (!rowptr || !col || !X || (!Y && x.epi != kEpiQuantize))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
     if (!aligned(rowptr, 8) || !aligned(col, 4) || !aligned(X, 4) || !aligned(Y, 4) ||
         (w && !aligned(w, 4)))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned pointer", name);
@@ -426,16 +519,22 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.long_rows = long_rows; a.long_ptr = long_ptr; a.n_long = n_long; a.workspace = workspace;
     a.n_dense = n_dense;
     a.wire32 = n_wire > 0 ? reinterpret_cast<const uint32_t *>(wire) : nullptr;
+    a.row_begin = x.row_begin;
+    a.wire_out = x.wire_out;
+    a.ckey = x.ckey;
+    a.seg_ptr = x.seg_ptr;
+    a.seg_rows = x.seg_rows;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (x.epi == kEpiQuantize) { Y = const_cast<float *>(X); ld_y = ld_x; }   // Y is unused
     const bool a16 = aligned(X, 16) && aligned(Y, 16) && ld_x % 4 == 0 && ld_y % 4 == 0 &&
                      d % 4 == 0 && (!addend || (aligned(addend, 16) && ld_addend % 4 == 0));
     const bool a8 = aligned(X, 8) && aligned(Y, 8) && ld_x % 2 == 0 && ld_y % 2 == 0 &&
                     d % 2 == 0 && (!addend || (aligned(addend, 8) && ld_addend % 2 == 0));
     bool ok;
-    if (a16) ok = launch_vec<4>(a, n_tasks, st);
-    else if (a8) ok = launch_vec<2>(a, n_tasks, st);
-    else ok = launch_vec<1>(a, n_tasks, st);
+    if (a16) ok = launch_vec<4>(a, n_tasks, x.epi, st);
+    else if (a8) ok = launch_vec<2>(a, n_tasks, x.epi, st);
+    else ok = launch_vec<1>(a, n_tasks, x.epi, st);
     if (!ok)
         return fail(SYLVIE_ERR_UNIMPLEMENTED,
                     "%s: d = %d is wider than one launch covers at this alignment "
@@ -485,8 +584,51 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
     int64_t n_dense, const uint64_t *wire, int64_t n_wire, float *Y, int64_t ld_y, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
     int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
 {
+    sylvie::AggExtra x;
+    x.n_dense = n_dense;
+    x.wire = wire;
+    x.n_wire = n_wire;
     return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
                                     col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
                                     long_rows, long_ptr, n_long, n_tasks, workspace,
-                                    workspace_bytes, stream, n_dense, wire, n_wire);
+                                    workspace_bytes, stream, x);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
+    const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
+    const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
+    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int32_t chunk,
+    const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+    float *workspace, size_t workspace_bytes, void *stream)
+{
+    sylvie::AggExtra x;
+    x.row_begin = row_begin;
+    x.epi = sylvie::kEpiQuantize;
+    x.wire_out = wire_out;
+    x.ckey = sylvie::call_key(seed, stream_id);
+    return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_quantize", rowptrT, colT, wT,
+                                    row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr, ld_dy,
+                                    nullptr, 0, 0, chunk, long_rows, long_ptr, n_long, n_tasks,
+                                    workspace, workspace_bytes, stream, x);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
+    const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
+    const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
+    int32_t d, float *dX, int64_t ld_dx, const float *addend, int64_t ld_addend,
+    int64_t addend_rows, const uint64_t *wire, int64_t n_wire, const int64_t *seg_ptr,
+    const int32_t *seg_rows, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+{
+    sylvie::AggExtra x;
+    x.row_begin = row_begin;
+    x.epi = sylvie::kEpiIntegrate;
+    x.wire = wire;
+    x.n_wire = n_wire;
+    x.seg_ptr = seg_ptr;
+    x.seg_rows = seg_rows;
+    return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_integrate", rowptrT, colT, wT,
+                                    row_scale, col_scale, n_rows, dY, ld_dy, d, dX, ld_dx, addend,
+                                    ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long,
+                                    n_tasks, workspace, workspace_bytes, stream, x);
 }

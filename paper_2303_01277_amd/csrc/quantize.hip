@@ -9,49 +9,12 @@
 #include <utility>
 
 #include "common.hpp"
+#include "rounding.hpp"
 
 namespace sylvie {
 
-// Counter hash behind the rounding draws.  Keys: (seed, stream) -> call key on
-// the host; (call key, wire row) -> row key, scalar unit; (row key, column) ->
-// 24 uniform bits per element.
-constexpr uint32_t kM1 = 0xce6e1acdu;
-constexpr uint32_t kM2 = 0x6d3cb3a7u;
-constexpr uint32_t kColStride = 0x9e3779b9u;
-constexpr uint32_t kDomain = 0x53594c56u;
-
-__host__ __device__ __forceinline__ uint32_t mix32(uint32_t x)
-{
-    x ^= x >> 16;
-    x *= kM1;
-    x ^= x >> 15;
-    x *= kM2;
-    x ^= x >> 16;
-    return x;
-}
-
-static uint32_t call_key(uint64_t seed, uint32_t stream_id)
-{
-    uint32_t k = mix32(static_cast<uint32_t>(seed) ^ kDomain);
-    k = mix32(k ^ static_cast<uint32_t>(seed >> 32));
-    return mix32(k ^ stream_id);
-}
-
-// Top 24 bits of the second product: the draw for one element.  Both xor-shifts
-// are by 16 so that each is a single VALU op (the shifted operand is a sub-dword
-// select of the same register).
-__device__ __forceinline__ uint32_t draw24(uint32_t x)
-{
-    x ^= x >> 16;
-    x *= kM1;
-    x ^= x >> 16;
-    x *= kM2;
-    return x >> 8;
-}
-
 constexpr int kWavesPerBlock = 4;
 
-// dst[lane LANE] = value (wave-uniform, taken from a scalar register); other lanes keep theirs.
 // lo[LANE] = low half, hi[LANE] = high half of a wave-uniform 64-bit value held in
 // scalar registers; other lanes keep theirs.  The lane select has to be an inline
 // constant (data and select may not both be scalar registers).  The value is

@@ -14,6 +14,8 @@
 namespace sylvie {
 
 constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int NI = BK / 8;        // 4-element fetches per thread per operand tile
+constexpr int KCT = BK / 4;       // threads that share one row of a k-contiguous tile
 constexpr int kPadXC = 128;      // row stride of a tile filled along x (16-byte rows)
 constexpr int kPadKC = 130;      // row stride of a tile filled along k (spreads banks)
 constexpr int kGemmThreads = 256;
@@ -88,7 +90,8 @@ __device__ __forceinline__ void masked4(float (&o)[4], const MaskedJ &m, int64_t
 
 // ---- LDS tile fill patterns ----------------------------------------------------
 // XC: the 4 fetched elements run along x (tile columns): thread -> (k = t/32 + 8 i, x = 4 (t%32))
-// KC: the 4 fetched elements run along k (tile rows):    thread -> (x = t/4 + 64 i, k = 4 (t%4))
+// KC: the 4 fetched elements run along k (tile rows):    thread -> (x = t/KCT + (256/KCT) i,
+//                                                                   k = 4 (t%KCT)),  i < NI
 
 __device__ __forceinline__ void put_xc(float *T, int i, const float (&v)[4])
 {
@@ -99,7 +102,7 @@ __device__ __forceinline__ void put_xc(float *T, int i, const float (&v)[4])
 __device__ __forceinline__ void put_kc(float *T, int i, const float (&v)[4])
 {
     const int t = threadIdx.x;
-    float *p = T + (4 * (t % 4)) * kPadKC + (t / 4 + 64 * i);
+    float *p = T + (4 * (t % KCT)) * kPadKC + (t / KCT + (256 / KCT) * i);
 #pragma unroll
     for (int q = 0; q < 4; ++q) p[q * kPadKC] = v[q];
 }
@@ -163,11 +166,11 @@ __global__ __launch_bounds__(kGemmThreads) void transform_fwd_kernel(CatA a, con
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    float ra[2][4], rb[2][4];
+    float ra[NI][4], rb[NI][4];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            cat_row4<V>(ra[i], a, m0 + t / 4 + 64 * i, k0 + 4 * (t % 4));
+        for (int i = 0; i < NI; ++i) {
+            cat_row4<V>(ra[i], a, m0 + t / KCT + (256 / KCT) * i, k0 + 4 * (t % KCT));
             const int k = k0 + t / 32 + 8 * i, x = n0 + 4 * (t % 32);
             const int valid = (k < K && x < h) ? (h - x < 4 ? h - x : 4) : 0;
             fetch4<V>(rb[i], Wm + static_cast<int64_t>(k) * h + x, valid);
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(kGemmThreads) void transform_fwd_kernel(CatA a, con
     for (int k0 = 0; k0 < K; k0 += BK) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             put_kc(As, i, ra[i]);
             put_xc(Bs, i, rb[i]);
         }
@@ -224,13 +227,13 @@ __global__ __launch_bounds__(kGemmThreads) void transform_bwd_da_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    float ra[2][4], rb[2][4];
+    float ra[NI][4], rb[NI][4];
     auto fetch = [&](int j0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            masked4<V>(ra[i], m, m0 + t / 4 + 64 * i, j0 + 4 * (t % 4));
+        for (int i = 0; i < NI; ++i) {
+            masked4<V>(ra[i], m, m0 + t / KCT + (256 / KCT) * i, j0 + 4 * (t % KCT));
             // B(k = j, n = kcol) = W[kcol][j]: contiguous along k
-            const int kcol = n0 + t / 4 + 64 * i, j = j0 + 4 * (t % 4);
+            const int kcol = n0 + t / KCT + (256 / KCT) * i, j = j0 + 4 * (t % KCT);
             const int valid = (kcol < K && j < h) ? (h - j < 4 ? h - j : 4) : 0;
             fetch4<V>(rb[i], Wm + static_cast<int64_t>(kcol) * h + j, valid);
         }
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(kGemmThreads) void transform_bwd_da_kernel(
     for (int j0 = 0; j0 < h; j0 += BK) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             put_kc(As, i, ra[i]);
             put_kc(Bs, i, rb[i]);
         }
@@ -288,10 +291,10 @@ __global__ __launch_bounds__(kGemmThreads) void transform_bwd_g_kernel(CatA a, M
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    float ra[2][4], rb[2][4];
+    float ra[NI][4], rb[NI][4];
     auto fetch = [&](int64_t r0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int64_t row = r0 + t / 32 + 8 * i;
             // A(m = kcol, k = row) = [A1|A2][row][kcol]: contiguous along m
             cat_row4<V>(ra[i], a, row < r_end ? row : a.n, m0 + 4 * (t % 32));
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(kGemmThreads) void transform_bwd_g_kernel(CatA a, M
     for (int64_t r0 = r_begin; r0 < r_end; r0 += BK) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             put_xc(As, i, ra[i]);
             put_xc(Bs, i, rb[i]);
         }

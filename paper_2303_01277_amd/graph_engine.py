@@ -57,13 +57,17 @@ def transpose_csr(rowptr, col, w, n_cols):
     return rowptrT, rows[order].to(torch.int32), w[order].contiguous()
 
 
-def long_row_plan(rowptr, chunk):
-    """Rows longer than `chunk` entries and the prefix sum of their task counts.
+def long_row_plan(rowptr, chunk, row_begin=0, row_end=None):
+    """Rows longer than `chunk` entries (absolute indices, optionally only those in
+    [row_begin, row_end)) and the prefix sum of their task counts.
     Returns (long_rows int32 [n_long], long_ptr int64 [n_long + 1], n_tasks)."""
     if chunk <= 0 or chunk % 64:
         raise ValueError("chunk must be a positive multiple of 64")
     counts = rowptr[1:] - rowptr[:-1]
     long_rows = torch.nonzero(counts > chunk).flatten()
+    if row_end is not None or row_begin:
+        hi = counts.numel() if row_end is None else row_end
+        long_rows = long_rows[(long_rows >= row_begin) & (long_rows < hi)]
     tasks = (counts[long_rows] + chunk - 1) // chunk
     long_ptr = torch.zeros(long_rows.numel() + 1, dtype=torch.int64, device=rowptr.device)
     long_ptr[1:] = torch.cumsum(tasks, 0)
@@ -83,3 +87,13 @@ def scatter_segments(dst_row):
     seg_ptr = torch.zeros(dst_ids.numel() + 1, dtype=torch.int64, device=dst_row.device)
     seg_ptr[1:] = torch.cumsum(counts, 0)
     return seg_ptr, order.to(torch.int32), dst_ids.to(torch.int32)
+
+
+def scatter_segments_dense(dst_row, n_dst):
+    """Like scatter_segments, but with one (possibly empty) segment for every
+    destination row 0 .. n_dst - 1: returns (seg_ptr int64 [n_dst + 1], seg_rows int32 [n])."""
+    d64 = dst_row.to(torch.int64)
+    order = torch.sort(d64, stable=True).indices
+    seg_ptr = torch.zeros(n_dst + 1, dtype=torch.int64, device=dst_row.device)
+    seg_ptr[1:] = torch.cumsum(torch.bincount(d64, minlength=n_dst), 0)
+    return seg_ptr, order.to(torch.int32)

@@ -30,6 +30,8 @@ class Block:
     seg_ptr: torch.Tensor
     seg_rows: torch.Tensor
     dst_ids: torch.Tensor
+    planT: tuple = None         # long-row plan of the transposed operator on these halo rows
+    inb_off: int = 0            # first row of this block in the owner's inbound wire
 
 
 @dataclass
@@ -54,6 +56,12 @@ class PartState:
     ws_aggT: Optional[torch.Tensor] = None
     ws_g: Optional[torch.Tensor] = None
     wire: Optional[torch.Tensor] = None                       # int64 words, n_halo wire rows
+    # fused backward: gradients arriving from every sender, concatenated (sender ascending)
+    inbound: Optional[torch.Tensor] = None                    # int64 words, n_inbound wire rows
+    n_inbound: int = 0
+    inb_seg_ptr: Optional[torch.Tensor] = None                # int64 [n_in + 1]
+    inb_seg_rows: Optional[torch.Tensor] = None               # int32 [n_inbound]
+    planT_inner: tuple = None
 
 
 class LayerLoop:
@@ -61,7 +69,8 @@ class LayerLoop:
     (mean aggregator, H = sigma([H_self | mean] W)).  ReLU on all layers but the last."""
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
-                 exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True):
+                 exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True,
+                 fused_bwd: bool = True):
         """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
         partition int32 tensors naming the owner partition and owner-local inner row of
         each halo row (grouped by owner, ascending)."""
@@ -73,6 +82,10 @@ class LayerLoop:
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)
         self.fused = fused and wire == "1bit"
+        # fused_bwd: the transposed aggregation quantizes the halo gradients on the spot
+        # and adds the received ones in its epilogue (no float halo-gradient block, no
+        # separate quantize / dequantize passes)
+        self.fused_bwd = fused_bwd and wire == "1bit"
         self.record = None          # set to a dict to keep copies of every wire
         dev = X[0].device
         self.dev = dev
@@ -116,11 +129,29 @@ class LayerLoop:
             st.dHtil = [None] * self.L
             lo = 0 if exchange_first_layer else 1
             for l in range(lo, self.L):
-                st.dHtil[l] = torch.empty(n_loc, dims[l], dtype=torch.float32, device=dev)
+                rows = part.n_in if self.fused_bwd else n_loc
+                st.dHtil[l] = torch.empty(rows, dims[l], dtype=torch.float32, device=dev)
             st.dZ = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
             if model == "sage":
                 st.dself = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
             self.parts.append(st)
+        if self.fused_bwd:
+            Wd = B.sylvie_wire_row_words(dmax)
+            for q, sq in enumerate(self.parts):
+                dst = []
+                for p, sp_ in enumerate(self.parts):
+                    for b in sp_.blocks:
+                        if b.owner != q:
+                            continue
+                        b.inb_off = sq.n_inbound
+                        b.planT = GE.long_row_plan(sp_.opT[0], chunk, sp_.n_in + b.j0,
+                                                   sp_.n_in + b.j1)
+                        sq.n_inbound += b.j1 - b.j0
+                        dst.append(b.rows)
+                dst = torch.cat(dst) if dst else torch.zeros(0, dtype=torch.int32, device=dev)
+                sq.inb_seg_ptr, sq.inb_seg_rows = GE.scatter_segments_dense(dst, sq.n_in)
+                sq.inbound = torch.empty(max(1, sq.n_inbound) * Wd, dtype=torch.int64, device=dev)
+                sq.planT_inner = GE.long_row_plan(sq.opT[0], chunk, 0, sq.n_in)
 
     # -- helpers ---------------------------------------------------------------
     def _keep(self, key, wire, n, W):
@@ -205,12 +236,15 @@ class LayerLoop:
                                            st.n_in, relu, Hout, Hout.stride(0), Jl, Jl.stride(0),
                                            st.G[l], dself if need_dx else None, d,
                                            dZ if need_dx else None, d, st.ws_g)
-                if need_dx:
+                if need_dx and not self.fused_bwd:
                     g = st.dHtil[l - 1]
                     self._aggregate(B.sylvie_aggregate_csr_bwd, st.opT, st.planT, st.ws_aggT,
                                     st.n_in + st.n_halo, dZ, d, g, addend=dself,
                                     addend_rows=st.n_in)
             if not need_dx:
+                continue
+            if self.fused_bwd:
+                self._backward_exchange_fused(l, d, Wd, seed, pair_seed)
                 continue
             # exchange the halo gradients; all transposed aggregates above are complete
             # before any partition's inner rows are touched (same stream, in order)
@@ -228,3 +262,35 @@ class LayerLoop:
                                                      b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
                     else:
                         tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())
+
+    def _backward_exchange_fused(self, l, d, Wd, seed, pair_seed):
+        """Halo gradients: aggregate + quantize straight into the owner's inbound wire;
+        then inner gradients: aggregate + add the inbound wire rows, one store per row."""
+        for me, st in enumerate(self.parts):
+            rpT, clT, wT = st.opT
+            dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+            for b in st.blocks:
+                tgt = self.parts[b.owner]
+                wire = tgt.inbound[b.inb_off * Wd:]
+                lr, lp, nt = b.planT
+                B.sylvie_aggregate_csr_bwd_quantize(
+                    rpT, clT, wT, None, None, st.n_in + b.j0, b.j1 - b.j0, dZ, d, d,
+                    pair_seed(seed, me, b.owner), 2 * l + 1, wire, chunk=self.chunk,
+                    long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                    n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                    workspace=st.ws_aggT if nt else None)
+                self._keep(("bwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
+        for st in self.parts:
+            rpT, clT, wT = st.opT
+            dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+            dself = None
+            if self.model == "sage":
+                dself = st.dself.view(-1)[: st.n_in * d].view(st.n_in, d)
+            g = st.dHtil[l - 1]
+            lr, lp, nt = st.planT_inner
+            B.sylvie_aggregate_csr_bwd_integrate(
+                rpT, clT, wT, None, None, 0, st.n_in, dZ, d, d, g, g.stride(0), dself,
+                0 if dself is None else d, st.n_in, st.inbound, st.n_inbound, st.inb_seg_ptr,
+                st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
+                long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                workspace=st.ws_aggT if nt else None)

@@ -44,8 +44,11 @@ class Run:
         self.wl = wl
         p0 = wl.parts[0]
         owner = [torch.zeros(p0.n_halo, dtype=torch.int32, device=DEV)]
+        # the two-step backward exposes the float halo gradients the oracle is fed with;
+        # the fused backward bench.py times is then required to match it bit for bit
         self.loop = LayerLoop(wl.parts, owner, [wl.mirror], wl.X, wl.J, wl.W, spec.model,
-                              spec.dims, chunk=1024, exchange_first_layer=False, fused=True)
+                              spec.dims, chunk=1024, exchange_first_layer=False, fused=True,
+                              fused_bwd=False)
         self.loop.record = {}
         self.loop.forward(SEED, OL.pair_seed)
         self.pre = {}
@@ -66,6 +69,13 @@ class Run:
             self.loop.backward(SEED, OL.pair_seed)
         finally:
             B.sylvie_quantize_1bit_bwd = orig
+        torch.cuda.synchronize()
+        self.fused = LayerLoop(wl.parts, owner, [wl.mirror], wl.X, wl.J, wl.W, spec.model,
+                               spec.dims, chunk=1024, exchange_first_layer=False, fused=True,
+                               fused_bwd=True)
+        self.fused.record = {}
+        self.fused.forward(SEED, OL.pair_seed)
+        self.fused.backward(SEED, OL.pair_seed)
         torch.cuda.synchronize()
         self.st = self.loop.parts[0]
         rp, cl, dg = np_c(p0.rowptr), np_c(p0.col), np_c(p0.deg)
@@ -266,3 +276,18 @@ def test_backward_aggregate_and_exchange(oracle, run):
             J[i] = tgt[0]
         got = np_c(st.dHtil[l - 1][torch.from_numpy(dsts).to(DEV)])
         assert np.array_equal(bits32(got), bits32(J)), ("integrate", l)
+
+
+@allruns
+def test_fused_backward_matches(run):
+    """bench.py's configuration (fused backward) against the two-step backward checked above."""
+    a, b = run.loop, run.fused
+    assert a.record.keys() == b.record.keys()
+    for k in a.record:
+        assert torch.equal(a.record[k], b.record[k]), k
+    sa, sb = a.parts[0], b.parts[0]
+    for l in range(1, len(run.spec.dims) - 1):
+        assert torch.equal(sa.dHtil[l][: sa.n_in], sb.dHtil[l]), l
+    for l in range(1, len(run.spec.dims)):
+        assert torch.equal(sa.G[l], sb.G[l]), l
+    assert torch.equal(sa.out, sb.out)

@@ -30,7 +30,7 @@ def close(got, ref, S, what):
     assert not bad.any(), (what, int(bad.sum()), float((err / np.maximum(bound, 1e-300)).max()))
 
 
-def build_loop(wl, wire="1bit", chunk=256, fused=True):
+def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False):
     from paper_2303_01277_amd.trainer import LayerLoop
     spec = wl.spec
     parts = wl.parts
@@ -45,7 +45,7 @@ def build_loop(wl, wire="1bit", chunk=256, fused=True):
         rows = [p.halo_row for p in parts]
     return LayerLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
                      [w.to(DEV) for w in wl.W], spec.model, spec.dims, chunk=chunk,
-                     exchange_first_layer=True, wire=wire, fused=fused)
+                     exchange_first_layer=True, wire=wire, fused=fused, fused_bwd=fused_bwd)
 
 
 def replay(oracle, wl, loop, pdata, seed):
@@ -221,3 +221,31 @@ def test_layer_loop_end_to_end_fp32_wire(oracle, cfg, n_nodes):
         for l in range(1, len(W) + 1):
             g = np_c(st.G[l])
             assert np.abs(g - pd.G[l]).max() <= 2e-5 * np.abs(pd.G[l]).max()
+
+
+@pytest.mark.parametrize("cfg,n_nodes", CASES)
+def test_fused_backward_equals_two_step_backward(cfg, n_nodes):
+    """The transposed aggregation with the quantize / integrate epilogues must give, bit
+    for bit, the wires and gradients of aggregate -> quantize -> dequantize-accumulate
+    (which the teacher-forced test ties to the oracle)."""
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    seed = 0xABCD + len(cfg)
+    loops = []
+    for fb in (False, True):
+        loop = build_loop(wl, fused_bwd=fb, chunk=128)
+        loop.record = {}
+        loop.forward(seed, OL.pair_seed)
+        loop.backward(seed, OL.pair_seed)
+        torch.cuda.synchronize()
+        loops.append(loop)
+    a, b = loops
+    assert a.record.keys() == b.record.keys() and any(k[0] == "bwd" for k in a.record)
+    for k in a.record:
+        assert torch.equal(a.record[k], b.record[k]), k
+    for sa, sb in zip(a.parts, b.parts):
+        for l in range(len(wl.W)):
+            assert np.array_equal(bits32(np_c(sa.dHtil[l][: sa.n_in])), bits32(np_c(sb.dHtil[l]))), l
+        for l in range(1, len(wl.W) + 1):
+            assert torch.equal(sa.G[l], sb.G[l]), l
+        assert torch.equal(sa.out, sb.out)
