@@ -146,6 +146,16 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         int nd = cnt;                          // entries [0, nd) are dense, [nd, cnt) wire
         if constexpr (WIRE)
             nd = __builtin_popcountll(__ballot(lane < cnt && my_c < a.n_dense));
+        // wire entries: each lane fetches the metadata word of ITS entry now, so that the
+        // fetch is in flight while the dense rows are gathered
+        [[maybe_unused]] uint2 meta = make_uint2(0u, 0u);
+        if constexpr (WIRE) {
+            if (nd < cnt) {
+                const bool mine = lane >= nd && lane < cnt;
+                const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
+                meta = *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (W32 + 2) + W32);
+            }
+        }
         int j = 0;
         // full groups: U * EP valid entries, all gathers issued before any is used
         for (; j + EP * U <= nd; j += EP * U) {
@@ -206,9 +216,6 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 // aligned with the dense loops; an entry before nd is masked with weight
                 // 0 and reads wire row 0.
                 const bool mine = lane >= nd && lane < cnt;
-                const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
-                const uint2 meta =
-                    *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (W32 + 2) + W32);
                 const float my_zp = __uint_as_float(meta.y);
                 const float my_hi = my_zp + __uint_as_float(meta.x);
                 const float my_ww = mine ? my_w : 0.0f;

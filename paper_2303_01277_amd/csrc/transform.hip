@@ -147,7 +147,7 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r / 4) + 4
 // ---- forward: H = relu?([A1|A2] W) ----------------------------------------------
 
 template <int V>
-__global__ __launch_bounds__(kGemmThreads) void transform_fwd_kernel(CatA a, const float *__restrict__ Wm,
+__global__ __launch_bounds__(kGemmThreads, 3) void transform_fwd_kernel(CatA a, const float *__restrict__ Wm,
                                                                     int h, int relu,
                                                                     float *__restrict__ H, int64_t ldh)
 {
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kGemmThreads) void transform_fwd_kernel(CatA a, con
 // ---- backward, feature gradient: [dA1 | dA2] = M W^T -----------------------------
 
 template <int V>
-__global__ __launch_bounds__(kGemmThreads) void transform_bwd_da_kernel(
+__global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_da_kernel(
     MaskedJ m, const float *__restrict__ Wm, int k1, int k2, float *__restrict__ dA1, int64_t ld1,
     float *__restrict__ dA2, int64_t ld2)
 {
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(kGemmThreads) void transform_bwd_da_kernel(
 
 // Partial product of one slab of rows: part[slab][K][h].
 template <int V>
-__global__ __launch_bounds__(kGemmThreads) void transform_bwd_g_kernel(CatA a, MaskedJ m,
+__global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_g_kernel(CatA a, MaskedJ m,
                                                                       int64_t rows_per_slab,
                                                                       float *__restrict__ part)
 {
