@@ -271,3 +271,86 @@ def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
         torch.cuda.synchronize()
         close(Y.cpu().numpy(), Z, S, ("wire", chunk))
         assert np.array_equal(bits32(Y.cpu().numpy()), bits32(Y2.cpu().numpy())), chunk
+
+
+@pytest.mark.parametrize("d", [2, 7, 64, 100, 256, 602])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
+def test_backward_epilogues_equal_two_step(oracle, d, cfg, n_nodes, model):
+    """aggregate_csr_bwd_quantize / _integrate against the GPU's own aggregate_csr_bwd +
+    quantize_1bit_bwd + dequantize_1bit_bwd (bit for bit), whose pieces are tied to the
+    oracle above; the wire is also recomputed by the oracle from the GPU's float rows."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + 3)
+    dZ = dev(make_rows(rng, p.n_in, d, "heavy"))
+    add = dev(make_rows(rng, p.n_in, d, "normal"))
+    mirror = dev(rng.integers(0, p.n_in, p.n_halo).astype(np.int32))
+    rpT, clT, wT = GE.transpose_csr(dev(rp), dev(cl), dev(w), n_loc)
+    W1 = (d + 63) // 64 + 1
+    seed, sid, chunk = 4242 + d, 5, 128
+    # two-step reference on the GPU
+    lr, lp, nt = GE.long_row_plan(rpT, chunk)
+    ws = torch.empty(max(1, nt) * d, device=DEV)
+    G = torch.full((n_loc, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd(rpT, clT, wT, None, None, n_loc, dZ, d, d, G, d, addend=add,
+                               ld_addend=d, addend_rows=p.n_in, chunk=chunk, long_rows=lr,
+                               long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt, workspace=ws)
+    wire_ref = torch.full((p.n_halo * W1,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_1bit_bwd(G, d, d, None, p.n_in, p.n_halo, seed, sid, wire_ref)
+    sp_, sr, di = GE.scatter_segments(mirror)
+    Gpre = G.clone()
+    B.sylvie_dequantize_1bit_bwd(wire_ref, p.n_halo, d, G, d, sp_, sr, int(di.numel()), di)
+    # fused
+    lrh, lph, nth = GE.long_row_plan(rpT, chunk, p.n_in, n_loc)
+    wire = torch.full((p.n_halo * W1,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_aggregate_csr_bwd_quantize(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, seed,
+                                        sid, wire, chunk=chunk, long_rows=lrh, long_ptr=lph,
+                                        n_long=int(lrh.numel()), n_tasks=nth, workspace=ws)
+    lri, lpi, nti = GE.long_row_plan(rpT, chunk, 0, p.n_in)
+    sp2, sr2 = GE.scatter_segments_dense(mirror, p.n_in)
+    J = torch.full((p.n_in, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd_integrate(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, J, d, add, d,
+                                         p.n_in, wire, p.n_halo, sp2, sr2, chunk=chunk,
+                                         long_rows=lri, long_ptr=lpi, n_long=int(lri.numel()),
+                                         n_tasks=nti, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(wire, wire_ref)
+    assert np.array_equal(bits32(J.cpu().numpy()), bits32(G[: p.n_in].cpu().numpy()))
+    # the oracle's quantizer on the GPU's float halo rows gives the same wire
+    ref = oracle.quantize_1bit(Gpre.cpu().numpy(), d, p.n_halo, seed, sid, row_offset=p.n_in)
+    pk, sc, zp = split_wire(wire.cpu().numpy(), p.n_halo, d)
+    assert np.array_equal(pk, ref[0]) and np.array_equal(bits32(sc), bits32(ref[1])) and \
+        np.array_equal(bits32(zp), bits32(ref[2]))
+
+
+def test_loop_without_halo(oracle):
+    """A partition that owns the whole graph: no halo rows, empty wires, nothing to exchange."""
+    from oracle import layers as OL
+    from paper_2303_01277_amd.trainer import LayerLoop
+    from util import np_c, to_partdata
+    spec = scaled(CONFIGS["tiny"], 3000)
+    spec = type(spec)(**{**spec.__dict__, "n_parts": 1, "dims": (64, 32, 16)})
+    wl = build_workload(spec)
+    pdata = to_partdata(wl)
+    Wn = [np_c(w) for w in wl.W]
+    OL.forward(pdata, "gcn", Wn, 1, "1bit")
+    OL.backward(pdata, "gcn", Wn, 1, "1bit")
+    p = wl.parts[0]
+    assert p.n_halo == 0
+    for f in ("rowptr", "col", "deg", "halo_gid", "halo_part", "halo_row"):
+        setattr(p, f, getattr(p, f).to(DEV))
+    for fused in (True, False):
+        loop = LayerLoop([p], [p.halo_part], [p.halo_row], [wl.X[0].to(DEV)], [wl.J[0].to(DEV)],
+                         [w.to(DEV) for w in wl.W], "gcn", spec.dims, chunk=64, fused=fused,
+                         fused_bwd=fused)
+        loop.forward(1)
+        loop.backward(1)
+        torch.cuda.synchronize()
+        st = loop.parts[0]
+        ref = pdata[0]
+        assert np.abs(st.out.cpu().numpy() - ref.H[-1]).max() <= 2e-5 * np.abs(ref.H[-1]).max()
+        assert np.abs(st.dHtil[1].cpu().numpy()[: p.n_in] - ref.Jin[1]).max() <= \
+            2e-5 * np.abs(ref.Jin[1]).max()
+        assert np.abs(st.G[1].cpu().numpy() - ref.G[1]).max() <= 2e-5 * np.abs(ref.G[1]).max()
