@@ -338,7 +338,13 @@ __global__ void transform_bwd_g_reduce_kernel(const float *__restrict__ part, in
     G[e] = s;
 }
 
-static int g_slabs(int64_t n) { return static_cast<int>(n <= 0 ? 1 : (n + 4095) / 4096 > 256 ? 256 : (n + 4095) / 4096); }
+// Row slabs of the weight-gradient product: enough of them to fill the chip even when
+// the output is a single tile, at most 256 (the partial products go through a workspace).
+static int g_slabs(int64_t n)
+{
+    const int64_t s = (n + 511) / 512;
+    return static_cast<int>(s < 1 ? 1 : (s > 256 ? 256 : s));
+}
 
 static int32_t check_common(const char *name, const float *A1, int64_t ld_a1, int32_t k1,
                             const float *A2, int64_t ld_a2, int32_t k2, const float *W, int32_t h,
