@@ -238,6 +238,68 @@ def cpu_baseline(torch, loop, st, dims, budget_s=20.0):
             "quant_dequant_GBps": qd_gbps}
 
 
+def lowbit_microbench(torch, B, loop, st, d, iters=10):
+    """The four stand-alone Low-bit entry points on this workload's exchange (all halo rows of
+    layer width d), timed one by one with HIP events.  The default loop fuses three of them into
+    the aggregation, so this is where their own GB/s is measured."""
+    n = st.n_halo
+    if n == 0:
+        return None
+    dev = st.X.device
+    Wb = 8 * ((d + 63) // 64)
+    W1 = B.sylvie_wire_row_words(d)
+    src = torch.randn(st.n_in, d, device=dev)
+    halo = torch.empty(n, d, device=dev)
+    J = torch.randn(st.n_in, d, device=dev)
+    wire = torch.empty(n * W1, dtype=torch.int64, device=dev)
+    b0 = st.blocks[0]
+    rows = torch.cat([b.rows for b in st.blocks]) if len(st.blocks) > 1 else b0.rows
+    from paper_2303_01277_amd import graph_engine as GE
+    sp, sr, di = GE.scatter_segments(rows.clamp(max=st.n_in - 1))
+    n_dst = int(di.numel())
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    idx = rows.clamp(max=st.n_in - 1)
+    out = {}
+    cases = {
+        "quantize_1bit_fwd (gathered rows)": (
+            lambda: B.sylvie_quantize_1bit_fwd(src, d, d, idx, 0, n, 1, 2, wire),
+            n * (4 * d + 4 + Wb + 8)),
+        "dequantize_1bit_fwd": (
+            lambda: B.sylvie_dequantize_1bit_fwd(wire, n, d, halo, d, 0), n * (Wb + 8 + 4 * d)),
+        "quantize_1bit_bwd (contiguous rows)": (
+            lambda: B.sylvie_quantize_1bit_bwd(halo, d, d, None, 0, n, 1, 3, wire),
+            n * (4 * d + Wb + 8)),
+        "dequantize_1bit_bwd (scatter-add)": (
+            lambda: B.sylvie_dequantize_1bit_bwd(wire, n, d, J, d, sp, sr, n_dst, di),
+            n * (Wb + 8 + 4) + n_dst * (8 * d + 12)),
+    }
+    tot_b, tot_ms = 0, 0.0
+    for name, (fn, nbytes) in cases.items():
+        ms = timed(fn)
+        out[name] = {"ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "rows_per_s": n / (ms * 1e-3)}
+        tot_b += nbytes
+        tot_ms += ms
+    out["all four"] = {"ms": tot_ms, "GBps": tot_b / (tot_ms * 1e-3) / 1e9,
+                       "frac_hbm_peak": tot_b / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    out["rows"] = n
+    out["d"] = d
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -377,6 +439,7 @@ def main():
         "kernels": {k: {kk: (round(vv, 6) if isinstance(vv, float) else vv)
                         for kk, vv in v.items()} for k, v in ops.items()},
     }
+    out["lowbit_kernels"] = lowbit_microbench(torch, B, loop, loop.parts[0], spec.dims[-2])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(torch, loop, loop.parts[0], spec.dims)

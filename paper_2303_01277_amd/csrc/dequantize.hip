@@ -42,7 +42,10 @@ __device__ __forceinline__ void select_store(float *p, uint32_t bits, float lo, 
     }
 }
 
-template <int VEC>
+// ONEPASS: d <= 64 VEC, every lane owns at most one vector of a row.  Then the loads
+// of all the wave's rows (metadata word + the lane's bit word) are issued before the
+// first store, so one wave keeps several rows in flight.
+template <int VEC, bool ONEPASS>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel(
     const uint64_t *__restrict__ wire, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
     int64_t row_offset)
@@ -52,25 +55,54 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel
     const int64_t first =
         (static_cast<int64_t>(blockIdx.x) * kDqWavesPerBlock + wave) * kDqRowsPerWave;
     const int W = (d + 63) >> 6;
+    if constexpr (ONEPASS) {
+        const int c0 = lane * VEC;
+        const int cw = (c0 < d ? c0 : 0) >> 6;
+        uint64_t meta[kDqRowsPerWave], word[kDqRowsPerWave];
+#pragma unroll
+        for (int r = 0; r < kDqRowsPerWave; ++r) {
+            meta[r] = 0;
+            word[r] = 0;
+            if (first + r < n_rows) {
+                const uint64_t *prow = wire + (first + r) * (W + 1);
+                meta[r] = prow[W];
+                word[r] = prow[cw];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kDqRowsPerWave; ++r) {
+            if (first + r < n_rows && c0 < d) {
+                const float zp = __uint_as_float(static_cast<uint32_t>(meta[r] >> 32));
+                const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta[r]));
+                const uint32_t bits = static_cast<uint32_t>(word[r] >> (c0 & 63));
+                select_store<VEC>(dst + (row_offset + first + r) * ld + c0, bits, zp, hi);
+            }
+        }
+    } else {
 #pragma unroll 1
-    for (int r = 0; r < kDqRowsPerWave; ++r) {
-        const int64_t i = first + r;
-        if (i >= n_rows) break;
-        const uint64_t *prow = wire + i * (W + 1);
-        const uint64_t meta = prow[W];                      // scale | zero << 32
-        const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
-        const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
-        float *orow = dst + (row_offset + i) * ld;
-        for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
-            const uint64_t word = prow[c0 >> 6];
-            const uint32_t bits = static_cast<uint32_t>(word >> (c0 & 63));
-            select_store<VEC>(orow + c0, bits, zp, hi);
+        for (int r = 0; r < kDqRowsPerWave; ++r) {
+            const int64_t i = first + r;
+            if (i >= n_rows) break;
+            const uint64_t *prow = wire + i * (W + 1);
+            const uint64_t meta = prow[W];                      // scale | zero << 32
+            const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
+            const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
+            float *orow = dst + (row_offset + i) * ld;
+            for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
+                const uint64_t word = prow[c0 >> 6];
+                const uint32_t bits = static_cast<uint32_t>(word >> (c0 & 63));
+                select_store<VEC>(orow + c0, bits, zp, hi);
+            }
         }
     }
 }
 
-// One wavefront per destination row k: dst[dst_ids[k]] += the dequantised wire
-// rows seg_rows[seg_ptr[k] .. seg_ptr[k+1]) in that order, float32.
+constexpr int kDqDstPerWave = 4;
+
+// dst[dst_ids[k]] += the dequantised wire rows seg_rows[seg_ptr[k] .. seg_ptr[k+1]) in
+// that order, float32.  One wavefront takes kDqDstPerWave destinations and walks their
+// (independent) load chains side by side: segment bounds, first wire row id, its
+// words, the destination row; further entries of a segment (rare) follow in a loop.
 template <int VEC>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel(
     const uint64_t *__restrict__ wire, int d, float *__restrict__ dst, int64_t ld,
@@ -78,30 +110,64 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
     int64_t n_dst_rows, const int32_t *__restrict__ dst_ids)
 {
     using V = typename VecT<VEC>::type;
+    constexpr int D = kDqDstPerWave;
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kDqWavesPerBlock + wave;
-    if (k >= n_dst_rows) return;
+    const int64_t k0 = (static_cast<int64_t>(blockIdx.x) * kDqWavesPerBlock + wave) * D;
+    if (k0 >= n_dst_rows) return;
     const int W = (d + 63) >> 6;
-    const int64_t j0 = seg_ptr[k], j1 = seg_ptr[k + 1];
-    if (j0 >= j1) return;
-    float *orow = dst + static_cast<int64_t>(dst_ids[k]) * ld;
-    for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
-        V accv = *reinterpret_cast<const V *>(orow + c0);
-        float acc[VEC];
-        __builtin_memcpy(acc, &accv, sizeof(V));
-        for (int64_t j = j0; j < j1; ++j) {
-            const uint64_t *prow = wire + static_cast<int64_t>(seg_rows[j]) * (W + 1);
-            const uint64_t meta = prow[W];
-            const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
-            const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
-            const uint64_t word = prow[c0 >> 6];
-            const uint32_t bits = static_cast<uint32_t>(word >> (c0 & 63));
+    // every load below is unconditional (indices clamped to something valid) so that the
+    // loads of the D chains are issued together; a slot past the end gets an empty segment
+    int64_t j0[D], j1[D];
+    float *orow[D];
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) acc[t] = acc[t] + (((bits >> t) & 1u) ? hi : zp);
+    for (int q = 0; q < D; ++q) {
+        const bool valid = k0 + q < n_dst_rows;
+        const int64_t kk = valid ? k0 + q : k0;
+        j0[q] = seg_ptr[kk];
+        j1[q] = seg_ptr[kk + 1];
+        orow[q] = dst + static_cast<int64_t>(dst_ids[kk]) * ld;
+        if (!valid) j1[q] = j0[q];
+    }
+#pragma unroll
+    for (int q = 0; q < D; ++q) {
+        j0[q] = uniform(j0[q]);
+        j1[q] = uniform(j1[q]);
+    }
+    for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
+        float acc[D][VEC];
+        const uint64_t *prow[D];
+        uint64_t meta[D], word[D];
+#pragma unroll
+        for (int q = 0; q < D; ++q) {
+            V accv = *reinterpret_cast<const V *>(orow[q] + c0);
+            __builtin_memcpy(acc[q], &accv, sizeof(V));
+            const int64_t jj = j0[q] < j1[q] ? j0[q] : 0;
+            prow[q] = wire + static_cast<int64_t>(seg_rows[jj]) * (W + 1);
         }
-        __builtin_memcpy(&accv, acc, sizeof(V));
-        *reinterpret_cast<V *>(orow + c0) = accv;
+#pragma unroll
+        for (int q = 0; q < D; ++q) {
+            meta[q] = prow[q][W];
+            word[q] = prow[q][c0 >> 6];
+        }
+#pragma unroll
+        for (int q = 0; q < D; ++q) {
+            if (j0[q] >= j1[q]) continue;
+            for (int64_t j = j0[q];;) {
+                const float zp = __uint_as_float(static_cast<uint32_t>(meta[q] >> 32));
+                const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta[q]));
+                const uint32_t bits = static_cast<uint32_t>(word[q] >> (c0 & 63));
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) acc[q][t] = acc[q][t] + (((bits >> t) & 1u) ? hi : zp);
+                if (++j >= j1[q]) break;
+                const uint64_t *pr = wire + static_cast<int64_t>(seg_rows[j]) * (W + 1);
+                meta[q] = pr[W];
+                word[q] = pr[c0 >> 6];
+            }
+            V accv;
+            __builtin_memcpy(&accv, acc[q], sizeof(V));
+            *reinterpret_cast<V *>(orow[q] + c0) = accv;
+        }
     }
 }
 
@@ -144,15 +210,17 @@ extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_ro
     const dim3 block(kDqWavesPerBlock * kWave);
     // the vector width must also hold for the first written row
     const int vec = pick_vec(d, ld_dst, dst + row_offset * ld_dst);
-    if (vec == 4)
-        hipLaunchKernelGGL(dequantize_fwd_kernel<4>, grid, block, 0, st, wire, n_rows,
-                           d, dst, ld_dst, row_offset);
-    else if (vec == 2)
-        hipLaunchKernelGGL(dequantize_fwd_kernel<2>, grid, block, 0, st, wire, n_rows,
-                           d, dst, ld_dst, row_offset);
-    else
-        hipLaunchKernelGGL(dequantize_fwd_kernel<1>, grid, block, 0, st, wire, n_rows,
-                           d, dst, ld_dst, row_offset);
+#define SYLVIE_DQ_LAUNCH(V, ONE)                                                                  \
+    hipLaunchKernelGGL((dequantize_fwd_kernel<V, ONE>), grid, block, 0, st, wire, n_rows, d, dst, \
+                       ld_dst, row_offset)
+    if (vec == 4) {
+        if (d <= 256) SYLVIE_DQ_LAUNCH(4, true); else SYLVIE_DQ_LAUNCH(4, false);
+    } else if (vec == 2) {
+        if (d <= 128) SYLVIE_DQ_LAUNCH(2, true); else SYLVIE_DQ_LAUNCH(2, false);
+    } else {
+        if (d <= 64) SYLVIE_DQ_LAUNCH(1, true); else SYLVIE_DQ_LAUNCH(1, false);
+    }
+#undef SYLVIE_DQ_LAUNCH
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
@@ -173,7 +241,8 @@ extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_ro
     if (!aligned(seg_ptr, 8) || !aligned(seg_rows, 4) || !aligned(dst_ids, 4))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned index array", name);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid(static_cast<unsigned>((n_dst_rows + kDqWavesPerBlock - 1) / kDqWavesPerBlock));
+    const int64_t per_block = kDqWavesPerBlock * kDqDstPerWave;
+    const dim3 grid(static_cast<unsigned>((n_dst_rows + per_block - 1) / per_block));
     const dim3 block(kDqWavesPerBlock * kWave);
     const int vec = pick_vec(d, ld_dst, dst);
     if (vec == 4)
