@@ -205,7 +205,9 @@ def test_aggregate_scales_and_unit_weights(oracle):
 
 
 @pytest.mark.parametrize("n,k1,k2,h", [(1000, 64, 0, 64), (777, 256, 0, 256), (300, 602, 0, 256),
-                                        (515, 100, 100, 128), (129, 128, 0, 40), (64, 20, 0, 7)])
+                                        (515, 100, 100, 128), (129, 128, 0, 40), (64, 20, 0, 7),
+                                        (515, 96, 32, 128), (300, 64, 0, 384), (2000, 256, 256, 256),
+                                        (131, 128, 128, 200), (1, 16, 0, 4), (4100, 16, 16, 16)])
 def test_transform_parity(oracle, n, k1, k2, h):
     from paper_2303_01277_amd import binding as B
     rng = np.random.default_rng(n + k1)
@@ -234,6 +236,50 @@ def test_transform_parity(oracle, n, k1, k2, h):
         close(dA1.cpu().numpy(), r["dA1"], r["SdA1"], ("dA1", relu))
         if k2:
             close(dA2.cpu().numpy(), r["dA2"], r["SdA2"], ("dA2", relu))
+
+
+@pytest.mark.parametrize("n,k1,k2,h", [(700, 128, 0, 256), (300, 64, 64, 144), (257, 100, 0, 36)])
+def test_transform_strided(oracle, n, k1, k2, h):
+    """Operands and results that are column blocks of wider row-major buffers (leading
+    dimension > width); whatever lies outside the blocks must stay untouched."""
+    from paper_2303_01277_amd import binding as B
+    rng = np.random.default_rng(n + h)
+    A1 = make_rows(rng, n, k1, "relu")
+    A2 = make_rows(rng, n, k2, "normal") if k2 else None
+    W = (rng.standard_normal((k1 + k2, h)) / np.sqrt(k1 + k2)).astype(np.float32)
+    J = make_rows(rng, n, h, "normal")
+
+    def wide(a, pad):
+        """device buffer [rows, width + pad] holding a in its first columns, 7.0 elsewhere"""
+        buf = torch.full((a.shape[0], a.shape[1] + pad), 7.0, device=DEV)
+        buf[:, : a.shape[1]] = dev(a)
+        return buf
+
+    for relu in (True, False):
+        Href, S = oracle.transform_fwd(A1, W, relu, A2=A2, want_S=True)
+        a1 = wide(A1, 8)
+        a2 = wide(A2, 4) if k2 else None
+        Hg = torch.full((n, h + 12), 7.0, device=DEV)
+        B.sylvie_transform_fwd(a1, k1 + 8, k1, a2, k2 + 4, k2, dev(W), h, n, relu, Hg, h + 12)
+        torch.cuda.synchronize()
+        Hgn = np.ascontiguousarray(Hg[:, :h].cpu().numpy())
+        close(Hgn, Href, S, ("H", relu))
+        assert bool((Hg[:, h:] == 7.0).all())
+        r = oracle.transform_bwd(A1, W, relu, Hgn, J, A2=A2, want_S=True)
+        G = torch.full((k1 + k2, h), float("nan"), device=DEV)
+        dA1 = torch.full((n, k1 + 4), 7.0, device=DEV)
+        dA2 = torch.full((n, k2 + 8), 7.0, device=DEV) if k2 else None
+        jw = wide(J, 4)
+        ws = torch.empty(B.sylvie_transform_bwd_workspace_bytes(k1, k2, h, n) // 4, device=DEV)
+        B.sylvie_transform_bwd(a1, k1 + 8, k1, a2, k2 + 4, k2, dev(W), h, n, relu, Hg, h + 12, jw, h + 4,
+                               G, dA1, k1 + 4, dA2, k2 + 8, ws)
+        torch.cuda.synchronize()
+        close(G.cpu().numpy(), r["G"], r["SG"], ("G", relu))
+        close(np.ascontiguousarray(dA1[:, :k1].cpu().numpy()), r["dA1"], r["SdA1"], ("dA1", relu))
+        assert bool((dA1[:, k1:] == 7.0).all())
+        if k2:
+            close(np.ascontiguousarray(dA2[:, :k2].cpu().numpy()), r["dA2"], r["SdA2"], ("dA2", relu))
+            assert bool((dA2[:, k2:] == 7.0).all())
 
 
 @pytest.mark.parametrize("d", [2, 64, 100, 128, 256, 602])
