@@ -336,7 +336,9 @@ __global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_g_kernel(CatA a
 // one 32-bit lane offset computed once, the k advance in the scalar offset; rows past
 // the end of the matrix fail the range check and read as zero), LDS is double
 // buffered (one barrier per k-step), a k-contiguous operand keeps its global layout
-// in LDS ([x][k], one 16-byte write per fetch) and is read back 16 bytes at a time,
+// in LDS ([x][k], one 16-byte write per fetch, the four 16-byte pieces of a row
+// permuted by a function of the row so that neither the fill nor the read pattern
+// meets a bank twice) and is read back 16 bytes at a time,
 // and full output tiles leave through buffer stores whose row offset is scalar.
 //
 // MFMA k-slots: the 16 k of a step are two groups of 8; in group g, step j (0..3)
@@ -347,8 +349,7 @@ __global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_g_kernel(CatA a
 // =====================================================================================
 
 constexpr int64_t kMaxFastLd = int64_t(1) << 22;   // 128 rows of this many floats stay below 2^31 bytes
-constexpr int kPadF = 20;                  // row stride of a [x][k] tile (dwords)
-constexpr int kTileKC = BM * kPadF;        // floats per [x][k] tile
+constexpr int kTileKC = BM * BK;           // floats per [x][k] tile
 constexpr int kTileXC = BK * 128;          // floats per [k][x] tile
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buf(const void *p, uint32_t bytes)
@@ -366,10 +367,14 @@ __device__ __forceinline__ void buf_load4(float (&o)[4], __amdgpu_buffer_rsrc_t 
 // Fill patterns (256 threads, NI fetches of 4 floats each):
 //   [x][k] tile: thread -> x = t/4 + 64 i, k = 4 (t%4)
 //   [k][x] tile: thread -> k = t/32 + 8 i, x = 4 (t%32)
+// [x][k] tile: row x holds its pieces q = 0..3 (k = 4 q .. 4 q + 3) at piece slot q ^ kc_perm(x).
+// Eight (or sixteen) consecutive rows read the same q, four lanes fill the four q of one
+// row: with this permutation both patterns cover all banks once.
+__device__ __forceinline__ int kc_perm(int x) { return ((x >> 1) ^ (x >> 2)) & 3; }
 __device__ __forceinline__ void put_f_kc(float *T, int i, const float (&v)[4])
 {
-    const int t = threadIdx.x;
-    *reinterpret_cast<float4 *>(T + (t / 4 + 64 * i) * kPadF + 4 * (t % 4)) = make_float4(v[0], v[1], v[2], v[3]);
+    const int t = threadIdx.x, x = t / 4 + 64 * i;
+    *reinterpret_cast<float4 *>(T + x * BK + 4 * ((t % 4) ^ kc_perm(x))) = make_float4(v[0], v[1], v[2], v[3]);
 }
 __device__ __forceinline__ void put_f_xc(float *T, int i, const float (&v)[4])
 {
@@ -390,7 +395,7 @@ __device__ __forceinline__ void mma_step(floatx16 (&acc)[2][2], const float *As,
         for (int g = 0; g < 2; ++g)
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const float4 v = *reinterpret_cast<const float4 *>(As + (xa + 64 * i) * kPadF + 8 * g + 4 * kh);
+                const float4 v = *reinterpret_cast<const float4 *>(As + (xa + 64 * i) * BK + 4 * ((2 * g + kh) ^ kc_perm(xa)));
                 a4[g][i][0] = v.x; a4[g][i][1] = v.y; a4[g][i][2] = v.z; a4[g][i][3] = v.w;
             }
     }
@@ -399,7 +404,7 @@ __device__ __forceinline__ void mma_step(floatx16 (&acc)[2][2], const float *As,
         for (int g = 0; g < 2; ++g)
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const float4 v = *reinterpret_cast<const float4 *>(Bs + (xb + 64 * i) * kPadF + 8 * g + 4 * kh);
+                const float4 v = *reinterpret_cast<const float4 *>(Bs + (xb + 64 * i) * BK + 4 * ((2 * g + kh) ^ kc_perm(xb)));
                 b4[g][i][0] = v.x; b4[g][i][1] = v.y; b4[g][i][2] = v.z; b4[g][i][3] = v.w;
             }
     }
