@@ -22,6 +22,8 @@ __all__ = [
     "build", "words_per_row", "uniform24", "quantize_1bit", "dequantize_1bit_fwd",
     "dequantize_1bit_bwd", "gcn_operator", "mean_weights", "aggregate_fwd", "aggregate_bwd",
     "aggregate_bwd_rows", "transform_fwd", "transform_bwd", "num_threads",
+    "words_per_row_bits", "quantize_bbit", "dequantize_bbit_fwd", "dequantize_bbit_bwd",
+    "words_per_row_fp16", "convert_fp16", "recover_fp16_fwd", "recover_fp16_bwd",
 ]
 
 
@@ -44,6 +46,10 @@ def _L():
             lib.orc_uniform24.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32]
             lib.orc_words_per_row.restype = C.c_int64
             lib.orc_words_per_row.argtypes = [C.c_int32]
+            lib.orc_words_per_row_bits.restype = C.c_int64
+            lib.orc_words_per_row_bits.argtypes = [C.c_int32, C.c_int32]
+            lib.orc_words_per_row_fp16.restype = C.c_int64
+            lib.orc_words_per_row_fp16.argtypes = [C.c_int32]
             lib.orc_aggregate_bwd.restype = C.c_int
             lib.orc_num_threads.restype = C.c_int
             _lib = lib
@@ -111,6 +117,76 @@ def dequantize_1bit_bwd(packed, scale, zero, d, J, dst_row):
     n = packed.shape[0]
     _L().orc_dequantize_1bit_bwd(_p(packed), _p(scale), _p(zero), C.c_int64(n), C.c_int32(d),
                                  _p(J), C.c_int64(J.shape[1]), _p(dst_row))
+
+
+def words_per_row_bits(d: int, bits: int) -> int:
+    return int(_L().orc_words_per_row_bits(int(d), int(bits)))
+
+
+def _bits_ok(bits):
+    if bits not in (1, 2, 4, 8):
+        raise ValueError("bits must be 1, 2, 4 or 8")
+
+
+def quantize_bbit(src, d, n_rows, bits, seed, stream, idx=None, row_offset=0, wire_row0=0):
+    """b-bit codes -> (packed uint64 [n_rows, ceil(d*bits/64)], scale f32, zero f32)."""
+    _bits_ok(bits)
+    _f32(src, "src")
+    W = words_per_row_bits(d, bits)
+    packed = np.empty((n_rows, W), np.uint64)
+    scale = np.empty(n_rows, np.float32)
+    zero = np.empty(n_rows, np.float32)
+    if idx is not None:
+        _chk(idx, np.int32, "idx")
+    _L().orc_quantize_bbit(_p(src), C.c_int64(src.shape[1]), C.c_int32(d), _p(idx),
+                           C.c_int64(row_offset), C.c_int64(n_rows), C.c_int32(bits),
+                           C.c_uint64(seed), C.c_uint32(stream), C.c_int64(wire_row0), _p(packed),
+                           _p(scale), _p(zero))
+    return packed, scale, zero
+
+
+def dequantize_bbit_fwd(packed, scale, zero, d, bits, dst, row_offset):
+    _bits_ok(bits)
+    _chk(packed, np.uint64, "packed"); _f32(scale, "scale"); _f32(zero, "zero"); _f32(dst, "dst")
+    _L().orc_dequantize_bbit_fwd(_p(packed), _p(scale), _p(zero), C.c_int64(packed.shape[0]),
+                                 C.c_int32(d), C.c_int32(bits), _p(dst), C.c_int64(dst.shape[1]),
+                                 C.c_int64(row_offset))
+
+
+def dequantize_bbit_bwd(packed, scale, zero, d, bits, J, dst_row):
+    _bits_ok(bits)
+    _chk(packed, np.uint64, "packed"); _f32(scale, "scale"); _f32(zero, "zero"); _f32(J, "J")
+    _chk(dst_row, np.int32, "dst_row")
+    _L().orc_dequantize_bbit_bwd(_p(packed), _p(scale), _p(zero), C.c_int64(packed.shape[0]),
+                                 C.c_int32(d), C.c_int32(bits), _p(J), C.c_int64(J.shape[1]),
+                                 _p(dst_row))
+
+
+def words_per_row_fp16(d: int) -> int:
+    return int(_L().orc_words_per_row_fp16(int(d)))
+
+
+def convert_fp16(src, d, n_rows, idx=None, row_offset=0):
+    """-> wire uint16 [n_rows, 4*ceil(d/4)]: binary16 bit patterns, zero padded."""
+    _f32(src, "src")
+    if idx is not None:
+        _chk(idx, np.int32, "idx")
+    wire = np.empty((n_rows, 4 * words_per_row_fp16(d)), np.uint16)
+    _L().orc_convert_fp16(_p(src), C.c_int64(src.shape[1]), C.c_int32(d), _p(idx),
+                          C.c_int64(row_offset), C.c_int64(n_rows), _p(wire))
+    return wire
+
+
+def recover_fp16_fwd(wire, d, dst, row_offset):
+    _chk(wire, np.uint16, "wire"); _f32(dst, "dst")
+    _L().orc_recover_fp16_fwd(_p(wire), C.c_int64(wire.shape[0]), C.c_int32(d), _p(dst),
+                              C.c_int64(dst.shape[1]), C.c_int64(row_offset))
+
+
+def recover_fp16_bwd(wire, d, J, dst_row):
+    _chk(wire, np.uint16, "wire"); _f32(J, "J"); _chk(dst_row, np.int32, "dst_row")
+    _L().orc_recover_fp16_bwd(_p(wire), C.c_int64(wire.shape[0]), C.c_int32(d), _p(J),
+                              C.c_int64(J.shape[1]), _p(dst_row))
 
 
 def gcn_operator(rowptr, col, deg, n_in):

@@ -182,6 +182,206 @@ void orc_dequantize_1bit_bwd(const uint64_t *packed, const float *scale, const f
 }
 
 /* ------------------------------------------------------------------------- */
+/* b-bit quantizer / dequantizer: Eq. 3, Eq. 4 and Eq. 5 for b in {1, 2, 4, 8}, */
+/* B = 2^b - 1 bins (Sec. 3.2; the bit-width study of Sec. 5.4).               */
+/* ------------------------------------------------------------------------- */
+
+int64_t orc_words_per_row_bits(int32_t d, int32_t bits) { return ((int64_t)d * bits + 63) / 64; }
+
+/*
+ * Row selection, extrema, random draws and the metadata convention are those of
+ * orc_quantize_1bit.  Per row, in single precision, one IEEE operation each:
+ *
+ *   range = mx - mn,  zero = mn,  scale = range / B           (Sec. 3.2 "Communicator":
+ *                                                              scale is the ratio of the range to B)
+ *   g     = 2^64 if range < 2^-60, else 1                      (exact rescaling that keeps the
+ *                                                              reciprocal below finite)
+ *   inv   = B / (range * g)   if range > 0, else 0
+ * and per element
+ *   t  = ((r_c - mn) * g) * inv,  then t = min(t, B)           (Eq. 3: hbar in [0, B])
+ *   q  = floor(t) + [ u < t - floor(t) ],  u = k * 2^-24        (Eq. 4: up with probability frac(hbar))
+ *
+ * t - floor(t) is exact, so the comparison with u involves no rounding.  The clamp
+ * covers the one case where rounding of inv pushes the arg-max element above B.
+ * A constant row has inv = 0, hence all codes 0.
+ *
+ * Packing: 64/b codes per 64-bit word; the code of column c sits in bits
+ * [b (c mod 64/b), b (c mod 64/b) + b) of word c / (64/b); unused high codes are 0.
+ */
+void orc_quantize_bbit(const float *src, int64_t ld, int32_t d, const int32_t *idx,
+                       int64_t row_offset, int64_t n_rows, int32_t bits, uint64_t seed,
+                       uint32_t stream, int64_t wire_row0, uint64_t *packed, float *scale,
+                       float *zero)
+{
+    const int64_t W = orc_words_per_row_bits(d, bits);
+    const int32_t per = 64 / bits;
+    const uint32_t ck = orc_call_key(seed, stream);
+    const float two_m24 = 1.0f / 16777216.0f;
+    const float Bf = (float)((1 << bits) - 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t srow = idx ? (int64_t)idx[i] : row_offset + i;
+        const float *r = src + srow * ld;
+        float mn = r[0], mx = r[0];
+        for (int32_t c = 1; c < d; ++c) {
+            if (r[c] < mn) mn = r[c];
+            if (r[c] > mx) mx = r[c];
+        }
+        mn = mn + 0.0f;
+        mx = mx + 0.0f;
+        const float range = mx - mn;
+        zero[i] = mn;
+        scale[i] = range / Bf;
+        float g = 1.0f;
+        if (range < 0x1p-60f) g = 0x1p64f;
+        float inv = 0.0f;
+        if (range > 0.0f) inv = Bf / (range * g);
+        const uint32_t rk = orc_row_key(ck, (uint32_t)(wire_row0 + i));
+        for (int64_t k = 0; k < W; ++k) packed[i * W + k] = 0;
+        for (int32_t c = 0; c < d; ++c) {
+            const float u = (float)orc_elem_u24(rk, (uint32_t)c) * two_m24;
+            const float diff = r[c] - mn;
+            const float scaled = diff * g;
+            float t = scaled * inv;
+            if (t > Bf) t = Bf;
+            const float fl = floorf(t);
+            const float fr = t - fl;
+            uint64_t q = (uint64_t)fl;
+            if (u < fr) q += 1;
+            packed[i * W + c / per] |= q << (bits * (c % per));
+        }
+    }
+}
+
+/* Eq. 5: (max - min) * q / B + min, evaluated as fl(fl(scale * q) + zero). */
+static float orc_deq_bbit(const uint64_t *prow, float sc, float zp, int32_t bits, int32_t c)
+{
+    const int32_t per = 64 / bits;
+    const uint64_t q = (prow[c / per] >> (bits * (c % per))) & (((uint64_t)1 << bits) - 1);
+    const float step = sc * (float)q;
+    return step + zp;
+}
+
+void orc_dequantize_bbit_fwd(const uint64_t *packed, const float *scale, const float *zero,
+                             int64_t n_rows, int32_t d, int32_t bits, float *dst, int64_t ld,
+                             int64_t row_offset)
+{
+    const int64_t W = orc_words_per_row_bits(d, bits);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        float *o = dst + (row_offset + i) * ld;
+        for (int32_t c = 0; c < d; ++c)
+            o[c] = orc_deq_bbit(packed + i * W, scale[i], zero[i], bits, c);
+    }
+}
+
+/* Backward integrate, as orc_dequantize_1bit_bwd: ascending wire-row order. */
+void orc_dequantize_bbit_bwd(const uint64_t *packed, const float *scale, const float *zero,
+                             int64_t n_rows, int32_t d, int32_t bits, float *J, int64_t ld,
+                             const int32_t *dst_row)
+{
+    const int64_t W = orc_words_per_row_bits(d, bits);
+    for (int64_t i = 0; i < n_rows; ++i) {
+        float *o = J + (int64_t)dst_row[i] * ld;
+        for (int32_t c = 0; c < d; ++c) {
+            const float v = orc_deq_bbit(packed + i * W, scale[i], zero[i], bits, c);
+            o[c] = o[c] + v;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Half-precision wire (the FP16 point of the bit-width study, Sec. 5.4): each  */
+/* element is rounded to IEEE binary16, nearest-even; no side channel.          */
+/* ------------------------------------------------------------------------- */
+
+/* binary32 -> binary16, round to nearest, ties to even; overflow gives infinity. */
+static uint16_t orc_f32_to_f16(float f)
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    const uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    const uint32_t mag = x & 0x7fffffffu;
+    if (mag >= 0x7f800000u) /* infinity or NaN */
+        return (uint16_t)(sign | 0x7c00u | (mag > 0x7f800000u ? 0x200u : 0u));
+    const int32_t e = (int32_t)(mag >> 23) - 127; /* unbiased exponent of a normal input */
+    if (e >= 16) return (uint16_t)(sign | 0x7c00u); /* >= 2^16: beyond the largest half */
+    if (e >= -14) {
+        /* normal half: keep 10 fraction bits, round on the 13 dropped ones */
+        uint32_t h = ((uint32_t)(e + 15) << 10) | ((mag >> 13) & 0x3ffu);
+        const uint32_t rest = mag & 0x1fffu;
+        if (rest > 0x1000u || (rest == 0x1000u && (h & 1u))) h += 1; /* may carry into the exponent: correct */
+        return (uint16_t)(sign | h);
+    }
+    if (e < -25) return sign; /* below half of the smallest subnormal: zero */
+    /* subnormal half: value = m * 2^-24, m = round(|f| * 2^24) */
+    const uint32_t sig = (mag & 0x7fffffu) | 0x800000u; /* 24-bit significand, |f| = sig * 2^(e-23) */
+    const int32_t shift = -e - 1;                       /* m = sig >> shift, shift in [14, 24] */
+    uint32_t m = sig >> shift;
+    const uint32_t rest = sig & (((uint32_t)1 << shift) - 1);
+    const uint32_t half = (uint32_t)1 << (shift - 1);
+    if (rest > half || (rest == half && (m & 1u))) m += 1;
+    return (uint16_t)(sign | m);
+}
+
+static float orc_f16_to_f32(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    const uint32_t e = (h >> 10) & 0x1fu, m = h & 0x3ffu;
+    float v;
+    if (e == 0) {
+        v = (float)m * 0x1p-24f;
+    } else if (e == 31) {
+        const uint32_t x = 0x7f800000u | (m << 13);
+        memcpy(&v, &x, 4);
+    } else {
+        const uint32_t x = ((e + 112u) << 23) | (m << 13);
+        memcpy(&v, &x, 4);
+    }
+    uint32_t x;
+    memcpy(&x, &v, 4);
+    x |= sign;
+    memcpy(&v, &x, 4);
+    return v;
+}
+
+int64_t orc_words_per_row_fp16(int32_t d) { return ((int64_t)d + 3) / 4; }
+
+/* Wire row i: the d halves of the selected source row, then zero halves up to a
+ * multiple of four (rows are whole 64-bit words). */
+void orc_convert_fp16(const float *src, int64_t ld, int32_t d, const int32_t *idx,
+                      int64_t row_offset, int64_t n_rows, uint16_t *wire)
+{
+    const int64_t dp = 4 * orc_words_per_row_fp16(d);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i) {
+        const int64_t srow = idx ? (int64_t)idx[i] : row_offset + i;
+        for (int64_t c = 0; c < dp; ++c)
+            wire[i * dp + c] = c < d ? orc_f32_to_f16(src[srow * ld + c]) : 0;
+    }
+}
+
+void orc_recover_fp16_fwd(const uint16_t *wire, int64_t n_rows, int32_t d, float *dst,
+                          int64_t ld, int64_t row_offset)
+{
+    const int64_t dp = 4 * orc_words_per_row_fp16(d);
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t c = 0; c < d; ++c)
+            dst[(row_offset + i) * ld + c] = orc_f16_to_f32(wire[i * dp + c]);
+}
+
+void orc_recover_fp16_bwd(const uint16_t *wire, int64_t n_rows, int32_t d, float *J, int64_t ld,
+                          const int32_t *dst_row)
+{
+    const int64_t dp = 4 * orc_words_per_row_fp16(d);
+    for (int64_t i = 0; i < n_rows; ++i) {
+        float *o = J + (int64_t)dst_row[i] * ld;
+        for (int32_t c = 0; c < d; ++c) o[c] = o[c] + orc_f16_to_f32(wire[i * dp + c]);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Normalised operators (Sec. 3.4: A_hat = D^-1/2 (A + I) D^-1/2 for GCN;       */
 /* mean over neighbours for GraphSAGE, Eq. 1 with rho = mean).                  */
 /* ------------------------------------------------------------------------- */
