@@ -122,6 +122,42 @@ int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_rows, int32_t
                                    const int32_t *dst_ids, void *stream);
 
 /*
+ * b-bit Low-bit Module (Sec. 3.2, Eq. 3-5 with B = 2^b - 1 bins; the bit-width study of
+ * Sec. 5.4, which also has a half-precision point).  `bits` is 1, 2, 4 or 8 for b-bit
+ * stochastic rounding, or 16 for IEEE binary16 (round to nearest even, no side channel,
+ * seed ignored).  bits = 1 is exactly the 1-bit entry points above.
+ *
+ * Arithmetic for bits in {2, 4, 8}, single precision, one operation each:
+ *   mn, mx as for 1 bit;  range = mx - mn;  zero = mn;  scale = range / B;
+ *   g = 2^64 if range < 2^-60 else 1;  inv = B / (range * g), 0 for a constant row;
+ *   t = min(((x - mn) * g) * inv, B);  q = floor(t) + [k * 2^-24 < t - floor(t)]
+ * with k the 24-bit draw of (seed, stream_id, wire row i, column c), the same draws as
+ * the 1-bit quantizer.  Recovered value (Eq. 5): fl(fl(scale * q) + zero).
+ *
+ * Wire row for bits in {2, 4, 8}: uint64 [ceil(d * bits / 64) + 1]; the code of column
+ * c is bits [bits * (c mod 64/bits), + bits) of word c / (64/bits), unused high codes
+ * are 0; the last word is scale | zero << 32 as for 1 bit.  Wire row for bits = 16:
+ * uint64 [ceil(d / 4)] holding d binary16 values in column order, zero padded.
+ * sylvie_wire_row_words_bits returns that word count (0 for an invalid argument).
+ *
+ * All other arguments, row selection, destinations, ordering and error behaviour are
+ * those of the 1-bit entry points of the same direction.
+ */
+size_t sylvie_wire_row_words_bits(int32_t d, int32_t bits);
+int32_t sylvie_quantize_bbit_fwd(const float *src, int64_t ld_src, int32_t d, const int32_t *idx,
+                                 int64_t row_offset, int64_t n_rows, int32_t bits, uint64_t seed,
+                                 uint32_t stream_id, uint64_t *wire_out, void *stream);
+int32_t sylvie_quantize_bbit_bwd(const float *src, int64_t ld_src, int32_t d, const int32_t *idx,
+                                 int64_t row_offset, int64_t n_rows, int32_t bits, uint64_t seed,
+                                 uint32_t stream_id, uint64_t *wire_out, void *stream);
+int32_t sylvie_dequantize_bbit_fwd(const uint64_t *wire, int64_t n_rows, int32_t d, int32_t bits,
+                                   float *dst, int64_t ld_dst, int64_t row_offset, void *stream);
+int32_t sylvie_dequantize_bbit_bwd(const uint64_t *wire, int64_t n_rows, int32_t d, int32_t bits,
+                                   float *dst, int64_t ld_dst, const int64_t *seg_ptr,
+                                   const int32_t *seg_rows, int64_t n_dst_rows,
+                                   const int32_t *dst_ids, void *stream);
+
+/*
  * Neighbour aggregation, forward (Eq. 1; Alg. 1, the product A_n * H~ with A_n
  * the normalised local adjacency, Sec. 3.4):
  *     Y[v][c] = row_scale[v] * sum_{e in [rowptr[v], rowptr[v+1])}

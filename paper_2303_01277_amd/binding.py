@@ -36,11 +36,15 @@ def lib():
         L.sylvie_last_error.restype = C.c_char_p
         L.sylvie_wire_row_words.restype = C.c_int64
         L.sylvie_wire_row_words.argtypes = [C.c_int32]
+        L.sylvie_wire_row_words_bits.restype = C.c_size_t
+        L.sylvie_wire_row_words_bits.argtypes = [C.c_int32, C.c_int32]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
         L.sylvie_transform_bwd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32,
                                                            C.c_int64]
         for name in ("sylvie_quantize_1bit_fwd", "sylvie_quantize_1bit_bwd",
                      "sylvie_dequantize_1bit_fwd", "sylvie_dequantize_1bit_bwd",
+                     "sylvie_quantize_bbit_fwd", "sylvie_quantize_bbit_bwd",
+                     "sylvie_dequantize_bbit_fwd", "sylvie_dequantize_bbit_bwd",
                      "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
                      "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
                      "sylvie_aggregate_csr_bwd_integrate",
@@ -95,6 +99,44 @@ def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stre
 def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
     _quantize(lib().sylvie_quantize_1bit_bwd, src, ld_src, d, idx, row_offset, n_rows, seed,
               stream_id, wire_out)
+
+
+def sylvie_wire_row_words_bits(d: int, bits: int) -> int:
+    return int(lib().sylvie_wire_row_words_bits(int(d), int(bits)))
+
+
+def _quantize_bbit(fn, src, ld_src, d, idx, row_offset, n_rows, bits, seed, stream_id, wire_out):
+    _check(fn(_ptr(src, torch.float32, "src"), C.c_int64(ld_src), C.c_int32(d),
+              _ptr(idx, torch.int32, "idx"), C.c_int64(row_offset), C.c_int64(n_rows),
+              C.c_int32(bits), C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
+              _ptr(wire_out, torch.int64, "wire_out"), _stream()))
+
+
+def sylvie_quantize_bbit_fwd(src, ld_src, d, idx, row_offset, n_rows, bits, seed, stream_id,
+                             wire_out):
+    _quantize_bbit(lib().sylvie_quantize_bbit_fwd, src, ld_src, d, idx, row_offset, n_rows, bits,
+                   seed, stream_id, wire_out)
+
+
+def sylvie_quantize_bbit_bwd(src, ld_src, d, idx, row_offset, n_rows, bits, seed, stream_id,
+                             wire_out):
+    _quantize_bbit(lib().sylvie_quantize_bbit_bwd, src, ld_src, d, idx, row_offset, n_rows, bits,
+                   seed, stream_id, wire_out)
+
+
+def sylvie_dequantize_bbit_fwd(wire, n_rows, d, bits, dst, ld_dst, row_offset):
+    _check(lib().sylvie_dequantize_bbit_fwd(
+        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d), C.c_int32(bits),
+        _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), C.c_int64(row_offset), _stream()))
+
+
+def sylvie_dequantize_bbit_bwd(wire, n_rows, d, bits, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows,
+                               dst_ids):
+    _check(lib().sylvie_dequantize_bbit_bwd(
+        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d), C.c_int32(bits),
+        _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), _ptr(seg_ptr, torch.int64, "seg_ptr"),
+        _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int64(n_dst_rows),
+        _ptr(dst_ids, torch.int32, "dst_ids"), _stream()))
 
 
 def sylvie_dequantize_1bit_fwd(wire, n_rows, d, dst, ld_dst, row_offset):

@@ -19,6 +19,7 @@ _SOURCES = {
     "api.hip": [],
     "quantize.hip": ["-ffp-contract=off", "-fno-honor-nans"],
     "dequantize.hip": ["-ffp-contract=off"],
+    "lowbit_bbit.hip": ["-ffp-contract=off", "-fno-honor-nans"],
     "aggregate.hip": ["-ffp-contract=off"],
     "transform.hip": [],
 }

@@ -46,6 +46,13 @@ def test_version_and_strings(lib):
     assert b"argument" in lib.sylvie_status_string(-1)
     lib.sylvie_wire_row_words.restype = C.c_int64
     assert [lib.sylvie_wire_row_words(d) for d in (1, 64, 65, 100, 602)] == [2, 2, 3, 3, 11]
+    lib.sylvie_wire_row_words_bits.restype = C.c_size_t
+    w = lambda d, b: lib.sylvie_wire_row_words_bits(C.c_int32(d), C.c_int32(b))
+    assert [w(d, 1) for d in (1, 64, 65, 602)] == [2, 2, 3, 11]
+    assert [w(256, b) for b in (2, 4, 8, 16)] == [9, 17, 33, 64]
+    assert [w(d, 8) for d in (1, 8, 9, 602)] == [2, 2, 3, 77]
+    assert [w(d, 16) for d in (1, 4, 5, 602)] == [1, 1, 2, 151]
+    assert w(256, 3) == 0 and w(0, 4) == 0
 
 
 def test_bad_arguments_are_rejected_without_gpu(lib):
@@ -69,6 +76,19 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     dq.restype = C.c_int32
     assert dq(p, C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
     assert dq(p, C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
+    qb = lib.sylvie_quantize_bbit_fwd
+    qb.restype = C.c_int32
+    bargs = lambda bits, d=64, ld=64, n=8: [p, C.c_int64(ld), C.c_int32(d), None, C.c_int64(0),
+                                            C.c_int64(n), C.c_int32(bits), C.c_uint64(1),
+                                            C.c_uint32(0), p, None]
+    assert qb(*bargs(3)) == -1 and b"bits" in lib.sylvie_last_error()
+    assert qb(*bargs(4, d=65)) == -1
+    assert qb(*bargs(8, n=0)) == 0 and qb(*bargs(16, n=0)) == 0 and qb(*bargs(1, n=0)) == 0
+    dqb = lib.sylvie_dequantize_bbit_fwd
+    dqb.restype = C.c_int32
+    assert dqb(p, C.c_int64(4), C.c_int32(64), C.c_int32(5), p, C.c_int64(64), C.c_int64(0), None) == -1
+    assert dqb(p, C.c_int64(4), C.c_int32(64), C.c_int32(4), p, C.c_int64(32), C.c_int64(0), None) == -1
+    assert dqb(p, C.c_int64(0), C.c_int32(64), C.c_int32(4), p, C.c_int64(64), C.c_int64(0), None) == 0
     ag = lib.sylvie_aggregate_csr_fwd
     ag.restype = C.c_int32
     base = [p, p, None, None, None, C.c_int64(4), p, C.c_int64(64), C.c_int32(64), p,
