@@ -75,6 +75,18 @@ class OpTimer:
         def dqb_cost(wire, n, d, dst, ld, sp, sr, n_dst, di):
             return {"bytes": n * (W(d) + 8 + 4) + n_dst * (8 * d + 12), "rows": n}
 
+        def Wb(d, bits):                       # bytes of a whole wire row of the b-bit formats
+            return 8 * ((d + 3) // 4) if bits == 16 else 8 * ((d * bits + 63) // 64 + 1)
+
+        def qb_cost(src, ld, d, idx, off, n, bits, *rest):
+            return {"bytes": n * (4 * d + (4 if idx is not None else 0) + Wb(d, bits)), "rows": n}
+
+        def dqfb_cost(wire, n, d, bits, *rest):
+            return {"bytes": n * (Wb(d, bits) + 4 * d), "rows": n}
+
+        def dqbb_cost(wire, n, d, bits, dst, ld, sp, sr, n_dst, di):
+            return {"bytes": n * (Wb(d, bits) + 4) + n_dst * (8 * d + 12), "rows": n}
+
         def ag_cost(rp, cl, w, rs, cs, n_rows, X, ldx, d, Y, ldy, **kw):
             info = self.op_info[rp.data_ptr()]
             b = info["nnz"] * (4 + (4 if w is not None else 0)) + info["touched"] * 4 * d \
@@ -124,6 +136,10 @@ class OpTimer:
         self._wrap("sylvie_quantize_1bit_bwd", q_cost)
         self._wrap("sylvie_dequantize_1bit_fwd", dqf_cost)
         self._wrap("sylvie_dequantize_1bit_bwd", dqb_cost)
+        self._wrap("sylvie_quantize_bbit_fwd", qb_cost)
+        self._wrap("sylvie_quantize_bbit_bwd", qb_cost)
+        self._wrap("sylvie_dequantize_bbit_fwd", dqfb_cost)
+        self._wrap("sylvie_dequantize_bbit_bwd", dqbb_cost)
         self._wrap("sylvie_aggregate_csr_fwd", ag_cost)
         self._wrap("sylvie_aggregate_csr_bwd", ag_cost)
         self._wrap("sylvie_aggregate_csr_fwd_wire", agw_cost)
@@ -297,6 +313,35 @@ def lowbit_microbench(torch, B, loop, st, d, iters=10):
                        "frac_hbm_peak": tot_b / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     out["rows"] = n
     out["d"] = d
+    # the bit-width study (Sec. 5.4): the same four calls at b = 2, 4, 8 and on the
+    # half-precision wire; wire row bytes = 8 * sylvie_wire_row_words_bits(d, bits)
+    sweep = {}
+    for bits in (2, 4, 8, 16):
+        wb = 8 * B.sylvie_wire_row_words_bits(d, bits)
+        wire_b = torch.empty(n * wb // 8, dtype=torch.int64, device=dev)
+        cases = {
+            "quantize_fwd": (lambda: B.sylvie_quantize_bbit_fwd(src, d, d, idx, 0, n, bits, 1, 2, wire_b),
+                             n * (4 * d + 4 + wb)),
+            "dequantize_fwd": (lambda: B.sylvie_dequantize_bbit_fwd(wire_b, n, d, bits, halo, d, 0),
+                               n * (wb + 4 * d)),
+            "quantize_bwd": (lambda: B.sylvie_quantize_bbit_bwd(halo, d, d, None, 0, n, bits, 1, 3, wire_b),
+                             n * (4 * d + wb)),
+            "dequantize_bwd": (lambda: B.sylvie_dequantize_bbit_bwd(wire_b, n, d, bits, J, d, sp, sr, n_dst, di),
+                               n * (wb + 4) + n_dst * (8 * d + 12)),
+        }
+        row = {"wire_bytes_per_row": wb}
+        tb, tm = 0, 0.0
+        for name, (fn, nbytes) in cases.items():
+            ms = timed(fn)
+            row[name] = {"ms": ms, "GBps": nbytes / (ms * 1e-3) / 1e9,
+                         "frac_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            tb += nbytes
+            tm += ms
+        row["all four"] = {"ms": tm, "GBps": tb / (tm * 1e-3) / 1e9,
+                           "frac_hbm_peak": tb / (tm * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        sweep["fp16" if bits == 16 else f"{bits}bit"] = row
+        del wire_b
+    out["bit_width_sweep"] = sweep
     return out
 
 
@@ -308,6 +353,9 @@ def main():
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--nodes", type=int, default=0, help="shrink the workload to this many nodes")
     ap.add_argument("--chunk", type=int, default=1024)
+    ap.add_argument("--wire", default="1bit", choices=["1bit", "2bit", "4bit", "8bit", "fp16", "fp32"],
+                    help="exchange format: 1bit is the paper's method and the headline; the others "
+                         "are the points of its bit-width study (unfused quantize / dequantize)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (scales the rocprofv3 "
@@ -354,7 +402,7 @@ def main():
     forced = spec.name.startswith("tiny")
     t0 = time.time()
     loop = LayerLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, spec.model, spec.dims,
-                     chunk=args.chunk, exchange_first_layer=forced)
+                     chunk=args.chunk, exchange_first_layer=forced, wire=args.wire)
     torch.cuda.synchronize()
     log(f"[bench] set-up (operators, transpose, plans, buffers): {time.time() - t0:.1f} s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -415,7 +463,8 @@ def main():
         roof = {"kernel": dom_name, "bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": dom["GBps"] / HBM_PEAK_GBS, "traffic": None}
     roof["avg_launch_ms"] = dom["avg_ms_per_call"]
-    default_cfg = args.workload == "stress" and not args.nodes and args.chunk == 1024
+    default_cfg = (args.workload == "stress" and not args.nodes and args.chunk == 1024
+                   and args.wire == "1bit")
     if default_cfg and dom_name in ROCPROF_TRAFFIC_BYTES:
         roof["traffic"] = ROCPROF_TRAFFIC_BYTES[dom_name]
         roof["traffic_GBps"] = roof["traffic"] / (dom["avg_ms_per_call"] * 1e-3) / 1e9
@@ -428,6 +477,7 @@ def main():
         "config": {"workload": spec.name, "graph": spec.graph, "n_nodes": spec.n_nodes,
                    "n_in": p0.n_in, "n_halo": p0.n_halo, "nnz_adjacency": p0.nnz,
                    "layer_model": spec.model, "dims": list(spec.dims), "chunk": args.chunk,
+                   "wire": args.wire,
                    "value_is": "aggregated edges (fwd+bwd, all layers) per second of the whole "
                                "step, every hot-path kernel inside the timed region"},
         "roofline": roof,

@@ -9,6 +9,8 @@ partition whose halo rows all name itself is the "loopback" stand-in for absent
 peers.
 
 wire = "1bit": quantize -> (packed, scale, zero) -> dequantize (Sec. 3.2).
+wire = "2bit" / "4bit" / "8bit": the same with B = 2^b - 1 bins; wire = "fp16": rows
+rounded to binary16 (the other points of the bit-width study, Sec. 5.4).
 wire = "fp32": the rows are copied unchanged (vanilla full-precision exchange,
 Sec. 2.2), used where a check must not depend on the rounding randomness.
 """
@@ -20,6 +22,9 @@ from typing import List, Optional
 import numpy as np
 
 from . import api as O
+
+
+WIRE_BITS = {"2bit": 2, "4bit": 4, "8bit": 8}
 
 
 @dataclass
@@ -91,6 +96,13 @@ def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, w
                     pk, sc, zp = O.quantize_1bit(src, d, j1 - j0, pair_seed(seed, q, me),
                                                  2 * l + 0, idx=idx)
                     O.dequantize_1bit_fwd(pk, sc, zp, d, ht, p.n_in + j0)
+                elif wire in WIRE_BITS:
+                    b = WIRE_BITS[wire]
+                    pk, sc, zp = O.quantize_bbit(src, d, j1 - j0, b, pair_seed(seed, q, me),
+                                                 2 * l + 0, idx=idx)
+                    O.dequantize_bbit_fwd(pk, sc, zp, d, b, ht, p.n_in + j0)
+                elif wire == "fp16":
+                    O.recover_fp16_fwd(O.convert_fp16(src, d, j1 - j0, idx=idx), d, ht, p.n_in + j0)
                 else:
                     ht[p.n_in + j0: p.n_in + j1] = src[idx]
             p.Htil.append(ht)
@@ -153,5 +165,13 @@ def backward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, 
                     pk, sc, zp = O.quantize_1bit(g, d, j1 - j0, pair_seed(seed, me, q), 2 * l + 1,
                                                  row_offset=p.n_in + j0)
                     O.dequantize_1bit_bwd(pk, sc, zp, d, parts[q].Jin[l - 1], dst)
+                elif wire in WIRE_BITS:
+                    b = WIRE_BITS[wire]
+                    pk, sc, zp = O.quantize_bbit(g, d, j1 - j0, b, pair_seed(seed, me, q),
+                                                 2 * l + 1, row_offset=p.n_in + j0)
+                    O.dequantize_bbit_bwd(pk, sc, zp, d, b, parts[q].Jin[l - 1], dst)
+                elif wire == "fp16":
+                    O.recover_fp16_bwd(O.convert_fp16(g, d, j1 - j0, row_offset=p.n_in + j0), d,
+                                       parts[q].Jin[l - 1], dst)
                 else:
                     np.add.at(parts[q].Jin[l - 1], dst, g[p.n_in + j0: p.n_in + j1])

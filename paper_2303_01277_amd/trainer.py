@@ -64,6 +64,9 @@ class PartState:
     planT_inner: tuple = None
 
 
+WIRE_BITS = {"1bit": 1, "2bit": 2, "4bit": 4, "8bit": 8, "fp16": 16}
+
+
 class LayerLoop:
     """model: "gcn" (A_hat = D^-1/2 (A+I) D^-1/2, H = sigma(A_hat Htil W)) or "sage"
     (mean aggregator, H = sigma([H_self | mean] W)).  ReLU on all layers but the last."""
@@ -79,6 +82,11 @@ class LayerLoop:
         self.chunk = chunk
         self.exchange_first_layer = exchange_first_layer
         self.wire = wire
+        if wire not in WIRE_BITS and wire != "fp32":
+            raise ValueError(f"wire must be one of {sorted(WIRE_BITS)} or 'fp32'")
+        # bits per element on the wire: 1 = the paper's default; 2, 4, 8 and 16 (binary16)
+        # are the other points of its bit-width study (Sec. 5.4); None = float rows
+        self.bits = WIRE_BITS.get(wire)
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)
         self.fused = fused and wire == "1bit"
@@ -110,7 +118,7 @@ class LayerLoop:
                     blocks.append(Block(o, j, j + c, rows, sp, sr, di))
                     j += c
             st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
-            Wd = B.sylvie_wire_row_words(dmax)
+            Wd = self._words(dmax)
             st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
             st.ws_aggT = torch.empty(max(1, planT[2]) * dmax, dtype=torch.float32, device=dev)
@@ -158,6 +166,12 @@ class LayerLoop:
         if self.record is not None:
             self.record[key] = wire[: n * W].clone()
 
+    def _words(self, d):
+        """64-bit words of one wire row of width d."""
+        if self.bits in (None, 1):
+            return B.sylvie_wire_row_words(d)
+        return B.sylvie_wire_row_words_bits(d, self.bits)
+
     def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0):
         rp, cl, w = op
         lr, lp, nt = plan
@@ -171,7 +185,7 @@ class LayerLoop:
     def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
         for l in range(1, self.L + 1):
             d = self.dims[l - 1]
-            Wd = B.sylvie_wire_row_words(d)
+            Wd = self._words(d)
             for me, st in enumerate(self.parts):
                 ht = st.Htil[l - 1]
                 for b in st.blocks:
@@ -187,6 +201,13 @@ class LayerLoop:
                         if not self.fused:
                             B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
                                                          st.n_in + b.j0)
+                    elif self.bits:
+                        wire = st.wire[b.j0 * Wd:]
+                        B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
+                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
+                        self._keep(("fwd", l, me, b.j0), wire, n, Wd)
+                        B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
+                                                     st.n_in + b.j0)
                     else:   # full-precision exchange: plain device copy of the rows
                         ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
             for st in self.parts:
@@ -218,7 +239,7 @@ class LayerLoop:
         for l in range(self.L, 0, -1):
             d, h = self.dims[l - 1], self.dims[l]
             need_dx = l > 1 or self.exchange_first_layer
-            Wd = B.sylvie_wire_row_words(d)
+            Wd = self._words(d)
             for st in self.parts:
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
@@ -260,6 +281,14 @@ class LayerLoop:
                         self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
                         B.sylvie_dequantize_1bit_bwd(st.wire, n, d, tgt, tgt.stride(0), b.seg_ptr,
                                                      b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
+                    elif self.bits:
+                        B.sylvie_quantize_bbit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
+                                                   self.bits, pair_seed(seed, me, b.owner),
+                                                   2 * l + 1, st.wire)
+                        self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
+                        B.sylvie_dequantize_bbit_bwd(st.wire, n, d, self.bits, tgt, tgt.stride(0),
+                                                     b.seg_ptr, b.seg_rows,
+                                                     int(b.dst_ids.numel()), b.dst_ids)
                     else:
                         tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())
 

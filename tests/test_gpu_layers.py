@@ -30,6 +30,52 @@ def close(got, ref, S, what):
     assert not bad.any(), (what, int(bad.sum()), float((err / np.maximum(bound, 1e-300)).max()))
 
 
+def wire_words(d, bits):
+    return (d + 3) // 4 if bits == 16 else (d * bits + 63) // 64 + 1
+
+
+def o_quantize(oracle, bits, src, d, n, seed, stream, **kw):
+    """The oracle's wire for `bits` as one uint64 array [n, words] in the GPU's row format."""
+    from util import join_wire
+    if bits == 16:
+        return oracle.convert_fp16(src, d, n, **kw).view(np.uint64)
+    if bits == 1:
+        return join_wire(*oracle.quantize_1bit(src, d, n, seed, stream, **kw)).view(np.uint64)
+    return join_wire(*oracle.quantize_bbit(src, d, n, bits, seed, stream, **kw)).view(np.uint64)
+
+
+def o_dequantize(oracle, bits, wire, d, dst, row_offset=None, dst_row=None):
+    """Forward placement (row_offset) or backward accumulate (dst_row) of an oracle wire."""
+    if bits == 16:
+        w16 = np.ascontiguousarray(wire).view(np.uint16)
+        if dst_row is None:
+            oracle.recover_fp16_fwd(w16, d, dst, row_offset)
+        else:
+            oracle.recover_fp16_bwd(w16, d, dst, dst_row)
+        return
+    n = wire.shape[0]
+    pk = np.ascontiguousarray(wire[:, :-1])
+    meta = np.ascontiguousarray(wire[:, -1])
+    sc = (meta & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.float32)
+    zp = (meta >> np.uint64(32)).astype(np.uint32).view(np.float32)
+    assert pk.shape[0] == n
+    if bits == 1:
+        if dst_row is None:
+            oracle.dequantize_1bit_fwd(pk, sc, zp, d, dst, row_offset)
+        else:
+            oracle.dequantize_1bit_bwd(pk, sc, zp, d, dst, dst_row)
+    elif dst_row is None:
+        oracle.dequantize_bbit_fwd(pk, sc, zp, d, bits, dst, row_offset)
+    else:
+        oracle.dequantize_bbit_bwd(pk, sc, zp, d, bits, dst, dst_row)
+
+
+def gpu_wire(loop, key, n, d, bits):
+    w = np_c(loop.record[key]).view(np.uint64)
+    W = wire_words(d, bits)
+    return w[: n * W].reshape(n, W)
+
+
 def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False):
     from paper_2303_01277_amd.trainer import LayerLoop
     spec = wl.spec
@@ -51,6 +97,7 @@ def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False):
 def replay(oracle, wl, loop, pdata, seed):
     """Teacher-forced check of every step of one forward + backward pass."""
     model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
+    bits = loop.bits
     W = [np_c(w) for w in wl.W]
     ops = []
     for pd in pdata:
@@ -66,13 +113,10 @@ def replay(oracle, wl, loop, pdata, seed):
                 src = np_c(loop.parts[b.owner].Htil[l - 1])
                 idx = np_c(b.rows)
                 n = b.j1 - b.j0
-                ref = oracle.quantize_1bit(src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=idx)
-                pk, sc, zp = split_wire(np_c(loop.record[("fwd", l, me, b.j0)]), n, d)
-                assert np.array_equal(pk, ref[0]), ("fwd wire", l)
-                assert np.array_equal(bits32(sc), bits32(ref[1]))
-                assert np.array_equal(bits32(zp), bits32(ref[2]))
+                ref = o_quantize(oracle, bits, src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=idx)
+                assert np.array_equal(gpu_wire(loop, ("fwd", l, me, b.j0), n, d, bits), ref), ("fwd wire", l)
                 want = np.empty((n, d), np.float32)
-                oracle.dequantize_1bit_fwd(ref[0], ref[1], ref[2], d, want, 0)
+                o_dequantize(oracle, bits, ref, d, want, row_offset=0)
                 if loop.fused:
                     ht[st.n_in + b.j0: st.n_in + b.j1] = want
                 else:
@@ -92,6 +136,7 @@ def replay(oracle, wl, loop, pdata, seed):
 
 def replay_backward(oracle, wl, loop, pdata, seed, snaps):
     model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
+    bits = loop.bits
     W = [np_c(w) for w in wl.W]
     for l in range(L, 0, -1):
         d, h = dims[l - 1], dims[l]
@@ -126,13 +171,10 @@ def replay_backward(oracle, wl, loop, pdata, seed, snaps):
                     if b.owner != q:
                         continue
                     n = b.j1 - b.j0
-                    ref = oracle.quantize_1bit(gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
-                                               row_offset=st.n_in + b.j0)
-                    pk, sc, zp = split_wire(np_c(loop.record[("bwd", l, me, b.j0)]), n, d)
-                    assert np.array_equal(pk, ref[0]), ("bwd wire", l)
-                    assert np.array_equal(bits32(sc), bits32(ref[1]))
-                    assert np.array_equal(bits32(zp), bits32(ref[2]))
-                    oracle.dequantize_1bit_bwd(ref[0], ref[1], ref[2], d, want, np_c(b.rows))
+                    ref = o_quantize(oracle, bits, gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
+                                     row_offset=st.n_in + b.j0)
+                    assert np.array_equal(gpu_wire(loop, ("bwd", l, me, b.j0), n, d, bits), ref), ("bwd wire", l)
+                    o_dequantize(oracle, bits, ref, d, want, dst_row=np_c(b.rows))
             got = np_c(stq.dHtil[l - 1][: stq.n_in])
             assert np.array_equal(bits32(got), bits32(want)), ("J after integrate", l, q)
 
@@ -145,11 +187,20 @@ class SnapLoop:
         from paper_2303_01277_amd import binding as B
         snaps = {}
         orig_q = B.sylvie_quantize_1bit_bwd
+        orig_qb = B.sylvie_quantize_bbit_bwd
         state = {"l": None}
 
         # snapshot J^(l), dZ, dself and the pre-exchange dHtil of every partition: hook the
         # first backward quantize call of each layer (all aggregates of that layer are done)
+        def hook_b(src, ld, d, idx, off, n, bits, sd, stream_id, wire):
+            take(stream_id)
+            return orig_qb(src, ld, d, idx, off, n, bits, sd, stream_id, wire)
+
         def hook(src, ld, d, idx, off, n, sd, stream_id, wire):
+            take(stream_id)
+            return orig_q(src, ld, d, idx, off, n, sd, stream_id, wire)
+
+        def take(stream_id):
             l = (stream_id - 1) // 2
             if state["l"] != l:
                 state["l"] = l
@@ -164,13 +215,14 @@ class SnapLoop:
                             st.dself.view(-1)[: st.n_in * dd].view(st.n_in, dd)),
                         "dHtil_pre": np_c(st.dHtil[l - 1]),
                     }
-            return orig_q(src, ld, d, idx, off, n, sd, stream_id, wire)
 
         B.sylvie_quantize_1bit_bwd = hook
+        B.sylvie_quantize_bbit_bwd = hook_b
         try:
             loop.backward(seed, OL.pair_seed)
         finally:
             B.sylvie_quantize_1bit_bwd = orig_q
+            B.sylvie_quantize_bbit_bwd = orig_qb
         torch.cuda.synchronize()
         return snaps
 
@@ -193,6 +245,25 @@ def test_layer_loop_teacher_forced(oracle, cfg, n_nodes, fused):
     loop = build_loop(wl, fused=fused)
     loop.record = {}
     seed = 0x5EED0000 + len(cfg)
+    loop.forward(seed, OL.pair_seed)
+    torch.cuda.synchronize()
+    replay(oracle, wl, loop, pdata, seed)
+    snaps = SnapLoop.run(loop, seed)
+    replay_backward(oracle, wl, loop, pdata, seed, snaps)
+
+
+@pytest.mark.parametrize("wire", ["2bit", "4bit", "8bit", "fp16"])
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("co_purchase", 12_000), ("dense_social", 5_000)])
+def test_layer_loop_bit_widths(oracle, cfg, n_nodes, wire):
+    """The other wire formats of the bit-width study (Sec. 5.4) through the same
+    teacher-forced replay: wires bit-exact, recovered rows and accumulate bit-exact."""
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    pdata = to_partdata(wl)
+    loop = build_loop(wl, wire=wire)
+    assert not loop.fused and not loop.fused_bwd
+    loop.record = {}
+    seed = 0xB175 + len(cfg)
     loop.forward(seed, OL.pair_seed)
     torch.cuda.synchronize()
     replay(oracle, wl, loop, pdata, seed)

@@ -146,3 +146,32 @@ def test_one_bit_loop_runs_and_is_unbiased_in_the_mean(oracle):
     assert err_mean < err_one * 2.5 / np.sqrt(S) + 1e-7
     OL.backward(parts, "gcn", W, 0, "1bit", exchange_first_layer=True)
     assert parts[0].Jin[0].shape == parts[0].X.shape and np.isfinite(parts[0].Jin[0]).all()
+
+
+def test_more_bits_less_exchange_error(oracle):
+    """Bit-width study (Sec. 5.4): against the full-precision exchange, the error that the
+    wire adds to the layer outputs and to the propagated gradients shrinks as the wire gets
+    wider: 1 > 2 > 4 > 8 bits > half precision."""
+    import numpy as np
+    from oracle import layers as OL
+    from synth import CONFIGS, build_workload
+    from util import np_c, to_partdata
+    wl = build_workload(CONFIGS["tiny"])
+    W = [np_c(w) for w in wl.W]
+
+    def run(wire):
+        pd = to_partdata(wl)
+        OL.forward(pd, wl.spec.model, W, 7, wire)
+        OL.backward(pd, wl.spec.model, W, 7, wire, exchange_first_layer=True)
+        return (np.concatenate([p.H[-1].ravel() for p in pd]).astype(np.float64),
+                np.concatenate([p.Jin[0].ravel() for p in pd]).astype(np.float64))
+
+    ref_h, ref_j = run("fp32")
+    errs_h, errs_j = [], []
+    for wire in ("1bit", "2bit", "4bit", "8bit", "fp16"):
+        h, j = run(wire)
+        errs_h.append(np.linalg.norm(h - ref_h) / np.linalg.norm(ref_h))
+        errs_j.append(np.linalg.norm(j - ref_j) / np.linalg.norm(ref_j))
+    assert all(a > 1.5 * b for a, b in zip(errs_h, errs_h[1:])), errs_h
+    assert all(a > 1.5 * b for a, b in zip(errs_j, errs_j[1:])), errs_j
+    assert errs_h[-1] < 1e-3 and errs_j[-1] < 1e-3
