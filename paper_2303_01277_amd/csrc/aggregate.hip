@@ -26,8 +26,14 @@
 //     columns 64 apart", the layout in which a wave-wide compare is a packed word)
 //     and write only the wire row; or, for the inner block, add the dequantized
 //     wire rows that belong to it (Alg. 2 "integrate") before the one store.
+#include <type_traits>
+
 #include "common.hpp"
 #include "rounding.hpp"
+
+#ifndef SYLVIE_UW4
+#define SYLVIE_UW4 8
+#endif
 
 namespace sylvie {
 
@@ -117,9 +123,21 @@ __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int c
 // halo row costs 8 W + 8 bytes instead of 4 d.  Inside a row all dense columns
 // precede all wire columns (columns ascending), so each 64-entry batch splits
 // at one point found with a ballot.
+//
+// WIRE with a full-width lane group (G == 64): the wire entries are summed in a second
+// set of accumulators, accw[k] = column 64 k + lane, because in that layout word k of a
+// wire row IS the lane mask of the select between its two levels: the words come in
+// through scalar loads, one v_cndmask + one v_fma per word and entry.  The weight and
+// the two levels of an entry reach all lanes through a broadcast read of a record that
+// the lane owning the entry put into LDS (`bcast`, 64 records of 16 bytes per wave).
+// The caller folds accw into acc afterwards (merge_wire_sums); `used_w` says whether
+// there is anything to fold.
 template <int VEC, int G, int P, bool WIRE>
 __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int64_t e1,
-                                           const AggArgs &a, int lane)
+                                           const AggArgs &a, int lane,
+                                           [[maybe_unused]] float (&accw)[P * VEC],
+                                           [[maybe_unused]] float *bcast,
+                                           [[maybe_unused]] bool &used_w)
 {
     constexpr int EP = 64 / G;                 // rows gathered at once
     constexpr int U = (P >= 4) ? 2 : (8 / P);  // gathers in flight per lane group
@@ -219,6 +237,83 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 const float my_zp = __uint_as_float(meta.y);
                 const float my_hi = my_zp + __uint_as_float(meta.x);
                 const float my_ww = mine ? my_w : 0.0f;
+                if constexpr (EP == 1) {
+                    typedef const __attribute__((address_space(4))) uint64_t *const_words;
+                    constexpr int NW = P * VEC;                     // >= words per wire row
+                    constexpr int UW = NW <= 4 ? SYLVIE_UW4 : (NW <= 8 ? 2 : 1);
+                    const int W = W32 >> 1;
+                    reinterpret_cast<float4 *>(bcast)[lane] = make_float4(my_ww, my_zp, my_hi, 0.0f);
+                    used_w = true;
+                    const_words wbase = (const_words)(reinterpret_cast<uintptr_t>(a.wire32));
+                    // N entries starting at batch slot j0 (all valid): their mask words by
+                    // scalar loads, their records by broadcast reads, then select + FMA.
+                    // FULLW: the row has exactly NW words; otherwise the words past the last
+                    // one re-read the metadata word and feed accumulators nobody reads.
+                    auto entries = [&](auto n_c, auto full_c, int j0) {
+                        constexpr int N = decltype(n_c)::value;
+                        constexpr bool FULLW = decltype(full_c)::value;
+                        float4 rec[N];
+                        const float4 *recs = reinterpret_cast<const float4 *>(bcast) + j0;
+                        if constexpr (FULLW && NW == 4) {
+                            // the four words of each entry in one scalar load; all N loads are
+                            // issued before the first use so that N rows are in flight.  The
+                            // loads are written out because the compiler, short of scalar
+                            // registers, otherwise issues them one at a time.
+                            typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+                            u32x8 m8[N];
+#pragma unroll
+                            for (int u = 0; u < N; ++u) {
+                                const int64_t wr =
+                                    static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
+                                const_words prow = wbase + wr * (NW + 1);
+                                asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(m8[u]) : "s"(prow));
+                                rec[u] = recs[u];
+                            }
+                            asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+                            for (int u = 0; u < N; ++u) asm volatile("" : "+s"(m8[u]));   // uses come after the wait
+#pragma unroll
+                            for (int u = 0; u < N; ++u)
+#pragma unroll
+                                for (int k = 0; k < NW; ++k) {
+                                    const uint64_t mk = (static_cast<uint64_t>(m8[u][2 * k + 1]) << 32) | m8[u][2 * k];
+                                    float x;
+                                    asm("v_cndmask_b32_e64 %0, %1, %2, %3"
+                                        : "=v"(x)
+                                        : "v"(rec[u].y), "v"(rec[u].z), "s"(mk));
+                                    accw[k] = fmaf(rec[u].x, x, accw[k]);
+                                }
+                        } else {
+                            uint64_t m[N][NW];
+#pragma unroll
+                            for (int u = 0; u < N; ++u) {
+                                const int64_t wr =
+                                    static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
+                                const_words prow = wbase + wr * (W + 1);
+#pragma unroll
+                                for (int k = 0; k < NW; ++k) m[u][k] = prow[FULLW ? k : (k < W ? k : W)];
+                                rec[u] = recs[u];
+                            }
+#pragma unroll
+                            for (int u = 0; u < N; ++u)
+#pragma unroll
+                                for (int k = 0; k < NW; ++k) {
+                                    float x;
+                                    asm("v_cndmask_b32_e64 %0, %1, %2, %3"
+                                        : "=v"(x)
+                                        : "v"(rec[u].y), "v"(rec[u].z), "s"(m[u][k]));
+                                    accw[k] = fmaf(rec[u].x, x, accw[k]);
+                                }
+                        }
+                    };
+                    auto all_entries = [&](auto full_c) {
+                        int jj = nd;
+                        for (; jj + UW <= cnt; jj += UW) entries(std::integral_constant<int, UW>{}, full_c, jj);
+                        for (; jj < cnt; ++jj) entries(std::integral_constant<int, 1>{}, full_c, jj);
+                    };
+                    if (W == NW) all_entries(std::true_type{});
+                    else all_entries(std::false_type{});
+                } else {
                 constexpr int UW = (P >= 4) ? 4 : (16 / P);
                 for (j = nd - nd % EP; j < cnt; j += EP * UW) {
                     uint32_t dw[UW][P];
@@ -226,26 +321,15 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
 #pragma unroll
                     for (int u = 0; u < UW; ++u) {
                         const int sl = j + u * EP + sub;
-                        int64_t wr;
-                        if constexpr (EP == 1) {
-                            const int slc = sl < cnt ? sl : cnt - 1;   // wave-uniform, >= nd
-                            wr = static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, slc)) - a.n_dense;
-                            wv[u] = sl < cnt ? __int_as_float(__builtin_amdgcn_readlane(
-                                                   __float_as_int(my_ww), slc))
-                                             : 0.0f;
-                            zp[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_zp), slc));
-                            hi[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_hi), slc));
-                        } else {
-                            const int src = sl & 63;
-                            const bool ok = sl >= nd && sl < cnt;
-                            // every lane takes part in the lane reads; select afterwards
-                            const int cs = __shfl(my_c, src);
-                            wr = ok ? static_cast<int64_t>(cs) - a.n_dense : 0;
-                            wv[u] = __shfl(my_ww, src);
-                            if (!ok) wv[u] = 0.0f;
-                            zp[u] = __shfl(my_zp, src);
-                            hi[u] = __shfl(my_hi, src);
-                        }
+                        const int src = sl & 63;
+                        const bool ok = sl >= nd && sl < cnt;
+                        // every lane takes part in the lane reads; select afterwards
+                        const int cs = __shfl(my_c, src);
+                        const int64_t wr = ok ? static_cast<int64_t>(cs) - a.n_dense : 0;
+                        wv[u] = __shfl(my_ww, src);
+                        if (!ok) wv[u] = 0.0f;
+                        zp[u] = __shfl(my_zp, src);
+                        hi[u] = __shfl(my_hi, src);
                         const uint32_t *pr = a.wire32 + wr * (W32 + 2);
 #pragma unroll
                         for (int p = 0; p < P; ++p) dw[u][p] = pr[coff[p] >> 5];
@@ -268,6 +352,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             }
                         }
                 }
+                }
             }
         }
     }
@@ -282,6 +367,24 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
     }
 }
 
+// acc += accw, the latter moved from "lane = column 64 k + lane" to the lane's own VEC
+// adjacent columns through a wave-private LDS row of 64 P VEC floats.
+template <int VEC, int P>
+__device__ __forceinline__ void merge_wire_sums(float (&acc)[P][VEC], const float (&accw)[P * VEC],
+                                                float *row, int d, int lane)
+{
+#pragma unroll
+    for (int k = 0; k < P * VEC; ++k) row[64 * k + lane] = accw[k];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const int cc = (p * 64 + lane) * VEC;
+        if (cc < d) {
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) acc[p][t] += row[cc + t];
+        }
+    }
+}
+
 // One launch covers everything that gathers.  The first ceil(n_tasks/4) workgroups
 // take the pieces of the long rows (they start first, so the heaviest rows never
 // trail the launch); every later wavefront takes one ordinary row and skips the
@@ -292,6 +395,14 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
 {
     constexpr int kStage = EPI == kEpiQuantize ? VEC * G * P : 1;
     __shared__ float stage[kAgWavesPerBlock][kStage];
+    // wire entries of full-width rows: broadcast records, then the fold of their sums
+    constexpr bool kWireAcc = WIRE && G == 64;
+    constexpr int kWStage = kWireAcc ? (64 * P * VEC > 256 ? 64 * P * VEC : 256) : 4;
+    __shared__ __align__(16) float wstage[kAgWavesPerBlock][kWStage];
+    float accw[P * VEC];
+#pragma unroll
+    for (int k = 0; k < P * VEC; ++k) accw[k] = 0.0f;
+    bool used_w = false;
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t task_blocks = (n_tasks + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
@@ -317,7 +428,10 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         const int64_t r1 = uniform(a.rowptr[v + 1]);
         const int64_t e0 = r0 + piece * a.chunk;
         const int64_t e1 = e0 + a.chunk < r1 ? e0 + a.chunk : r1;
-        gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane);
+        gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane, accw, wstage[wave], used_w);
+        if constexpr (kWireAcc) {
+            if (used_w) merge_wire_sums<VEC, P>(acc, accw, wstage[wave], a.d, lane);
+        }
         if (lane >= G) return;
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -333,7 +447,10 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
     const int64_t e0 = uniform(a.rowptr[v]);
     const int64_t e1 = uniform(a.rowptr[v + 1]);
     if (a.chunk > 0 && e1 - e0 > a.chunk) return;
-    gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane);
+    gather_sum<VEC, G, P, WIRE>(acc, e0, e1, a, lane, accw, wstage[wave], used_w);
+    if constexpr (kWireAcc) {
+        if (used_w) merge_wire_sums<VEC, P>(acc, accw, wstage[wave], a.d, lane);
+    }
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
     if (lane < G) {

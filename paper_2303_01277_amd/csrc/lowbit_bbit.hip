@@ -66,10 +66,10 @@ __device__ __forceinline__ uint32_t bb_code(float x, const BbRow &r, uint32_t ct
     if constexpr (TINY) diff = diff * 0x1p64f;
     float t = diff * r.inv;
     t = t > Bf ? Bf : t;
-    const float fl = __builtin_floorf(t);
-    const float fr = t - fl;
+    // t >= 0: the conversion truncates to floor(t) and v_fract_f32 is t - floor(t), exact
+    const float fr = __builtin_amdgcn_fractf(t);
     const float u = static_cast<float>(draw24(ctr)) * kTwoM24;
-    return static_cast<uint32_t>(fl) + (u < fr ? 1u : 0u);
+    return static_cast<uint32_t>(t) + (u < fr ? 1u : 0u);
 }
 
 // P passes of 64 VEC columns cover the row (64 VEC (P-1) < d <= 64 VEC P).  VEC = 4

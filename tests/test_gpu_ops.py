@@ -282,12 +282,13 @@ def test_transform_strided(oracle, n, k1, k2, h):
             assert bool((dA2[:, k2:] == 7.0).all())
 
 
-@pytest.mark.parametrize("d", [2, 64, 100, 128, 256, 602])
+@pytest.mark.parametrize("d", [2, 64, 100, 128, 160, 256, 300, 602, 1024])
 @pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 40_000, "gcn"),
                                                ("co_purchase", 30_000, "sage")])
 def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
     """Fused dequantize + aggregate: against the oracle's dequantize followed by its
-    aggregate, and bit for bit against the GPU's own two-step path."""
+    aggregate, and against the GPU's own two-step path (same terms; wide rows sum their
+    wire entries in accumulators of their own, so the order of the additions differs)."""
     from paper_2303_01277_amd import binding as B
     from paper_2303_01277_amd import graph_engine as GE
     p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
@@ -316,7 +317,7 @@ def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):
         B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, Y2, d, **kw)
         torch.cuda.synchronize()
         close(Y.cpu().numpy(), Z, S, ("wire", chunk))
-        assert np.array_equal(bits32(Y.cpu().numpy()), bits32(Y2.cpu().numpy())), chunk
+        close(Y.cpu().numpy(), Y2.cpu().numpy().astype(np.float64), S, ("wire vs two-step", chunk))
 
 
 @pytest.mark.parametrize("d", [2, 7, 64, 100, 256, 602])
