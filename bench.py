@@ -345,6 +345,29 @@ def lowbit_microbench(torch, B, loop, st, d, iters=10):
     return out
 
 
+def pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced):
+    """Sylvie-A (Sec. 3.3) on one GPU: epochs that compute with the previous epoch's wires while
+    this epoch's wires are produced on a second stream, against sequential epochs of the same
+    loop object.  Without a transport the only thing left to overlap is the Low-bit Module's
+    own kernels, so the saving is small by construction; it is reported, not folded into value."""
+    loop = LayerLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, spec.model, spec.dims,
+                     chunk=args.chunk, exchange_first_layer=forced, pipeline=True)
+    seed = 20230301
+    loop.step(seed, mode="sync")
+    loop.step(seed + 1, mode="async")
+    torch.cuda.synchronize()
+    res = {}
+    for mode in ("sync", "async", "sync", "async"):
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            loop.step(seed + 10 + i, mode=mode)
+        torch.cuda.synchronize()
+        res.setdefault(mode, []).append((time.perf_counter() - t0) * 1e3 / args.steps)
+    a, b = min(res["sync"]), min(res["async"])
+    return {"ms_per_step_sequential": a, "ms_per_step_pipelined": b, "saving_ms": a - b,
+            "schedule": "every epoch after the first in pipeline mode (eps_s = infinity)"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -490,6 +513,8 @@ def main():
                         for kk, vv in v.items()} for k, v in ops.items()},
     }
     out["lowbit_kernels"] = lowbit_microbench(torch, B, loop, loop.parts[0], spec.dims[-2])
+    if args.wire == "1bit":
+        out["pipeline"] = pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(torch, loop, loop.parts[0], spec.dims)

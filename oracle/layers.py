@@ -11,6 +11,9 @@ peers.
 wire = "1bit": quantize -> (packed, scale, zero) -> dequantize (Sec. 3.2).
 wire = "2bit" / "4bit" / "8bit": the same with B = 2^b - 1 bins; wire = "fp16": rows
 rounded to binary16 (the other points of the bit-width study, Sec. 5.4).
+Sylvie-A (Sec. 3.3): with `prev` given, every layer computes with the wires of the
+previous epoch found there, while this epoch's wires are still produced (and stored in
+`keep`), to be used by the next epoch.  1-bit wire only.
 wire = "fp32": the rows are copied unchanged (vanilla full-precision exchange,
 Sec. 2.2), used where a check must not depend on the rounding randomness.
 """
@@ -75,9 +78,14 @@ def build_operator(p: PartData, model: str):
         raise ValueError(model)
 
 
-def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, wire="1bit"):
-    """Alg. 1 lines 8-17 for one epoch."""
+def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, wire="1bit",
+            prev: Optional[dict] = None, keep: Optional[dict] = None):
+    """Alg. 1 lines 8-17 for one epoch.  keep: dict that receives this epoch's wires under
+    ("fwd", l, receiver, j0); prev: such a dict of the previous epoch, whose wires are then
+    the ones dequantized into the halo block (Sylvie-A)."""
     L = len(W)
+    if (prev is not None or keep is not None) and wire != "1bit":
+        raise ValueError("prev / keep are for the 1-bit wire")
     for me, p in enumerate(parts):
         if p.op is None:
             build_operator(p, model)
@@ -95,6 +103,10 @@ def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, w
                 if wire == "1bit":
                     pk, sc, zp = O.quantize_1bit(src, d, j1 - j0, pair_seed(seed, q, me),
                                                  2 * l + 0, idx=idx)
+                    if keep is not None:
+                        keep[("fwd", l, me, j0)] = (pk, sc, zp)
+                    if prev is not None:
+                        pk, sc, zp = prev[("fwd", l, me, j0)]
                     O.dequantize_1bit_fwd(pk, sc, zp, d, ht, p.n_in + j0)
                 elif wire in WIRE_BITS:
                     b = WIRE_BITS[wire]
@@ -119,7 +131,7 @@ def forward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, w
 
 
 def backward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, wire="1bit",
-             exchange_first_layer=False):
+             exchange_first_layer=False, prev: Optional[dict] = None, keep: Optional[dict] = None):
     """Alg. 2 for one epoch (weight gradients stay per partition: no all-reduce).
 
     exchange_first_layer=True also computes and exchanges J^(0), as if another
@@ -164,6 +176,10 @@ def backward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, 
                 if wire == "1bit":
                     pk, sc, zp = O.quantize_1bit(g, d, j1 - j0, pair_seed(seed, me, q), 2 * l + 1,
                                                  row_offset=p.n_in + j0)
+                    if keep is not None:
+                        keep[("bwd", l, me, j0)] = (pk, sc, zp)
+                    if prev is not None:
+                        pk, sc, zp = prev[("bwd", l, me, j0)]
                     O.dequantize_1bit_bwd(pk, sc, zp, d, parts[q].Jin[l - 1], dst)
                 elif wire in WIRE_BITS:
                     b = WIRE_BITS[wire]

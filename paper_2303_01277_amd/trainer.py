@@ -1,4 +1,7 @@
-"""Per-layer call sequence of Sylvie-S on one GPU (Alg. 1 forward, Alg. 2 backward).
+"""Per-layer call sequence of Sylvie-S on one GPU (Alg. 1 forward, Alg. 2 backward), and
+of Sylvie-A (Sec. 3.3): the same calls, but every layer computes with the wires received
+in the previous epoch while this epoch's wires are produced on a second stream, with a
+sequential epoch every eps_s epochs (Bounded Staleness Adaptor).
 
 Every partition handed in lives on the same GPU; "send / receive" is the wire
 arrays staying where the quantizer wrote them.  This module only allocates device
@@ -9,6 +12,8 @@ from __future__ import annotations
 
 from dataclasses import dataclass, field
 from typing import Callable, List, Optional
+
+import contextlib
 
 import torch
 
@@ -62,6 +67,10 @@ class PartState:
     inb_seg_ptr: Optional[torch.Tensor] = None                # int64 [n_in + 1]
     inb_seg_rows: Optional[torch.Tensor] = None               # int32 [n_inbound]
     planT_inner: tuple = None
+    # pipeline mode: one wire per layer and two generations of each (this epoch / previous)
+    fwd_wires: Optional[list] = None                          # [gen][l] int64 words
+    inb_wires: Optional[list] = None                          # [gen][l] int64 words
+    ws_aggT2: Optional[torch.Tensor] = None                   # long-row workspace of the side stream
 
 
 WIRE_BITS = {"1bit": 1, "2bit": 2, "4bit": 4, "8bit": 8, "fp16": 16}
@@ -73,7 +82,7 @@ class LayerLoop:
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
                  exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True,
-                 fused_bwd: bool = True):
+                 fused_bwd: bool = True, pipeline: bool = False):
         """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
         partition int32 tensors naming the owner partition and owner-local inner row of
         each halo row (grouped by owner, ascending)."""
@@ -95,6 +104,13 @@ class LayerLoop:
         # separate quantize / dequantize passes)
         self.fused_bwd = fused_bwd and wire == "1bit"
         self.record = None          # set to a dict to keep copies of every wire
+        # pipeline: keep every layer's wires of this and of the previous epoch so that an
+        # epoch can run on the previous epoch's wires (mode "async" of forward / backward)
+        self.pipeline = pipeline
+        if pipeline and wire != "1bit":
+            raise ValueError("pipeline mode is built for the 1-bit wire")
+        self.gen = 0                # generation that holds the wires of the running epoch
+        self.have_prev = False
         dev = X[0].device
         self.dev = dev
         dmax = max(dims)
@@ -143,7 +159,7 @@ class LayerLoop:
             if model == "sage":
                 st.dself = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
             self.parts.append(st)
-        if self.fused_bwd:
+        if self.fused_bwd or pipeline:
             Wd = B.sylvie_wire_row_words(dmax)
             for q, sq in enumerate(self.parts):
                 dst = []
@@ -160,6 +176,21 @@ class LayerLoop:
                 sq.inb_seg_ptr, sq.inb_seg_rows = GE.scatter_segments_dense(dst, sq.n_in)
                 sq.inbound = torch.empty(max(1, sq.n_inbound) * Wd, dtype=torch.int64, device=dev)
                 sq.planT_inner = GE.long_row_plan(sq.opT[0], chunk, 0, sq.n_in)
+        if pipeline:
+            self.side = torch.cuda.Stream()        # default priority
+            lo = 1 if exchange_first_layer else 2  # layers whose backward exchanges gradients
+            for st in self.parts:
+                st.fwd_wires = [[None] * (self.L + 1) for _ in range(2)]
+                st.inb_wires = [[None] * (self.L + 1) for _ in range(2)]
+                for g in range(2):
+                    for l in range(1, self.L + 1):
+                        Wl = B.sylvie_wire_row_words(dims[l - 1])
+                        st.fwd_wires[g][l] = torch.empty(max(1, st.n_halo) * Wl, dtype=torch.int64,
+                                                         device=dev)
+                        if l >= lo:
+                            st.inb_wires[g][l] = torch.empty(max(1, st.n_inbound) * Wl,
+                                                             dtype=torch.int64, device=dev)
+                st.ws_aggT2 = torch.empty_like(st.ws_aggT)
 
     # -- helpers ---------------------------------------------------------------
     def _keep(self, key, wire, n, W):
@@ -182,7 +213,12 @@ class LayerLoop:
            workspace=ws if nt else None)
 
     # -- Alg. 1 ------------------------------------------------------------------
-    def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+    def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed,
+                mode: str = "sync"):
+        if self.pipeline:
+            return self._forward_pipeline(seed, pair_seed, mode)
+        if mode != "sync":
+            raise ValueError("mode 'async' needs pipeline=True")
         for l in range(1, self.L + 1):
             d = self.dims[l - 1]
             Wd = self._words(d)
@@ -235,7 +271,12 @@ class LayerLoop:
                                            st.n_in, relu, Hout, Hout.stride(0))
 
     # -- Alg. 2 ------------------------------------------------------------------
-    def backward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+    def backward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed,
+                 mode: str = "sync"):
+        if self.pipeline:
+            return self._backward_pipeline(seed, pair_seed, mode)
+        if mode != "sync":
+            raise ValueError("mode 'async' needs pipeline=True")
         for l in range(self.L, 0, -1):
             d, h = self.dims[l - 1], self.dims[l]
             need_dx = l > 1 or self.exchange_first_layer
@@ -323,3 +364,174 @@ class LayerLoop:
                 st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
                 long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
                 workspace=st.ws_aggT if nt else None)
+
+    # -- Sylvie-A (Sec. 3.3): pipeline mode ------------------------------------------
+    def _gen(self, which):
+        return self.gen if which == "cur" else self.gen ^ 1
+
+    def _side(self, stale):
+        """Context in which this epoch's wires are produced: the side stream when the layer
+        computes with the previous epoch's wires, the caller's stream otherwise."""
+        if not stale:
+            return contextlib.nullcontext()
+        self.side.wait_stream(torch.cuda.current_stream())
+        return torch.cuda.stream(self.side)
+
+    def _check_mode(self, mode):
+        if mode not in ("sync", "async"):
+            raise ValueError("mode must be 'sync' or 'async'")
+        if mode == "async" and not self.have_prev:
+            raise ValueError("the first epoch has no previous wires: run it with mode='sync'")
+        return mode == "async"
+
+    def _forward_pipeline(self, seed, pair_seed, mode):
+        stale = self._check_mode(mode)
+        main = torch.cuda.current_stream()
+        use = "prev" if stale else "cur"
+        for l in range(1, self.L + 1):
+            d = self.dims[l - 1]
+            Wd = B.sylvie_wire_row_words(d)
+            # this epoch's wires (every partition's H^(l-1) is complete on the main stream)
+            with self._side(stale):
+                for me, st in enumerate(self.parts):
+                    cur = st.fwd_wires[self._gen("cur")][l]
+                    for b in st.blocks:
+                        src = self.parts[b.owner].Htil[l - 1]
+                        wire = cur[b.j0 * Wd:]
+                        B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, b.j1 - b.j0,
+                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
+                        self._keep(("fwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
+            for st in self.parts:
+                ht, Z = st.Htil[l - 1], st.Z[l - 1]
+                wire = st.fwd_wires[self._gen(use)][l]
+                if self.fused:
+                    rp, cl, w = st.op
+                    lr, lp, nt = st.plan
+                    B.sylvie_aggregate_csr_fwd_wire(
+                        rp, cl, w, None, None, st.n_in, ht, ht.stride(0), d, st.n_in, wire,
+                        st.n_halo, Z, Z.stride(0), chunk=self.chunk,
+                        long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                        n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                        workspace=st.ws_agg if nt else None)
+                else:
+                    if st.n_halo:
+                        B.sylvie_dequantize_1bit_fwd(wire, st.n_halo, d, ht, ht.stride(0), st.n_in)
+                    self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
+                                    st.n_in, ht, d, Z)
+                relu = l != self.L
+                Hout = st.Htil[l] if l < self.L else st.out
+                h = self.dims[l]
+                if self.model == "gcn":
+                    B.sylvie_transform_fwd(Z, Z.stride(0), d, None, 0, 0, self.W[l - 1], h, st.n_in,
+                                           relu, Hout, Hout.stride(0))
+                else:
+                    B.sylvie_transform_fwd(ht, ht.stride(0), d, Z, Z.stride(0), d, self.W[l - 1], h,
+                                           st.n_in, relu, Hout, Hout.stride(0))
+        if stale:
+            main.wait_stream(self.side)
+
+    def _backward_pipeline(self, seed, pair_seed, mode):
+        stale = self._check_mode(mode)
+        main = torch.cuda.current_stream()
+        use = "prev" if stale else "cur"
+        for l in range(self.L, 0, -1):
+            d, h = self.dims[l - 1], self.dims[l]
+            need_dx = l > 1 or self.exchange_first_layer
+            Wd = B.sylvie_wire_row_words(d)
+            for st in self.parts:
+                relu = l != self.L
+                Hout = st.Htil[l] if l < self.L else st.out
+                Jl = st.J if l == self.L else st.dHtil[l]
+                ht, Z = st.Htil[l - 1], st.Z[l - 1]
+                dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+                if self.model == "gcn":
+                    B.sylvie_transform_bwd(Z, Z.stride(0), d, None, 0, 0, self.W[l - 1], h, st.n_in,
+                                           relu, Hout, Hout.stride(0), Jl, Jl.stride(0), st.G[l],
+                                           dZ if need_dx else None, d, None, 0, st.ws_g)
+                    dself = None
+                else:
+                    dself = st.dself.view(-1)[: st.n_in * d].view(st.n_in, d)
+                    B.sylvie_transform_bwd(ht, ht.stride(0), d, Z, Z.stride(0), d, self.W[l - 1], h,
+                                           st.n_in, relu, Hout, Hout.stride(0), Jl, Jl.stride(0),
+                                           st.G[l], dself if need_dx else None, d,
+                                           dZ if need_dx else None, d, st.ws_g)
+                if need_dx and not self.fused_bwd:
+                    g = st.dHtil[l - 1]
+                    self._aggregate(B.sylvie_aggregate_csr_bwd, st.opT, st.planT, st.ws_aggT,
+                                    st.n_in + st.n_halo, dZ, d, g, addend=dself,
+                                    addend_rows=st.n_in)
+            if not need_dx:
+                continue
+            # this epoch's gradient wires, written into the owners' inbound buffers
+            with self._side(stale):
+                for me, st in enumerate(self.parts):
+                    rpT, clT, wT = st.opT
+                    dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+                    g = st.dHtil[l - 1]
+                    for b in st.blocks:
+                        tgt = self.parts[b.owner]
+                        wire = tgt.inb_wires[self._gen("cur")][l][b.inb_off * Wd:]
+                        if self.fused_bwd:
+                            lr, lp, nt = b.planT
+                            ws = st.ws_aggT2 if stale else st.ws_aggT
+                            B.sylvie_aggregate_csr_bwd_quantize(
+                                rpT, clT, wT, None, None, st.n_in + b.j0, b.j1 - b.j0, dZ, d, d,
+                                pair_seed(seed, me, b.owner), 2 * l + 1, wire, chunk=self.chunk,
+                                long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                                n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                                workspace=ws if nt else None)
+                        else:
+                            B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0,
+                                                       b.j1 - b.j0, pair_seed(seed, me, b.owner),
+                                                       2 * l + 1, wire)
+                        self._keep(("bwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
+            # integrate the gradient wires in use (Alg. 2, J = J + R~)
+            for st in self.parts:
+                inb = st.inb_wires[self._gen(use)][l]
+                g = st.dHtil[l - 1]
+                if self.fused_bwd:
+                    rpT, clT, wT = st.opT
+                    dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
+                    dself = None
+                    if self.model == "sage":
+                        dself = st.dself.view(-1)[: st.n_in * d].view(st.n_in, d)
+                    lr, lp, nt = st.planT_inner
+                    B.sylvie_aggregate_csr_bwd_integrate(
+                        rpT, clT, wT, None, None, 0, st.n_in, dZ, d, d, g, g.stride(0), dself,
+                        0 if dself is None else d, st.n_in, inb, st.n_inbound, st.inb_seg_ptr,
+                        st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
+                        long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0,
+                        n_tasks=nt, workspace=st.ws_aggT if nt else None)
+            if not self.fused_bwd:
+                for sp_ in self.parts:
+                    for b in sp_.blocks:
+                        tgt = self.parts[b.owner]
+                        inb = tgt.inb_wires[self._gen(use)][l][b.inb_off * Wd:]
+                        gt = tgt.dHtil[l - 1]
+                        B.sylvie_dequantize_1bit_bwd(inb, b.j1 - b.j0, d, gt, gt.stride(0),
+                                                     b.seg_ptr, b.seg_rows, int(b.dst_ids.numel()),
+                                                     b.dst_ids)
+            if stale:
+                main.wait_stream(self.side)    # dZ and the float halo block are reused next layer
+
+    def step(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed,
+             mode: str = "sync"):
+        """One epoch (forward + backward); in pipeline mode its wires then become the
+        previous epoch's."""
+        self.forward(seed, pair_seed, mode)
+        self.backward(seed, pair_seed, mode)
+        if self.pipeline:
+            self.gen ^= 1
+            self.have_prev = True
+
+    def run_epochs(self, n: int, seed0: int, eps_s: int = 0,
+                   pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+        """Bounded Staleness Adaptor (Sec. 3.3): epoch e runs sequentially ("sync") when
+        e == 0 or eps_s > 0 and e % eps_s == 0, in pipeline mode ("async") otherwise.
+        Returns the list of modes."""
+        modes = []
+        for e in range(n):
+            mode = "sync" if (e == 0 or not self.pipeline or (eps_s > 0 and e % eps_s == 0)) else "async"
+            self.step(seed0 + e, pair_seed, mode)
+            modes.append(mode)
+        return modes

@@ -76,7 +76,7 @@ def gpu_wire(loop, key, n, d, bits):
     return w[: n * W].reshape(n, W)
 
 
-def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False):
+def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False, pipeline=False):
     from paper_2303_01277_amd.trainer import LayerLoop
     spec = wl.spec
     parts = wl.parts
@@ -91,11 +91,13 @@ def build_loop(wl, wire="1bit", chunk=256, fused=True, fused_bwd=False):
         rows = [p.halo_row for p in parts]
     return LayerLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
                      [w.to(DEV) for w in wl.W], spec.model, spec.dims, chunk=chunk,
-                     exchange_first_layer=True, wire=wire, fused=fused, fused_bwd=fused_bwd)
+                     exchange_first_layer=True, wire=wire, fused=fused, fused_bwd=fused_bwd,
+                     pipeline=pipeline)
 
 
-def replay(oracle, wl, loop, pdata, seed):
-    """Teacher-forced check of every step of one forward + backward pass."""
+def replay(oracle, wl, loop, pdata, seed, prev=None):
+    """Teacher-forced check of every step of one forward + backward pass.  prev: the wires
+    recorded in the previous epoch, when this epoch computed with them (pipeline mode)."""
     model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
     bits = loop.bits
     W = [np_c(w) for w in wl.W]
@@ -116,7 +118,8 @@ def replay(oracle, wl, loop, pdata, seed):
                 ref = o_quantize(oracle, bits, src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=idx)
                 assert np.array_equal(gpu_wire(loop, ("fwd", l, me, b.j0), n, d, bits), ref), ("fwd wire", l)
                 want = np.empty((n, d), np.float32)
-                o_dequantize(oracle, bits, ref, d, want, row_offset=0)
+                used = ref if prev is None else np_c(prev[("fwd", l, me, b.j0)]).view(np.uint64).reshape(ref.shape)
+                o_dequantize(oracle, bits, used, d, want, row_offset=0)
                 if loop.fused:
                     ht[st.n_in + b.j0: st.n_in + b.j1] = want
                 else:
@@ -134,7 +137,7 @@ def replay(oracle, wl, loop, pdata, seed):
             close(Hg, H, SH, ("H", l))
 
 
-def replay_backward(oracle, wl, loop, pdata, seed, snaps):
+def replay_backward(oracle, wl, loop, pdata, seed, snaps, prev=None):
     model, dims, L = wl.spec.model, wl.spec.dims, len(wl.W)
     bits = loop.bits
     W = [np_c(w) for w in wl.W]
@@ -174,7 +177,8 @@ def replay_backward(oracle, wl, loop, pdata, seed, snaps):
                     ref = o_quantize(oracle, bits, gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
                                      row_offset=st.n_in + b.j0)
                     assert np.array_equal(gpu_wire(loop, ("bwd", l, me, b.j0), n, d, bits), ref), ("bwd wire", l)
-                    o_dequantize(oracle, bits, ref, d, want, dst_row=np_c(b.rows))
+                    used = ref if prev is None else np_c(prev[("bwd", l, me, b.j0)]).view(np.uint64).reshape(ref.shape)
+                    o_dequantize(oracle, bits, used, d, want, dst_row=np_c(b.rows))
             got = np_c(stq.dHtil[l - 1][: stq.n_in])
             assert np.array_equal(bits32(got), bits32(want)), ("J after integrate", l, q)
 
@@ -184,6 +188,10 @@ class SnapLoop:
 
     @staticmethod
     def run(loop, seed):
+        return SnapLoop.run_mode(loop, seed, "sync")
+
+    @staticmethod
+    def run_mode(loop, seed, mode):
         from paper_2303_01277_amd import binding as B
         snaps = {}
         orig_q = B.sylvie_quantize_1bit_bwd
@@ -219,7 +227,7 @@ class SnapLoop:
         B.sylvie_quantize_1bit_bwd = hook
         B.sylvie_quantize_bbit_bwd = hook_b
         try:
-            loop.backward(seed, OL.pair_seed)
+            loop.backward(seed, OL.pair_seed, mode)
         finally:
             B.sylvie_quantize_1bit_bwd = orig_q
             B.sylvie_quantize_bbit_bwd = orig_qb
@@ -320,3 +328,118 @@ def test_fused_backward_equals_two_step_backward(cfg, n_nodes):
         for l in range(1, len(wl.W) + 1):
             assert torch.equal(sa.G[l], sb.G[l]), l
         assert torch.equal(sa.out, sb.out)
+
+
+# ---- Sylvie-A: pipeline mode (Sec. 3.3) ---------------------------------------------------
+
+def _outputs(loop):
+    out = []
+    for st in loop.parts:
+        out.append(st.out.clone())
+        out.append(st.dHtil[0][: st.n_in].clone())
+        out += [st.G[l].clone() for l in range(1, loop.L + 1)]
+    return out
+
+
+@pytest.mark.parametrize("fused,fused_bwd", [(True, True), (True, False), (False, False)])
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("co_purchase", 12_000), ("stress", 24_000)])
+def test_pipeline_epoch_reuses_previous_wires(cfg, n_nodes, fused, fused_bwd):
+    """An epoch in pipeline mode computes with the previous epoch's wires while it produces its
+    own on a second stream.  With nothing changed between epochs (same weights, same seed) it
+    must reproduce the sequential epoch bit for bit; with a new seed it still computes with the
+    old wires (same outputs) but records new ones."""
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    loop = build_loop(wl, fused=fused, fused_bwd=fused_bwd, pipeline=True, chunk=128)
+    with pytest.raises(ValueError):
+        loop.step(1, OL.pair_seed, mode="async")          # no previous epoch yet
+    loop.record = {}
+    loop.step(11, OL.pair_seed, mode="sync")
+    torch.cuda.synchronize()
+    ref_out, ref_rec = _outputs(loop), dict(loop.record)
+    for seed in (11, 11, 12):
+        loop.record = {}
+        loop.step(seed, OL.pair_seed, mode="async")
+        torch.cuda.synchronize()
+        for a, b in zip(_outputs(loop), ref_out):
+            assert torch.equal(a, b), seed
+        assert loop.record.keys() == ref_rec.keys()
+        same = [torch.equal(loop.record[k], ref_rec[k]) for k in ref_rec]
+        if seed == 11:
+            assert all(same)
+        else:
+            assert not any(same[i] for i, k in enumerate(ref_rec) if k[0] == "fwd" and k[1] == 1)
+    # a sequential epoch on the new seed now differs, and the epoch after it, pipelined, equals it
+    loop.record = {}
+    loop.step(12, OL.pair_seed, mode="sync")
+    torch.cuda.synchronize()
+    new_out = _outputs(loop)
+    assert not all(torch.equal(a, b) for a, b in zip(new_out, ref_out))
+    loop.step(12, OL.pair_seed, mode="async")
+    torch.cuda.synchronize()
+    for a, b in zip(_outputs(loop), new_out):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("citation", 20_000)])
+def test_pipeline_teacher_forced(oracle, cfg, n_nodes):
+    """Pipeline-mode epoch against the oracle, step by step: this epoch's wires are the
+    quantized current rows, the halo block and the integrated gradients come from the wires
+    of the previous epoch (whose weights differed)."""
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    pdata = to_partdata(wl)
+    loop = build_loop(wl, fused=False, fused_bwd=False, pipeline=True)
+    loop.record = {}
+    loop.step(21, OL.pair_seed, mode="sync")
+    torch.cuda.synchronize()
+    prev = dict(loop.record)
+    for w in loop.W:
+        w.mul_(0.9)                                            # the model moved between epochs
+    wl.W = [w.clone() for w in loop.W]
+    loop.record = {}
+    seed = 22
+    loop.forward(seed, OL.pair_seed, mode="async")
+    torch.cuda.synchronize()
+    replay(oracle, wl, loop, pdata, seed, prev=prev)
+    snaps = SnapLoop.run_mode(loop, seed, "async")
+    replay_backward(oracle, wl, loop, pdata, seed, snaps, prev=prev)
+
+
+@pytest.mark.parametrize("cfg,n_nodes", [("co_purchase", 12_000), ("stress", 24_000)])
+def test_pipeline_fused_equals_two_step(cfg, n_nodes):
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    res = []
+    for fb in (False, True):
+        loop = build_loop(wl, fused=True, fused_bwd=fb, pipeline=True, chunk=128)
+        recs = []
+        for e, mode in enumerate(["sync", "async", "async"]):
+            loop.record = {}
+            if e == 1:
+                for w in loop.W:
+                    w.mul_(1.1)
+            loop.step(100 + e, OL.pair_seed, mode=mode)
+            torch.cuda.synchronize()
+            recs.append((dict(loop.record), _outputs(loop)))
+        for w in loop.W:
+            w.div_(1.1)
+        res.append(recs)
+    for (ra, oa), (rb, ob) in zip(*res):
+        assert ra.keys() == rb.keys()
+        for k in ra:
+            assert torch.equal(ra[k], rb[k]), k
+        for a, b in zip(oa, ob):
+            assert torch.equal(a, b)
+
+
+def test_bounded_staleness_schedule():
+    wl = build_workload(CONFIGS["tiny"])
+    loop = build_loop(wl, pipeline=True, fused_bwd=True)
+    assert loop.run_epochs(5, 7, eps_s=2, pair_seed=OL.pair_seed) == ["sync", "async", "sync", "async", "sync"]
+    assert loop.run_epochs(4, 9, eps_s=0, pair_seed=OL.pair_seed) == ["sync", "async", "async", "async"]
+    plain = build_loop(wl)
+    assert plain.run_epochs(3, 7, eps_s=2, pair_seed=OL.pair_seed) == ["sync"] * 3
+    with pytest.raises(ValueError):
+        plain.forward(1, OL.pair_seed, mode="async")
+    torch.cuda.synchronize()

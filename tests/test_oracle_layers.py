@@ -175,3 +175,43 @@ def test_more_bits_less_exchange_error(oracle):
     assert all(a > 1.5 * b for a, b in zip(errs_h, errs_h[1:])), errs_h
     assert all(a > 1.5 * b for a, b in zip(errs_j, errs_j[1:])), errs_j
     assert errs_h[-1] < 1e-3 and errs_j[-1] < 1e-3
+
+
+def test_pipeline_epoch_uses_previous_wires(oracle):
+    """Sylvie-A (Sec. 3.3): an epoch that computes with the previous epoch's wires.  With
+    nothing changed between the two epochs (same inputs, weights and seed) the previous
+    wires equal the current ones, so the pipelined epoch must reproduce the sequential one
+    bit for bit; with a new seed only layer 1's wires can be predicted (its input is X) and
+    the outputs must be those of a sequential epoch run on the OLD seed's halo data."""
+    import numpy as np
+    from oracle import layers as OL
+    from synth import CONFIGS, build_workload, scaled
+    from util import np_c, to_partdata
+    wl = build_workload(scaled(CONFIGS["co_purchase"], 6000))
+    W = [np_c(w) for w in wl.W]
+    model = wl.spec.model
+
+    def epoch(seed, prev):
+        pd = to_partdata(wl)
+        keep = {}
+        OL.forward(pd, model, W, seed, "1bit", prev=prev, keep=keep)
+        OL.backward(pd, model, W, seed, "1bit", exchange_first_layer=True, prev=prev, keep=keep)
+        return pd, keep
+
+    a, wa = epoch(5, None)
+    b, wb = epoch(5, wa)                       # pipelined, nothing changed
+    assert wa.keys() == wb.keys() and any(k[0] == "bwd" for k in wa)
+    for k in wa:
+        assert all(np.array_equal(x, y) for x, y in zip(wa[k], wb[k])), k
+    for pa, pb in zip(a, b):
+        assert np.array_equal(pa.H[-1], pb.H[-1]) and np.array_equal(pa.Jin[0], pb.Jin[0])
+        for l in range(1, len(W) + 1):
+            assert np.array_equal(pa.G[l], pb.G[l])
+    c, wc = epoch(6, wa)                       # pipelined with a new seed
+    s6, w6 = epoch(6, None)
+    k1 = [k for k in wa if k[0] == "fwd" and k[1] == 1]
+    for k in k1:                               # layer 1 quantizes X: same wires as sequentially
+        assert all(np.array_equal(x, y) for x, y in zip(wc[k], w6[k]))
+        assert not np.array_equal(wc[k][0], wa[k][0])
+    for pa, pc in zip(a, c):                   # but it computed with the old wires throughout
+        assert np.array_equal(pa.H[-1], pc.H[-1]) and np.array_equal(pa.Jin[0], pc.Jin[0])
