@@ -24,6 +24,7 @@ __all__ = [
     "aggregate_bwd_rows", "transform_fwd", "transform_bwd", "num_threads",
     "words_per_row_bits", "quantize_bbit", "dequantize_bbit_fwd", "dequantize_bbit_bwd",
     "words_per_row_fp16", "convert_fp16", "recover_fp16_fwd", "recover_fp16_bwd",
+    "softmax_xent", "sum_gradients", "sgd_update",
 ]
 
 
@@ -50,6 +51,7 @@ def _L():
             lib.orc_words_per_row_bits.argtypes = [C.c_int32, C.c_int32]
             lib.orc_words_per_row_fp16.restype = C.c_int64
             lib.orc_words_per_row_fp16.argtypes = [C.c_int32]
+            lib.orc_softmax_xent.restype = C.c_double
             lib.orc_aggregate_bwd.restype = C.c_int
             lib.orc_num_threads.restype = C.c_int
             _lib = lib
@@ -281,3 +283,30 @@ def transform_bwd(A1, Wm, relu, H, J, A2=None, want_G=True, want_dA=True, want_S
                            _p(dA1), C.c_int64(k1), _p(dA2), C.c_int64(k2), _p(S1), _p(S2))
     out.update(G=G, dA1=dA1, dA2=dA2, SG=SG, SdA1=S1, SdA2=S2)
     return out
+
+
+def softmax_xent(H, label, count, want_S=False):
+    """-> (loss contribution of these rows, J f32 [n, C][, SJ])."""
+    _f32(H, "H"); _chk(label, np.int32, "label")
+    n, Cc = H.shape
+    J = np.empty((n, Cc), np.float32)
+    SJ = np.empty((n, Cc), np.float32) if want_S else None
+    loss = _L().orc_softmax_xent(_p(H), C.c_int64(Cc), C.c_int64(n), C.c_int32(Cc), _p(label),
+                                 C.c_double(float(count)), _p(J), C.c_int64(Cc), _p(SJ))
+    return (float(loss), J, SJ) if want_S else (float(loss), J)
+
+
+def sum_gradients(srcs):
+    """Sum of equally shaped float32 arrays in list order, single precision."""
+    for a in srcs:
+        _f32(a, "src")
+    dst = np.empty_like(srcs[0])
+    ptrs = (C.c_void_p * len(srcs))(*[a.ctypes.data for a in srcs])
+    _L().orc_sum_gradients(_p(dst), ptrs, C.c_int32(len(srcs)), C.c_int64(dst.size))
+    return dst
+
+
+def sgd_update(W, G, eta):
+    """In place: W = W - eta * G (single precision)."""
+    _f32(W, "W"); _f32(G, "G")
+    _L().orc_sgd_update(_p(W), _p(G), C.c_int64(W.size), C.c_float(eta))

@@ -612,6 +612,73 @@ void orc_transform_bwd(const float *A1, int64_t ld1, int32_t k1, const float *A2
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Loss, gradient synchronisation and model update (Alg. 1 last line; Alg. 2    */
+/* J^(L) = gradient of the loss, G = AllReduce(G_n), W_t = W_{t-1} - eta G).    */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Softmax cross-entropy over the labelled rows, averaged over `count` rows (the number
+ * of labelled nodes of the WHOLE graph, so that partition sums add up to the
+ * unpartitioned loss):
+ *   p_ic = exp(H_ic - max_c H_ic) / sum_c exp(H_ic - max_c H_ic)
+ *   loss = -(1/count) sum_{i labelled} log p_{i, y_i}
+ *   J_ic = (p_ic - [c == y_i]) / count for labelled rows, 0 for the others (label < 0).
+ * Everything in double; J is rounded to float once.  SJ (optional) receives
+ * (p_ic + [c == y_i]) / count, the magnitude the tolerance is taken against.
+ * Returns the loss contribution of these rows.
+ */
+double orc_softmax_xent(const float *H, int64_t ldh, int64_t n, int32_t C, const int32_t *label,
+                        double count, float *J, int64_t ldj, float *SJ)
+{
+    double loss = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float *h = H + i * ldh;
+        float *j = J + i * ldj;
+        const int32_t y = label[i];
+        if (y < 0) {
+            for (int32_t c = 0; c < C; ++c) {
+                j[c] = 0.0f;
+                if (SJ) SJ[i * C + c] = 0.0f;
+            }
+            continue;
+        }
+        double mx = h[0];
+        for (int32_t c = 1; c < C; ++c)
+            if (h[c] > mx) mx = h[c];
+        double sum = 0.0;
+        for (int32_t c = 0; c < C; ++c) sum += exp((double)h[c] - mx);
+        loss -= ((double)h[y] - mx) - log(sum);
+        for (int32_t c = 0; c < C; ++c) {
+            const double p = exp((double)h[c] - mx) / sum;
+            const double onehot = c == y ? 1.0 : 0.0;
+            j[c] = (float)((p - onehot) / count);
+            if (SJ) SJ[i * C + c] = (float)((p + onehot) / count);
+        }
+    }
+    return loss / count;
+}
+
+/* Gradient synchronisation of one process that holds every partition: dst = the sum of
+ * the n_src arrays, added in ascending order in single precision (dst may be srcs[0]). */
+void orc_sum_gradients(float *dst, const float *const *srcs, int32_t n_src, int64_t elems)
+{
+    for (int64_t e = 0; e < elems; ++e) {
+        float s = srcs[0][e];
+        for (int32_t k = 1; k < n_src; ++k) s = s + srcs[k][e];
+        dst[e] = s;
+    }
+}
+
+/* Plain SGD: W = fl(W - fl(eta * G)), single precision, two operations per element. */
+void orc_sgd_update(float *W, const float *G, int64_t elems, float eta)
+{
+    for (int64_t e = 0; e < elems; ++e) {
+        const float step = eta * G[e];
+        W[e] = W[e] - step;
+    }
+}
+
 int orc_num_threads(void)
 {
     int n = 1;
