@@ -302,6 +302,31 @@ int32_t sylvie_transform_bwd(const float *A1, int64_t ld_a1, int32_t k1, const f
                              int64_t ld_da2, float *workspace, size_t workspace_bytes,
                              void *stream);
 
+/*
+ * Loss and its gradient (Alg. 1, last line: L = Loss(softmax(H^(L)), Y); Alg. 2:
+ * J^(L) = dL/dH^(L)).  Softmax cross-entropy over the labelled rows, divided by `count`,
+ * the number of labelled nodes of the whole graph (so partition losses and gradients add
+ * up to the unpartitioned ones):
+ *     p = softmax(H[i][0 .. n_classes)),  loss_i = -log p[label[i]] / count,
+ *     J[i][c] = (p[c] - [c == label[i]]) / count;   label[i] < 0: row unlabelled, J row = 0.
+ * Single precision.  loss_rows float [n] is scratch that receives loss_i; loss_out double
+ * [1] (device memory) receives their sum, added in double in a fixed order.
+ */
+int32_t sylvie_softmax_xent(const float *H, int64_t ld_h, int64_t n, int32_t n_classes,
+                            const int32_t *label, double count, float *J, int64_t ld_j,
+                            float *loss_rows, double *loss_out, void *stream);
+
+/*
+ * Gradient synchronisation inside one process (Alg. 2, G = AllReduce(G_n), for partitions
+ * that share a GPU): dst[e] = ((srcs[0][e] + srcs[1][e]) + ...) in single precision, in
+ * that order.  srcs is a HOST array of n_src (1..16) device pointers; dst may be srcs[0].
+ */
+int32_t sylvie_sum_gradients(float *dst, const float *const *srcs, int32_t n_src, int64_t elems,
+                             void *stream);
+
+/* Model update (Alg. 2, W_t = W_{t-1} - eta G): W[e] = fl(W[e] - fl(eta * G[e])). */
+int32_t sylvie_sgd_update(float *W, const float *G, int64_t elems, float eta, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -48,7 +48,8 @@ def lib():
                      "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
                      "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
                      "sylvie_aggregate_csr_bwd_integrate",
-                     "sylvie_transform_fwd", "sylvie_transform_bwd"):
+                     "sylvie_transform_fwd", "sylvie_transform_bwd", "sylvie_softmax_xent",
+                     "sylvie_sum_gradients", "sylvie_sgd_update"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -257,3 +258,23 @@ def sylvie_transform_bwd(A1, ld_a1, k1, A2, ld_a2, k2, W, h, n, relu, H, ld_h, J
         C.c_int64(ld_j), _ptr(G, torch.float32, "G"), _ptr(dA1, torch.float32, "dA1"),
         C.c_int64(ld_da1), _ptr(dA2, torch.float32, "dA2"), C.c_int64(ld_da2),
         _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_softmax_xent(H, ld_h, n, n_classes, label, count, J, ld_j, loss_rows, loss_out):
+    _check(lib().sylvie_softmax_xent(
+        _ptr(H, torch.float32, "H"), C.c_int64(ld_h), C.c_int64(n), C.c_int32(n_classes),
+        _ptr(label, torch.int32, "label"), C.c_double(float(count)), _ptr(J, torch.float32, "J"),
+        C.c_int64(ld_j), _ptr(loss_rows, torch.float32, "loss_rows"),
+        _ptr(loss_out, torch.float64, "loss_out"), _stream()))
+
+
+def sylvie_sum_gradients(dst, srcs, n_src, elems):
+    """srcs: list of n_src float32 GPU tensors."""
+    ptrs = (C.c_void_p * n_src)(*[_ptr(t, torch.float32, "src").value for t in srcs[:n_src]])
+    _check(lib().sylvie_sum_gradients(_ptr(dst, torch.float32, "dst"), ptrs, C.c_int32(n_src),
+                                      C.c_int64(elems), _stream()))
+
+
+def sylvie_sgd_update(W, G, elems, eta):
+    _check(lib().sylvie_sgd_update(_ptr(W, torch.float32, "W"), _ptr(G, torch.float32, "G"),
+                                   C.c_int64(elems), C.c_float(eta), _stream()))

@@ -22,6 +22,7 @@ _SOURCES = {
     "lowbit_bbit.hip": ["-ffp-contract=off", "-fno-honor-nans"],
     "aggregate.hip": ["-ffp-contract=off"],
     "transform.hip": [],
+    "training.hip": ["-ffp-contract=off"],
 }
 
 
