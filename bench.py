@@ -345,6 +345,38 @@ def lowbit_microbench(torch, B, loop, st, d, iters=10):
     return out
 
 
+def training_tail_bench(torch, loop, wl, ms_per_step):
+    """What turns the forward + backward pass into a full training step (Alg. 1 last line,
+    Alg. 2 first and last lines): softmax cross-entropy + its gradient on the logits, the sum
+    of the partitions' weight gradients and the SGD update.  Timed on their own; the headline
+    step does not contain them (its upstream gradient is a fixed seeded array)."""
+    labels = wl.labels
+    count = float(sum(int((y >= 0).sum()) for y in labels))
+
+    def timed(fn, iters=5):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    keepJ = [st.J.clone() for st in loop.parts]
+    t_loss = timed(lambda: loop.loss_and_gradient(labels, count))
+    for st, j in zip(loop.parts, keepJ):
+        st.J.copy_(j)
+    t_upd = timed(lambda: loop.update_weights(0.0))          # eta = 0: the weights stay put
+    n = sum(st.n_in for st in loop.parts)
+    C_ = loop.dims[-1]
+    return {"loss_and_gradient_ms": t_loss, "gradient_sum_and_update_ms": t_upd,
+            "loss_GBps": n * (8 * C_ + 8) / (t_loss * 1e-3) / 1e9,
+            "training_step_ms": ms_per_step + t_loss + t_upd}
+
+
 def pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced):
     """Sylvie-A (Sec. 3.3) on one GPU: epochs that compute with the previous epoch's wires while
     this epoch's wires are produced on a second stream, against sequential epochs of the same
@@ -513,6 +545,7 @@ def main():
                         for kk, vv in v.items()} for k, v in ops.items()},
     }
     out["lowbit_kernels"] = lowbit_microbench(torch, B, loop, loop.parts[0], spec.dims[-2])
+    out["training_tail"] = training_tail_bench(torch, loop, wl, ms_per_step)
     if args.wire == "1bit":
         out["pipeline"] = pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced)
     if not args.no_cpu_baseline:

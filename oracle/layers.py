@@ -191,3 +191,22 @@ def backward(parts: List[PartData], model: str, W: List[np.ndarray], seed: int, 
                                        parts[q].Jin[l - 1], dst)
                 else:
                     np.add.at(parts[q].Jin[l - 1], dst, g[p.n_in + j0: p.n_in + j1])
+
+
+def loss_and_gradient(parts: List[PartData], labels: List[np.ndarray], count: float):
+    """Alg. 1 last line / Alg. 2 first line: J^(L) of every partition from its H^(L); returns
+    the loss of the whole graph (sum of the partition contributions)."""
+    total = 0.0
+    for p, y in zip(parts, labels):
+        loss, J = O.softmax_xent(np.ascontiguousarray(p.H[-1]), y, count)
+        p.J = J
+        total += loss
+    return total
+
+
+def update_weights(parts: List[PartData], W: List[np.ndarray], eta: float):
+    """Alg. 2 last two lines with every partition in one process: G = sum over partitions
+    (ascending), W = W - eta G, in place."""
+    for l in range(1, len(W) + 1):
+        G = O.sum_gradients([np.ascontiguousarray(p.G[l]) for p in parts])
+        O.sgd_update(W[l - 1], G, eta)

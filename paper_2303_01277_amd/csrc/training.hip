@@ -23,8 +23,54 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// One wavefront per row.  Unlabelled rows (label < 0) get a zero gradient row and no loss.
+// One wavefront per row; the row (P values per lane, column lane + 64 k) is read once and
+// stays in registers.  Unlabelled rows (label < 0) get a zero gradient row and no loss.
+template <int P>
 __global__ __launch_bounds__(kTrWavesPerBlock *kWave) void softmax_xent_kernel(
+    const float *__restrict__ H, int64_t ldh, int64_t n, int C, const int32_t *__restrict__ label,
+    float inv_count, float *__restrict__ J, int64_t ldj, float *__restrict__ loss_rows)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kTrWavesPerBlock + wave;
+    if (i >= n) return;
+    const float *h = H + i * ldh;
+    float *j = J + i * ldj;
+    const int y = uniform(label[i]);
+    if (y < 0) {
+        for (int c = lane; c < C; c += 64) j[c] = 0.0f;
+        if (lane == 0) loss_rows[i] = 0.0f;
+        return;
+    }
+    float v[P];
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int c = lane + 64 * k;
+        v[k] = c < C ? h[c] : -__builtin_inff();
+    }
+    float mx = v[0];
+#pragma unroll
+    for (int k = 1; k < P; ++k) mx = v[k] > mx ? v[k] : mx;
+    mx = wave_max(mx);
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        v[k] = __expf(v[k] - mx);              // exp(-inf) = 0 for the columns past C
+        sum += v[k];
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+    const float hy = h[y];
+#pragma unroll
+    for (int k = 0; k < P; ++k) {
+        const int c = lane + 64 * k;
+        if (c < C) j[c] = (v[k] * inv - (c == y ? 1.0f : 0.0f)) * inv_count;
+    }
+    if (lane == 0) loss_rows[i] = (__logf(sum) - (hy - mx)) * inv_count;
+}
+
+// Any number of classes: the row is read three times (the re-reads hit the cache).
+__global__ __launch_bounds__(kTrWavesPerBlock *kWave) void softmax_xent_wide_kernel(
     const float *__restrict__ H, int64_t ldh, int64_t n, int C, const int32_t *__restrict__ label,
     float inv_count, float *__restrict__ J, int64_t ldj, float *__restrict__ loss_rows)
 {
@@ -54,16 +100,28 @@ __global__ __launch_bounds__(kTrWavesPerBlock *kWave) void softmax_xent_kernel(
     if (lane == 0) loss_rows[i] = (__logf(sum) - (h[y] - mx)) * inv_count;
 }
 
-// out[0] = sum of v[0..n) in double, fixed order: thread t adds elements t, t + 1024, ...,
-// then a fixed tree over the 1024 partial sums.
+// out[0] = sum of v[0..n) in double, in a fixed order: thread t owns elements t + 1024 m;
+// it keeps eight running sums (m mod 8) so that eight loads are in flight, adds them
+// in ascending order, and a fixed tree joins the 1024 threads.
 __global__ __launch_bounds__(1024) void sum_to_double_kernel(const float *__restrict__ v, int64_t n,
                                                             double *__restrict__ out)
 {
     __shared__ double part[1024];
     const int t = threadIdx.x;
-    double s = 0.0;
-    for (int64_t e = t; e < n; e += 1024) s += static_cast<double>(v[e]);
-    part[t] = s;
+    double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int64_t e = t;
+    for (; e + 7 * 1024 < n; e += 8 * 1024) {
+        float x[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) x[q] = v[e + q * 1024];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s[q] += static_cast<double>(x[q]);
+    }
+    for (int q = 0; e < n; e += 1024, ++q) s[q] += static_cast<double>(v[e]);
+    double tot = s[0];
+#pragma unroll
+    for (int q = 1; q < 8; ++q) tot += s[q];
+    part[t] = tot;
     __syncthreads();
     for (int w = 512; w >= 1; w >>= 1) {
         if (t < w) part[t] += part[t + w];
@@ -115,8 +173,18 @@ extern "C" int32_t sylvie_softmax_xent(const float *H, int64_t ld_h, int64_t n, 
     if (n > 0) {
         if (!H || !label || !J || !loss_rows) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
         const dim3 grid(static_cast<unsigned>((n + kTrWavesPerBlock - 1) / kTrWavesPerBlock));
-        hipLaunchKernelGGL(softmax_xent_kernel, grid, dim3(kTrWavesPerBlock * kWave), 0, st, H, ld_h, n,
-                           n_classes, label, static_cast<float>(1.0 / count), J, ld_j, loss_rows);
+        const dim3 block(kTrWavesPerBlock * kWave);
+        const float ic = static_cast<float>(1.0 / count);
+#define SYLVIE_XENT(P) hipLaunchKernelGGL(softmax_xent_kernel<P>, grid, block, 0, st, H, ld_h, n, n_classes, label, ic, J, ld_j, loss_rows)
+        if (n_classes <= 64) SYLVIE_XENT(1);
+        else if (n_classes <= 128) SYLVIE_XENT(2);
+        else if (n_classes <= 256) SYLVIE_XENT(4);
+        else if (n_classes <= 512) SYLVIE_XENT(8);
+        else if (n_classes <= 1024) SYLVIE_XENT(16);
+        else
+            hipLaunchKernelGGL(softmax_xent_wide_kernel, grid, block, 0, st, H, ld_h, n, n_classes, label, ic,
+                               J, ld_j, loss_rows);
+#undef SYLVIE_XENT
     }
     hipLaunchKernelGGL(sum_to_double_kernel, dim3(1), dim3(1024), 0, st, loss_rows, n, loss_out);
     SYLVIE_HIP_LAUNCH_CHECK(name);

@@ -535,3 +535,41 @@ class LayerLoop:
             self.step(seed0 + e, pair_seed, mode)
             modes.append(mode)
         return modes
+
+    # -- the rest of the training step (Alg. 1 last line, Alg. 2 first and last lines) -------
+    def loss_and_gradient(self, labels, count: float):
+        """J^(L) of every partition = gradient of the softmax cross-entropy of its H^(L) over its
+        labelled nodes (labels[p] int32 [n_in], -1 = unlabelled; count = labelled nodes of the
+        whole graph).  Returns the per-partition loss sums as a float64 GPU tensor."""
+        if not hasattr(self, "_loss_rows"):
+            self._loss_rows = [torch.empty(max(1, st.n_in), dtype=torch.float32, device=self.dev)
+                               for st in self.parts]
+            self._loss = torch.zeros(len(self.parts), dtype=torch.float64, device=self.dev)
+        C_ = self.dims[-1]
+        for p, st in enumerate(self.parts):
+            B.sylvie_softmax_xent(st.out, st.out.stride(0), st.n_in, C_, labels[p], count, st.J,
+                                  st.J.stride(0), self._loss_rows[p], self._loss[p:p + 1])
+        return self._loss
+
+    def update_weights(self, eta: float):
+        """G = sum of the partitions' weight gradients (ascending partition order, the stand-in
+        for the all-reduce between GPUs); W = W - eta G."""
+        if not hasattr(self, "_gsum"):
+            self._gsum = [None] + [torch.empty_like(w) for w in self.W]
+        for l in range(1, self.L + 1):
+            srcs = [st.G[l] for st in self.parts]
+            B.sylvie_sum_gradients(self._gsum[l], srcs, len(srcs), self._gsum[l].numel())
+            B.sylvie_sgd_update(self.W[l - 1], self._gsum[l], self.W[l - 1].numel(), eta)
+
+    def train_step(self, seed: int, labels, count: float, eta: float,
+                   pair_seed: Callable[[int, int, int], int] = default_pair_seed,
+                   mode: str = "sync"):
+        """forward -> loss and J^(L) -> backward -> gradient sum -> SGD update."""
+        self.forward(seed, pair_seed, mode)
+        loss = self.loss_and_gradient(labels, count)
+        self.backward(seed, pair_seed, mode)
+        if self.pipeline:
+            self.gen ^= 1
+            self.have_prev = True
+        self.update_weights(eta)
+        return loss

@@ -59,6 +59,7 @@ class Workload:
     W: List[torch.Tensor]         # per layer: fp32 [k_l, d_l], k_l = d_{l-1} (gcn) or 2 d_{l-1} (sage)
     J: List[torch.Tensor]         # per partition: upstream gradient fp32 [n_in, d_L]
     n_edges_undirected: int
+    labels: List[torch.Tensor] = None   # per partition: int32 [n_in] class in [0, d_L), -1 = unlabelled
 
 
 def build_workload(spec: WorkloadSpec, device="cpu") -> Workload:
@@ -92,4 +93,13 @@ def build_workload(spec: WorkloadSpec, device="cpu") -> Workload:
     mirror = None
     if not spec.all_parts:
         mirror = loopback_mirror(parts[0].n_halo, parts[0].n_in, spec.seed + 77, device)
-    return Workload(spec, parts, mirror, X, W, J, n_und)
+    # node labels for the training step: uniform classes, about 60 % of the nodes labelled
+    # (own generator, so that everything above is unchanged by their presence)
+    gl = torch.Generator(device=device)
+    gl.manual_seed(spec.seed * 104729 + 5)
+    labels = []
+    for p in parts:
+        y = torch.randint(0, spec.dims[-1], (p.n_in,), generator=gl, device=device, dtype=torch.int32)
+        keep = torch.rand(p.n_in, generator=gl, device=device) < 0.6
+        labels.append(torch.where(keep, y, torch.full_like(y, -1)))
+    return Workload(spec, parts, mirror, X, W, J, n_und, labels)
