@@ -42,7 +42,8 @@ def log(*a):
 
 class OpTimer:
     """Brackets every C-ABI call with HIP events on the stream the kernels run on and
-    books the call's algorithmic bytes / flops (formulas stated in the design doc)."""
+    books the call's algorithmic bytes / flops (the formulas are the cost functions in
+    install())."""
 
     def __init__(self, B, torch, op_info):
         self.B, self.torch, self.op_info = B, torch, op_info
@@ -403,8 +404,8 @@ def pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="stress")
     ap.add_argument("--nodes", type=int, default=0, help="shrink the workload to this many nodes")
     ap.add_argument("--chunk", type=int, default=1024)
@@ -487,15 +488,19 @@ def main():
 
     timer = OpTimer(B, torch, op_info)
     timer.install()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         loop.forward(seed + 100 + i)
         loop.backward(seed + 100 + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     timer.remove()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     ops = timer.summary(args.steps)
 
     edges_per_step = sum(o["edges"] for o in ops.values())
@@ -541,6 +546,10 @@ def main():
         "metric": METRIC, "value": value, "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "device": {"name": torch.cuda.get_device_properties(0).name,
+                   "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
+                   "memory_GiB": round(torch.cuda.get_device_properties(0).total_memory / 2**30, 1)},
         "config": {"workload": spec.name, "graph": spec.graph, "n_nodes": spec.n_nodes,
                    "n_in": p0.n_in, "n_halo": p0.n_halo, "nnz_adjacency": p0.nnz,
                    "layer_model": spec.model, "dims": list(spec.dims), "chunk": args.chunk,
