@@ -25,6 +25,8 @@ __all__ = [
     "words_per_row_bits", "quantize_bbit", "dequantize_bbit_fwd", "dequantize_bbit_bwd",
     "words_per_row_fp16", "convert_fp16", "recover_fp16_fwd", "recover_fp16_bwd",
     "softmax_xent", "sum_gradients", "sgd_update",
+    "row_dot", "edge_softmax_fwd", "sddmm", "edge_softmax_bwd", "segment_sum", "column_sum",
+    "rank1_add",
 ]
 
 
@@ -310,3 +312,66 @@ def sgd_update(W, G, eta):
     """In place: W = W - eta * G (single precision)."""
     _f32(W, "W"); _f32(G, "G")
     _L().orc_sgd_update(_p(W), _p(G), C.c_int64(W.size), C.c_float(eta))
+
+
+def row_dot(P, a, n=None):
+    _f32(P, "P"); _f32(a, "a")
+    n = P.shape[0] if n is None else n
+    out = np.empty(n, np.float32)
+    _L().orc_row_dot(_p(P), C.c_int64(P.shape[1]), C.c_int64(n), C.c_int32(a.shape[0]), _p(a), _p(out))
+    return out
+
+
+def edge_softmax_fwd(rowptr, col, s_dst, s_src, slope):
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(s_dst, "s_dst"); _f32(s_src, "s_src")
+    n = rowptr.shape[0] - 1
+    alpha = np.zeros(int(rowptr[-1]), np.float32)
+    _L().orc_edge_softmax_fwd(_p(rowptr), _p(col), C.c_int64(n), _p(s_dst), _p(s_src), C.c_float(slope),
+                              _p(alpha))
+    return alpha
+
+
+def sddmm(rowptr, col, A, Bm, F, want_S=False):
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(A, "A"); _f32(Bm, "B")
+    n = rowptr.shape[0] - 1
+    out = np.zeros(int(rowptr[-1]), np.float32)
+    S = np.zeros_like(out) if want_S else None
+    _L().orc_sddmm(_p(rowptr), _p(col), C.c_int64(n), _p(A), C.c_int64(A.shape[1]), _p(Bm),
+                   C.c_int64(Bm.shape[1]), C.c_int32(F), _p(out), _p(S))
+    return (out, S) if want_S else out
+
+
+def edge_softmax_bwd(rowptr, col, alpha, dalpha, s_dst, s_src, slope, want_S=False):
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col")
+    for a_, nm in ((alpha, "alpha"), (dalpha, "dalpha"), (s_dst, "s_dst"), (s_src, "s_src")):
+        _f32(a_, nm)
+    n = rowptr.shape[0] - 1
+    de = np.zeros(int(rowptr[-1]), np.float32)
+    S = np.zeros_like(de) if want_S else None
+    _L().orc_edge_softmax_bwd(_p(rowptr), _p(col), C.c_int64(n), _p(alpha), _p(dalpha), _p(s_dst),
+                              _p(s_src), C.c_float(slope), _p(de), _p(S))
+    return (de, S) if want_S else de
+
+
+def segment_sum(rowptr, vals, want_S=False):
+    _chk(rowptr, np.int64, "rowptr"); _f32(vals, "vals")
+    n = rowptr.shape[0] - 1
+    out = np.empty(n, np.float32)
+    S = np.empty(n, np.float32) if want_S else None
+    _L().orc_segment_sum(_p(rowptr), C.c_int64(n), _p(vals), _p(out), _p(S))
+    return (out, S) if want_S else out
+
+
+def column_sum(rowptr, col, n_cols, vals, want_S=False):
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col"); _f32(vals, "vals")
+    n = rowptr.shape[0] - 1
+    out = np.empty(n_cols, np.float32)
+    S = np.empty(n_cols, np.float32) if want_S else None
+    _L().orc_column_sum(_p(rowptr), _p(col), C.c_int64(n), C.c_int64(n_cols), _p(vals), _p(out), _p(S))
+    return (out, S) if want_S else out
+
+
+def rank1_add(X, n, s, a):
+    """In place: X[i, :F] += s[i] * a for i < n (single precision)."""
+    _f32(X, "X"); _f32(s, "s"); _f32(a, "a")
+    _L().orc_rank1_add(_p(X), C.c_int64(X.shape[1]), C.c_int64(n), C.c_int32(a.shape[0]), _p(s), _p(a))

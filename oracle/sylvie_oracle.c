@@ -613,6 +613,139 @@ void orc_transform_bwd(const float *A1, int64_t ld1, int32_t k1, const float *A2
 }
 
 /* ------------------------------------------------------------------------- */
+/* Attention aggregator (the GAT model of Sec. 2.1 / Sec. 5.1; the paper cites   */
+/* the model and gives no formulas, so these are the cited model's):             */
+/*   P = Htilde W,  s_dst[v] = P_v . a_dst,  s_src[u] = P_u . a_src               */
+/*   e_vu = leaky_relu(s_dst[v] + s_src[u]),  alpha_v. = softmax_u e_vu           */
+/*   z_v = sum_u alpha_vu P_u   (the aggregation of Eq. 1 with learned weights)   */
+/* over the entries (v, u) of the local operator pattern (self loop included).    */
+/* Sums in double, results rounded to float once.                                */
+/* ------------------------------------------------------------------------- */
+
+/* out[i] = P_i . a for i < n. */
+void orc_row_dot(const float *P, int64_t ld, int64_t n, int32_t F, const float *a, float *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double acc = 0.0;
+        for (int32_t c = 0; c < F; ++c) acc += (double)P[i * ld + c] * (double)a[c];
+        out[i] = (float)acc;
+    }
+}
+
+static double orc_lrelu(double x, double slope) { return x > 0.0 ? x : slope * x; }
+
+/* alpha[e] for every entry e of rows 0 .. n_rows-1 (softmax over each row's entries). */
+void orc_edge_softmax_fwd(const int64_t *rowptr, const int32_t *col, int64_t n_rows,
+                          const float *s_dst, const float *s_src, float slope, float *alpha)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        const int64_t e0 = rowptr[v], e1 = rowptr[v + 1];
+        if (e0 == e1) continue;
+        double mx = -INFINITY;
+        for (int64_t e = e0; e < e1; ++e) {
+            const double x = orc_lrelu((double)s_dst[v] + (double)s_src[col[e]], slope);
+            if (x > mx) mx = x;
+        }
+        double sum = 0.0;
+        for (int64_t e = e0; e < e1; ++e)
+            sum += exp(orc_lrelu((double)s_dst[v] + (double)s_src[col[e]], slope) - mx);
+        for (int64_t e = e0; e < e1; ++e)
+            alpha[e] = (float)(exp(orc_lrelu((double)s_dst[v] + (double)s_src[col[e]], slope) - mx) / sum);
+    }
+}
+
+/* out[e] = A_v . B_u for every entry e = (v, u): the gradient of z_v = sum alpha_vu P_u with
+ * respect to alpha_vu is dZ_v . P_u.  S (optional): sum of |terms|. */
+void orc_sddmm(const int64_t *rowptr, const int32_t *col, int64_t n_rows, const float *A,
+               int64_t lda, const float *Bm, int64_t ldb, int32_t F, float *out, float *S)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_rows; ++v)
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            double acc = 0.0, mag = 0.0;
+            for (int32_t c = 0; c < F; ++c) {
+                const double t = (double)A[v * lda + c] * (double)Bm[(int64_t)col[e] * ldb + c];
+                acc += t;
+                mag += fabs(t);
+            }
+            out[e] = (float)acc;
+            if (S) S[e] = (float)mag;
+        }
+}
+
+/* Backward of the edge softmax and of the leaky ReLU in front of it:
+ *   g_e  = alpha_e (dalpha_e - sum_{w in row} alpha_w dalpha_w)
+ *   de_e = g_e * (s_dst[v] + s_src[u] > 0 ? 1 : slope)
+ * S (optional): |alpha_e dalpha_e| + alpha_e sum_w |alpha_w dalpha_w|, times the same factor. */
+void orc_edge_softmax_bwd(const int64_t *rowptr, const int32_t *col, int64_t n_rows,
+                          const float *alpha, const float *dalpha, const float *s_dst,
+                          const float *s_src, float slope, float *de, float *S)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        double dot = 0.0, mag = 0.0;
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const double t = (double)alpha[e] * (double)dalpha[e];
+            dot += t;
+            mag += fabs(t);
+        }
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            const double raw = (double)s_dst[v] + (double)s_src[col[e]];
+            const double f = raw > 0.0 ? 1.0 : (double)slope;
+            const double t = (double)alpha[e] * (double)dalpha[e];
+            de[e] = (float)((t - (double)alpha[e] * dot) * f);
+            if (S) S[e] = (float)((fabs(t) + (double)alpha[e] * mag) * fabs(f));
+        }
+    }
+}
+
+/* out[v] = sum of vals over the entries of row v (S optional: sum of |vals|). */
+void orc_segment_sum(const int64_t *rowptr, int64_t n_rows, const float *vals, float *out, float *S)
+{
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t v = 0; v < n_rows; ++v) {
+        double acc = 0.0, mag = 0.0;
+        for (int64_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            acc += (double)vals[e];
+            mag += fabs((double)vals[e]);
+        }
+        out[v] = (float)acc;
+        if (S) S[v] = (float)mag;
+    }
+}
+
+/* out[u] = sum of vals[e] over the entries e with col[e] = u (scatter form, from the
+ * forward pattern, so that the transposed pattern of the product is itself checked). */
+void orc_column_sum(const int64_t *rowptr, const int32_t *col, int64_t n_rows, int64_t n_cols,
+                    const float *vals, float *out, float *S)
+{
+    double *acc = (double *)calloc((size_t)n_cols * 2, sizeof(double));
+    double *mag = acc + n_cols;
+    for (int64_t e = 0; e < rowptr[n_rows]; ++e) {
+        acc[col[e]] += (double)vals[e];
+        mag[col[e]] += fabs((double)vals[e]);
+    }
+    for (int64_t u = 0; u < n_cols; ++u) {
+        out[u] = (float)acc[u];
+        if (S) S[u] = (float)mag[u];
+    }
+    free(acc);
+}
+
+/* X[i][c] = fl(X[i][c] + fl(s[i] * a[c])) for i < n: the part of dP that comes through the
+ * attention scores (single precision, two operations per element). */
+void orc_rank1_add(float *X, int64_t ld, int64_t n, int32_t F, const float *s, const float *a)
+{
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t c = 0; c < F; ++c) {
+            const float t = s[i] * a[c];
+            X[i * ld + c] = X[i * ld + c] + t;
+        }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Loss, gradient synchronisation and model update (Alg. 1 last line; Alg. 2    */
 /* J^(L) = gradient of the loss, G = AllReduce(G_n), W_t = W_{t-1} - eta G).    */
 /* ------------------------------------------------------------------------- */
