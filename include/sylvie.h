@@ -327,6 +327,61 @@ int32_t sylvie_sum_gradients(float *dst, const float *const *srcs, int32_t n_src
 /* Model update (Alg. 2, W_t = W_{t-1} - eta G): W[e] = fl(W[e] - fl(eta * G[e])). */
 int32_t sylvie_sgd_update(float *W, const float *G, int64_t elems, float eta, void *stream);
 
+/*
+ * Attention aggregator: the GAT model of the evaluation (Sec. 5.1), i.e. Eq. 1 with learned
+ * edge weights.  The paper cites the model without formulas; these are the cited model's:
+ *     P = H~ W,  s_dst[v] = P_v . a_dst,  s_src[u] = P_u . a_src,
+ *     alpha_v. = softmax over the entries (v, u) of row v of leaky_relu(s_dst[v] + s_src[u]),
+ *     z_v = sum_u alpha_vu P_u       (sylvie_aggregate_csr_fwd with w = alpha)
+ * and backward
+ *     dalpha_vu = dZ_v . P_u (sylvie_sddmm),  g = alpha (dalpha - sum_row alpha dalpha),
+ *     de = g * (s_dst[v] + s_src[u] > 0 ? 1 : slope)            (sylvie_edge_softmax_bwd),
+ *     ds_dst = row sums of de, ds_src = column sums of de        (sylvie_segment_sum on the
+ *     operator and, after sylvie_permute_f32, on its transpose),
+ *     dP = A^T(alpha) dZ + ds_src (x) a_src + ds_dst (x) a_dst   (sylvie_aggregate_csr_bwd,
+ *     sylvie_rank1_add).
+ *
+ * Piece table (built at set-up, shared by these calls): every row's entries are cut into
+ * pieces of at most `chunk` consecutive entries, one wavefront per piece; rows without
+ * entries have no piece.
+ *     piece_ptr int64 [n_pieces + 1]  entry offsets, ascending, piece k = [piece_ptr[k], piece_ptr[k+1])
+ *     piece_row int32 [n_pieces]      row of piece k
+ *     row_piece int64 [n_rows + 1]    pieces of row v = [row_piece[v], row_piece[v+1])
+ * Row-wide quantities are reduced per piece and joined per row in piece order (no atomics).
+ * `col` is the operator's column array (entry e of the CSR the pieces were cut from).
+ * Workspaces are caller-owned device memory: sylvie_edge_softmax_workspace_bytes for the two
+ * softmax calls (the backward needs (n_pieces + n_rows) floats, which is less),
+ * n_pieces floats for sylvie_segment_sum.
+ */
+int32_t sylvie_row_dot(const float *P, int64_t ld_p, int64_t n, int32_t F, const float *a, float *out,
+                       void *stream);
+size_t sylvie_edge_softmax_workspace_bytes(int64_t n_pieces, int64_t n_rows);
+int32_t sylvie_edge_softmax_fwd(const int64_t *piece_ptr, const int32_t *piece_row,
+                                const int64_t *row_piece, int64_t n_pieces, int64_t n_rows,
+                                const int32_t *col, const float *s_dst, const float *s_src, float slope,
+                                float *alpha, void *workspace, size_t workspace_bytes, void *stream);
+int32_t sylvie_sddmm(const int64_t *piece_ptr, const int32_t *piece_row, const int64_t *row_piece,
+                     int64_t n_pieces, int64_t n_rows, const int32_t *col, const float *A, int64_t ld_a,
+                     const float *B, int64_t ld_b, int32_t F, float *out, void *stream);
+int32_t sylvie_edge_softmax_bwd(const int64_t *piece_ptr, const int32_t *piece_row,
+                                const int64_t *row_piece, int64_t n_pieces, int64_t n_rows,
+                                const int32_t *col, const float *alpha, const float *dalpha,
+                                const float *s_dst, const float *s_src, float slope, float *de,
+                                void *workspace, size_t workspace_bytes, void *stream);
+int32_t sylvie_segment_sum(const int64_t *piece_ptr, const int32_t *piece_row, const int64_t *row_piece,
+                           int64_t n_pieces, int64_t n_rows, const float *vals, float *out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+/* out[i] = in[perm[i]], i < n (edge values from operator order into transposed-operator order). */
+int32_t sylvie_permute_f32(const float *in, const int64_t *perm, int64_t n, float *out, void *stream);
+/* X[i][c] = fl(X[i][c] + fl(s[i] * a[c])), i < n, c < F. */
+int32_t sylvie_rank1_add(float *X, int64_t ld_x, int64_t n, int32_t F, const float *s, const float *a,
+                         void *stream);
+/* H = max(Z, 0);  dZ = H > 0 ? J : 0 (the activation sits after the aggregation in this model). */
+int32_t sylvie_relu_fwd(const float *Z, int64_t ld_z, int64_t n, int32_t F, float *H, int64_t ld_h,
+                        void *stream);
+int32_t sylvie_relu_bwd(const float *H, int64_t ld_h, const float *J, int64_t ld_j, int64_t n, int32_t F,
+                        float *dZ, int64_t ld_dz, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

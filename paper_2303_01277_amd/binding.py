@@ -38,6 +38,8 @@ def lib():
         L.sylvie_wire_row_words.argtypes = [C.c_int32]
         L.sylvie_wire_row_words_bits.restype = C.c_size_t
         L.sylvie_wire_row_words_bits.argtypes = [C.c_int32, C.c_int32]
+        L.sylvie_edge_softmax_workspace_bytes.restype = C.c_size_t
+        L.sylvie_edge_softmax_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
         L.sylvie_transform_bwd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32,
                                                            C.c_int64]
@@ -49,7 +51,10 @@ def lib():
                      "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
                      "sylvie_aggregate_csr_bwd_integrate",
                      "sylvie_transform_fwd", "sylvie_transform_bwd", "sylvie_softmax_xent",
-                     "sylvie_sum_gradients", "sylvie_sgd_update"):
+                     "sylvie_sum_gradients", "sylvie_sgd_update", "sylvie_row_dot",
+                     "sylvie_edge_softmax_fwd", "sylvie_sddmm", "sylvie_edge_softmax_bwd",
+                     "sylvie_segment_sum", "sylvie_permute_f32", "sylvie_rank1_add",
+                     "sylvie_relu_fwd", "sylvie_relu_bwd"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -278,3 +283,74 @@ def sylvie_sum_gradients(dst, srcs, n_src, elems):
 def sylvie_sgd_update(W, G, elems, eta):
     _check(lib().sylvie_sgd_update(_ptr(W, torch.float32, "W"), _ptr(G, torch.float32, "G"),
                                    C.c_int64(elems), C.c_float(eta), _stream()))
+
+
+# ---- attention aggregator ------------------------------------------------------------------
+# `pieces` is the tuple (piece_ptr int64, piece_row int32, row_piece int64) of graph_engine.piece_table.
+
+def _pieces(pieces):
+    pp, pr, rp = pieces
+    return (_ptr(pp, torch.int64, "piece_ptr"), _ptr(pr, torch.int32, "piece_row"),
+            _ptr(rp, torch.int64, "row_piece"), C.c_int64(pr.numel()), C.c_int64(rp.numel() - 1))
+
+
+def _ws(workspace):
+    n = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return _ptr(workspace, None, "workspace"), C.c_size_t(n)
+
+
+def sylvie_row_dot(P, ld_p, n, F, a, out):
+    _check(lib().sylvie_row_dot(_ptr(P, torch.float32, "P"), C.c_int64(ld_p), C.c_int64(n), C.c_int32(F),
+                                _ptr(a, torch.float32, "a"), _ptr(out, torch.float32, "out"), _stream()))
+
+
+def sylvie_edge_softmax_workspace_bytes(n_pieces, n_rows) -> int:
+    return int(lib().sylvie_edge_softmax_workspace_bytes(int(n_pieces), int(n_rows)))
+
+
+def sylvie_edge_softmax_fwd(pieces, col, s_dst, s_src, slope, alpha, workspace):
+    _check(lib().sylvie_edge_softmax_fwd(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(s_dst, torch.float32, "s_dst"),
+        _ptr(s_src, torch.float32, "s_src"), C.c_float(slope), _ptr(alpha, torch.float32, "alpha"),
+        *_ws(workspace), _stream()))
+
+
+def sylvie_sddmm(pieces, col, A, ld_a, Bm, ld_b, F, out):
+    _check(lib().sylvie_sddmm(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(A, torch.float32, "A"), C.c_int64(ld_a),
+        _ptr(Bm, torch.float32, "B"), C.c_int64(ld_b), C.c_int32(F), _ptr(out, torch.float32, "out"),
+        _stream()))
+
+
+def sylvie_edge_softmax_bwd(pieces, col, alpha, dalpha, s_dst, s_src, slope, de, workspace):
+    _check(lib().sylvie_edge_softmax_bwd(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(alpha, torch.float32, "alpha"),
+        _ptr(dalpha, torch.float32, "dalpha"), _ptr(s_dst, torch.float32, "s_dst"),
+        _ptr(s_src, torch.float32, "s_src"), C.c_float(slope), _ptr(de, torch.float32, "de"),
+        *_ws(workspace), _stream()))
+
+
+def sylvie_segment_sum(pieces, vals, out, workspace):
+    _check(lib().sylvie_segment_sum(*_pieces(pieces), _ptr(vals, torch.float32, "vals"),
+                                    _ptr(out, torch.float32, "out"), *_ws(workspace), _stream()))
+
+
+def sylvie_permute_f32(inp, perm, n, out):
+    _check(lib().sylvie_permute_f32(_ptr(inp, torch.float32, "in"), _ptr(perm, torch.int64, "perm"),
+                                    C.c_int64(n), _ptr(out, torch.float32, "out"), _stream()))
+
+
+def sylvie_rank1_add(X, ld_x, n, F, s, a):
+    _check(lib().sylvie_rank1_add(_ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int64(n), C.c_int32(F),
+                                  _ptr(s, torch.float32, "s"), _ptr(a, torch.float32, "a"), _stream()))
+
+
+def sylvie_relu_fwd(Z, ld_z, n, F, H, ld_h):
+    _check(lib().sylvie_relu_fwd(_ptr(Z, torch.float32, "Z"), C.c_int64(ld_z), C.c_int64(n), C.c_int32(F),
+                                 _ptr(H, torch.float32, "H"), C.c_int64(ld_h), _stream()))
+
+
+def sylvie_relu_bwd(H, ld_h, J, ld_j, n, F, dZ, ld_dz):
+    _check(lib().sylvie_relu_bwd(_ptr(H, torch.float32, "H"), C.c_int64(ld_h), _ptr(J, torch.float32, "J"),
+                                 C.c_int64(ld_j), C.c_int64(n), C.c_int32(F), _ptr(dZ, torch.float32, "dZ"),
+                                 C.c_int64(ld_dz), _stream()))

@@ -23,6 +23,7 @@ _SOURCES = {
     "aggregate.hip": ["-ffp-contract=off"],
     "transform.hip": [],
     "training.hip": ["-ffp-contract=off"],
+    "gat.hip": ["-ffp-contract=off"],
 }
 
 

@@ -97,3 +97,34 @@ def scatter_segments_dense(dst_row, n_dst):
     seg_ptr = torch.zeros(n_dst + 1, dtype=torch.int64, device=dst_row.device)
     seg_ptr[1:] = torch.cumsum(torch.bincount(d64, minlength=n_dst), 0)
     return seg_ptr, order.to(torch.int32)
+
+
+def piece_table(rowptr, chunk):
+    """Cuts every row's entries into pieces of at most `chunk` consecutive entries (rows without
+    entries get none).  Returns (piece_ptr int64 [n_pieces + 1], piece_row int32 [n_pieces],
+    row_piece int64 [n_rows + 1])."""
+    if chunk <= 0:
+        raise ValueError("chunk must be positive")
+    dev = rowptr.device
+    counts = rowptr[1:] - rowptr[:-1]
+    per_row = (counts + (chunk - 1)) // chunk
+    row_piece = torch.zeros(rowptr.numel(), dtype=torch.int64, device=dev)
+    row_piece[1:] = torch.cumsum(per_row, 0)
+    n_pieces = int(row_piece[-1])
+    piece_row = torch.repeat_interleave(torch.arange(counts.numel(), device=dev), per_row)
+    k_in_row = torch.arange(n_pieces, device=dev) - row_piece[:-1][piece_row]
+    start = rowptr[:-1][piece_row] + k_in_row * chunk
+    piece_ptr = torch.empty(n_pieces + 1, dtype=torch.int64, device=dev)
+    piece_ptr[:-1] = start
+    piece_ptr[-1] = rowptr[-1]
+    return piece_ptr, piece_row.to(torch.int32), row_piece
+
+
+def transpose_permutation(rowptr, col, n_cols):
+    """perm int64 [nnz]: entry i of the transposed operator (as built by transpose_csr) is entry
+    perm[i] of the operator, so that valuesT = values[perm]."""
+    n_rows = int(rowptr.numel()) - 1
+    counts = rowptr[1:] - rowptr[:-1]
+    rows = torch.repeat_interleave(torch.arange(n_rows, device=rowptr.device), counts)
+    key = col.to(torch.int64) * n_rows + rows
+    return torch.sort(key, stable=True).indices
