@@ -38,6 +38,8 @@ def lib():
         L.sylvie_wire_row_words.argtypes = [C.c_int32]
         L.sylvie_wire_row_words_bits.restype = C.c_size_t
         L.sylvie_wire_row_words_bits.argtypes = [C.c_int32, C.c_int32]
+        L.sylvie_scaled_column_sum_workspace_bytes.restype = C.c_size_t
+        L.sylvie_scaled_column_sum_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
         L.sylvie_edge_softmax_workspace_bytes.restype = C.c_size_t
         L.sylvie_edge_softmax_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
@@ -54,6 +56,7 @@ def lib():
                      "sylvie_sum_gradients", "sylvie_sgd_update", "sylvie_row_dot",
                      "sylvie_edge_softmax_fwd", "sylvie_sddmm", "sylvie_edge_softmax_bwd",
                      "sylvie_segment_sum", "sylvie_permute_f32", "sylvie_rank1_add",
+                     "sylvie_scaled_column_sum",
                      "sylvie_relu_fwd", "sylvie_relu_bwd"):
             getattr(L, name).restype = C.c_int32
         _lib = L
@@ -354,3 +357,13 @@ def sylvie_relu_bwd(H, ld_h, J, ld_j, n, F, dZ, ld_dz):
     _check(lib().sylvie_relu_bwd(_ptr(H, torch.float32, "H"), C.c_int64(ld_h), _ptr(J, torch.float32, "J"),
                                  C.c_int64(ld_j), C.c_int64(n), C.c_int32(F), _ptr(dZ, torch.float32, "dZ"),
                                  C.c_int64(ld_dz), _stream()))
+
+
+def sylvie_scaled_column_sum_workspace_bytes(n, F) -> int:
+    return int(lib().sylvie_scaled_column_sum_workspace_bytes(int(n), int(F)))
+
+
+def sylvie_scaled_column_sum(X, ld_x, n, F, s, out, workspace):
+    _check(lib().sylvie_scaled_column_sum(_ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int64(n),
+                                          C.c_int32(F), _ptr(s, torch.float32, "s"),
+                                          _ptr(out, torch.float32, "out"), *_ws(workspace), _stream()))

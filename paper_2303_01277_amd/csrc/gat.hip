@@ -234,6 +234,34 @@ __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void softmax_bwd_kernel(
     }
 }
 
+// ---- out[c] = sum_i s[i] X[i][c]: gradients of the attention vectors -----------------------
+
+constexpr int kColSumRows = 2048;     // rows per slab
+
+// Slab z of rows -> part[z][0..F): thread t owns columns t, t + 256, ...; rows in order.
+__global__ __launch_bounds__(256) void scaled_column_sum_slab_kernel(
+    const float *__restrict__ X, int64_t ld, int64_t n, int F, const float *__restrict__ s,
+    float *__restrict__ part)
+{
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kColSumRows;
+    const int64_t r1 = r0 + kColSumRows < n ? r0 + kColSumRows : n;
+    for (int c = threadIdx.x; c < F; c += 256) {
+        float acc = 0.0f;
+        for (int64_t i = r0; i < r1; ++i) acc = fmaf(s[i], X[i * ld + c], acc);
+        part[static_cast<int64_t>(blockIdx.x) * F + c] = acc;
+    }
+}
+
+__global__ void scaled_column_sum_join_kernel(const float *__restrict__ part, int64_t n_slabs, int F,
+                                              float *__restrict__ out)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= F) return;
+    float acc = 0.0f;
+    for (int64_t z = 0; z < n_slabs; ++z) acc += part[z * F + c];
+    out[c] = acc;
+}
+
 // ---- small element-wise pieces ------------------------------------------------------------
 
 __global__ void permute_kernel(const float *__restrict__ in, const int64_t *__restrict__ perm, int64_t n,
@@ -421,6 +449,36 @@ extern "C" int32_t sylvie_edge_softmax_bwd(const int64_t *piece_ptr, const int32
                        ps, row_dot);
     hipLaunchKernelGGL(softmax_bwd_kernel, piece_grid(n_pieces), block, 0, st, pc, col, alpha, dalpha, s_dst,
                        s_src, slope, row_dot, de);
+    SYLVIE_HIP_LAUNCH_CHECK(name);
+    return SYLVIE_OK;
+}
+
+extern "C" size_t sylvie_scaled_column_sum_workspace_bytes(int64_t n, int32_t F)
+{
+    if (n < 0 || F < 1) return 0;
+    return static_cast<size_t>((n + sylvie::kColSumRows - 1) / sylvie::kColSumRows) * static_cast<size_t>(F) *
+           sizeof(float);
+}
+
+extern "C" int32_t sylvie_scaled_column_sum(const float *X, int64_t ld_x, int64_t n, int32_t F,
+                                            const float *s, float *out, void *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_scaled_column_sum";
+    if (n < 0 || n >= (int64_t(1) << 31) || F < 1 || F > 65536 || ld_x < F)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (!out) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null output", name);
+    if (n > 0 && (!X || !s)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    const int64_t slabs = (n + kColSumRows - 1) / kColSumRows;
+    if (slabs > 0 && (!workspace || workspace_bytes < sylvie_scaled_column_sum_workspace_bytes(n, F)))
+        return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *part = static_cast<float *>(workspace);
+    if (slabs > 0)
+        hipLaunchKernelGGL(scaled_column_sum_slab_kernel, dim3(static_cast<unsigned>(slabs)), dim3(256), 0, st, X,
+                           ld_x, n, F, s, part);
+    hipLaunchKernelGGL(scaled_column_sum_join_kernel, dim3((F + 255) / 256), dim3(256), 0, st, part, slabs, F, out);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }

@@ -212,6 +212,62 @@ class LayerLoop:
            long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
            workspace=ws if nt else None)
 
+    def _exchange_forward(self, l, d, Wd, seed, pair_seed):
+        """Alg. 1, the exchange of layer l: every owner quantizes the rows its peers need; the
+        receiver keeps the wire (fused aggregation) or recovers the rows into its halo block."""
+        for me, st in enumerate(self.parts):
+            ht = st.Htil[l - 1]
+            for b in st.blocks:
+                n = b.j1 - b.j0
+                src = self.parts[b.owner].Htil[l - 1]
+                if self.wire == "1bit":
+                    # the wire of halo rows [j0, j1) sits at the same offset in the
+                    # receiver's wire arrays, so all blocks stay resident side by side
+                    wire = st.wire[b.j0 * Wd:]
+                    B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
+                                               pair_seed(seed, b.owner, me), 2 * l + 0, wire)
+                    self._keep(("fwd", l, me, b.j0), wire, n, Wd)
+                    if not self.fused:
+                        B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
+                                                     st.n_in + b.j0)
+                elif self.bits:
+                    wire = st.wire[b.j0 * Wd:]
+                    B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
+                                               pair_seed(seed, b.owner, me), 2 * l + 0, wire)
+                    self._keep(("fwd", l, me, b.j0), wire, n, Wd)
+                    B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
+                                                 st.n_in + b.j0)
+                else:   # full-precision exchange: plain device copy of the rows
+                    ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
+
+    def _exchange_backward(self, l, d, Wd, seed, pair_seed):
+        """Alg. 2, the exchange of layer l in two steps: quantize the halo block of every
+        partition's gradient, add the recovered rows into the owners' inner rows."""
+        # exchange the halo gradients; all transposed aggregates above are complete
+        # before any partition's inner rows are touched (same stream, in order)
+        for me, st in enumerate(self.parts):
+            g = st.dHtil[l - 1]
+            for b in st.blocks:
+                n = b.j1 - b.j0
+                tgt = self.parts[b.owner].dHtil[l - 1]
+                if self.wire == "1bit":
+                    B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
+                                               pair_seed(seed, me, b.owner), 2 * l + 1,
+                                               st.wire)
+                    self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
+                    B.sylvie_dequantize_1bit_bwd(st.wire, n, d, tgt, tgt.stride(0), b.seg_ptr,
+                                                 b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
+                elif self.bits:
+                    B.sylvie_quantize_bbit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
+                                               self.bits, pair_seed(seed, me, b.owner),
+                                               2 * l + 1, st.wire)
+                    self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
+                    B.sylvie_dequantize_bbit_bwd(st.wire, n, d, self.bits, tgt, tgt.stride(0),
+                                                 b.seg_ptr, b.seg_rows,
+                                                 int(b.dst_ids.numel()), b.dst_ids)
+                else:
+                    tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())
+
     # -- Alg. 1 ------------------------------------------------------------------
     def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed,
                 mode: str = "sync"):
@@ -222,30 +278,7 @@ class LayerLoop:
         for l in range(1, self.L + 1):
             d = self.dims[l - 1]
             Wd = self._words(d)
-            for me, st in enumerate(self.parts):
-                ht = st.Htil[l - 1]
-                for b in st.blocks:
-                    n = b.j1 - b.j0
-                    src = self.parts[b.owner].Htil[l - 1]
-                    if self.wire == "1bit":
-                        # the wire of halo rows [j0, j1) sits at the same offset in the
-                        # receiver's wire arrays, so all blocks stay resident side by side
-                        wire = st.wire[b.j0 * Wd:]
-                        B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
-                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
-                        self._keep(("fwd", l, me, b.j0), wire, n, Wd)
-                        if not self.fused:
-                            B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
-                                                         st.n_in + b.j0)
-                    elif self.bits:
-                        wire = st.wire[b.j0 * Wd:]
-                        B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
-                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
-                        self._keep(("fwd", l, me, b.j0), wire, n, Wd)
-                        B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
-                                                     st.n_in + b.j0)
-                    else:   # full-precision exchange: plain device copy of the rows
-                        ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
+            self._exchange_forward(l, d, Wd, seed, pair_seed)
             for st in self.parts:
                 ht, Z = st.Htil[l - 1], st.Z[l - 1]
                 if self.fused:
@@ -308,30 +341,7 @@ class LayerLoop:
             if self.fused_bwd:
                 self._backward_exchange_fused(l, d, Wd, seed, pair_seed)
                 continue
-            # exchange the halo gradients; all transposed aggregates above are complete
-            # before any partition's inner rows are touched (same stream, in order)
-            for me, st in enumerate(self.parts):
-                g = st.dHtil[l - 1]
-                for b in st.blocks:
-                    n = b.j1 - b.j0
-                    tgt = self.parts[b.owner].dHtil[l - 1]
-                    if self.wire == "1bit":
-                        B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
-                                                   pair_seed(seed, me, b.owner), 2 * l + 1,
-                                                   st.wire)
-                        self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
-                        B.sylvie_dequantize_1bit_bwd(st.wire, n, d, tgt, tgt.stride(0), b.seg_ptr,
-                                                     b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
-                    elif self.bits:
-                        B.sylvie_quantize_bbit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
-                                                   self.bits, pair_seed(seed, me, b.owner),
-                                                   2 * l + 1, st.wire)
-                        self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
-                        B.sylvie_dequantize_bbit_bwd(st.wire, n, d, self.bits, tgt, tgt.stride(0),
-                                                     b.seg_ptr, b.seg_rows,
-                                                     int(b.dst_ids.numel()), b.dst_ids)
-                    else:
-                        tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())
+            self._exchange_backward(l, d, Wd, seed, pair_seed)
 
     def _backward_exchange_fused(self, l, d, Wd, seed, pair_seed):
         """Halo gradients: aggregate + quantize straight into the owner's inbound wire;
@@ -573,3 +583,149 @@ class LayerLoop:
             self.have_prev = True
         self.update_weights(eta)
         return loss
+
+
+class AttentionLoop(LayerLoop):
+    """The attention model (GAT) under the same exchange: layer l transforms inner and recovered
+    halo rows, P = Htilde W, scores every operator entry with leaky_relu(P_v . a_dst + P_u . a_src),
+    normalises the scores of each row with a softmax and aggregates Z = sum alpha P_u;
+    H = relu(Z) except on the last layer.  `heads` attention heads share W column-wise: head k
+    owns columns [k F, (k+1) F) of P, F = d_l / heads, and its own slices of a_dst / a_src.
+    The exchange is the two-step one (the transform needs the halo rows as floats)."""
+
+    def __init__(self, parts, halo_owner, halo_row, X, J, W, att, dims, heads: int = 1,
+                 slope: float = 0.2, chunk: int = 1024, exchange_first_layer: bool = False,
+                 wire: str = "1bit"):
+        super().__init__(parts, halo_owner, halo_row, X, J, W, "gcn", dims, chunk=chunk,
+                         exchange_first_layer=exchange_first_layer, wire=wire, fused=False,
+                         fused_bwd=False)
+        self.model = "gat"
+        self.att, self.heads, self.slope = att, heads, slope
+        if any(d % heads for d in dims[1:]):
+            raise ValueError("every layer width must be a multiple of heads")
+        dev = self.dev
+        for st in self.parts:
+            n_loc = st.n_in + st.n_halo
+            nnz = int(st.op[0][-1])
+            st.pieces = GE.piece_table(st.op[0], chunk)
+            st.piecesT = GE.piece_table(st.opT[0], chunk)
+            st.perm = GE.transpose_permutation(st.op[0], st.op[1], n_loc)
+            st.P = [None] + [torch.empty(n_loc, dims[l], dtype=torch.float32, device=dev)
+                             for l in range(1, self.L + 1)]
+            st.Zg = [None] + [torch.empty(st.n_in, dims[l], dtype=torch.float32, device=dev)
+                              for l in range(1, self.L + 1)]
+            st.alpha = [None] + [[torch.empty(nnz, dtype=torch.float32, device=dev) for _ in range(heads)]
+                                 for _ in range(self.L)]
+            st.s_dst = [None] + [[torch.empty(st.n_in, dtype=torch.float32, device=dev) for _ in range(heads)]
+                                 for _ in range(self.L)]
+            st.s_src = [None] + [[torch.empty(n_loc, dtype=torch.float32, device=dev) for _ in range(heads)]
+                                 for _ in range(self.L)]
+            st.edge = [torch.empty(nnz, dtype=torch.float32, device=dev) for _ in range(4)]
+            st.ds_dst = torch.empty(st.n_in, dtype=torch.float32, device=dev)
+            st.ds_src = torch.empty(n_loc, dtype=torch.float32, device=dev)
+            st.dP = torch.empty(n_loc, max(dims[1:]), dtype=torch.float32, device=dev)
+            st.dZg = torch.empty(st.n_in, max(dims[1:]), dtype=torch.float32, device=dev)
+            n_ws = max(B.sylvie_edge_softmax_workspace_bytes(st.pieces[1].numel(), st.n_in) // 4,
+                       st.piecesT[1].numel() + n_loc, 1)
+            st.ws_att = torch.empty(n_ws, dtype=torch.float32, device=dev)
+            nbytes = B.sylvie_transform_bwd_workspace_bytes(max(dims), 0, max(dims[1:]), n_loc)
+            st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
+            st.Ga = [None] + [(torch.empty(dims[l], dtype=torch.float32, device=dev),
+                               torch.empty(dims[l], dtype=torch.float32, device=dev))
+                              for l in range(1, self.L + 1)]
+            st.ws_col = torch.empty(max(1, B.sylvie_scaled_column_sum_workspace_bytes(n_loc, max(dims[1:])) // 4),
+                                    dtype=torch.float32, device=dev)
+
+    def forward(self, seed, pair_seed=default_pair_seed, mode="sync"):
+        if mode != "sync":
+            raise ValueError("the attention loop runs sequentially")
+        K = self.heads
+        for l in range(1, self.L + 1):
+            d, h = self.dims[l - 1], self.dims[l]
+            F = h // K
+            self._exchange_forward(l, d, self._words(d), seed, pair_seed)
+            a_dst, a_src = self.att[l - 1]
+            for st in self.parts:
+                n_loc = st.n_in + st.n_halo
+                ht, P = st.Htil[l - 1], st.P[l]
+                Z = st.Zg[l] if l < self.L else st.out       # no activation after the last layer
+                B.sylvie_transform_fwd(ht, ht.stride(0), d, None, 0, 0, self.W[l - 1], h, n_loc, False,
+                                       P, P.stride(0))
+                rp, cl, _ = st.op
+                lr, lp, nt = st.plan
+                for k in range(K):
+                    Pk, Zk = P[:, k * F:], Z[:, k * F:]
+                    sd, ss, al = st.s_dst[l][k], st.s_src[l][k], st.alpha[l][k]
+                    B.sylvie_row_dot(Pk, h, st.n_in, F, a_dst[k * F:], sd)
+                    B.sylvie_row_dot(Pk, h, n_loc, F, a_src[k * F:], ss)
+                    B.sylvie_edge_softmax_fwd(st.pieces, cl, sd, ss, self.slope, al, st.ws_att)
+                    B.sylvie_aggregate_csr_fwd(rp, cl, al, None, None, st.n_in, Pk, h, F, Zk, h,
+                                               chunk=self.chunk, long_rows=lr if nt else None,
+                                               long_ptr=lp if nt else None,
+                                               n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                                               workspace=st.ws_agg if nt else None)
+                if l != self.L:
+                    Hout = st.Htil[l]
+                    B.sylvie_relu_fwd(Z, h, st.n_in, h, Hout, Hout.stride(0))
+
+    def backward(self, seed, pair_seed=default_pair_seed, mode="sync"):
+        if mode != "sync":
+            raise ValueError("the attention loop runs sequentially")
+        K = self.heads
+        for l in range(self.L, 0, -1):
+            d, h = self.dims[l - 1], self.dims[l]
+            F = h // K
+            need_dx = l > 1 or self.exchange_first_layer
+            a_dst, a_src = self.att[l - 1]
+            for st in self.parts:
+                n_loc = st.n_in + st.n_halo
+                nnz = st.alpha[l][0].numel()
+                Hout = st.Htil[l] if l < self.L else st.out
+                Jl = st.J if l == self.L else st.dHtil[l]
+                P, dP = st.P[l], st.dP
+                if l != self.L:
+                    dZ = st.dZg
+                    B.sylvie_relu_bwd(Hout, Hout.stride(0), Jl, Jl.stride(0), st.n_in, h, dZ, dZ.stride(0))
+                else:
+                    dZ = Jl
+                ldz, ldp = dZ.stride(0), dP.stride(0)
+                rp, cl, _ = st.op
+                rpT, clT, _ = st.opT
+                lr, lp, nt = st.planT
+                dal, de, deT, alT = st.edge
+                da_dst, da_src = st.Ga[l]
+                for k in range(K):
+                    Pk, dZk, dPk = P[:, k * F:], dZ[:, k * F:], dP[:, k * F:]
+                    sd, ss, al = st.s_dst[l][k], st.s_src[l][k], st.alpha[l][k]
+                    B.sylvie_sddmm(st.pieces, cl, dZk, ldz, Pk, h, F, dal)
+                    B.sylvie_edge_softmax_bwd(st.pieces, cl, al, dal, sd, ss, self.slope, de, st.ws_att)
+                    B.sylvie_segment_sum(st.pieces, de, st.ds_dst, st.ws_att)
+                    B.sylvie_permute_f32(de, st.perm, nnz, deT)
+                    B.sylvie_segment_sum(st.piecesT, deT, st.ds_src, st.ws_att)
+                    B.sylvie_permute_f32(al, st.perm, nnz, alT)
+                    B.sylvie_aggregate_csr_bwd(rpT, clT, alT, None, None, n_loc, dZk, ldz, F, dPk, ldp,
+                                               chunk=self.chunk, long_rows=lr if nt else None,
+                                               long_ptr=lp if nt else None,
+                                               n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                                               workspace=st.ws_aggT if nt else None)
+                    B.sylvie_rank1_add(dPk, ldp, n_loc, F, st.ds_src, a_src[k * F:])
+                    B.sylvie_rank1_add(dPk, ldp, st.n_in, F, st.ds_dst, a_dst[k * F:])
+                    B.sylvie_scaled_column_sum(Pk, h, st.n_in, F, st.ds_dst, da_dst[k * F:], st.ws_col)
+                    B.sylvie_scaled_column_sum(Pk, h, n_loc, F, st.ds_src, da_src[k * F:], st.ws_col)
+                ht = st.Htil[l - 1]
+                g = st.dHtil[l - 1] if need_dx else None
+                B.sylvie_transform_bwd(ht, ht.stride(0), d, None, 0, 0, self.W[l - 1], h, n_loc, False,
+                                       None, 0, dP, ldp, st.G[l], g, 0 if g is None else g.stride(0),
+                                       None, 0, st.ws_g)
+            if need_dx:
+                self._exchange_backward(l, d, self._words(d), seed, pair_seed)
+
+    def update_weights(self, eta: float):
+        super().update_weights(eta)
+        if not hasattr(self, "_gasum"):
+            self._gasum = [None] + [(torch.empty_like(a), torch.empty_like(b)) for a, b in self.att]
+        for l in range(1, self.L + 1):
+            for i in (0, 1):
+                srcs = [st.Ga[l][i] for st in self.parts]
+                B.sylvie_sum_gradients(self._gasum[l][i], srcs, len(srcs), srcs[0].numel())
+                B.sylvie_sgd_update(self.att[l - 1][i], self._gasum[l][i], srcs[0].numel(), eta)

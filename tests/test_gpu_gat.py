@@ -135,3 +135,23 @@ def test_attention_kernels_degenerate(oracle):
     B.sylvie_segment_sum(empty, None, out[:3], None)
     torch.cuda.synchronize()
     assert out[:3].cpu().tolist() == [0, 0, 0]
+
+
+@pytest.mark.parametrize("F", [1, 7, 64, 100, 256])
+@pytest.mark.parametrize("n", [0, 1, 5, 2047, 2048, 2049, 10_000])
+def test_scaled_column_sum_parity(F, n):
+    """out[f] = sum_i s[i] X[i][f]: the gradient of an attention vector from the projected rows
+    and the summed score gradients. The plain definition in float64 is the reference."""
+    from paper_2303_01277_amd import binding as B
+    rng = np.random.default_rng(F * 13 + n)
+    ld = F + (3 if F % 2 else 4)
+    X = make_rows(rng, max(n, 1), ld, "heavy")
+    s = rng.standard_normal(max(n, 1)).astype(np.float32)
+    out = torch.full((F + 2,), 7.0, device=DEV)
+    ws = torch.empty(max(B.sylvie_scaled_column_sum_workspace_bytes(n, F) // 4, 1), device=DEV)
+    B.sylvie_scaled_column_sum(dev(X), ld, n, F, dev(s), out, ws)
+    torch.cuda.synchronize()
+    X64, s64 = X[:n, :F].astype(np.float64), s[:n].astype(np.float64)
+    got = out.cpu().numpy()
+    close(got[:F], (X64.T @ s64).astype(np.float32), np.abs(X64).T @ np.abs(s64), "column sum")
+    assert (got[F:] == 7.0).all()

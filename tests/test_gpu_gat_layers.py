@@ -1,0 +1,174 @@
+"""GPU parity of the attention model's layer loop: end to end against the oracle's loop with an
+exact exchange, and layer by layer (teacher-forced: the oracle recomputes each layer from the
+GPU's own inputs to it) with the 1-bit exchange, whose wires must match bit for bit."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as OL
+from synth import CONFIGS, build_workload, scaled
+from test_gpu_layers import SnapLoop, bits32, gpu_wire, o_dequantize, o_quantize
+from util import np_c, to_partdata
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make_att(wl, seed):
+    g = torch.Generator().manual_seed(seed)
+    return [(torch.randn(w.shape[1], generator=g) / w.shape[1] ** 0.5,
+             torch.randn(w.shape[1], generator=g) / w.shape[1] ** 0.5) for w in wl.W]
+
+
+def build_attention_loop(wl, att, heads, wire, chunk=128):
+    from paper_2303_01277_amd.trainer import AttentionLoop
+    parts = wl.parts
+    for p in parts:
+        for f in ("rowptr", "col", "deg", "halo_gid", "halo_part", "halo_row"):
+            setattr(p, f, getattr(p, f).to(DEV))
+    if wl.mirror is not None:
+        owner = [torch.zeros(parts[0].n_halo, dtype=torch.int32, device=DEV)]
+        rows = [wl.mirror.to(DEV)]
+    else:
+        owner = [p.halo_part for p in parts]
+        rows = [p.halo_row for p in parts]
+    return AttentionLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
+                         [w.to(DEV) for w in wl.W], [(a.to(DEV), b.to(DEV)) for a, b in att],
+                         wl.spec.dims, heads=heads, chunk=chunk, exchange_first_layer=True, wire=wire)
+
+
+def rel(got, ref):
+    return float(np.abs(got.astype(np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def workload(cfg, n_nodes):
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    return build_workload(dataclasses.replace(spec, model="gcn"))
+
+
+@pytest.mark.parametrize("heads", [1, 4])
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("citation", 8_000)])
+def test_attention_loop_end_to_end_exact_exchange(oracle, cfg, n_nodes, heads):
+    wl = workload(cfg, n_nodes)
+    att = make_att(wl, 3)
+    pd = to_partdata(wl)
+    W = [np_c(w) for w in wl.W]
+    att_np = [(np_c(a), np_c(b)) for a, b in att]
+    OL.forward_gat(pd, W, att_np, heads, 0.2, 1, "fp32")
+    OL.backward_gat(pd, W, att_np, heads, 0.2, 1, "fp32", exchange_first_layer=True)
+    loop = build_attention_loop(wl, att, heads, "fp32")
+    loop.forward(1)
+    loop.backward(1)
+    torch.cuda.synchronize()
+    for st, p in zip(loop.parts, pd):
+        assert rel(np_c(st.out), p.H[-1]) < 5e-5
+        assert rel(np_c(st.dHtil[0][: st.n_in]), p.Jin[0]) < 1e-4
+        for l in range(1, len(W) + 1):
+            assert rel(np_c(st.G[l]), p.G[l]) < 1e-4, l
+            assert rel(np_c(st.Ga[l][0]), p.Gatt[l][0]) < 1e-4, l
+            assert rel(np_c(st.Ga[l][1]), p.Gatt[l][1]) < 1e-4, l
+
+
+def oracle_layer(oracle, rp, cl, n_in, ht, W, a_dst, a_src, heads, slope, relu, J, H_gpu, P_gpu):
+    """One attention layer, forward and backward, from the given inputs (float64 sums). The
+    projection is returned for comparison; everything after it starts from the GPU's own
+    projection, since the exponential amplifies a rounding difference in the scores."""
+    n_loc, h = ht.shape[0], W.shape[1]
+    F = h // heads
+    P_ref = oracle.transform_fwd(ht, W, False)
+    P = P_gpu
+    Z = np.empty((n_in, h), np.float32)
+    dZ = np.where(H_gpu > 0, J, np.float32(0)).astype(np.float32) if relu else J
+    dP = np.empty((n_loc, h), np.float32)
+    da_dst, da_src = np.empty(h, np.float32), np.empty(h, np.float32)
+    S_dst, S_src = np.empty(h), np.empty(h)
+    for k in range(heads):
+        sl = slice(k * F, (k + 1) * F)
+        Pk = np.ascontiguousarray(P[:, sl]); dZk = np.ascontiguousarray(dZ[:, sl])
+        sd = oracle.row_dot(Pk, np.ascontiguousarray(a_dst[sl]), n=n_in)
+        ss = oracle.row_dot(Pk, np.ascontiguousarray(a_src[sl]))
+        al = oracle.edge_softmax_fwd(rp, cl, sd, ss, slope)
+        Z[:, sl] = oracle.aggregate_fwd(rp, cl, al, Pk, F)
+        dal = oracle.sddmm(rp, cl, dZk, Pk, F)
+        de = oracle.edge_softmax_bwd(rp, cl, al, dal, sd, ss, slope)
+        # the softmax gradient of a row sums to zero before the slope factor: its terms cancel, so
+        # the sums over it are judged against the sum of the magnitudes of what was added up
+        a64, row = al.astype(np.float64), np.repeat(np.arange(n_in), np.diff(rp))
+        dot = np.bincount(row, a64 * np.abs(dal), n_in)
+        mag = a64 * (np.abs(dal) + dot[row])
+        S_dst[sl] = np.abs(Pk[:n_in]).astype(np.float64).T @ np.bincount(row, mag, n_in)
+        S_src[sl] = np.abs(Pk).astype(np.float64).T @ np.bincount(cl, mag, n_loc)
+        dsd, dss = oracle.segment_sum(rp, de), oracle.column_sum(rp, cl, n_loc, de)
+        dPk = oracle.aggregate_bwd(rp, cl, al, n_loc, dZk, F)
+        oracle.rank1_add(dPk, n_loc, dss, np.ascontiguousarray(a_src[sl]))
+        oracle.rank1_add(dPk, n_in, dsd, np.ascontiguousarray(a_dst[sl]))
+        dP[:, sl] = dPk
+        da_dst[sl] = (Pk[:n_in].astype(np.float64).T @ dsd.astype(np.float64)).astype(np.float32)
+        da_src[sl] = (Pk.astype(np.float64).T @ dss.astype(np.float64)).astype(np.float32)
+    r = oracle.transform_bwd(ht, W, False, dP, dP)
+    return {"P": P_ref, "Z": Z, "G": r["G"], "dHt": r["dA1"], "da_dst": da_dst, "da_src": da_src,
+            "S_dst": S_dst, "S_src": S_src}
+
+
+@pytest.mark.parametrize("heads,wire", [(1, "1bit"), (2, "1bit"), (2, "4bit")])
+@pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("stress", 12_000)])
+def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire):
+    wl = workload(cfg, n_nodes)
+    att = make_att(wl, 5)
+    pdata = to_partdata(wl)
+    for pd in pdata:
+        OL.build_operator(pd, "gat")
+    loop = build_attention_loop(wl, att, heads, wire)
+    bits = loop.bits
+    loop.record = {}
+    seed = 0x6A7
+    loop.forward(seed, OL.pair_seed)
+    torch.cuda.synchronize()
+    snaps = SnapLoop.run(loop, seed)
+    W = [np_c(w) for w in wl.W]
+    L = len(W)
+    for l in range(L, 0, -1):
+        d, h = loop.dims[l - 1], loop.dims[l]
+        a_dst, a_src = np_c(att[l - 1][0]), np_c(att[l - 1][1])
+        for me, (st, pd) in enumerate(zip(loop.parts, pdata)):
+            rp, cl, _ = pd.op
+            ht = np_c(st.Htil[l - 1])
+            # forward exchange: wires from the owners' rows, halo block recovered from them
+            for b in st.blocks:
+                n = b.j1 - b.j0
+                src = np_c(loop.parts[b.owner].Htil[l - 1])
+                ref = o_quantize(oracle, bits, src, d, n, OL.pair_seed(seed, b.owner, me), 2 * l, idx=np_c(b.rows))
+                assert np.array_equal(gpu_wire(loop, ("fwd", l, me, b.j0), n, d, bits), ref)
+                want = np.empty((n, d), np.float32)
+                o_dequantize(oracle, bits, ref, d, want, row_offset=0)
+                assert np.array_equal(bits32(ht[st.n_in + b.j0: st.n_in + b.j1]), bits32(want))
+            Hg = np_c(st.Htil[l][: st.n_in] if l < L else st.out)
+            J = snaps[(l, me)]["J"]
+            o = oracle_layer(oracle, rp, cl, st.n_in, ht, W[l - 1], a_dst, a_src, heads, 0.2, l != L, J, Hg,
+                             np_c(st.P[l]))
+            assert rel(np_c(st.P[l]), o["P"]) < 2e-5
+            Zg = np_c(st.Zg[l]) if l < L else Hg
+            assert rel(Zg, o["Z"]) < 5e-5
+            if l < L:
+                assert np.array_equal(Hg, np.maximum(Zg, 0))
+            assert rel(np_c(st.G[l]), o["G"]) < 1e-4
+            for got, ref, S in ((st.Ga[l][0], o["da_dst"], o["S_dst"]), (st.Ga[l][1], o["da_src"], o["S_src"])):
+                err = np.abs(np_c(got).astype(np.float64) - ref)
+                assert (err <= 1e-5 * np.maximum(np.abs(ref), S)).all(), float((err / np.maximum(np.abs(ref), S)).max())
+            assert rel(snaps[(l, me)]["dHtil_pre"], o["dHt"]) < 1e-4
+        # backward exchange: wires from the GPU's halo gradients, accumulate bit for bit
+        for q, stq in enumerate(loop.parts):
+            want = snaps[(l, q)]["dHtil_pre"][: stq.n_in].copy()
+            for me, st in enumerate(loop.parts):
+                gpre = snaps[(l, me)]["dHtil_pre"]
+                for b in st.blocks:
+                    if b.owner != q:
+                        continue
+                    n = b.j1 - b.j0
+                    ref = o_quantize(oracle, bits, gpre, d, n, OL.pair_seed(seed, me, q), 2 * l + 1,
+                                     row_offset=st.n_in + b.j0)
+                    assert np.array_equal(gpu_wire(loop, ("bwd", l, me, b.j0), n, d, bits), ref)
+                    o_dequantize(oracle, bits, ref, d, want, dst_row=np_c(b.rows))
+            assert np.array_equal(bits32(np_c(stq.dHtil[l - 1][: stq.n_in])), bits32(want))
