@@ -27,6 +27,8 @@ __all__ = [
     "softmax_xent", "sum_gradients", "sgd_update",
     "row_dot", "edge_softmax_fwd", "sddmm", "edge_softmax_bwd", "segment_sum", "column_sum",
     "rank1_add",
+    "halo_set", "relabel_columns", "rows_in_owner", "recv_sets", "send_set", "transpose_csr",
+    "scatter_segments",
 ]
 
 
@@ -56,6 +58,8 @@ def _L():
             lib.orc_softmax_xent.restype = C.c_double
             lib.orc_aggregate_bwd.restype = C.c_int
             lib.orc_num_threads.restype = C.c_int
+            lib.orc_halo_set.restype = C.c_int64
+            lib.orc_send_set.restype = C.c_int64
             _lib = lib
     return _lib
 
@@ -375,3 +379,76 @@ def rank1_add(X, n, s, a):
     """In place: X[i, :F] += s[i] * a for i < n (single precision)."""
     _f32(X, "X"); _f32(s, "s"); _f32(a, "a")
     _L().orc_rank1_add(_p(X), C.c_int64(X.shape[1]), C.c_int64(n), C.c_int32(a.shape[0]), _p(s), _p(a))
+
+
+# ---- Graph Engine set-up (Alg. 1, the lines before the epoch loop) -------------------
+
+def halo_set(rowptr, gcol, n_in, owner, part):
+    """-> (halo_gid int32 ascending, pos int32 [n_nodes], n_inner): V_HALO,n and the local numbering."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(gcol, np.int32, "gcol"); _chk(owner, np.int32, "owner")
+    n_nodes = owner.shape[0]
+    pos = np.empty(n_nodes, np.int32)
+    halo = np.empty(n_nodes, np.int32)
+    n_inner = C.c_int64(0)
+    n_halo = _L().orc_halo_set(_p(rowptr), _p(gcol), C.c_int64(n_in), _p(owner), C.c_int64(n_nodes),
+                               C.c_int32(part), _p(pos), _p(halo), C.byref(n_inner))
+    return halo[:n_halo].copy(), pos, int(n_inner.value)
+
+
+def relabel_columns(gcol, pos):
+    _chk(gcol, np.int32, "gcol"); _chk(pos, np.int32, "pos")
+    col = np.empty(gcol.shape[0], np.int32)
+    _L().orc_relabel_columns(_p(gcol), C.c_int64(gcol.shape[0]), _p(pos), _p(col))
+    return col
+
+
+def rows_in_owner(owner, n_parts):
+    """-> (row_of int32 [n_nodes], part_ptr int64 [n_parts + 1])."""
+    _chk(owner, np.int32, "owner")
+    row_of = np.empty(owner.shape[0], np.int32)
+    part_ptr = np.empty(n_parts + 1, np.int64)
+    _L().orc_rows_in_owner(_p(owner), C.c_int64(owner.shape[0]), C.c_int32(n_parts), _p(row_of), _p(part_ptr))
+    return row_of, part_ptr
+
+
+def recv_sets(halo_gid, owner, row_of, n_parts):
+    """-> (R_ptr int64 [n_parts + 1], R_halo int32, R_row int32): R_k = V_HALO,n & V_k."""
+    _chk(halo_gid, np.int32, "halo_gid"); _chk(owner, np.int32, "owner"); _chk(row_of, np.int32, "row_of")
+    n = halo_gid.shape[0]
+    R_ptr = np.empty(n_parts + 1, np.int64)
+    R_halo = np.empty(n, np.int32); R_row = np.empty(n, np.int32)
+    _L().orc_recv_sets(_p(halo_gid), C.c_int64(n), _p(owner), _p(row_of), C.c_int32(n_parts),
+                       _p(R_ptr), _p(R_halo), _p(R_row))
+    return R_ptr, R_halo, R_row
+
+
+def send_set(peer_halo, owner, row_of, part):
+    """-> S_row int32: S_k = V_n & V_HALO,k as rows of partition `part`'s inner block."""
+    _chk(peer_halo, np.int32, "peer_halo"); _chk(owner, np.int32, "owner"); _chk(row_of, np.int32, "row_of")
+    S = np.empty(peer_halo.shape[0], np.int32)
+    n = _L().orc_send_set(_p(peer_halo), C.c_int64(peer_halo.shape[0]), _p(owner), _p(row_of),
+                          C.c_int32(part), _p(S))
+    return S[:n].copy()
+
+
+def transpose_csr(rowptr, col, w, n_cols):
+    """-> (rowptrT int64, colT int32, wT float32 | None, perm int64)."""
+    _chk(rowptr, np.int64, "rowptr"); _chk(col, np.int32, "col")
+    if w is not None:
+        _f32(w, "w")
+    n_rows, nnz = rowptr.shape[0] - 1, col.shape[0]
+    rowptrT = np.empty(n_cols + 1, np.int64)
+    colT = np.empty(nnz, np.int32); perm = np.empty(nnz, np.int64)
+    wT = np.empty(nnz, np.float32) if w is not None else None
+    _L().orc_transpose_csr(_p(rowptr), _p(col), _p(w), C.c_int64(n_rows), C.c_int64(n_cols),
+                           _p(rowptrT), _p(colT), _p(wT), _p(perm))
+    return rowptrT, colT, wT, perm
+
+
+def scatter_segments(dst_row, n_dst):
+    """-> (seg_ptr int64 [n_dst + 1], seg_rows int32 [n])."""
+    _chk(dst_row, np.int32, "dst_row")
+    seg_ptr = np.empty(n_dst + 1, np.int64)
+    seg_rows = np.empty(dst_row.shape[0], np.int32)
+    _L().orc_scatter_segments(_p(dst_row), C.c_int64(dst_row.shape[0]), C.c_int64(n_dst), _p(seg_ptr), _p(seg_rows))
+    return seg_ptr, seg_rows

@@ -812,6 +812,140 @@ void orc_sgd_update(float *W, const float *G, int64_t elems, float eta)
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Graph Engine set-up (Sec. 3.2; Alg. 1, the lines before the epoch loop):      */
+/* HALO node set, send / receive sets, local numbering, transposed operator.     */
+/* Sequential loops in the order of the definitions; integers only.              */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * V_HALO,n = { v in G_n : v not in V_n }: the nodes that the adjacency of the
+ * partition's inner rows names and the partition does not own, in ascending
+ * global id.  owner[g] = partition of node g; (rowptr, gcol) = adjacency of the
+ * n_in inner rows in global ids.  Also numbers the partition's local rows:
+ * pos[g] = rank of g among the partition's own nodes (ascending id) for an inner
+ * node, n_in + rank in V_HALO,n for a halo node, -1 for every other node.
+ * Returns |V_HALO,n|; *n_inner receives |V_n|.
+ */
+int64_t orc_halo_set(const int64_t *rowptr, const int32_t *gcol, int64_t n_in,
+                     const int32_t *owner, int64_t n_nodes, int32_t part, int32_t *pos,
+                     int32_t *halo_gid, int64_t *n_inner)
+{
+    int64_t inner = 0, halo = 0;
+    for (int64_t g = 0; g < n_nodes; ++g) pos[g] = -1;
+    for (int64_t e = 0; e < rowptr[n_in]; ++e)
+        if (owner[gcol[e]] != part) pos[gcol[e]] = -2;          /* named, not owned */
+    for (int64_t g = 0; g < n_nodes; ++g)
+        if (owner[g] == part) ++inner;
+    for (int64_t g = 0, r = 0; g < n_nodes; ++g) {
+        if (owner[g] == part) pos[g] = (int32_t)r++;
+        else if (pos[g] == -2) {
+            halo_gid[halo] = (int32_t)g;
+            pos[g] = (int32_t)(inner + halo);
+            ++halo;
+        }
+    }
+    *n_inner = inner;
+    return halo;
+}
+
+/* Local column of every adjacency entry: col[e] = pos[gcol[e]]. */
+void orc_relabel_columns(const int32_t *gcol, int64_t nnz, const int32_t *pos, int32_t *col)
+{
+    for (int64_t e = 0; e < nnz; ++e) col[e] = pos[gcol[e]];
+}
+
+/* row_of[g] = rank of node g among the nodes of its own partition (ascending id): its row
+ * in the owner's inner block.  part_ptr[k] = number of nodes owned by partitions < k. */
+void orc_rows_in_owner(const int32_t *owner, int64_t n_nodes, int32_t n_parts, int32_t *row_of,
+                       int64_t *part_ptr)
+{
+    for (int32_t k = 0; k <= n_parts; ++k) part_ptr[k] = 0;
+    for (int64_t g = 0; g < n_nodes; ++g) {
+        row_of[g] = (int32_t)part_ptr[owner[g] + 1];
+        ++part_ptr[owner[g] + 1];
+    }
+    for (int32_t k = 0; k < n_parts; ++k) part_ptr[k + 1] += part_ptr[k];
+}
+
+/*
+ * R_k = V_HALO,n intersected with V_k, for k = 0 .. n_parts-1, each in ascending id:
+ * R_halo lists the halo rows j (indices into halo_gid) of R_0, R_1, ... one after the
+ * other, R_ptr[k] .. R_ptr[k+1] delimits R_k, and R_row[i] = row of that node in its
+ * owner's inner block, i.e. the row the owner has to send.
+ */
+void orc_recv_sets(const int32_t *halo_gid, int64_t n_halo, const int32_t *owner,
+                   const int32_t *row_of, int32_t n_parts, int64_t *R_ptr, int32_t *R_halo,
+                   int32_t *R_row)
+{
+    int64_t o = 0;
+    for (int32_t k = 0; k < n_parts; ++k) {
+        R_ptr[k] = o;
+        for (int64_t j = 0; j < n_halo; ++j)
+            if (owner[halo_gid[j]] == k) {
+                R_halo[o] = (int32_t)j;
+                R_row[o] = row_of[halo_gid[j]];
+                ++o;
+            }
+    }
+    R_ptr[n_parts] = o;
+}
+
+/*
+ * S_k = V_n intersected with V_HALO,k for one peer k: the inner rows of partition `part`
+ * that peer k's halo set names, in ascending id.  peer_halo = V_HALO,k (ascending).
+ * Returns |S_k|.
+ */
+int64_t orc_send_set(const int32_t *peer_halo, int64_t n_peer_halo, const int32_t *owner,
+                     const int32_t *row_of, int32_t part, int32_t *S_row)
+{
+    int64_t o = 0;
+    for (int64_t j = 0; j < n_peer_halo; ++j)
+        if (owner[peer_halo[j]] == part) S_row[o++] = row_of[peer_halo[j]];
+    return o;
+}
+
+/*
+ * Transposed operator as a CSR of its own: row c of the transpose lists the entries
+ * (r, c) of the operator in ascending r (the order a row-by-row sweep meets them).
+ * colT[i] = r, wT[i] = w of that entry, perm[i] = its index in the operator.
+ * w / wT may be NULL.
+ */
+void orc_transpose_csr(const int64_t *rowptr, const int32_t *col, const float *w, int64_t n_rows,
+                       int64_t n_cols, int64_t *rowptrT, int32_t *colT, float *wT, int64_t *perm)
+{
+    for (int64_t c = 0; c <= n_cols; ++c) rowptrT[c] = 0;
+    for (int64_t e = 0; e < rowptr[n_rows]; ++e) ++rowptrT[col[e] + 1];
+    for (int64_t c = 0; c < n_cols; ++c) rowptrT[c + 1] += rowptrT[c];
+    int64_t *next = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_cols > 0 ? n_cols : 1));
+    for (int64_t c = 0; c < n_cols; ++c) next[c] = rowptrT[c];
+    for (int64_t r = 0; r < n_rows; ++r)
+        for (int64_t e = rowptr[r]; e < rowptr[r + 1]; ++e) {
+            const int64_t o = next[col[e]]++;
+            colT[o] = (int32_t)r;
+            if (w) wT[o] = w[e];
+            perm[o] = e;
+        }
+    free(next);
+}
+
+/*
+ * Wire rows grouped by destination row for the backward accumulate (Alg. 2, "integrate
+ * gradients"): destination r receives wire rows seg_rows[seg_ptr[r] .. seg_ptr[r+1]),
+ * ascending.  One segment per destination row 0 .. n_dst-1, empty ones included.
+ */
+void orc_scatter_segments(const int32_t *dst_row, int64_t n, int64_t n_dst, int64_t *seg_ptr,
+                          int32_t *seg_rows)
+{
+    for (int64_t r = 0; r <= n_dst; ++r) seg_ptr[r] = 0;
+    for (int64_t i = 0; i < n; ++i) ++seg_ptr[dst_row[i] + 1];
+    for (int64_t r = 0; r < n_dst; ++r) seg_ptr[r + 1] += seg_ptr[r];
+    int64_t *next = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_dst > 0 ? n_dst : 1));
+    for (int64_t r = 0; r < n_dst; ++r) next[r] = seg_ptr[r];
+    for (int64_t i = 0; i < n; ++i) seg_rows[next[dst_row[i]]++] = (int32_t)i;
+    free(next);
+}
+
 int orc_num_threads(void)
 {
     int n = 1;
