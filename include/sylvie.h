@@ -388,6 +388,74 @@ int32_t sylvie_relu_fwd(const float *Z, int64_t ld_z, int64_t n, int32_t F, floa
 int32_t sylvie_relu_bwd(const float *H, int64_t ld_h, const float *J, int64_t ld_j, int64_t n, int32_t F,
                         float *dZ, int64_t ld_dz, void *stream);
 
+/*
+ * Graph Engine set-up on the device (Sec. 3.2; Alg. 1, the lines before the epoch loop).
+ * Not on the per-layer path: each call waits for `stream` before it returns, because it
+ * reports counts and the result of the kernels' own range checks (a bad id gives
+ * SYLVIE_ERR_INVALID_ARG, never an out-of-range access).  All arrays are device memory
+ * unless named *_host; ids and rows are int32, pointers into arrays int64; item counts must
+ * stay below 2^31 - 4096.  Workspace: caller-owned device memory of at least
+ * sylvie_graph_workspace_bytes(n) bytes, n = the largest item count of the call (stated per
+ * call); contents are scratch.
+ */
+size_t sylvie_graph_workspace_bytes(int64_t n);
+
+/*
+ * V_HALO,n = { v in G_n : v not in V_n } and the local numbering of partition `part`.
+ * gcol int32 [nnz]: global neighbour ids of the partition's inner rows (any order);
+ * owner int32 [n_nodes]: partition of every node.  Writes pos int32 [n_nodes]: the row of
+ * node g in this partition = its rank among the partition's own nodes (ascending id), or
+ * n_in + its rank in V_HALO,n, or -1 for a node the partition neither owns nor names; and
+ * halo_gid int32 [<= halo_capacity]: V_HALO,n ascending.  counts_host int64 [2] (host)
+ * receives |V_n| and |V_HALO,n|.  Fails if |V_n| != n_in or the halo set exceeds the capacity
+ * (counts_host is valid then, so the caller can retry with room).  Workspace n = n_nodes.
+ */
+int32_t sylvie_graph_local_index(const int32_t *gcol, int64_t nnz, int64_t n_in, const int32_t *owner,
+                                 int64_t n_nodes, int32_t part, int32_t *pos, int32_t *halo_gid,
+                                 int64_t halo_capacity, int64_t *counts_host, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/* col[e] = pos[gcol[e]]: the adjacency in local rows.  Fails if an entry names a node with
+ * pos < 0.  Workspace: 256 bytes. */
+int32_t sylvie_graph_relabel_columns(const int32_t *gcol, int64_t nnz, const int32_t *pos, int64_t n_nodes,
+                                     int32_t *col, void *workspace, size_t workspace_bytes, void *stream);
+
+/* row_of[g] = rank of node g among the nodes of owner[g], ascending id (its row in the
+ * owner's inner block); part_ptr int64 [n_parts + 1]: nodes owned by partitions < k.
+ * Workspace n = n_nodes. */
+int32_t sylvie_graph_rows_in_owner(const int32_t *owner, int64_t n_nodes, int32_t n_parts, int32_t *row_of,
+                                   int64_t *part_ptr, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * R_k = V_HALO,n intersected with V_k for every partition k (Alg. 1, the receive sets):
+ * R_halo int32 [n_halo] lists the halo rows j (indices into halo_gid) of R_0, R_1, ... one
+ * after the other, each ascending; R_ptr int64 [n_parts + 1] delimits them; R_row[i] =
+ * row_of[halo_gid[R_halo[i]]], the row the owner sends.  The send set S_k of partition n
+ * toward k (V_n intersected with V_HALO,k) is the slice [R_ptr[n], R_ptr[n+1]) of R_row as
+ * computed for partition k: nothing further is computed for it.  Workspace n = n_halo.
+ */
+int32_t sylvie_graph_recv_sets(const int32_t *halo_gid, int64_t n_halo, const int32_t *owner,
+                               const int32_t *row_of, int64_t n_nodes, int32_t n_parts, int64_t *R_ptr,
+                               int32_t *R_halo, int32_t *R_row, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/*
+ * The transposed operator as a CSR of its own (Alg. 2 aggregates with it): row c lists the
+ * entries (r, c) of the operator in ascending entry order (ascending r).  rowptrT int64
+ * [n_cols + 1], colT int32 [nnz] = r, wT = w of the entry (w and wT both NULL: no weights),
+ * perm int64 [nnz] | NULL = index of the entry in the operator (valuesT = values[perm]).
+ * nnz must equal rowptr[n_rows]; columns of a row need not ascend.  Workspace n = nnz.
+ */
+int32_t sylvie_graph_transpose_csr(const int64_t *rowptr, const int32_t *col, const float *w, int64_t n_rows,
+                                   int64_t n_cols, int64_t nnz, int64_t *rowptrT, int32_t *colT, float *wT,
+                                   int64_t *perm, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Wire rows grouped by destination row for the backward accumulate: destination r receives
+ * wire rows seg_rows[seg_ptr[r] .. seg_ptr[r+1]), ascending; seg_ptr int64 [n_dst + 1].
+ * Workspace n = n. */
+int32_t sylvie_graph_scatter_segments(const int32_t *dst_row, int64_t n, int64_t n_dst, int64_t *seg_ptr,
+                                      int32_t *seg_rows, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,8 @@ def lib():
         L.sylvie_scaled_column_sum_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
         L.sylvie_edge_softmax_workspace_bytes.restype = C.c_size_t
         L.sylvie_edge_softmax_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
+        L.sylvie_graph_workspace_bytes.restype = C.c_size_t
+        L.sylvie_graph_workspace_bytes.argtypes = [C.c_int64]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
         L.sylvie_transform_bwd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32,
                                                            C.c_int64]
@@ -57,7 +59,10 @@ def lib():
                      "sylvie_edge_softmax_fwd", "sylvie_sddmm", "sylvie_edge_softmax_bwd",
                      "sylvie_segment_sum", "sylvie_permute_f32", "sylvie_rank1_add",
                      "sylvie_scaled_column_sum",
-                     "sylvie_relu_fwd", "sylvie_relu_bwd"):
+                     "sylvie_relu_fwd", "sylvie_relu_bwd",
+                     "sylvie_graph_local_index", "sylvie_graph_relabel_columns",
+                     "sylvie_graph_rows_in_owner", "sylvie_graph_recv_sets",
+                     "sylvie_graph_transpose_csr", "sylvie_graph_scatter_segments"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -367,3 +372,53 @@ def sylvie_scaled_column_sum(X, ld_x, n, F, s, out, workspace):
     _check(lib().sylvie_scaled_column_sum(_ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int64(n),
                                           C.c_int32(F), _ptr(s, torch.float32, "s"),
                                           _ptr(out, torch.float32, "out"), *_ws(workspace), _stream()))
+
+
+# ---- Graph Engine set-up (each call waits for the current stream) ------------------------
+
+def sylvie_graph_workspace_bytes(n) -> int:
+    return int(lib().sylvie_graph_workspace_bytes(int(n)))
+
+
+def sylvie_graph_local_index(gcol, nnz, n_in, owner, n_nodes, part, pos, halo_gid, halo_capacity, workspace):
+    """Returns (|V_n|, |V_HALO,n|) as the library reported them; raises on a failed check."""
+    counts = (C.c_int64 * 2)(0, 0)
+    _check(lib().sylvie_graph_local_index(_ptr(gcol, torch.int32, "gcol"), C.c_int64(nnz), C.c_int64(n_in),
+                                          _ptr(owner, torch.int32, "owner"), C.c_int64(n_nodes), C.c_int32(part),
+                                          _ptr(pos, torch.int32, "pos"), _ptr(halo_gid, torch.int32, "halo_gid"),
+                                          C.c_int64(halo_capacity), counts, *_ws(workspace), _stream()))
+    return int(counts[0]), int(counts[1])
+
+
+def sylvie_graph_relabel_columns(gcol, nnz, pos, n_nodes, col, workspace):
+    _check(lib().sylvie_graph_relabel_columns(_ptr(gcol, torch.int32, "gcol"), C.c_int64(nnz),
+                                              _ptr(pos, torch.int32, "pos"), C.c_int64(n_nodes),
+                                              _ptr(col, torch.int32, "col"), *_ws(workspace), _stream()))
+
+
+def sylvie_graph_rows_in_owner(owner, n_nodes, n_parts, row_of, part_ptr, workspace):
+    _check(lib().sylvie_graph_rows_in_owner(_ptr(owner, torch.int32, "owner"), C.c_int64(n_nodes), C.c_int32(n_parts),
+                                            _ptr(row_of, torch.int32, "row_of"), _ptr(part_ptr, torch.int64, "part_ptr"),
+                                            *_ws(workspace), _stream()))
+
+
+def sylvie_graph_recv_sets(halo_gid, n_halo, owner, row_of, n_nodes, n_parts, R_ptr, R_halo, R_row, workspace):
+    _check(lib().sylvie_graph_recv_sets(_ptr(halo_gid, torch.int32, "halo_gid"), C.c_int64(n_halo),
+                                        _ptr(owner, torch.int32, "owner"), _ptr(row_of, torch.int32, "row_of"),
+                                        C.c_int64(n_nodes), C.c_int32(n_parts), _ptr(R_ptr, torch.int64, "R_ptr"),
+                                        _ptr(R_halo, torch.int32, "R_halo"), _ptr(R_row, torch.int32, "R_row"),
+                                        *_ws(workspace), _stream()))
+
+
+def sylvie_graph_transpose_csr(rowptr, col, w, n_rows, n_cols, nnz, rowptrT, colT, wT, perm, workspace):
+    _check(lib().sylvie_graph_transpose_csr(_ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
+                                            _ptr(w, torch.float32, "w"), C.c_int64(n_rows), C.c_int64(n_cols),
+                                            C.c_int64(nnz), _ptr(rowptrT, torch.int64, "rowptrT"),
+                                            _ptr(colT, torch.int32, "colT"), _ptr(wT, torch.float32, "wT"),
+                                            _ptr(perm, torch.int64, "perm"), *_ws(workspace), _stream()))
+
+
+def sylvie_graph_scatter_segments(dst_row, n, n_dst, seg_ptr, seg_rows, workspace):
+    _check(lib().sylvie_graph_scatter_segments(_ptr(dst_row, torch.int32, "dst_row"), C.c_int64(n), C.c_int64(n_dst),
+                                               _ptr(seg_ptr, torch.int64, "seg_ptr"),
+                                               _ptr(seg_rows, torch.int32, "seg_rows"), *_ws(workspace), _stream()))

@@ -1,14 +1,67 @@
 """One-off set-up of a partition (the "Graph Engine" step, Sec. 3.2; Alg. 1 lines 3-7).
 
-Builds, once per graph, the index structures the kernels consume: the normalised
-operator of the partition (Sec. 3.4), its transpose as a CSR of its own, the plan
-that cuts long rows into tasks, and the scatter segments of the backward
-dequantizer.  All functions take and return torch tensors and run on whatever
-device the inputs live on; none of this is on the per-layer hot path.
+Builds, once per graph, the index structures the kernels consume: the HALO set and the
+local numbering of a partition, its receive / send sets, the normalised operator
+(Sec. 3.4), its transpose as a CSR of its own, the plan that cuts long rows into tasks,
+and the scatter segments of the backward dequantizer.  The set constructions, the
+transpose and the segments run in the library's own kernels (GPU tensors only); the
+operator weights and the small plans are tensor arithmetic on whatever device the
+inputs live on.  None of this is on the per-layer hot path.
 """
 from __future__ import annotations
 
 import torch
+
+from . import binding as B
+
+
+def _workspace(n, dev):
+    return torch.empty(B.sylvie_graph_workspace_bytes(n) // 8 + 1, dtype=torch.int64, device=dev)
+
+
+def local_index(gcol, n_in, owner, part):
+    """V_HALO,n and the local numbering of partition `part` (Alg. 1, the HALO node set).
+
+    gcol int32 [nnz]: global neighbour ids of the partition's inner rows; owner int32
+    [n_nodes].  Returns (pos int32 [n_nodes], halo_gid int32 [n_halo] ascending, col int32
+    [nnz]): pos[g] = local row of node g or -1, col = the adjacency in local rows.
+    """
+    dev = owner.device
+    n_nodes, nnz = int(owner.numel()), int(gcol.numel())
+    ws = _workspace(n_nodes, dev)
+    pos = torch.empty(n_nodes, dtype=torch.int32, device=dev)
+    # every named node is a distinct node that the partition does not own
+    cap = max(0, min(nnz, n_nodes - n_in))
+    halo_gid = torch.empty(max(cap, 1), dtype=torch.int32, device=dev)
+    _, n_halo = B.sylvie_graph_local_index(gcol, nnz, n_in, owner, n_nodes, part, pos, halo_gid, cap, ws)
+    col = torch.empty(nnz, dtype=torch.int32, device=dev)
+    B.sylvie_graph_relabel_columns(gcol, nnz, pos, n_nodes, col, ws)
+    return pos, halo_gid[:n_halo].clone(), col
+
+
+def rows_in_owner(owner, n_parts):
+    """(row_of int32 [n_nodes], part_ptr int64 [n_parts + 1]): every node's row in its owner's
+    inner block (its rank among the owner's nodes, ascending id) and the partitions' sizes."""
+    dev = owner.device
+    n_nodes = int(owner.numel())
+    row_of = torch.empty(n_nodes, dtype=torch.int32, device=dev)
+    part_ptr = torch.empty(n_parts + 1, dtype=torch.int64, device=dev)
+    B.sylvie_graph_rows_in_owner(owner, n_nodes, n_parts, row_of, part_ptr, _workspace(n_nodes, dev))
+    return row_of, part_ptr
+
+
+def recv_sets(halo_gid, owner, row_of, n_parts):
+    """R_k = V_HALO,n & V_k for every k (Alg. 1, the receive sets): (R_ptr int64 [n_parts + 1],
+    R_halo int32 [n_halo], R_row int32 [n_halo]); see sylvie_graph_recv_sets.  The rows partition
+    n sends to k are R_row[R_ptr[n] : R_ptr[n+1]] of partition k's result."""
+    dev = owner.device
+    n_halo = int(halo_gid.numel())
+    R_ptr = torch.empty(n_parts + 1, dtype=torch.int64, device=dev)
+    R_halo = torch.empty(n_halo, dtype=torch.int32, device=dev)
+    R_row = torch.empty(n_halo, dtype=torch.int32, device=dev)
+    B.sylvie_graph_recv_sets(halo_gid if n_halo else None, n_halo, owner, row_of, int(owner.numel()), n_parts,
+                             R_ptr, R_halo if n_halo else None, R_row if n_halo else None, _workspace(n_halo, dev))
+    return R_ptr, R_halo, R_row
 
 
 def gcn_operator(rowptr, col, deg, n_in):
@@ -43,18 +96,21 @@ def mean_operator(rowptr, col, n_in):
     return rowptr, col, w
 
 
-def transpose_csr(rowptr, col, w, n_cols):
+def transpose_csr(rowptr, col, w, n_cols, want_perm=False):
     """CSR of the transposed operator: n_cols rows; entries of a row in ascending
-    original-row order.  Returns (rowptrT int64, colT int32, wT float32)."""
+    original-row order.  Returns (rowptrT int64, colT int32, wT float32) and, with
+    want_perm, perm int64 [nnz]: entry i of the transpose is entry perm[i] of the
+    operator (valuesT = values[perm])."""
     dev = rowptr.device
-    n_rows = int(rowptr.numel()) - 1
-    counts = rowptr[1:] - rowptr[:-1]
-    rows = torch.repeat_interleave(torch.arange(n_rows, device=dev), counts)
-    c64 = col.to(torch.int64)
-    order = torch.argsort(c64 * n_rows + rows)
-    rowptrT = torch.zeros(n_cols + 1, dtype=torch.int64, device=dev)
-    rowptrT[1:] = torch.cumsum(torch.bincount(c64, minlength=n_cols), 0)
-    return rowptrT, rows[order].to(torch.int32), w[order].contiguous()
+    n_rows, nnz = int(rowptr.numel()) - 1, int(col.numel())
+    rowptrT = torch.empty(n_cols + 1, dtype=torch.int64, device=dev)
+    colT = torch.empty(nnz, dtype=torch.int32, device=dev)
+    wT = None if w is None else torch.empty(nnz, dtype=torch.float32, device=dev)
+    perm = torch.empty(nnz, dtype=torch.int64, device=dev) if want_perm else None
+    B.sylvie_graph_transpose_csr(rowptr, col if nnz else None, w if nnz else None, n_rows, n_cols, nnz, rowptrT,
+                                 colT if nnz else None, wT if nnz else None, perm if nnz else None,
+                                 _workspace(nnz, dev))
+    return (rowptrT, colT, wT, perm) if want_perm else (rowptrT, colT, wT)
 
 
 def long_row_plan(rowptr, chunk, row_begin=0, row_end=None):
@@ -74,29 +130,33 @@ def long_row_plan(rowptr, chunk, row_begin=0, row_end=None):
     return long_rows.to(torch.int32), long_ptr, int(long_ptr[-1])
 
 
-def scatter_segments(dst_row):
-    """Group wire rows by destination row for the backward dequantizer.
+def scatter_segments_dense(dst_row, n_dst):
+    """Wire rows grouped by destination row, one (possibly empty) segment for every
+    destination row 0 .. n_dst - 1: returns (seg_ptr int64 [n_dst + 1], seg_rows int32 [n]);
+    destination r receives wire rows seg_rows[seg_ptr[r] : seg_ptr[r+1]], ascending."""
+    dev = dst_row.device
+    n = int(dst_row.numel())
+    seg_ptr = torch.empty(n_dst + 1, dtype=torch.int64, device=dev)
+    seg_rows = torch.empty(n, dtype=torch.int32, device=dev)
+    B.sylvie_graph_scatter_segments(dst_row if n else None, n, n_dst, seg_ptr, seg_rows if n else None,
+                                    _workspace(n, dev))
+    return seg_ptr, seg_rows
+
+
+def scatter_segments(dst_row, n_dst=None):
+    """Group wire rows by destination row for the backward dequantizer, destinations
+    without wire rows left out.
 
     dst_row int32 [n]: destination of wire row i.  Returns (seg_ptr int64 [m + 1],
     seg_rows int32 [n], dst_ids int32 [m]): destination dst_ids[k] receives wire
     rows seg_rows[seg_ptr[k] : seg_ptr[k+1]], ascending.
     """
-    d64 = dst_row.to(torch.int64)
-    order = torch.sort(d64, stable=True).indices
-    dst_ids, counts = torch.unique_consecutive(d64[order], return_counts=True)
-    seg_ptr = torch.zeros(dst_ids.numel() + 1, dtype=torch.int64, device=dst_row.device)
-    seg_ptr[1:] = torch.cumsum(counts, 0)
-    return seg_ptr, order.to(torch.int32), dst_ids.to(torch.int32)
-
-
-def scatter_segments_dense(dst_row, n_dst):
-    """Like scatter_segments, but with one (possibly empty) segment for every
-    destination row 0 .. n_dst - 1: returns (seg_ptr int64 [n_dst + 1], seg_rows int32 [n])."""
-    d64 = dst_row.to(torch.int64)
-    order = torch.sort(d64, stable=True).indices
-    seg_ptr = torch.zeros(n_dst + 1, dtype=torch.int64, device=dst_row.device)
-    seg_ptr[1:] = torch.cumsum(torch.bincount(d64, minlength=n_dst), 0)
-    return seg_ptr, order.to(torch.int32)
+    if n_dst is None:
+        n_dst = int(dst_row.max()) + 1 if dst_row.numel() else 1
+    dense_ptr, seg_rows = scatter_segments_dense(dst_row, n_dst)
+    dst_ids = torch.nonzero(dense_ptr[1:] > dense_ptr[:-1]).flatten()
+    seg_ptr = torch.cat([dense_ptr[dst_ids], dense_ptr[-1:]])
+    return seg_ptr, seg_rows, dst_ids.to(torch.int32)
 
 
 def piece_table(rowptr, chunk):
@@ -118,13 +178,3 @@ def piece_table(rowptr, chunk):
     piece_ptr[:-1] = start
     piece_ptr[-1] = rowptr[-1]
     return piece_ptr, piece_row.to(torch.int32), row_piece
-
-
-def transpose_permutation(rowptr, col, n_cols):
-    """perm int64 [nnz]: entry i of the transposed operator (as built by transpose_csr) is entry
-    perm[i] of the operator, so that valuesT = values[perm]."""
-    n_rows = int(rowptr.numel()) - 1
-    counts = rowptr[1:] - rowptr[:-1]
-    rows = torch.repeat_interleave(torch.arange(n_rows, device=rowptr.device), counts)
-    key = col.to(torch.int64) * n_rows + rows
-    return torch.sort(key, stable=True).indices

@@ -121,7 +121,8 @@ class LayerLoop:
             else:
                 op = GE.mean_operator(part.rowptr, part.col, part.n_in)
             n_loc = part.n_in + part.n_halo
-            opT = GE.transpose_csr(op[0], op[1], op[2], n_loc)
+            *opT, perm = GE.transpose_csr(op[0], op[1], op[2], n_loc, want_perm=True)
+            opT = tuple(opT)
             plan = GE.long_row_plan(op[0], chunk)
             planT = GE.long_row_plan(opT[0], chunk)
             blocks = []
@@ -130,10 +131,11 @@ class LayerLoop:
                 j = 0
                 for o, c in zip(own.tolist(), cnt.tolist()):
                     rows = halo_row[p][j:j + c].contiguous()
-                    sp, sr, di = GE.scatter_segments(rows)
+                    sp, sr, di = GE.scatter_segments(rows, parts[o].n_in)
                     blocks.append(Block(o, j, j + c, rows, sp, sr, di))
                     j += c
             st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
+            st.perm = perm              # entry i of opT is entry perm[i] of op
             Wd = self._words(dmax)
             st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
@@ -609,7 +611,6 @@ class AttentionLoop(LayerLoop):
             nnz = int(st.op[0][-1])
             st.pieces = GE.piece_table(st.op[0], chunk)
             st.piecesT = GE.piece_table(st.opT[0], chunk)
-            st.perm = GE.transpose_permutation(st.op[0], st.op[1], n_loc)
             st.P = [None] + [torch.empty(n_loc, dims[l], dtype=torch.float32, device=dev)
                              for l in range(1, self.L + 1)]
             st.Zg = [None] + [torch.empty(st.n_in, dims[l], dtype=torch.float32, device=dev)

@@ -81,8 +81,7 @@ def test_attention_kernels_parity(oracle, F, chunk):
     rs, Ss = oracle.segment_sum(rp, de, want_S=True)
     torch.cuda.synchronize()
     close(out.cpu().numpy(), rs, Ss, "ds_dst")
-    opT = GE.transpose_csr(rpd, cld, torch.ones(nnz, device=DEV), n_loc)
-    perm = GE.transpose_permutation(rpd, cld, n_loc)
+    *opT, perm = GE.transpose_csr(rpd, cld, torch.ones(nnz, device=DEV), n_loc, want_perm=True)
     piecesT = GE.piece_table(opT[0], chunk)
     deT = torch.empty(nnz, device=DEV)
     B.sylvie_permute_f32(de_g, perm, nnz, deT)
