@@ -146,3 +146,135 @@ def test_pipeline_mode_at_full_size(exchange):
             assert torch.equal(loop.record[k], rec[k]), k
     del loop, ref, rec
     torch.cuda.empty_cache()
+
+
+def test_graph_engine_at_full_size(oracle, exchange):
+    """Transpose (3 radix passes over 82.6 M entries), numbering and segments of the stress
+    partition, compared in full with the oracle's sequential loops."""
+    from paper_2303_01277_amd import graph_engine as GE
+    wl, n_in = exchange["wl"], exchange["n_in"]
+    p = wl.parts[0]
+    n_loc = p.n_in + p.n_halo
+    rp, cl, w = GE.gcn_operator(p.rowptr, p.col, p.deg, p.n_in)
+    rpT, clT, wT, perm = GE.transpose_csr(rp, cl, w, n_loc, want_perm=True)
+    torch.cuda.synchronize()
+    ref = oracle.transpose_csr(np_c(rp), np_c(cl), np_c(w), n_loc)
+    for name, got, want in zip(("rowptrT", "colT", "wT", "perm"), (rpT, clT, wT, perm), ref):
+        assert np.array_equal(np_c(got), want), name
+    del ref
+    seg_ptr, seg_rows = GE.scatter_segments_dense(exchange["idx"], n_in)
+    r_ptr, r_rows = oracle.scatter_segments(np_c(exchange["idx"]), n_in)
+    assert np.array_equal(np_c(seg_ptr), r_ptr) and np.array_equal(np_c(seg_rows), r_rows)
+    # numbering: local rows stand in for global ids, the halo rows spread over 7 other owners;
+    # only two thirds of the halo rows are named by the sampled adjacency
+    g = torch.Generator(device=DEV); g.manual_seed(11)
+    owner = torch.zeros(n_loc, dtype=torch.int32, device=DEV)
+    owner[n_in:] = torch.randint(1, 8, (p.n_halo,), generator=g, device=DEV, dtype=torch.int32)
+    gcol = cl[(cl < n_in) | (cl % 3 != 0)].contiguous()
+    pos, halo_gid, col = GE.local_index(gcol, n_in, owner, 0)
+    rp_stub = np.zeros(n_in + 1, np.int64); rp_stub[-1] = gcol.numel()
+    r_halo, r_pos, r_inner = oracle.halo_set(rp_stub, np_c(gcol), n_in, np_c(owner), 0)
+    assert r_inner == n_in and np.array_equal(np_c(halo_gid), r_halo) and np.array_equal(np_c(pos), r_pos)
+    assert np.array_equal(np_c(col), oracle.relabel_columns(np_c(gcol), r_pos))
+    row_of, part_ptr = GE.rows_in_owner(owner, 8)
+    r_row_of, r_part_ptr = oracle.rows_in_owner(np_c(owner), 8)
+    assert np.array_equal(np_c(row_of), r_row_of) and np.array_equal(np_c(part_ptr), r_part_ptr)
+    R = GE.recv_sets(halo_gid, owner, row_of, 8)
+    for got, want in zip(R, oracle.recv_sets(r_halo, np_c(owner), r_row_of, 8)):
+        assert np.array_equal(np_c(got), want)
+
+
+def sub_csr(rp, rows):
+    """Entries of the given rows (device tensors): (sub row pointer, entry indices)."""
+    starts, lens = rp[rows], rp[rows + 1] - rp[rows]
+    sub_rp = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=rp.device)
+    sub_rp[1:] = torch.cumsum(lens, 0)
+    eidx = torch.repeat_interleave(starts - sub_rp[:-1], lens) + torch.arange(int(sub_rp[-1]), device=rp.device)
+    return sub_rp, eidx
+
+
+def close(got, ref, S, what, tol=1e-5):
+    err = np.abs(np.asarray(got, np.float64) - np.asarray(ref, np.float64))
+    bound = tol * np.maximum(np.abs(np.asarray(ref, np.float64)), np.asarray(S, np.float64)) + 1e-30
+    assert (err <= bound).all(), (what, int((err > bound).sum()), float((err / bound).max()))
+
+
+def test_attention_layer_at_full_size(oracle, exchange):
+    """One attention layer (4 heads of 64 columns) forward and backward on the stress partition
+    through the layer loop; every step of the last head is recomputed by the oracle on sampled
+    rows (hub rows included) from the GPU's own inputs to that step."""
+    from paper_2303_01277_amd.trainer import AttentionLoop
+    wl = exchange["wl"]
+    p0 = wl.parts[0]
+    n_in, n_loc = p0.n_in, p0.n_in + p0.n_halo
+    K, F = 4, D // 4
+    g = torch.Generator().manual_seed(9)
+    att = [((torch.randn(D, generator=g) / F ** 0.5).to(DEV), (torch.randn(D, generator=g) / F ** 0.5).to(DEV))]
+    owner = [torch.zeros(p0.n_halo, dtype=torch.int32, device=DEV)]
+    Jout = torch.randn(n_in, D, device=DEV, generator=torch.Generator(device=DEV).manual_seed(10))
+    loop = AttentionLoop(wl.parts, owner, [wl.mirror], wl.X, [Jout], wl.W[:1], att, (D, D), heads=K,
+                         chunk=1024, exchange_first_layer=False)
+    loop.forward(5, OL.pair_seed)
+    loop.backward(5, OL.pair_seed)
+    torch.cuda.synchronize()
+    st = loop.parts[0]
+    rp, cl, _ = st.op
+    rpT, clT, _ = st.opT
+    c0 = (K - 1) * F
+    a_dst, a_src = np_c(att[0][0][c0:]), np_c(att[0][1][c0:])
+    rng = np.random.default_rng(1)
+    deg = rp[1:] - rp[:-1]
+    rows = np.unique(np.concatenate([rng.integers(0, n_in, 150), np_c(torch.argsort(deg, descending=True)[:4]),
+                                     [0, n_in - 1]]))
+    rows_d = torch.from_numpy(rows).to(DEV)
+    sub_rp, eidx = sub_csr(rp, rows_d)
+    sel, inv = torch.unique(cl[eidx].long(), return_inverse=True)
+    srp, scl = np_c(sub_rp), np_c(inv.to(torch.int32))
+    P, ht = st.P[1], st.Htil[0]
+    # projection on sampled inner and halo rows, from the GPU's recovered Htilde
+    some = torch.cat([rows_d, torch.from_numpy(rng.integers(n_in, n_loc, 100)).to(DEV)])
+    Pr, S = oracle.transform_fwd(np_c(ht[some]), np_c(wl.W[0]), False, want_S=True)
+    close(np_c(P[some]), Pr, S, "P")
+    Psel, Prow = np_c(P[sel][:, c0:]), np_c(P[rows_d][:, c0:])
+    sd, ss, al = st.s_dst[1][K - 1], st.s_src[1][K - 1], st.alpha[1][K - 1]
+    close(np_c(sd[rows_d]), oracle.row_dot(Prow, a_dst), np.abs(Prow.astype(np.float64)) @ np.abs(a_dst), "s_dst")
+    close(np_c(ss[sel]), oracle.row_dot(Psel, a_src), np.abs(Psel.astype(np.float64)) @ np.abs(a_src), "s_src")
+    sd_s, ss_s, al_s = np_c(sd[rows_d]), np_c(ss[sel]), np_c(al[eidx])
+    close(al_s, oracle.edge_softmax_fwd(srp, scl, sd_s, ss_s, 0.2), np.ones_like(al_s), "alpha")
+    Zr, S = oracle.aggregate_fwd(srp, scl, al_s, Psel, F, want_S=True)
+    close(np_c(st.out[rows_d][:, c0:]), Zr, S, "Z")
+    # backward of the last head: its edge arrays are still in the loop's scratch
+    dal, de, deT, alT = st.edge
+    dZr = np_c(Jout[rows_d][:, c0:])
+    ref, S = oracle.sddmm(srp, scl, dZr, Psel, F, want_S=True)
+    dal_s = np_c(dal[eidx])
+    close(dal_s, ref, S, "dalpha")
+    ref, S = oracle.edge_softmax_bwd(srp, scl, al_s, dal_s, sd_s, ss_s, 0.2, want_S=True)
+    de_s = np_c(de[eidx])
+    close(de_s, ref, S, "de")
+    ref, S = oracle.segment_sum(srp, de_s, want_S=True)
+    close(np_c(st.ds_dst[rows_d]), ref, S, "ds_dst")
+    assert torch.equal(deT, de[st.perm]) and torch.equal(alT, al[st.perm])
+    # sampled columns (rows of the transpose): hubs, inner and halo
+    degT = rpT[1:] - rpT[:-1]
+    cols = np.unique(np.concatenate([rng.integers(0, n_loc, 150), np_c(torch.argsort(degT, descending=True)[:4]),
+                                     [0, n_in - 1, n_in, n_loc - 1]]))
+    cols_d = torch.from_numpy(cols).to(DEV)
+    subT_rp, eT = sub_csr(rpT, cols_d)
+    selT, invT = torch.unique(clT[eT].long(), return_inverse=True)
+    sTrp, sTcl = np_c(subT_rp), np_c(invT.to(torch.int32))
+    ref, S = oracle.segment_sum(sTrp, np_c(deT[eT]), want_S=True)
+    ds_src_s = np_c(st.ds_src[cols_d])
+    close(ds_src_s, ref, S, "ds_src")
+    agg, S = oracle.aggregate_fwd(sTrp, sTcl, np_c(alT[eT]), np_c(Jout[selT][:, c0:]), F, want_S=True)
+    ds_dst_s = np.where(cols < n_in, np_c(st.ds_dst[cols_d.clamp(max=n_in - 1)]), 0).astype(np.float64)
+    t1 = ds_src_s.astype(np.float64)[:, None] * a_src.astype(np.float64)[None, :]
+    t2 = ds_dst_s[:, None] * a_dst.astype(np.float64)[None, :]
+    close(np_c(st.dP[cols_d][:, c0:c0 + F]), agg.astype(np.float64) + t1 + t2, S + np.abs(t1) + np.abs(t2), "dP")
+    # attention-vector gradients: the plain definition over all rows
+    Pk = np_c(P[:, c0:]).astype(np.float64)
+    dsd, dss = np_c(st.ds_dst).astype(np.float64), np_c(st.ds_src).astype(np.float64)
+    close(np_c(st.Ga[1][0][c0:]), Pk[:n_in].T @ dsd, np.abs(Pk[:n_in]).T @ np.abs(dsd), "da_dst")
+    close(np_c(st.Ga[1][1][c0:]), Pk.T @ dss, np.abs(Pk).T @ np.abs(dss), "da_src")
+    del loop
+    torch.cuda.empty_cache()
