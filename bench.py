@@ -401,6 +401,88 @@ def pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced):
             "schedule": "every epoch after the first in pipeline mode (eps_s = infinity)"}
 
 
+def attention_bench(torch, B, wl, owner, rows, spec, args, forced, heads=4):
+    """The attention model (GAT, Sec. 5.1) on the same partition and widths: whole forward +
+    backward step of the layer loop, and one more step with every entry point bracketed by
+    events.  Reported beside the headline; not part of value."""
+    from paper_2303_01277_amd.trainer import AttentionLoop
+    g = torch.Generator().manual_seed(7)
+    dev = wl.X[0].device
+    att = [((torch.randn(w.shape[1], generator=g) / (w.shape[1] // heads) ** 0.5).to(dev),
+            (torch.randn(w.shape[1], generator=g) / (w.shape[1] // heads) ** 0.5).to(dev)) for w in wl.W]
+    loop = AttentionLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, att, spec.dims, heads=heads,
+                         chunk=args.chunk, exchange_first_layer=forced)
+    seed = 20230301
+    for i in range(2):
+        loop.forward(seed + i)
+        loop.backward(seed + i)
+    torch.cuda.synchronize()
+    steps = max(2, min(args.steps, 5))
+    t0 = time.perf_counter()
+    for i in range(steps):
+        loop.forward(seed + 10 + i)
+        loop.backward(seed + 10 + i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    names = [n for n in dir(B) if n.startswith("sylvie_") and callable(getattr(B, n))]
+    orig = {n: getattr(B, n) for n in names}
+    acc = {}
+
+    def wrap(n):
+        f = orig[n]
+
+        def timed(*a, **k):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            r = f(*a, **k)
+            e1.record()
+            e1.synchronize()
+            acc[n] = acc.get(n, 0.0) + e0.elapsed_time(e1)
+            return r
+        return timed
+    try:
+        for n in names:
+            setattr(B, n, wrap(n))
+        loop.forward(seed + 50)
+        loop.backward(seed + 50)
+        torch.cuda.synchronize()
+    finally:
+        for n in names:
+            setattr(B, n, orig[n])
+    nnz = sum(int(st.op[0][-1]) for st in loop.parts)
+    return {"model": f"attention, {heads} heads, {loop.L} layers", "ms_per_step": ms,
+            "edges_per_s": 2 * loop.L * nnz / (ms * 1e-3),
+            "entry_points_ms": {k: round(v, 3) for k, v in sorted(acc.items(), key=lambda kv: -kv[1]) if v >= 0.05}}
+
+
+def graph_engine_bench(torch, wl):
+    """Set-up kernels (Alg. 1, before the epoch loop) on the partition's operator."""
+    from paper_2303_01277_amd import graph_engine as GE
+    p = wl.parts[0]
+    n_loc = p.n_in + p.n_halo
+    rp, cl, w = GE.gcn_operator(p.rowptr, p.col, p.deg, p.n_in)
+    owner = torch.zeros(n_loc, dtype=torch.int32, device=cl.device)
+    owner[p.n_in:] = 1
+    row_of, _ = GE.rows_in_owner(owner, 2)
+
+    def timed(fn, iters=3):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters
+    halo = GE.local_index(cl, p.n_in, owner, 0)[1]
+    return {"entries": int(cl.numel()), "columns": n_loc,
+            "transpose_with_permutation_ms": timed(lambda: GE.transpose_csr(rp, cl, w, n_loc, want_perm=True)),
+            "halo_set_numbering_relabel_ms": timed(lambda: GE.local_index(cl, p.n_in, owner, 0)),
+            "rows_in_owner_ms": timed(lambda: GE.rows_in_owner(owner, 2)),
+            "recv_sets_ms": timed(lambda: GE.recv_sets(halo, owner, row_of, 2)),
+            "scatter_segments_ms": (timed(lambda: GE.scatter_segments_dense(wl.mirror, p.n_in))
+                                    if wl.mirror is not None else None)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -412,6 +494,9 @@ def main():
     ap.add_argument("--wire", default="1bit", choices=["1bit", "2bit", "4bit", "8bit", "fp16", "fp32"],
                     help="exchange format: 1bit is the paper's method and the headline; the others "
                          "are the points of its bit-width study (unfused quantize / dequantize)")
+    ap.add_argument("--section", default="all", choices=["all", "headline", "attention"],
+                    help="headline: the timed step and its companions only; attention: only the "
+                         "attention model and the Graph Engine set-up kernels (for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (scales the rocprofv3 "
@@ -456,6 +541,12 @@ def main():
         owner = [p.halo_part for p in wl.parts]
         rows = [p.halo_row for p in wl.parts]
     forced = spec.name.startswith("tiny")
+    if args.section == "attention":
+        print(json.dumps({"section": "attention", "config": {"workload": spec.name},
+                          "graph_engine": graph_engine_bench(torch, wl),
+                          "attention_model": attention_bench(torch, B, wl, owner, rows, spec, args, forced)}),
+              flush=True)
+        return
     t0 = time.time()
     loop = LayerLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, spec.model, spec.dims,
                      chunk=args.chunk, exchange_first_layer=forced, wire=args.wire)
@@ -569,6 +660,10 @@ def main():
     out["training_tail"] = training_tail_bench(torch, loop, wl, ms_per_step)
     if args.wire == "1bit":
         out["pipeline"] = pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced)
+    if args.section == "all":
+        out["graph_engine"] = graph_engine_bench(torch, wl)
+        if not any(d % 4 for d in spec.dims[1:]):
+            out["attention_model"] = attention_bench(torch, B, wl, owner, rows, spec, args, forced)
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(torch, loop, loop.parts[0], spec.dims)

@@ -372,8 +372,9 @@ int32_t sylvie_segment_sum(const int64_t *piece_ptr, const int32_t *piece_row, c
                            int64_t n_pieces, int64_t n_rows, const float *vals, float *out,
                            void *workspace, size_t workspace_bytes, void *stream);
 /* out[c] = sum_{i < n} s[i] * X[i][c], c < F: the gradients of the attention vectors
- * (da_dst = sum_v ds_dst[v] P_v, da_src = sum_u ds_src[u] P_u).  Rows are added in slabs of
- * 2048 in ascending order, the slabs joined in ascending order.  Workspace: see the size query. */
+ * (da_dst = sum_v ds_dst[v] P_v, da_src = sum_u ds_src[u] P_u).  The order of the additions is
+ * fixed (slabs of 2048 rows, sixteen interleaved partial sums per slab, slabs joined in
+ * ascending order), so results repeat bit for bit.  Workspace: see the size query. */
 size_t sylvie_scaled_column_sum_workspace_bytes(int64_t n, int32_t F);
 int32_t sylvie_scaled_column_sum(const float *X, int64_t ld_x, int64_t n, int32_t F, const float *s,
                                  float *out, void *workspace, size_t workspace_bytes, void *stream);

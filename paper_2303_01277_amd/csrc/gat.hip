@@ -238,28 +238,61 @@ __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void softmax_bwd_kernel(
 
 constexpr int kColSumRows = 2048;     // rows per slab
 
-// Slab z of rows -> part[z][0..F): thread t owns columns t, t + 256, ...; rows in order.
+// Slab z of rows -> part[z][0..F).  Wave w of the block takes rows r0 + w, r0 + w + 4, ... of the
+// slab, lane l columns l, l + 64, ...; four independent chains per lane (rows 16 apart) keep
+// loads in flight.  Chains, then waves, are joined in a fixed order.
 __global__ __launch_bounds__(256) void scaled_column_sum_slab_kernel(
     const float *__restrict__ X, int64_t ld, int64_t n, int F, const float *__restrict__ s,
     float *__restrict__ part)
 {
+    __shared__ float red[4][kWave];
+    const int wave = static_cast<int>(threadIdx.x) / kWave, lane = lane_id();
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * kColSumRows;
     const int64_t r1 = r0 + kColSumRows < n ? r0 + kColSumRows : n;
-    for (int c = threadIdx.x; c < F; c += 256) {
-        float acc = 0.0f;
-        for (int64_t i = r0; i < r1; ++i) acc = fmaf(s[i], X[i * ld + c], acc);
-        part[static_cast<int64_t>(blockIdx.x) * F + c] = acc;
+    for (int c0 = 0; c0 < F; c0 += kWave) {
+        const int c = c0 + lane;
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+        if (c < F) {
+            int64_t i = r0 + wave;
+            for (; i + 12 < r1; i += 16) {
+                a0 = fmaf(s[i], X[i * ld + c], a0);
+                a1 = fmaf(s[i + 4], X[(i + 4) * ld + c], a1);
+                a2 = fmaf(s[i + 8], X[(i + 8) * ld + c], a2);
+                a3 = fmaf(s[i + 12], X[(i + 12) * ld + c], a3);
+            }
+            for (; i < r1; i += 4) a0 = fmaf(s[i], X[i * ld + c], a0);
+        }
+        red[wave][lane] = (a0 + a1) + (a2 + a3);
+        __syncthreads();
+        if (wave == 0 && c < F)
+            part[static_cast<int64_t>(blockIdx.x) * F + c] =
+                ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+        __syncthreads();
     }
 }
 
-__global__ void scaled_column_sum_join_kernel(const float *__restrict__ part, int64_t n_slabs, int F,
-                                              float *__restrict__ out)
+// out[c] = sum over the slabs of part[z][c].  One block per 64 columns: wave w adds slabs
+// w, w + 4, ... in four chains (slabs 16 apart), chains then waves are joined in a fixed order.
+__global__ __launch_bounds__(256) void scaled_column_sum_join_kernel(const float *__restrict__ part, int64_t n_slabs,
+                                                                    int F, float *__restrict__ out)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= F) return;
-    float acc = 0.0f;
-    for (int64_t z = 0; z < n_slabs; ++z) acc += part[z * F + c];
-    out[c] = acc;
+    __shared__ float red[4][kWave];
+    const int wave = static_cast<int>(threadIdx.x) / kWave, lane = lane_id();
+    const int c = static_cast<int>(blockIdx.x) * kWave + lane;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    if (c < F) {
+        int64_t z = wave;
+        for (; z + 12 < n_slabs; z += 16) {
+            a0 += part[z * F + c];
+            a1 += part[(z + 4) * F + c];
+            a2 += part[(z + 8) * F + c];
+            a3 += part[(z + 12) * F + c];
+        }
+        for (; z < n_slabs; z += 4) a0 += part[z * F + c];
+    }
+    red[wave][lane] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (wave == 0 && c < F) out[c] = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
 }
 
 // ---- small element-wise pieces ------------------------------------------------------------
@@ -478,7 +511,7 @@ extern "C" int32_t sylvie_scaled_column_sum(const float *X, int64_t ld_x, int64_
     if (slabs > 0)
         hipLaunchKernelGGL(scaled_column_sum_slab_kernel, dim3(static_cast<unsigned>(slabs)), dim3(256), 0, st, X,
                            ld_x, n, F, s, part);
-    hipLaunchKernelGGL(scaled_column_sum_join_kernel, dim3((F + 255) / 256), dim3(256), 0, st, part, slabs, F, out);
+    hipLaunchKernelGGL(scaled_column_sum_join_kernel, dim3((F + kWave - 1) / kWave), dim3(256), 0, st, part, slabs, F, out);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
