@@ -7,7 +7,9 @@
 // The weighted sums themselves (Z = sum alpha P_u and its transpose) are the ordinary CSR
 // aggregation kernels with alpha as the edge weights.
 //
-// Work unit of every kernel here: one wavefront per PIECE.  A piece is a run of at most
+// Work unit of every kernel here: one PIECE, walked by a wavefront (the sampled product, whose
+// lanes split the columns) or by a group of 16 lanes (the per-entry scalar kernels: most rows
+// have a few dozen entries, so four pieces share a wavefront).  A piece is a run of at most
 // `chunk` consecutive entries of one row; rows up to `chunk` entries are one piece, longer
 // rows (hubs) several, so that no wavefront walks a 100 000-entry row alone.  The piece table
 // is built at set-up: piece_ptr[k] .. piece_ptr[k+1] are the entries of piece k, piece_row[k]
@@ -45,46 +47,98 @@ __device__ __forceinline__ float gat_wave_sum(float v)
 }
 __device__ __forceinline__ float lrelu(float x, float slope) { return x > 0.0f ? x : slope * x; }
 
+// Sum over the 16 lanes of a DPP row, left in every lane of the row.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
+    return v;
+}
+
+__device__ __forceinline__ float row16_max(float v)
+{
+    float o;
+    o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+    v = o > v ? o : v;
+    o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+    v = o > v ? o : v;
+    o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));
+    v = o > v ? o : v;
+    o = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));
+    v = o > v ? o : v;
+    return v;
+}
+
+constexpr int kGroup = 16;                                         // lanes per piece
+constexpr int kPiecesPerBlock = kGatWavesPerBlock * kWave / kGroup;
+
+// Piece of this 16-lane group, or -1 past the end (the whole group leaves together).
+__device__ __forceinline__ int64_t group_piece(const Pieces &pc)
+{
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * kPiecesPerBlock + static_cast<int>(threadIdx.x) / kGroup;
+    return k < pc.n_pieces ? k : -1;
+}
+
 // ---- row dot products ---------------------------------------------------------------
 
+// 16 lanes per row, four rows per wavefront.  VEC = 4: 16-byte loads (ld, F multiples of 4,
+// 16-byte aligned base); VEC = 1: element by element.
+template <int VEC>
 __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void row_dot_kernel(
     const float *__restrict__ P, int64_t ld, int64_t n, int F, const float *__restrict__ a,
     float *__restrict__ out)
 {
-    const int lane = lane_id();
-    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t i = static_cast<int64_t>(blockIdx.x) * kGatWavesPerBlock + wave;
+    const int g = static_cast<int>(threadIdx.x) & (kGroup - 1);
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kPiecesPerBlock + static_cast<int>(threadIdx.x) / kGroup;
     if (i >= n) return;
     const float *row = P + i * ld;
     float acc = 0.0f;
-    for (int c = lane; c < F; c += 64) acc = fmaf(row[c], a[c], acc);
-    acc = gat_wave_sum(acc);
-    if (lane == 0) out[i] = acc;
+    if constexpr (VEC == 4) {
+        for (int c = g * 4; c < F; c += kGroup * 4) {
+            const float4 x = *reinterpret_cast<const float4 *>(row + c);
+            const float4 y = *reinterpret_cast<const float4 *>(a + c);
+            acc = fmaf(x.x, y.x, acc);
+            acc = fmaf(x.y, y.y, acc);
+            acc = fmaf(x.z, y.z, acc);
+            acc = fmaf(x.w, y.w, acc);
+        }
+    } else {
+        for (int c = g; c < F; c += kGroup) acc = fmaf(row[c], a[c], acc);
+    }
+    acc = row16_sum(acc);
+    if (g == 0) out[i] = acc;
 }
 
 // ---- edge softmax, forward ------------------------------------------------------------
 
-// Per piece: running maximum m and sum of exp(e - m) of its entries.
+// Per piece: maximum m and sum of exp(x - m) of its scores x = leaky_relu(s_dst + s_src), in one
+// sweep (a lane rescales its running sum whenever its maximum grows; the 16 lanes are joined
+// the same way).  The scores are left in `score` so that the last step need not gather again.
 __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void softmax_piece_stats_kernel(
     Pieces pc, const int32_t *__restrict__ col, const float *__restrict__ s_dst,
-    const float *__restrict__ s_src, float slope, float2 *__restrict__ piece_stats)
+    const float *__restrict__ s_src, float slope, float2 *__restrict__ piece_stats, float *__restrict__ score)
 {
-    const int lane = lane_id();
-    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kGatWavesPerBlock + wave;
-    if (k >= pc.n_pieces) return;
-    const int64_t e0 = uniform(pc.piece_ptr[k]), e1 = uniform(pc.piece_ptr[k + 1]);
-    const float sd = s_dst[uniform(pc.piece_row[k])];
-    float m = -__builtin_inff();
-    for (int64_t e = e0 + lane; e < e1; e += 64) {
+    const int g = static_cast<int>(threadIdx.x) & (kGroup - 1);
+    const int64_t k = group_piece(pc);
+    if (k < 0) return;
+    const int64_t e0 = pc.piece_ptr[k], e1 = pc.piece_ptr[k + 1];
+    const float sd = s_dst[pc.piece_row[k]];
+    float m = -__builtin_inff(), s = 0.0f;
+    for (int64_t e = e0 + g; e < e1; e += kGroup) {
         const float x = lrelu(sd + s_src[col[e]], slope);
-        m = x > m ? x : m;
+        score[e] = x;
+        if (x > m) {
+            s = s * __expf(m - x) + 1.0f;
+            m = x;
+        } else {
+            s += __expf(x - m);
+        }
     }
-    m = gat_wave_max(m);
-    float s = 0.0f;
-    for (int64_t e = e0 + lane; e < e1; e += 64) s += __expf(lrelu(sd + s_src[col[e]], slope) - m);
-    s = gat_wave_sum(s);
-    if (lane == 0) piece_stats[k] = make_float2(m, s);
+    const float M = row16_max(m);                   // finite: a piece has at least one entry
+    s = row16_sum(s * __expf(m - M));               // a lane without entries holds s = 0, m = -inf
+    if (g == 0) piece_stats[k] = make_float2(M, s);
 }
 
 // Per row: join the pieces in order: m = max m_k, s = sum s_k exp(m_k - m).
@@ -101,35 +155,20 @@ __global__ void softmax_row_stats_kernel(Pieces pc, const float2 *__restrict__ p
     row_stats[v] = make_float2(m, s);
 }
 
+// alpha = exp(score - m_row) / s_row, in place over the scores.
 __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void softmax_alpha_kernel(
-    Pieces pc, const int32_t *__restrict__ col, const float *__restrict__ s_dst,
-    const float *__restrict__ s_src, float slope, const float2 *__restrict__ row_stats,
-    float *__restrict__ alpha)
+    Pieces pc, const float2 *__restrict__ row_stats, float *__restrict__ alpha)
 {
-    const int lane = lane_id();
-    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kGatWavesPerBlock + wave;
-    if (k >= pc.n_pieces) return;
-    const int64_t e0 = uniform(pc.piece_ptr[k]), e1 = uniform(pc.piece_ptr[k + 1]);
-    const int v = uniform(pc.piece_row[k]);
-    const float sd = s_dst[v];
-    const float2 st = row_stats[v];
+    const int g = static_cast<int>(threadIdx.x) & (kGroup - 1);
+    const int64_t k = group_piece(pc);
+    if (k < 0) return;
+    const int64_t e0 = pc.piece_ptr[k], e1 = pc.piece_ptr[k + 1];
+    const float2 st = row_stats[pc.piece_row[k]];
     const float inv = 1.0f / st.y;
-    for (int64_t e = e0 + lane; e < e1; e += 64)
-        alpha[e] = __expf(lrelu(sd + s_src[col[e]], slope) - st.x) * inv;
+    for (int64_t e = e0 + g; e < e1; e += kGroup) alpha[e] = __expf(alpha[e] - st.x) * inv;
 }
 
 // ---- sampled dense-dense product: out[e] = A_v . B_u ----------------------------------------
-
-// Sum over the 16 lanes of a DPP row, left in every lane of the row.
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // row_mirror
-    return v;
-}
 
 // 16 lanes per entry, four entries at a time per wavefront.  VEC = 4: lane g of a group holds
 // the 4-column pieces g, g + 16, ... of A_v in registers (PP of them, F <= 64 PP) and loads the
@@ -155,23 +194,32 @@ __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void sddmm_kernel(
             coff[p] = c < F ? c : -1;
             av[p] = c < F ? *reinterpret_cast<const float4 *>(arow + c) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        for (int64_t e = e0; e < e1; e += 4) {
-            const int64_t me = e + grp;
-            const bool on = me < e1;
-            const float *brow = Bm + static_cast<int64_t>(col[on ? me : e0]) * ldb;
-            float acc = 0.0f;
+        // sixteen entries per step: four independent gathers per lane are in flight
+        for (int64_t e = e0; e < e1; e += 16) {
+            float4 b[4][PP];
+            int64_t me[4];
 #pragma unroll
-            for (int p = 0; p < PP; ++p) {
-                if (coff[p] >= 0) {
-                    const float4 b = *reinterpret_cast<const float4 *>(brow + coff[p]);
-                    acc = fmaf(av[p].x, b.x, acc);
-                    acc = fmaf(av[p].y, b.y, acc);
-                    acc = fmaf(av[p].z, b.z, acc);
-                    acc = fmaf(av[p].w, b.w, acc);
-                }
+            for (int u = 0; u < 4; ++u) {
+                me[u] = e + 4 * u + grp;
+                const float *brow = Bm + static_cast<int64_t>(col[me[u] < e1 ? me[u] : e0]) * ldb;
+#pragma unroll
+                for (int p = 0; p < PP; ++p)
+                    b[u][p] = coff[p] >= 0 ? *reinterpret_cast<const float4 *>(brow + coff[p])
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            acc = row16_sum(acc);
-            if (on && g == 0) out[me] = acc;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int p = 0; p < PP; ++p) {
+                    acc = fmaf(av[p].x, b[u][p].x, acc);
+                    acc = fmaf(av[p].y, b[u][p].y, acc);
+                    acc = fmaf(av[p].z, b[u][p].z, acc);
+                    acc = fmaf(av[p].w, b[u][p].w, acc);
+                }
+                acc = row16_sum(acc);
+                if (me[u] < e1 && g == 0) out[me[u]] = acc;
+            }
         }
     } else {
         for (int64_t e = e0; e < e1; e += 4) {
@@ -193,15 +241,14 @@ template <bool WEIGHTED>
 __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void piece_sum_kernel(
     Pieces pc, const float *__restrict__ a, const float *__restrict__ b, float *__restrict__ piece_sum)
 {
-    const int lane = lane_id();
-    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kGatWavesPerBlock + wave;
-    if (k >= pc.n_pieces) return;
-    const int64_t e0 = uniform(pc.piece_ptr[k]), e1 = uniform(pc.piece_ptr[k + 1]);
+    const int g = static_cast<int>(threadIdx.x) & (kGroup - 1);
+    const int64_t k = group_piece(pc);
+    if (k < 0) return;
+    const int64_t e0 = pc.piece_ptr[k], e1 = pc.piece_ptr[k + 1];
     float s = 0.0f;
-    for (int64_t e = e0 + lane; e < e1; e += 64) s += WEIGHTED ? a[e] * b[e] : a[e];
-    s = gat_wave_sum(s);
-    if (lane == 0) piece_sum[k] = s;
+    for (int64_t e = e0 + g; e < e1; e += kGroup) s += WEIGHTED ? a[e] * b[e] : a[e];
+    s = row16_sum(s);
+    if (g == 0) piece_sum[k] = s;
 }
 
 __global__ void row_sum_kernel(Pieces pc, const float *__restrict__ piece_sum, float *__restrict__ out)
@@ -221,14 +268,13 @@ __global__ __launch_bounds__(kGatWavesPerBlock *kWave) void softmax_bwd_kernel(
     const float *__restrict__ s_src, float slope, const float *__restrict__ row_dot,
     float *__restrict__ de)
 {
-    const int lane = lane_id();
-    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kGatWavesPerBlock + wave;
-    if (k >= pc.n_pieces) return;
-    const int64_t e0 = uniform(pc.piece_ptr[k]), e1 = uniform(pc.piece_ptr[k + 1]);
-    const int v = uniform(pc.piece_row[k]);
+    const int g = static_cast<int>(threadIdx.x) & (kGroup - 1);
+    const int64_t k = group_piece(pc);
+    if (k < 0) return;
+    const int64_t e0 = pc.piece_ptr[k], e1 = pc.piece_ptr[k + 1];
+    const int v = pc.piece_row[k];
     const float sd = s_dst[v], dot = row_dot[v];
-    for (int64_t e = e0 + lane; e < e1; e += 64) {
+    for (int64_t e = e0 + g; e < e1; e += kGroup) {
         const float f = sd + s_src[col[e]] > 0.0f ? 1.0f : slope;
         de[e] = (alpha[e] * dalpha[e] - alpha[e] * dot) * f;
     }
@@ -349,6 +395,10 @@ static dim3 piece_grid(int64_t n_pieces)
 {
     return dim3(static_cast<unsigned>((n_pieces + kGatWavesPerBlock - 1) / kGatWavesPerBlock));
 }
+static dim3 group_grid(int64_t n_pieces)       // kernels that walk a piece with 16 lanes
+{
+    return dim3(static_cast<unsigned>((n_pieces + kPiecesPerBlock - 1) / kPiecesPerBlock));
+}
 
 }  // namespace sylvie
 
@@ -361,8 +411,13 @@ extern "C" int32_t sylvie_row_dot(const float *P, int64_t ld_p, int64_t n, int32
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
     if (n == 0) return SYLVIE_OK;
     if (!P || !a || !out) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
-    hipLaunchKernelGGL(row_dot_kernel, piece_grid(n), dim3(kGatWavesPerBlock * kWave), 0,
-                       static_cast<hipStream_t>(stream), P, ld_p, n, F, a, out);
+    const bool v4 = F % 4 == 0 && ld_p % 4 == 0 && aligned(P, 16) && aligned(a, 16);
+    if (v4)
+        hipLaunchKernelGGL(row_dot_kernel<4>, group_grid(n), dim3(kGatWavesPerBlock * kWave), 0,
+                           static_cast<hipStream_t>(stream), P, ld_p, n, F, a, out);
+    else
+        hipLaunchKernelGGL(row_dot_kernel<1>, group_grid(n), dim3(kGatWavesPerBlock * kWave), 0,
+                           static_cast<hipStream_t>(stream), P, ld_p, n, F, a, out);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
@@ -393,12 +448,11 @@ extern "C" int32_t sylvie_edge_softmax_fwd(const int64_t *piece_ptr, const int32
     float2 *piece_stats = static_cast<float2 *>(workspace);
     float2 *row_stats = piece_stats + n_pieces;
     const dim3 block(kGatWavesPerBlock * kWave);
-    hipLaunchKernelGGL(softmax_piece_stats_kernel, piece_grid(n_pieces), block, 0, st, pc, col, s_dst, s_src,
-                       slope, piece_stats);
+    hipLaunchKernelGGL(softmax_piece_stats_kernel, group_grid(n_pieces), block, 0, st, pc, col, s_dst, s_src,
+                       slope, piece_stats, alpha);
     hipLaunchKernelGGL(softmax_row_stats_kernel, dim3(static_cast<unsigned>((n_rows + 255) / 256)), dim3(256),
                        0, st, pc, piece_stats, row_stats);
-    hipLaunchKernelGGL(softmax_alpha_kernel, piece_grid(n_pieces), block, 0, st, pc, col, s_dst, s_src, slope,
-                       row_stats, alpha);
+    hipLaunchKernelGGL(softmax_alpha_kernel, group_grid(n_pieces), block, 0, st, pc, row_stats, alpha);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
@@ -448,7 +502,7 @@ extern "C" int32_t sylvie_segment_sum(const int64_t *piece_ptr, const int32_t *p
     const Pieces pc{piece_ptr, piece_row, row_piece, n_pieces, n_rows};
     float *ps = static_cast<float *>(workspace);
     if (n_pieces > 0)
-        hipLaunchKernelGGL(piece_sum_kernel<false>, piece_grid(n_pieces), dim3(kGatWavesPerBlock * kWave), 0, st,
+        hipLaunchKernelGGL(piece_sum_kernel<false>, group_grid(n_pieces), dim3(kGatWavesPerBlock * kWave), 0, st,
                            pc, vals, nullptr, ps);
     hipLaunchKernelGGL(row_sum_kernel, dim3(static_cast<unsigned>((n_rows + 255) / 256)), dim3(256), 0, st, pc,
                        ps, out);
@@ -477,10 +531,10 @@ extern "C" int32_t sylvie_edge_softmax_bwd(const int64_t *piece_ptr, const int32
     float *ps = static_cast<float *>(workspace);
     float *row_dot = ps + n_pieces;
     const dim3 block(kGatWavesPerBlock * kWave);
-    hipLaunchKernelGGL(piece_sum_kernel<true>, piece_grid(n_pieces), block, 0, st, pc, alpha, dalpha, ps);
+    hipLaunchKernelGGL(piece_sum_kernel<true>, group_grid(n_pieces), block, 0, st, pc, alpha, dalpha, ps);
     hipLaunchKernelGGL(row_sum_kernel, dim3(static_cast<unsigned>((n_rows + 255) / 256)), dim3(256), 0, st, pc,
                        ps, row_dot);
-    hipLaunchKernelGGL(softmax_bwd_kernel, piece_grid(n_pieces), block, 0, st, pc, col, alpha, dalpha, s_dst,
+    hipLaunchKernelGGL(softmax_bwd_kernel, group_grid(n_pieces), block, 0, st, pc, col, alpha, dalpha, s_dst,
                        s_src, slope, row_dot, de);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
