@@ -495,8 +495,9 @@ def main():
                     help="exchange format: 1bit is the paper's method and the headline; the others "
                          "are the points of its bit-width study (unfused quantize / dequantize)")
     ap.add_argument("--section", default="all", choices=["all", "headline", "attention"],
-                    help="headline: the timed step and its companions only; attention: only the "
-                         "attention model and the Graph Engine set-up kernels (for profiling)")
+                    help="headline: the timed step and the stand-alone Low-bit kernels only (no second "
+                         "stream, so per-kernel times in a trace are undisturbed); attention: only the "
+                         "attention model and the Graph Engine set-up kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (scales the rocprofv3 "
@@ -657,10 +658,10 @@ def main():
                         for kk, vv in v.items()} for k, v in ops.items()},
     }
     out["lowbit_kernels"] = lowbit_microbench(torch, B, loop, loop.parts[0], spec.dims[-2])
-    out["training_tail"] = training_tail_bench(torch, loop, wl, ms_per_step)
-    if args.wire == "1bit":
-        out["pipeline"] = pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced)
     if args.section == "all":
+        out["training_tail"] = training_tail_bench(torch, loop, wl, ms_per_step)
+        if args.wire == "1bit":
+            out["pipeline"] = pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced)
         out["graph_engine"] = graph_engine_bench(torch, wl)
         if not any(d % 4 for d in spec.dims[1:]):
             out["attention_model"] = attention_bench(torch, B, wl, owner, rows, spec, args, forced)
