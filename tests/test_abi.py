@@ -105,6 +105,51 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
               C.c_int64(4), C.c_int32(1), p, C.c_int64(16), None) == -1   # ld_a1 < k1
 
 
+def test_widened_entry_points_reject_bad_arguments_without_gpu(lib):
+    """Training tail, attention and Graph Engine entry points: host-side validation only."""
+    p = C.c_void_p(4096)
+    i64, i32, sz = C.c_int64, C.c_int32, C.c_size_t
+    lib.sylvie_graph_workspace_bytes.restype = sz
+    lib.sylvie_graph_workspace_bytes.argtypes = [i64]
+    need = lib.sylvie_graph_workspace_bytes(1000)
+    assert need >= 4 * 4 * 1000 and lib.sylvie_graph_workspace_bytes(0) > 0
+    assert lib.sylvie_graph_workspace_bytes(10 ** 8) > lib.sylvie_graph_workspace_bytes(10 ** 7)
+    tr = lib.sylvie_graph_transpose_csr
+    tr.restype = i32
+    targs = lambda n_rows=4, n_cols=4, nnz=8, w=None, wT=None, ws=need: [
+        p, p, w, i64(n_rows), i64(n_cols), i64(nnz), p, p, wT, None, p, sz(ws), None]
+    assert tr(*targs(n_rows=0)) == -1 and tr(*targs(nnz=-1)) == -1 and tr(*targs(nnz=2 ** 31)) == -1
+    assert tr(*targs(w=p)) == -1 and b"together" in lib.sylvie_last_error()
+    assert tr(*targs(ws=64)) == -5
+    li = lib.sylvie_graph_local_index
+    li.restype = i32
+    counts = (C.c_int64 * 2)()
+    largs = lambda nnz=8, n_nodes=100, cap=10, ws=need: [p, i64(nnz), i64(4), p, i64(n_nodes), i32(0), p, p,
+                                                         i64(cap), counts, p, sz(ws), None]
+    assert li(*largs(n_nodes=0)) == -1 and li(*largs(cap=-1)) == -1 and li(*largs(ws=8)) == -5
+    rs = lib.sylvie_graph_recv_sets
+    rs.restype = i32
+    assert rs(p, i64(5), p, p, i64(100), i32(0), p, p, p, p, sz(need), None) == -1        # n_parts < 1
+    sg = lib.sylvie_graph_scatter_segments
+    sg.restype = i32
+    assert sg(p, i64(5), i64(0), p, p, p, sz(need), None) == -1                            # n_dst < 1
+    assert sg(p, i64(5), i64(9), None, p, p, sz(need), None) == -1                         # no output
+    rd = lib.sylvie_row_dot
+    rd.restype = i32
+    assert rd(p, i64(8), i64(4), i32(16), p, p, None) == -1                               # ld < F
+    assert rd(p, i64(16), i64(0), i32(16), p, p, None) == 0
+    cs = lib.sylvie_scaled_column_sum
+    cs.restype = i32
+    assert cs(p, i64(16), i64(5000), i32(16), p, p, p, sz(16), None) == -5
+    assert cs(p, i64(16), i64(5000), i32(0), p, p, p, sz(1 << 20), None) == -1
+    xe = lib.sylvie_softmax_xent
+    xe.restype = i32
+    assert xe(p, i64(4), i64(8), i32(8), p, C.c_double(1.0), p, i64(8), p, p, None) == -1  # ld_h < classes
+    sgd = lib.sylvie_sgd_update
+    sgd.restype = i32
+    assert sgd(p, p, i64(-1), C.c_float(0.1), None) == -1 and sgd(p, p, i64(0), C.c_float(0.1), None) == 0
+
+
 def test_graph_engine_host_logic(oracle):
     """Host-side set-up arithmetic of the product against the oracle's operator and plain counts
     (the transpose, the sets and the segments run in the library: GPU tests cover them)."""
