@@ -469,7 +469,21 @@ def attention_bench(torch, B, wl, owner, rows, spec, args, forced, heads=4):
         for n in names:
             setattr(B, n, orig[n])
     nnz = sum(int(st.op[0][-1]) for st in loop.parts)
+    # gather count of the three kernels that fetch one float row slice per operator entry
+    # (index + weight or result per entry, 4 F bytes of the gathered row, the rows written)
+    F = spec.dims[1] // heads
+    calls = heads * loop.L
+    n_in = sum(st.n_in for st in loop.parts)
+    n_loc = sum(st.n_in + st.n_halo for st in loop.parts)
+    gathers = {}
+    for name, rows_out in (("sylvie_sddmm", 0), ("sylvie_aggregate_csr_fwd", n_in), ("sylvie_aggregate_csr_bwd", n_loc)):
+        if name in acc:
+            per_call = nnz * (8 + 4 * F) + rows_out * (4 * F + 8) + (n_in * 4 * F if not rows_out else 0)
+            gbps = per_call * calls / (acc[name] * 1e-3) / 1e9
+            gathers[name] = {"gather_bytes_per_call": per_call, "gather_GBps": gbps,
+                             "frac_hbm_peak": gbps / HBM_PEAK_GBS}
     return {"model": f"attention, {heads} heads, {loop.L} layers", "ms_per_step": ms,
+            "gather_kernels": gathers,
             "edges_per_s": 2 * loop.L * nnz / (ms * 1e-3),
             "entry_points_ms": {k: round(v, 3) for k, v in sorted(acc.items(), key=lambda kv: -kv[1]) if v >= 0.05}}
 
@@ -493,8 +507,14 @@ def graph_engine_bench(torch, wl):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / iters
     halo = GE.local_index(cl, p.n_in, owner, 0)[1]
-    return {"entries": int(cl.numel()), "columns": n_loc,
-            "transpose_with_permutation_ms": timed(lambda: GE.transpose_csr(rp, cl, w, n_loc, want_perm=True)),
+    t_ms = timed(lambda: GE.transpose_csr(rp, cl, w, n_loc, want_perm=True))
+    nnz = int(cl.numel())
+    # what the definition moves: column + weight in, row + weight + permutation out, both row pointers
+    t_bytes = nnz * (8 + 16) + 8 * (int(rp.numel()) + n_loc + 1)
+    return {"entries": nnz, "columns": n_loc,
+            "transpose_with_permutation_ms": t_ms,
+            "transpose_algorithmic_GBps": t_bytes / (t_ms * 1e-3) / 1e9,
+            "transpose_frac_hbm_peak": t_bytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "halo_set_numbering_relabel_ms": timed(lambda: GE.local_index(cl, p.n_in, owner, 0)),
             "rows_in_owner_ms": timed(lambda: GE.rows_in_owner(owner, 2)),
             "recv_sets_ms": timed(lambda: GE.recv_sets(halo, owner, row_of, 2)),
