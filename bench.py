@@ -29,9 +29,9 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 # profiles/stress_step_kernels.txt (scaled by the copy calibration stated there).
 # Only quoted when bench.py runs that exact workload and launch configuration.
 ROCPROF_TRAFFIC_BYTES = {
-    "sylvie_aggregate_csr_fwd_wire": (34.550 + 2.591 + 0.046 + 0.013) * 1e9,
-    "sylvie_aggregate_csr_bwd_quantize": (53.231 + 0.192 + 0.025 + 0.001) * 1e9,
-    "sylvie_aggregate_csr_bwd_integrate": (21.897 + 2.565 + 0.010 + 0.003) * 1e9,
+    "sylvie_aggregate_csr_fwd_wire": (34.540 + 2.591 + 0.046 + 0.013) * 1e9,
+    "sylvie_aggregate_csr_bwd_quantize": (53.240 + 0.192 + 0.025 + 0.001) * 1e9,
+    "sylvie_aggregate_csr_bwd_integrate": (21.896 + 2.565 + 0.010 + 0.003) * 1e9,
     "sylvie_quantize_1bit_fwd": (2.963 + 0.115) * 1e9,
 }
 
