@@ -172,3 +172,42 @@ def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire):
                     assert np.array_equal(gpu_wire(loop, ("bwd", l, me, b.j0), n, d, bits), ref)
                     o_dequantize(oracle, bits, ref, d, want, dst_row=np_c(b.rows))
             assert np.array_equal(bits32(np_c(stq.dHtil[l - 1][: stq.n_in])), bits32(want))
+
+
+@pytest.mark.parametrize("heads", [1, 2])
+def test_attention_training_reduces_the_loss_like_the_oracle(oracle, heads):
+    """Exact exchange (no rounding randomness): GPU and oracle train the attention model
+    independently for six epochs — loss, J^(L), backward, gradient sums over the two partitions,
+    SGD on the weights and on the attention vectors; the losses agree and fall."""
+    wl = workload("tiny", None)
+    att = make_att(wl, 11)
+    labels = [np_c(y) for y in wl.labels]
+    count = float(sum(int((y >= 0).sum()) for y in labels))
+    pd = to_partdata(wl)
+    W = [np_c(w).copy() for w in wl.W]
+    att_np = [(np_c(a).copy(), np_c(b).copy()) for a, b in att]
+    eta = 1.0
+    ref = []
+    for e in range(6):
+        OL.forward_gat(pd, W, att_np, heads, 0.2, e, "fp32")
+        ref.append(OL.loss_and_gradient(pd, labels, count))
+        OL.backward_gat(pd, W, att_np, heads, 0.2, e, "fp32", exchange_first_layer=False)
+        OL.update_weights(pd, W, eta)
+        for l in range(1, len(W) + 1):
+            for i in (0, 1):
+                g = oracle.sum_gradients([np.ascontiguousarray(p.Gatt[l][i]) for p in pd])
+                oracle.sgd_update(att_np[l - 1][i], g, eta)
+    loop = build_attention_loop(wl, att, heads, "fp32")
+    loop.exchange_first_layer = False
+    lab_d = [y.to(DEV) for y in wl.labels]
+    got = []
+    for e in range(6):
+        got.append(float(loop.train_step(e, lab_d, count, eta).sum()))
+    torch.cuda.synchronize()
+    assert all(b < a for a, b in zip(got, got[1:])), got
+    assert np.allclose(got, ref, rtol=5e-5, atol=0), (got, ref)
+    for w, wr in zip(loop.W, W):
+        assert np.abs(np_c(w) - wr).max() <= 1e-4 * np.abs(wr).max()
+    for (a, b), (ar, br) in zip(loop.att, att_np):
+        assert np.abs(np_c(a) - ar).max() <= 1e-4 * np.abs(ar).max()
+        assert np.abs(np_c(b) - br).max() <= 1e-4 * np.abs(br).max()
