@@ -26,7 +26,11 @@
  *     word W       : the error-compensation pair of the row, scale in bits 0..31
  *                    and zero-point in bits 32..63, both float32:
  *                    scale = max - min (B = 2^1 - 1 = 1), zero = min (-0 stored as +0)
- * so one row (and one message to a peer) is a single contiguous run of bytes.
+ * so one row (and one message to a peer) is a single contiguous run of bytes.  Every 1-bit
+ * entry point takes the row stride of the array it reads or writes as `ld_wire` (64-bit
+ * words; 0 means W + 1, rows back to back): a resident wire may keep its rows further
+ * apart than they travel, e.g. at 8 words so that no row straddles a cache line.  Words
+ * W + 1 .. ld_wire - 1 of a row are never read or written.
  */
 #ifndef SYLVIE_H
 #define SYLVIE_H
@@ -52,7 +56,7 @@ const char *sylvie_status_string(int32_t status);
 /* Thread-local detail of the last error returned on this thread ("" if none). */
 const char *sylvie_last_error(void);
 
-/* uint64 words per wire row: ceil(d / 64) + 1. */
+/* uint64 words of one wire row: ceil(d / 64) + 1 (the smallest ld_wire). */
 int64_t sylvie_wire_row_words(int32_t d);
 
 /*
@@ -72,12 +76,17 @@ int64_t sylvie_wire_row_words(int32_t d);
  *   src        [*, ld_src] float32, d <= ld_src, 1 <= d <= 65536
  *   idx        int32 [n_rows] or NULL; duplicates allowed
  *   n_rows     0 <= n_rows < 2^31
- *   wire_out   uint64 [n_rows][ceil(d/64) + 1], 8-byte aligned
+ *   wire_out   uint64 [n_rows][ld_wire], 8-byte aligned; a row's ceil(d/64) + 1 words
+ *              come first, the rest of the row is not touched
+ *   ld_wire    64-bit words from one wire row to the next; 0 = ceil(d/64) + 1 (packed).
+ *              A receiver may keep its wire rows at a wider stride than they travel at:
+ *              with 8 words (64 bytes) for d = 256 a row never straddles a 128-byte line,
+ *              which is what the aggregation that gathers wire rows pays for per reference.
  */
 int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
                                  const int32_t *idx, int64_t row_offset, int64_t n_rows,
                                  uint64_t seed, uint32_t stream_id, uint64_t *wire_out,
-                                 void *stream);
+                                 int64_t ld_wire, void *stream);
 
 /*
  * Quantizer, backward direction (Alg. 2, "quantize([J(R_1), ..., J(R_N)])").
@@ -88,7 +97,7 @@ int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
 int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
                                  const int32_t *idx, int64_t row_offset, int64_t n_rows,
                                  uint64_t seed, uint32_t stream_id, uint64_t *wire_out,
-                                 void *stream);
+                                 int64_t ld_wire, void *stream);
 
 /*
  * Dequantizer, forward direction (Eq. 5; Alg. 1 "dequantize" + "concatenate"):
@@ -97,8 +106,8 @@ int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
  * below the inner rows, which is the concatenation.  Columns >= d of dst are not
  * touched.
  */
-int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_rows, int32_t d, float *dst,
-                                   int64_t ld_dst, int64_t row_offset, void *stream);
+int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t ld_wire, int64_t n_rows, int32_t d,
+                                   float *dst, int64_t ld_dst, int64_t row_offset, void *stream);
 
 /*
  * Dequantizer, backward direction (Eq. 5; Alg. 2 "integrate feature gradients",
@@ -116,8 +125,8 @@ int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_rows, int32_t
  *   seg_rows  int32 [seg_ptr[n_dst_rows]], wire row indices in [0, n_rows)
  *   dst_ids   int32 [n_dst_rows], distinct rows of dst
  */
-int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_rows, int32_t d, float *dst,
-                                   int64_t ld_dst, const int64_t *seg_ptr,
+int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_wire, int64_t n_rows, int32_t d,
+                                   float *dst, int64_t ld_dst, const int64_t *seg_ptr,
                                    const int32_t *seg_rows, int64_t n_dst_rows,
                                    const int32_t *dst_ids, void *stream);
 
@@ -203,8 +212,8 @@ int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, cons
 int32_t sylvie_aggregate_csr_fwd_wire(const int64_t *rowptr, const int32_t *col, const float *w,
                                       const float *row_scale, const float *col_scale,
                                       int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
-                                      int64_t n_dense, const uint64_t *wire, int64_t n_wire,
-                                      float *Y, int64_t ld_y, int32_t chunk,
+                                      int64_t n_dense, const uint64_t *wire, int64_t ld_wire,
+                                      int64_t n_wire, float *Y, int64_t ld_y, int32_t chunk,
                                       const int32_t *long_rows,
                                       const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
                                       float *workspace, size_t workspace_bytes, void *stream);
@@ -241,7 +250,7 @@ int32_t sylvie_aggregate_csr_bwd_quantize(const int64_t *rowptrT, const int32_t 
                                           const float *col_scale, int64_t row_begin,
                                           int64_t n_rows, const float *dY, int64_t ld_dy,
                                           int32_t d, uint64_t seed, uint32_t stream_id,
-                                          uint64_t *wire_out, int32_t chunk,
+                                          uint64_t *wire_out, int64_t ld_wire, int32_t chunk,
                                           const int32_t *long_rows, const int64_t *long_ptr,
                                           int64_t n_long, int64_t n_tasks, float *workspace,
                                           size_t workspace_bytes, void *stream);
@@ -264,7 +273,7 @@ int32_t sylvie_aggregate_csr_bwd_integrate(const int64_t *rowptrT, const int32_t
                                            int32_t d, float *dX, int64_t ld_dx,
                                            const float *addend, int64_t ld_addend,
                                            int64_t addend_rows, const uint64_t *wire,
-                                           int64_t n_wire, const int64_t *seg_ptr,
+                                           int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
                                            const int32_t *seg_rows, int32_t chunk,
                                            const int32_t *long_rows, const int64_t *long_ptr,
                                            int64_t n_long, int64_t n_tasks, float *workspace,

@@ -97,22 +97,25 @@ def sylvie_wire_row_words(d: int) -> int:
     return int(lib().sylvie_wire_row_words(int(d)))
 
 
-def _quantize(fn, src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
+def _quantize(fn, src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out, ld_wire):
     _check(fn(_ptr(src, torch.float32, "src"), C.c_int64(ld_src), C.c_int32(d),
               _ptr(idx, torch.int32, "idx"), C.c_int64(row_offset), C.c_int64(n_rows),
               C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
-              _ptr(wire_out, torch.int64, "wire_out"), _stream()))
+              _ptr(wire_out, torch.int64, "wire_out"), C.c_int64(ld_wire), _stream()))
 
 
-def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
-    """wire_out is an int64 tensor holding the uint64 wire words (torch has no uint64 kernels)."""
+def sylvie_quantize_1bit_fwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out,
+                             ld_wire=0):
+    """wire_out is an int64 tensor holding the uint64 wire words (torch has no uint64 kernels);
+    ld_wire = words from one wire row to the next, 0 = packed."""
     _quantize(lib().sylvie_quantize_1bit_fwd, src, ld_src, d, idx, row_offset, n_rows, seed,
-              stream_id, wire_out)
+              stream_id, wire_out, ld_wire)
 
 
-def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out):
+def sylvie_quantize_1bit_bwd(src, ld_src, d, idx, row_offset, n_rows, seed, stream_id, wire_out,
+                             ld_wire=0):
     _quantize(lib().sylvie_quantize_1bit_bwd, src, ld_src, d, idx, row_offset, n_rows, seed,
-              stream_id, wire_out)
+              stream_id, wire_out, ld_wire)
 
 
 def sylvie_wire_row_words_bits(d: int, bits: int) -> int:
@@ -153,16 +156,16 @@ def sylvie_dequantize_bbit_bwd(wire, n_rows, d, bits, dst, ld_dst, seg_ptr, seg_
         _ptr(dst_ids, torch.int32, "dst_ids"), _stream()))
 
 
-def sylvie_dequantize_1bit_fwd(wire, n_rows, d, dst, ld_dst, row_offset):
+def sylvie_dequantize_1bit_fwd(wire, n_rows, d, dst, ld_dst, row_offset, ld_wire=0):
     _check(lib().sylvie_dequantize_1bit_fwd(
-        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(ld_wire), C.c_int64(n_rows), C.c_int32(d),
         _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), C.c_int64(row_offset), _stream()))
 
 
 def sylvie_dequantize_1bit_bwd(wire, n_rows, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows,
-                               dst_ids):
+                               dst_ids, ld_wire=0):
     _check(lib().sylvie_dequantize_1bit_bwd(
-        _ptr(wire, torch.int64, "wire"), C.c_int64(n_rows), C.c_int32(d),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(ld_wire), C.c_int64(n_rows), C.c_int32(d),
         _ptr(dst, torch.float32, "dst"), C.c_int64(ld_dst), _ptr(seg_ptr, torch.int64, "seg_ptr"),
         _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int64(n_dst_rows),
         _ptr(dst_ids, torch.int32, "dst_ids"), _stream()))
@@ -192,14 +195,15 @@ def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld
 
 def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,
                                   wire, n_wire, Y, ld_y, chunk=0, long_rows=None,
-                                  long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+                                  long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_fwd_wire(
         _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
         _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
         _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), C.c_int64(n_dense),
-        _ptr(wire, torch.int64, "wire"), C.c_int64(n_wire), _ptr(Y, torch.float32, "Y"),
+        _ptr(wire, torch.int64, "wire"), C.c_int64(ld_wire), C.c_int64(n_wire),
+        _ptr(Y, torch.float32, "Y"),
         C.c_int64(ld_y), C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"),
         _ptr(long_ptr, torch.int64, "long_ptr"), C.c_int64(n_long), C.c_int64(n_tasks),
         _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))
@@ -215,7 +219,7 @@ def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, d
 
 def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
                                       ld_dy, d, seed, stream_id, wire_out, chunk=0, long_rows=None,
-                                      long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+                                      long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_bwd_quantize(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
@@ -223,7 +227,7 @@ def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, r
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
         _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
         C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
-        _ptr(wire_out, torch.int64, "wire_out"), C.c_int32(chunk),
+        _ptr(wire_out, torch.int64, "wire_out"), C.c_int64(ld_wire), C.c_int32(chunk),
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))
@@ -232,7 +236,7 @@ def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, r
 def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows,
                                        dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows,
                                        wire, n_wire, seg_ptr, seg_rows, chunk=0, long_rows=None,
-                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_bwd_integrate(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
@@ -241,7 +245,7 @@ def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, 
         _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
         _ptr(dX, torch.float32, "dX"), C.c_int64(ld_dx), _ptr(addend, torch.float32, "addend"),
         C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(wire, torch.int64, "wire"),
-        C.c_int64(n_wire), _ptr(seg_ptr, torch.int64, "seg_ptr"),
+        C.c_int64(ld_wire), C.c_int64(n_wire), _ptr(seg_ptr, torch.int64, "seg_ptr"),
         _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int32(chunk),
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),

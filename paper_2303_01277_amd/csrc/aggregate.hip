@@ -85,11 +85,13 @@ struct AggArgs {
     // optional packed tail of X: columns >= n_dense are rows of a 1-bit wire
     int64_t n_dense;
     const uint32_t *wire32;     // wire rows (W bit words + 1 metadata word) seen as dwords
+    int64_t ldw;                // 64-bit words from one wire row to the next (>= W + 1)
     // rows handled by this launch are row_begin .. row_begin + n_rows - 1 (absolute
     // indices into rowptr / Y / addend / row_scale)
     int64_t row_begin;
     // epilogue "quantize": wire row (v - row_begin) <- quantized row v
     uint64_t *wire_out;
+    int64_t ldw_out;            // row stride of wire_out in 64-bit words
     uint32_t ckey;
     // epilogue "integrate": row v += dequantized wire rows seg_rows[seg_ptr[v - row_begin] ..)
     const int64_t *seg_ptr;
@@ -106,7 +108,7 @@ __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int c
     const int W32 = ((a.d + 63) >> 6) * 2;
     const int64_t j0 = a.seg_ptr[s], j1 = a.seg_ptr[s + 1];
     for (int64_t j = j0; j < j1; ++j) {
-        const uint32_t *pr = a.wire32 + static_cast<int64_t>(a.seg_rows[j]) * (W32 + 2);
+        const uint32_t *pr = a.wire32 + static_cast<int64_t>(a.seg_rows[j]) * (2 * a.ldw);
         const uint2 meta = *reinterpret_cast<const uint2 *>(pr + W32);
         const float zp = __uint_as_float(meta.y);
         const float hi = zp + __uint_as_float(meta.x);
@@ -171,7 +173,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
             if (nd < cnt) {
                 const bool mine = lane >= nd && lane < cnt;
                 const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
-                meta = *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (W32 + 2) + W32);
+                meta = *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (2 * a.ldw) + W32);
             }
         }
         int j = 0;
@@ -265,7 +267,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             for (int u = 0; u < N; ++u) {
                                 const int64_t wr =
                                     static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
-                                const_words prow = wbase + wr * (NW + 1);
+                                const_words prow = wbase + wr * a.ldw;
                                 asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(m8[u]) : "s"(prow));
                                 rec[u] = recs[u];
                             }
@@ -289,7 +291,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             for (int u = 0; u < N; ++u) {
                                 const int64_t wr =
                                     static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
-                                const_words prow = wbase + wr * (W + 1);
+                                const_words prow = wbase + wr * a.ldw;
 #pragma unroll
                                 for (int k = 0; k < NW; ++k) m[u][k] = prow[FULLW ? k : (k < W ? k : W)];
                                 rec[u] = recs[u];
@@ -330,7 +332,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                         if (!ok) wv[u] = 0.0f;
                         zp[u] = __shfl(my_zp, src);
                         hi[u] = __shfl(my_hi, src);
-                        const uint32_t *pr = a.wire32 + wr * (W32 + 2);
+                        const uint32_t *pr = a.wire32 + wr * (2 * a.ldw);
 #pragma unroll
                         for (int p = 0; p < P; ++p) dw[u][p] = pr[coff[p] >> 5];
                     }
@@ -478,9 +480,8 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         }
     }
     if constexpr (EPI == kEpiQuantize) {
-        const int W1 = ((a.d + 63) >> 6) + 1;
         quantize_row_lds(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
-                         a.wire_out + local * W1, lane);
+                         a.wire_out + local * a.ldw_out, lane);
     }
 }
 
@@ -526,9 +527,8 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
         }
     }
     if constexpr (EPI == kEpiQuantize) {
-        const int W1 = ((a.d + 63) >> 6) + 1;
-        quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local), a.wire_out + local * W1,
-                         lane);
+        quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local),
+                         a.wire_out + local * a.ldw_out, lane);
     }
 }
 
@@ -579,6 +579,7 @@ struct AggExtra {
     int64_t n_dense = 0;            // forward: columns >= n_dense are wire rows
     const uint64_t *wire = nullptr; // forward: wire to read; integrate: wire to add
     int64_t n_wire = 0;
+    int64_t ld_wire = 0;            // row stride of wire / wire_out in words, 0 = W + 1
     int64_t row_begin = 0;
     int epi = kEpiStore;
     uint64_t *wire_out = nullptr;   // quantize epilogue
@@ -609,6 +610,9 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     if (n_wire > 0 && !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null wire", name);
     if (n_wire > 0 && !aligned(wire, 8))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
+    const int64_t row_words = (static_cast<int64_t>(d) + 63) / 64 + 1;
+    if (x.ld_wire != 0 && x.ld_wire < row_words)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_wire %lld shorter than a wire row", name, (long long)x.ld_wire);
     if (n_rows == 0) return SYLVIE_OK;
     if (x.row_begin < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_begin", name);
     if (x.epi == kEpiQuantize && (!x.wire_out || !aligned(x.wire_out, 8)))
@@ -643,6 +647,7 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.long_rows = long_rows; a.long_ptr = long_ptr; a.n_long = n_long; a.workspace = workspace;
     a.n_dense = n_dense;
     a.wire32 = n_wire > 0 ? reinterpret_cast<const uint32_t *>(wire) : nullptr;
+    a.ldw = a.ldw_out = x.ld_wire ? x.ld_wire : row_words;
     a.row_begin = x.row_begin;
     a.wire_out = x.wire_out;
     a.ckey = x.ckey;
@@ -705,12 +710,14 @@ extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_
 extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
     const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
     const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
-    int64_t n_dense, const uint64_t *wire, int64_t n_wire, float *Y, int64_t ld_y, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
-    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+    int64_t n_dense, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
+    int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+    float *workspace, size_t workspace_bytes, void *stream)
 {
     sylvie::AggExtra x;
     x.n_dense = n_dense;
     x.wire = wire;
+    x.ld_wire = ld_wire;
     x.n_wire = n_wire;
     return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
                                     col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
@@ -721,7 +728,7 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
 extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
     const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
-    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int32_t chunk,
+    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire, int32_t chunk,
     const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
     float *workspace, size_t workspace_bytes, void *stream)
 {
@@ -729,6 +736,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
     x.row_begin = row_begin;
     x.epi = sylvie::kEpiQuantize;
     x.wire_out = wire_out;
+    x.ld_wire = ld_wire;
     x.ckey = sylvie::call_key(seed, stream_id);
     return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_quantize", rowptrT, colT, wT,
                                     row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr, ld_dy,
@@ -740,7 +748,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
     const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
     int32_t d, float *dX, int64_t ld_dx, const float *addend, int64_t ld_addend,
-    int64_t addend_rows, const uint64_t *wire, int64_t n_wire, const int64_t *seg_ptr,
+    int64_t addend_rows, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
     const int32_t *seg_rows, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
     int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
 {
@@ -748,6 +756,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
     x.row_begin = row_begin;
     x.epi = sylvie::kEpiIntegrate;
     x.wire = wire;
+    x.ld_wire = ld_wire;
     x.n_wire = n_wire;
     x.seg_ptr = seg_ptr;
     x.seg_rows = seg_rows;

@@ -47,8 +47,8 @@ __device__ __forceinline__ void select_store(float *p, uint32_t bits, float lo, 
 // first store, so one wave keeps several rows in flight.
 template <int VEC, bool ONEPASS>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel(
-    const uint64_t *__restrict__ wire, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
-    int64_t row_offset)
+    const uint64_t *__restrict__ wire, int64_t ldw, int64_t n_rows, int d, float *__restrict__ dst,
+    int64_t ld, int64_t row_offset)
 {
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel
             meta[r] = 0;
             word[r] = 0;
             if (first + r < n_rows) {
-                const uint64_t *prow = wire + (first + r) * (W + 1);
+                const uint64_t *prow = wire + (first + r) * ldw;
                 meta[r] = prow[W];
                 word[r] = prow[cw];
             }
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_fwd_kernel
         for (int r = 0; r < kDqRowsPerWave; ++r) {
             const int64_t i = first + r;
             if (i >= n_rows) break;
-            const uint64_t *prow = wire + i * (W + 1);
+            const uint64_t *prow = wire + i * ldw;
             const uint64_t meta = prow[W];                      // scale | zero << 32
             const float zp = __uint_as_float(static_cast<uint32_t>(meta >> 32));
             const float hi = zp + __uint_as_float(static_cast<uint32_t>(meta));
@@ -105,7 +105,7 @@ constexpr int kDqDstPerWave = 4;
 // words, the destination row; further entries of a segment (rare) follow in a loop.
 template <int VEC>
 __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel(
-    const uint64_t *__restrict__ wire, int d, float *__restrict__ dst, int64_t ld,
+    const uint64_t *__restrict__ wire, int64_t ldw, int d, float *__restrict__ dst, int64_t ld,
     const int64_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_rows,
     int64_t n_dst_rows, const int32_t *__restrict__ dst_ids)
 {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
             V accv = *reinterpret_cast<const V *>(orow[q] + c0);
             __builtin_memcpy(acc[q], &accv, sizeof(V));
             const int64_t jj = j0[q] < j1[q] ? j0[q] : 0;
-            prow[q] = wire + static_cast<int64_t>(seg_rows[jj]) * (W + 1);
+            prow[q] = wire + static_cast<int64_t>(seg_rows[jj]) * ldw;
         }
 #pragma unroll
         for (int q = 0; q < D; ++q) {
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
 #pragma unroll
                 for (int t = 0; t < VEC; ++t) acc[q][t] = acc[q][t] + (((bits >> t) & 1u) ? hi : zp);
                 if (++j >= j1[q]) break;
-                const uint64_t *pr = wire + static_cast<int64_t>(seg_rows[j]) * (W + 1);
+                const uint64_t *pr = wire + static_cast<int64_t>(seg_rows[j]) * ldw;
                 meta[q] = pr[W];
                 word[q] = pr[c0 >> 6];
             }
@@ -178,13 +178,15 @@ static int pick_vec(int d, int64_t ld, const void *p)
     return 1;
 }
 
-static int32_t check_wire(const char *name, const uint64_t *wire, int64_t n_rows, int32_t d,
-                          const float *dst, int64_t ld)
+static int32_t check_wire(const char *name, const uint64_t *wire, int64_t ld_wire, int64_t n_rows,
+                          int32_t d, const float *dst, int64_t ld)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
     if (ld < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_dst %lld < d %d", name, (long long)ld, d);
+    if (ld_wire != 0 && ld_wire < (static_cast<int64_t>(d) + 63) / 64 + 1)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_wire %lld shorter than a wire row", name, (long long)ld_wire);
     if (n_rows == 0) return SYLVIE_OK;
     if (!wire || !dst) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
     if (!aligned(wire, 8) || !aligned(dst, 4))
@@ -194,13 +196,14 @@ static int32_t check_wire(const char *name, const uint64_t *wire, int64_t n_rows
 
 }  // namespace sylvie
 
-extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_rows, int32_t d,
-                                              float *dst, int64_t ld_dst, int64_t row_offset,
+extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t ld_wire, int64_t n_rows,
+                                              int32_t d, float *dst, int64_t ld_dst, int64_t row_offset,
                                               void *stream)
 {
     using namespace sylvie;
     const char *name = "sylvie_dequantize_1bit_fwd";
-    const int32_t rc = check_wire(name, wire, n_rows, d, dst, ld_dst);
+    const int32_t rc = check_wire(name, wire, ld_wire, n_rows, d, dst, ld_dst);
+    const int64_t ldw = ld_wire ? ld_wire : (static_cast<int64_t>(d) + 63) / 64 + 1;
     if (rc != SYLVIE_OK) return rc;
     if (row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
     if (n_rows == 0) return SYLVIE_OK;
@@ -211,8 +214,8 @@ extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_ro
     // the vector width must also hold for the first written row
     const int vec = pick_vec(d, ld_dst, dst + row_offset * ld_dst);
 #define SYLVIE_DQ_LAUNCH(V, ONE)                                                                  \
-    hipLaunchKernelGGL((dequantize_fwd_kernel<V, ONE>), grid, block, 0, st, wire, n_rows, d, dst, \
-                       ld_dst, row_offset)
+    hipLaunchKernelGGL((dequantize_fwd_kernel<V, ONE>), grid, block, 0, st, wire, ldw, n_rows, d, \
+                       dst, ld_dst, row_offset)
     if (vec == 4) {
         if (d <= 256) SYLVIE_DQ_LAUNCH(4, true); else SYLVIE_DQ_LAUNCH(4, false);
     } else if (vec == 2) {
@@ -225,14 +228,15 @@ extern "C" int32_t sylvie_dequantize_1bit_fwd(const uint64_t *wire, int64_t n_ro
     return SYLVIE_OK;
 }
 
-extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_rows, int32_t d,
-                                              float *dst, int64_t ld_dst, const int64_t *seg_ptr,
-                                              const int32_t *seg_rows, int64_t n_dst_rows,
-                                              const int32_t *dst_ids, void *stream)
+extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_wire, int64_t n_rows,
+                                              int32_t d, float *dst, int64_t ld_dst,
+                                              const int64_t *seg_ptr, const int32_t *seg_rows,
+                                              int64_t n_dst_rows, const int32_t *dst_ids, void *stream)
 {
     using namespace sylvie;
     const char *name = "sylvie_dequantize_1bit_bwd";
-    const int32_t rc = check_wire(name, wire, n_rows, d, dst, ld_dst);
+    const int32_t rc = check_wire(name, wire, ld_wire, n_rows, d, dst, ld_dst);
+    const int64_t ldw = ld_wire ? ld_wire : (static_cast<int64_t>(d) + 63) / 64 + 1;
     if (rc != SYLVIE_OK) return rc;
     if (n_dst_rows < 0 || n_dst_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_dst_rows out of range", name);
@@ -246,13 +250,13 @@ extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t n_ro
     const dim3 block(kDqWavesPerBlock * kWave);
     const int vec = pick_vec(d, ld_dst, dst);
     if (vec == 4)
-        hipLaunchKernelGGL(dequantize_bwd_kernel<4>, grid, block, 0, st, wire, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<4>, grid, block, 0, st, wire, ldw, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     else if (vec == 2)
-        hipLaunchKernelGGL(dequantize_bwd_kernel<2>, grid, block, 0, st, wire, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<2>, grid, block, 0, st, wire, ldw, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     else
-        hipLaunchKernelGGL(dequantize_bwd_kernel<1>, grid, block, 0, st, wire, d, dst,
+        hipLaunchKernelGGL(dequantize_bwd_kernel<1>, grid, block, 0, st, wire, ldw, d, dst,
                            ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;

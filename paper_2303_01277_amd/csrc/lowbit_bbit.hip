@@ -479,8 +479,8 @@ static int32_t quantize_bbit_common(const char *name, const float *src, int64_t 
 {
     if (!bits_ok(bits)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8 or 16 (got %d)", name, bits);
     if (bits == 1)
-        return fwd ? sylvie_quantize_1bit_fwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, stream)
-                   : sylvie_quantize_1bit_bwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, stream);
+        return fwd ? sylvie_quantize_1bit_fwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, 0, stream)
+                   : sylvie_quantize_1bit_bwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, 0, stream);
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
@@ -562,7 +562,7 @@ extern "C" int32_t sylvie_dequantize_bbit_fwd(const uint64_t *wire, int64_t n_ro
     const char *name = "sylvie_dequantize_bbit_fwd";
     const int32_t rc = check_bb_wire(name, wire, n_rows, d, bits, dst, ld_dst);
     if (rc != SYLVIE_OK) return rc;
-    if (bits == 1) return sylvie_dequantize_1bit_fwd(wire, n_rows, d, dst, ld_dst, row_offset, stream);
+    if (bits == 1) return sylvie_dequantize_1bit_fwd(wire, 0, n_rows, d, dst, ld_dst, row_offset, stream);
     if (row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
     if (n_rows == 0) return SYLVIE_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -596,7 +596,7 @@ extern "C" int32_t sylvie_dequantize_bbit_bwd(const uint64_t *wire, int64_t n_ro
     const int32_t rc = check_bb_wire(name, wire, n_rows, d, bits, dst, ld_dst);
     if (rc != SYLVIE_OK) return rc;
     if (bits == 1)
-        return sylvie_dequantize_1bit_bwd(wire, n_rows, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids, stream);
+        return sylvie_dequantize_1bit_bwd(wire, 0, n_rows, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids, stream);
     if (n_dst_rows < 0 || n_dst_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_dst_rows out of range", name);
     if (n_rows == 0 || n_dst_rows == 0) return SYLVIE_OK;

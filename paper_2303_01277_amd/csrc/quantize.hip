@@ -59,7 +59,7 @@ constexpr int rows_per_wave(int P) { return 64 / (P + 1) < 4 ? 64 / (P + 1) : 4;
 template <int P, bool FULL>
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire, int64_t ldw)
 {
     constexpr int R = rows_per_wave(P);
     static_assert(R >= 1 && R * (P + 1) <= 64, "one store must hold all words of a wave");
@@ -148,15 +148,18 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
             for (int p = 0; p < P; ++p) cur[p] = nxt[p];
         }
     });
-    if (lane < nrows * W1)
-        wire[first * W1 + lane] = (static_cast<uint64_t>(static_cast<uint32_t>(my_hi)) << 32) |
-                                  static_cast<uint32_t>(my_lo);
+    // lane l holds word l % W1 of the wave's row l / W1; rows sit ldw words apart
+    if (lane < nrows * W1) {
+        const int r = lane / W1;
+        wire[(first + r) * ldw + (lane - r * W1)] =
+            (static_cast<uint64_t>(static_cast<uint32_t>(my_hi)) << 32) | static_cast<uint32_t>(my_lo);
+    }
 }
 
 // Any width: the row is read twice (the second read hits the cache).
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
+    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire, int64_t ldw)
 {
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kern
     const float sc = mx - mn;
     const uint32_t rkey = mix32(ckey ^ static_cast<uint32_t>(i));
     uint32_t ctr = rkey + static_cast<uint32_t>(lane) * kColStride;
-    uint64_t *out = wire + i * (W + 1);
+    uint64_t *out = wire + i * ldw;
     for (int k = 0; k < W; ++k) {
         const int c = k * 64 + lane;
         const float x = c < d ? row[c] : 0.0f;
@@ -194,23 +197,27 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kern
 template <int P, bool FULL>
 static void launch_rows(const float *src, int64_t ld, int d, const int32_t *idx,
                         int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *wire,
-                        hipStream_t st)
+                        int64_t ldw, hipStream_t st)
 {
     const int64_t rows_per_block = rows_per_wave(P) * kWavesPerBlock;
     const int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
     hipLaunchKernelGGL((quantize_rows_kernel<P, FULL>), dim3(static_cast<unsigned>(blocks)),
                        dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset, n_rows,
-                       ckey, wire);
+                       ckey, wire, ldw);
 }
 
 static int32_t quantize_common(const char *name, const float *src, int64_t ld, int32_t d,
                                const int32_t *idx, int64_t row_offset, int64_t n_rows,
-                               uint64_t seed, uint32_t stream_id, uint64_t *wire, void *stream)
+                               uint64_t seed, uint32_t stream_id, uint64_t *wire, int64_t ld_wire,
+                               void *stream)
 {
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
     if (ld < d) return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_src %lld < d %d", name, (long long)ld, d);
+    const int64_t ldw = ld_wire ? ld_wire : (static_cast<int64_t>(d) + 63) / 64 + 1;
+    if (ldw < (static_cast<int64_t>(d) + 63) / 64 + 1)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_wire %lld shorter than a wire row", name, (long long)ld_wire);
     if (!idx && row_offset < 0) return fail(SYLVIE_ERR_INVALID_ARG, "%s: negative row_offset", name);
     if (n_rows == 0) return SYLVIE_OK;
     if (!src || !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
@@ -225,9 +232,9 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
 #define SYLVIE_Q_CASE(p)                                                                       \
     case p:                                                                                    \
         if (d == 64 * p)                                                                       \
-            launch_rows<p, true>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);                \
+            launch_rows<p, true>(src, ld, d, idx, row_offset, n_rows, ckey, wire, ldw, st);                \
         else                                                                                   \
-            launch_rows<p, false>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);              \
+            launch_rows<p, false>(src, ld, d, idx, row_offset, n_rows, ckey, wire, ldw, st);              \
         break;
     switch (P) {
         SYLVIE_Q_CASE(1)
@@ -250,7 +257,7 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
         const int64_t blocks = (n_rows + kWavesPerBlock - 1) / kWavesPerBlock;
         hipLaunchKernelGGL(quantize_rows_wide_kernel, dim3(static_cast<unsigned>(blocks)),
                            dim3(kWavesPerBlock * kWave), 0, st, src, ld, d, idx, row_offset,
-                           n_rows, ckey, wire);
+                           n_rows, ckey, wire, ldw);
     }
     }
 #undef SYLVIE_Q_CASE
@@ -263,17 +270,17 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
 extern "C" int32_t sylvie_quantize_1bit_fwd(const float *src, int64_t ld_src, int32_t d,
                                             const int32_t *idx, int64_t row_offset,
                                             int64_t n_rows, uint64_t seed, uint32_t stream_id,
-                                            uint64_t *wire_out, void *stream)
+                                            uint64_t *wire_out, int64_t ld_wire, void *stream)
 {
     return sylvie::quantize_common("sylvie_quantize_1bit_fwd", src, ld_src, d, idx, row_offset,
-                                   n_rows, seed, stream_id, wire_out, stream);
+                                   n_rows, seed, stream_id, wire_out, ld_wire, stream);
 }
 
 extern "C" int32_t sylvie_quantize_1bit_bwd(const float *src, int64_t ld_src, int32_t d,
                                             const int32_t *idx, int64_t row_offset,
                                             int64_t n_rows, uint64_t seed, uint32_t stream_id,
-                                            uint64_t *wire_out, void *stream)
+                                            uint64_t *wire_out, int64_t ld_wire, void *stream)
 {
     return sylvie::quantize_common("sylvie_quantize_1bit_bwd", src, ld_src, d, idx, row_offset,
-                                   n_rows, seed, stream_id, wire_out, stream);
+                                   n_rows, seed, stream_id, wire_out, ld_wire, stream);
 }

@@ -82,15 +82,17 @@ class LayerLoop:
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
                  exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True,
-                 fused_bwd: bool = True, pipeline: bool = False):
+                 fused_bwd: bool = True, pipeline: bool = False, pad_wire: bool = True):
         """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
         partition int32 tensors naming the owner partition and owner-local inner row of
-        each halo row (grouped by owner, ascending)."""
+        each halo row (grouped by owner, ascending).  pad_wire: keep the resident 1-bit wire
+        rows that the forward aggregation gathers at a line-friendly stride (see _stride)."""
         self.model, self.dims, self.W = model, tuple(dims), W
         self.L = len(W)
         self.chunk = chunk
         self.exchange_first_layer = exchange_first_layer
         self.wire = wire
+        self.pad_wire = pad_wire
         if wire not in WIRE_BITS and wire != "fp32":
             raise ValueError(f"wire must be one of {sorted(WIRE_BITS)} or 'fp32'")
         # bits per element on the wire: 1 = the paper's default; 2, 4, 8 and 16 (binary16)
@@ -136,7 +138,7 @@ class LayerLoop:
                     j += c
             st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
             st.perm = perm              # entry i of opT is entry perm[i] of op
-            Wd = self._words(dmax)
+            Wd = max(self._stride(d) for d in dims[:-1])
             st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
             st.ws_aggT = torch.empty(max(1, planT[2]) * dmax, dtype=torch.float32, device=dev)
@@ -187,17 +189,37 @@ class LayerLoop:
                 for g in range(2):
                     for l in range(1, self.L + 1):
                         Wl = B.sylvie_wire_row_words(dims[l - 1])
-                        st.fwd_wires[g][l] = torch.empty(max(1, st.n_halo) * Wl, dtype=torch.int64,
-                                                         device=dev)
+                        st.fwd_wires[g][l] = torch.empty(max(1, st.n_halo) * self._stride(dims[l - 1]),
+                                                         dtype=torch.int64, device=dev)
                         if l >= lo:
                             st.inb_wires[g][l] = torch.empty(max(1, st.n_inbound) * Wl,
                                                              dtype=torch.int64, device=dev)
                 st.ws_aggT2 = torch.empty_like(st.ws_aggT)
 
     # -- helpers ---------------------------------------------------------------
-    def _keep(self, key, wire, n, W):
+    def _keep(self, key, wire, n, W, stride=None):
+        """Copy of n wire rows of W words each, packed, whatever stride they are kept at."""
         if self.record is not None:
-            self.record[key] = wire[: n * W].clone()
+            if stride is None or stride == W:
+                self.record[key] = wire[: n * W].clone()
+            else:
+                self.record[key] = wire[: n * stride].view(n, stride)[:, :W].reshape(-1).clone()
+
+    def _stride(self, d):
+        """64-bit words between the resident wire rows that the forward aggregation gathers.
+        A gathered 1-bit row costs one 128-byte line if it does not straddle one: the row's
+        words are rounded up to a power of two (5 -> 8 words at d = 256), beyond 16 words to a
+        multiple of 16.  The rows still travel packed: the padding is never written or read.
+        Other wires (wider codes, gradient wires, which are read once in order) stay packed."""
+        W = self._words(d)
+        if self.bits not in (None, 1) or self.wire != "1bit" or not self.pad_wire:
+            return W
+        if W > 16:
+            return (W + 15) // 16 * 16
+        S = 1
+        while S < W:
+            S *= 2
+        return S
 
     def _words(self, d):
         """64-bit words of one wire row of width d."""
@@ -225,13 +247,14 @@ class LayerLoop:
                 if self.wire == "1bit":
                     # the wire of halo rows [j0, j1) sits at the same offset in the
                     # receiver's wire arrays, so all blocks stay resident side by side
-                    wire = st.wire[b.j0 * Wd:]
+                    S = self._stride(d)
+                    wire = st.wire[b.j0 * S:]
                     B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, n,
-                                               pair_seed(seed, b.owner, me), 2 * l + 0, wire)
-                    self._keep(("fwd", l, me, b.j0), wire, n, Wd)
+                                               pair_seed(seed, b.owner, me), 2 * l + 0, wire, ld_wire=S)
+                    self._keep(("fwd", l, me, b.j0), wire, n, Wd, S)
                     if not self.fused:
                         B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
-                                                     st.n_in + b.j0)
+                                                     st.n_in + b.j0, ld_wire=S)
                 elif self.bits:
                     wire = st.wire[b.j0 * Wd:]
                     B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
@@ -291,7 +314,7 @@ class LayerLoop:
                         st.n_halo, Z, Z.stride(0), chunk=self.chunk,
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                        workspace=st.ws_agg if nt else None)
+                        workspace=st.ws_agg if nt else None, ld_wire=self._stride(d))
                 else:
                     self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
                                     st.n_in, ht, d, Z)
@@ -403,16 +426,17 @@ class LayerLoop:
         for l in range(1, self.L + 1):
             d = self.dims[l - 1]
             Wd = B.sylvie_wire_row_words(d)
+            S = self._stride(d)
             # this epoch's wires (every partition's H^(l-1) is complete on the main stream)
             with self._side(stale):
                 for me, st in enumerate(self.parts):
                     cur = st.fwd_wires[self._gen("cur")][l]
                     for b in st.blocks:
                         src = self.parts[b.owner].Htil[l - 1]
-                        wire = cur[b.j0 * Wd:]
+                        wire = cur[b.j0 * S:]
                         B.sylvie_quantize_1bit_fwd(src, src.stride(0), d, b.rows, 0, b.j1 - b.j0,
-                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire)
-                        self._keep(("fwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
+                                                   pair_seed(seed, b.owner, me), 2 * l + 0, wire, ld_wire=S)
+                        self._keep(("fwd", l, me, b.j0), wire, b.j1 - b.j0, Wd, S)
             for st in self.parts:
                 ht, Z = st.Htil[l - 1], st.Z[l - 1]
                 wire = st.fwd_wires[self._gen(use)][l]
@@ -424,10 +448,11 @@ class LayerLoop:
                         st.n_halo, Z, Z.stride(0), chunk=self.chunk,
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                        workspace=st.ws_agg if nt else None)
+                        workspace=st.ws_agg if nt else None, ld_wire=S)
                 else:
                     if st.n_halo:
-                        B.sylvie_dequantize_1bit_fwd(wire, st.n_halo, d, ht, ht.stride(0), st.n_in)
+                        B.sylvie_dequantize_1bit_fwd(wire, st.n_halo, d, ht, ht.stride(0), st.n_in,
+                                                     ld_wire=S)
                     self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
                                     st.n_in, ht, d, Z)
                 relu = l != self.L

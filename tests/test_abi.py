@@ -63,7 +63,7 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     q.restype = C.c_int32
     args = lambda **kw: [kw.get("src", p), C.c_int64(kw.get("ld", 64)), C.c_int32(kw.get("d", 64)),
                          None, C.c_int64(0), C.c_int64(kw.get("n", 8)), C.c_uint64(1),
-                         C.c_uint32(0), kw.get("packed", p), None]
+                         C.c_uint32(0), kw.get("packed", p), C.c_int64(kw.get("ldw", 0)), None]
     assert q(*args(d=0)) == -1
     assert q(*args(d=65, ld=64)) == -1
     assert q(*args(n=-1)) == -1
@@ -71,11 +71,14 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     assert q(*args(src=None)) == -1
     assert q(*args(packed=C.c_void_p(4100))) == -2
     assert b"align" in lib.sylvie_last_error()
+    assert q(*args(ldw=1)) == -1 and b"ld_wire" in lib.sylvie_last_error()   # d = 64: a row has 2 words
+    assert q(*args(n=0, ldw=8)) == 0
     assert q(*args(n=0)) == 0                                  # empty exchange is a no-op
     dq = lib.sylvie_dequantize_1bit_fwd
     dq.restype = C.c_int32
-    assert dq(p, C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
-    assert dq(p, C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
+    assert dq(p, C.c_int64(0), C.c_int64(4), C.c_int32(64), p, C.c_int64(32), C.c_int64(0), None) == -1
+    assert dq(p, C.c_int64(1), C.c_int64(4), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == -1
+    assert dq(p, C.c_int64(0), C.c_int64(0), C.c_int32(64), p, C.c_int64(64), C.c_int64(0), None) == 0
     qb = lib.sylvie_quantize_bbit_fwd
     qb.restype = C.c_int32
     bargs = lambda bits, d=64, ld=64, n=8: [p, C.c_int64(ld), C.c_int32(d), None, C.c_int64(0),

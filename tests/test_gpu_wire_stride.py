@@ -1,0 +1,120 @@
+"""GPU parity of the 1-bit entry points with wire rows kept further apart than they travel
+(ld_wire > words per row): every reader and writer must treat row i as the words at i * ld_wire,
+leave the padding untouched, and produce what the packed call produces, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from test_gpu_ops import DEV, _operator, bits32, dev, make_rows
+from util import join_wire
+
+pytestmark = pytest.mark.gpu
+PAD = -0x0123456789ABCDEF
+
+
+def strided(packed_rows, n, W1, S):
+    """Packed wire (int64 [n * W1]) -> rows S words apart, padding filled with a sentinel."""
+    out = np.full((n, S), PAD, np.int64)
+    out[:, :W1] = np.asarray(packed_rows).reshape(n, W1)
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("d,S", [(1, 2), (1, 7), (64, 4), (100, 4), (256, 5), (256, 8), (256, 16), (602, 16),
+                                 (1100, 19), (1100, 32)])
+def test_quantize_and_dequantize_with_row_stride(oracle, d, S):
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    rng = np.random.default_rng(d * 7 + S)
+    W1 = (d + 63) // 64 + 1
+    assert S >= W1
+    n_src, n = 300, 517
+    x = make_rows(rng, n_src, d, "heavy")
+    idx = rng.integers(0, n_src, n).astype(np.int32)
+    ref = join_wire(*oracle.quantize_1bit(x, d, n, 99 + d, 3, idx=idx))
+    for fn in (B.sylvie_quantize_1bit_fwd, B.sylvie_quantize_1bit_bwd):
+        wire = torch.full((n * S + 5,), PAD, dtype=torch.int64, device=DEV)
+        fn(dev(x), d, d, dev(idx), 0, n, 99 + d, 3, wire, ld_wire=S)
+        torch.cuda.synchronize()
+        got = wire.cpu().numpy()
+        assert np.array_equal(got[: n * S], strided(ref, n, W1, S)), fn.__name__
+        assert (got[n * S:] == PAD).all()
+    # contiguous source rows
+    ref2 = join_wire(*oracle.quantize_1bit(x, d, 100, 5, 1, row_offset=50))
+    wire2 = torch.full((100 * S,), PAD, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_1bit_bwd(dev(x), d, d, None, 50, 100, 5, 1, wire2, ld_wire=S)
+    assert np.array_equal(wire2.cpu().numpy(), strided(ref2, 100, W1, S))
+    # readers: the strided wire against the packed one
+    packed = dev(ref)
+    wired = dev(strided(ref, n, W1, S))
+    a = torch.full((n + 9, d + 4), 7.0, device=DEV); b = a.clone()
+    B.sylvie_dequantize_1bit_fwd(packed, n, d, a, d + 4, 6)
+    B.sylvie_dequantize_1bit_fwd(wired, n, d, b, d + 4, 6, ld_wire=S)
+    assert torch.equal(a, b)
+    dst = rng.integers(0, 150, n).astype(np.int32)
+    dst[:40] = 9
+    sp_, sr, di = GE.scatter_segments(dev(dst))
+    J0 = dev(make_rows(rng, 200, d, "normal"))
+    Ja, Jb = J0.clone(), J0.clone()
+    B.sylvie_dequantize_1bit_bwd(packed, n, d, Ja, d, sp_, sr, int(di.numel()), di)
+    B.sylvie_dequantize_1bit_bwd(wired, n, d, Jb, d, sp_, sr, int(di.numel()), di, ld_wire=S)
+    torch.cuda.synchronize()
+    assert torch.equal(Ja, Jb)
+    with pytest.raises(B.SylvieError, match="ld_wire"):
+        B.sylvie_dequantize_1bit_fwd(wired, n, d, b, d + 4, 6, ld_wire=W1 - 1)
+
+
+@pytest.mark.parametrize("d,S", [(7, 2), (64, 4), (100, 4), (256, 8), (256, 13), (602, 16)])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
+def test_aggregations_with_row_stride(oracle, d, S, cfg, n_nodes, model):
+    """Wire-reading forward aggregation and both backward epilogues: strided == packed."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    W1 = (d + 63) // 64 + 1
+    rng = np.random.default_rng(d + S)
+    X = make_rows(rng, n_loc, d, "heavy")
+    ref = join_wire(*oracle.quantize_1bit(X, d, p.n_halo, 77, 2, row_offset=p.n_in))
+    rpd, cld, wd = dev(rp), dev(cl), dev(w)
+    Xin = dev(X[: p.n_in])
+    packed, wired = dev(ref), dev(strided(ref, p.n_halo, W1, S))
+    for chunk in (0, 128):
+        kw = {}
+        if chunk:
+            lr, lp, nt = GE.long_row_plan(rpd, chunk)
+            kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                      workspace=torch.empty(max(1, nt) * d, device=DEV))
+        Ya = torch.full((p.n_in, d), float("nan"), device=DEV); Yb = Ya.clone()
+        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, packed,
+                                        p.n_halo, Ya, d, **kw)
+        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, wired,
+                                        p.n_halo, Yb, d, ld_wire=S, **kw)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits32(Ya.cpu().numpy()), bits32(Yb.cpu().numpy())), chunk
+    # backward epilogues
+    dZ = dev(make_rows(rng, p.n_in, d, "heavy"))
+    mirror = dev(rng.integers(0, p.n_in, p.n_halo).astype(np.int32))
+    rpT, clT, wT = GE.transpose_csr(rpd, cld, wd, n_loc)
+    chunk = 128
+    lrh, lph, nth = GE.long_row_plan(rpT, chunk, p.n_in, n_loc)
+    ws = torch.empty(max(1, int(GE.long_row_plan(rpT, chunk)[2])) * d, device=DEV)
+    wa = torch.full((p.n_halo * W1,), PAD, dtype=torch.int64, device=DEV)
+    wb = torch.full((p.n_halo * S + 3,), PAD, dtype=torch.int64, device=DEV)
+    common = dict(chunk=chunk, long_rows=lrh, long_ptr=lph, n_long=int(lrh.numel()), n_tasks=nth, workspace=ws)
+    B.sylvie_aggregate_csr_bwd_quantize(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, 5, 9, wa, **common)
+    B.sylvie_aggregate_csr_bwd_quantize(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, 5, 9, wb,
+                                        ld_wire=S, **common)
+    torch.cuda.synchronize()
+    got = wb.cpu().numpy()
+    assert np.array_equal(got[: p.n_halo * S], strided(wa.cpu().numpy(), p.n_halo, W1, S))
+    assert (got[p.n_halo * S:] == PAD).all()
+    lri, lpi, nti = GE.long_row_plan(rpT, chunk, 0, p.n_in)
+    sp2, sr2 = GE.scatter_segments_dense(mirror, p.n_in)
+    Ja = torch.full((p.n_in, d), float("nan"), device=DEV); Jb = Ja.clone()
+    ci = dict(chunk=chunk, long_rows=lri, long_ptr=lpi, n_long=int(lri.numel()), n_tasks=nti, workspace=ws)
+    B.sylvie_aggregate_csr_bwd_integrate(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, Ja, d, None, 0, 0,
+                                         wa, p.n_halo, sp2, sr2, **ci)
+    B.sylvie_aggregate_csr_bwd_integrate(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, Jb, d, None, 0, 0,
+                                         wb, p.n_halo, sp2, sr2, ld_wire=S, **ci)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits32(Ja.cpu().numpy()), bits32(Jb.cpu().numpy()))
