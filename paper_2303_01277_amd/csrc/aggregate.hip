@@ -49,9 +49,33 @@ template <>
 struct Vec<1> { using type = float; };
 
 template <int VEC>
+struct NativeVec {
+    typedef float type __attribute__((ext_vector_type(VEC)));
+};
+template <>
+struct NativeVec<1> {
+    typedef float type;
+};
+
+// Every operand read through load_vec is device (global) memory; saying so keeps the load a
+// global one where the pointer was reassembled from lane reads and its origin is no longer visible.
+template <int VEC>
 __device__ __forceinline__ void load_vec(float (&o)[VEC], const float *p)
 {
-    typename Vec<VEC>::type v = *reinterpret_cast<const typename Vec<VEC>::type *>(p);
+    typedef typename NativeVec<VEC>::type V;
+    typedef const __attribute__((address_space(1))) V *global_ptr;
+    const V v = *(global_ptr)(p);
+    __builtin_memcpy(o, &v, sizeof(v));
+}
+// The same through a wave-uniform row address and a lane's own byte offset inside the row
+// (an unsigned 32-bit offset lets the load take the row address from scalar registers).
+template <int VEC>
+__device__ __forceinline__ void load_vec_at(float (&o)[VEC], const float *row, uint32_t byte_off)
+{
+    typedef typename NativeVec<VEC>::type V;
+    typedef const __attribute__((address_space(1))) char *global_bytes;
+    typedef const __attribute__((address_space(1))) V *global_ptr;
+    const V v = *(global_ptr)((global_bytes)(row) + byte_off);
     __builtin_memcpy(o, &v, sizeof(v));
 }
 template <int VEC>
@@ -163,17 +187,33 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
             my_w = a.w ? a.w[base + lane] : 1.0f;
             if (a.col_scale) my_w *= a.col_scale[my_c];
         }
+        // address of the lane's own gathered row, computed once on the vector unit; an entry's
+        // row is then addressed by two lane reads instead of a 64-bit scalar multiply-add
+        const uintptr_t my_xrow = reinterpret_cast<uintptr_t>(a.X + static_cast<int64_t>(my_c) * a.ld_x);
+        [[maybe_unused]] const int my_xlo = static_cast<int>(static_cast<uint32_t>(my_xrow));
+        [[maybe_unused]] const int my_xhi = static_cast<int>(static_cast<uint32_t>(my_xrow >> 32));
+        [[maybe_unused]] auto xrow_of_slot = [&](int slot) -> const float * {
+            const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(my_xlo, slot));
+            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(my_xhi, slot));
+            return reinterpret_cast<const float *>((static_cast<uint64_t>(hi) << 32) | lo);
+        };
         int nd = cnt;                          // entries [0, nd) are dense, [nd, cnt) wire
         if constexpr (WIRE)
             nd = __builtin_popcountll(__ballot(lane < cnt && my_c < a.n_dense));
         // wire entries: each lane fetches the metadata word of ITS entry now, so that the
         // fetch is in flight while the dense rows are gathered
         [[maybe_unused]] uint2 meta = make_uint2(0u, 0u);
+        // address of the lane's own wire row, computed once on the vector unit: the per-entry
+        // loop then needs two lane reads and no scalar arithmetic to address a row
+        [[maybe_unused]] uint32_t my_row_lo = 0, my_row_hi = 0;
         if constexpr (WIRE) {
             if (nd < cnt) {
                 const bool mine = lane >= nd && lane < cnt;
                 const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
-                meta = *reinterpret_cast<const uint2 *>(a.wire32 + my_wr * (2 * a.ldw) + W32);
+                const uint32_t *my_row = a.wire32 + my_wr * (2 * a.ldw);
+                meta = *reinterpret_cast<const uint2 *>(my_row + W32);
+                my_row_lo = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(my_row));
+                my_row_hi = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(my_row) >> 32);
             }
         }
         int j = 0;
@@ -184,17 +224,16 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int sl = j + u * EP + sub;
-                int c;
+                const float *xr;
                 if constexpr (EP == 1) {
-                    c = __builtin_amdgcn_readlane(my_c, sl);
+                    xr = xrow_of_slot(sl);
                     wv[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), sl));
                 } else {
-                    c = __shfl(my_c, sl);
+                    xr = a.X + static_cast<int64_t>(__shfl(my_c, sl)) * a.ld_x;
                     wv[u] = __shfl(my_w, sl);
                 }
-                const float *xr = a.X + static_cast<int64_t>(c) * a.ld_x;
 #pragma unroll
-                for (int p = 0; p < P; ++p) load_vec<VEC>(x[u][p], xr + coff[p]);
+                for (int p = 0; p < P; ++p) load_vec_at<VEC>(x[u][p], xr, static_cast<uint32_t>(coff[p]) * 4u);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -207,20 +246,20 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         // row 0 (lanes >= cnt hold column 0, weight 0)
         for (; j < nd; j += EP) {
             const int sl = j + sub;
-            int c;
+            const float *xr;
             float wj;
             if constexpr (EP == 1) {
-                c = __builtin_amdgcn_readlane(my_c, sl);
+                xr = xrow_of_slot(sl);
                 wj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_w), sl));
             } else {
-                c = __shfl(my_c, sl & 63);
+                int c = __shfl(my_c, sl & 63);
                 wj = __shfl(my_w, sl & 63);
                 if (sl >= nd) { wj = 0.0f; c = 0; }
+                xr = a.X + static_cast<int64_t>(c) * a.ld_x;
             }
-            const float *xr = a.X + static_cast<int64_t>(c) * a.ld_x;
             float x[P][VEC];
 #pragma unroll
-            for (int p = 0; p < P; ++p) load_vec<VEC>(x[p], xr + coff[p]);
+            for (int p = 0; p < P; ++p) load_vec_at<VEC>(x[p], xr, static_cast<uint32_t>(coff[p]) * 4u);
 #pragma unroll
             for (int p = 0; p < P; ++p)
 #pragma unroll
@@ -246,7 +285,11 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                     const int W = W32 >> 1;
                     reinterpret_cast<float4 *>(bcast)[lane] = make_float4(my_ww, my_zp, my_hi, 0.0f);
                     used_w = true;
-                    const_words wbase = (const_words)(reinterpret_cast<uintptr_t>(a.wire32));
+                    auto row_of_slot = [&](int slot) -> const_words {
+                        const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_lo), slot));
+                        const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_hi), slot));
+                        return (const_words)((static_cast<uint64_t>(hi) << 32) | lo);
+                    };
                     // N entries starting at batch slot j0 (all valid): their mask words by
                     // scalar loads, their records by broadcast reads, then select + FMA.
                     // FULLW: the row has exactly NW words; otherwise the words past the last
@@ -265,9 +308,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             u32x8 m8[N];
 #pragma unroll
                             for (int u = 0; u < N; ++u) {
-                                const int64_t wr =
-                                    static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
-                                const_words prow = wbase + wr * a.ldw;
+                                const_words prow = row_of_slot(j0 + u);
                                 asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(m8[u]) : "s"(prow));
                                 rec[u] = recs[u];
                             }
@@ -289,9 +330,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             uint64_t m[N][NW];
 #pragma unroll
                             for (int u = 0; u < N; ++u) {
-                                const int64_t wr =
-                                    static_cast<int64_t>(__builtin_amdgcn_readlane(my_c, j0 + u)) - a.n_dense;
-                                const_words prow = wbase + wr * a.ldw;
+                                const_words prow = row_of_slot(j0 + u);
 #pragma unroll
                                 for (int k = 0; k < NW; ++k) m[u][k] = prow[FULLW ? k : (k < W ? k : W)];
                                 rec[u] = recs[u];
