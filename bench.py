@@ -29,9 +29,9 @@ FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 # profiles/stress_step_kernels.txt (scaled by the copy calibration stated there).
 # Only quoted when bench.py runs that exact workload and launch configuration.
 ROCPROF_TRAFFIC_BYTES = {
-    "sylvie_aggregate_csr_fwd_wire": (32.132 + 2.591 + 0.046 + 0.013) * 1e9,
-    "sylvie_aggregate_csr_bwd_quantize": (53.243 + 0.192 + 0.025 + 0.001) * 1e9,
-    "sylvie_aggregate_csr_bwd_integrate": (21.896 + 2.565 + 0.010 + 0.003) * 1e9,
+    "sylvie_aggregate_csr_fwd_wire": (31.965 + 2.591 + 0.046 + 0.013) * 1e9,
+    "sylvie_aggregate_csr_bwd_quantize": (53.239 + 0.195 + 0.025 + 0.001) * 1e9,
+    "sylvie_aggregate_csr_bwd_integrate": (21.897 + 2.565 + 0.010 + 0.003) * 1e9,
     "sylvie_quantize_1bit_fwd": (2.963 + 0.126) * 1e9,
 }
 
@@ -677,6 +677,7 @@ def main():
         if default_cfg and name in ROCPROF_TRAFFIC_BYTES:
             roof["traffic"] = ROCPROF_TRAFFIC_BYTES[name]
             roof["traffic_GBps"] = roof["traffic"] / (op["avg_ms_per_call"] * 1e-3) / 1e9
+            roof["traffic_frac"] = roof["traffic_GBps"] / HBM_PEAK_GBS
             if roof["traffic"] < roof["algorithmic_bytes"]:
                 roof["note"] = ("the L2 serves part of the gathered rows, so fewer bytes leave it than the "
                                 "gather count credits; traffic_GBps is the rate at the HBM side")
