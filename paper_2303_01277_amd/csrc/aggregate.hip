@@ -600,7 +600,11 @@ template <int VEC>
 static bool launch_vec(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t st)
 {
     const int lanes = (a.d + VEC - 1) / VEC;   // lanes needed for one row, one pass
-    if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, epi, st);
+    // Rows that read a wire take a whole wavefront even when they are narrow: wire entries
+    // then go through the scalar path (mask words by scalar loads, one select + FMA per word),
+    // which costs half the vector instructions of the shared-wavefront path per entry.
+    if (epi == kEpiStore && a.wire32 && lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, st);
+    else if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, epi, st);
     else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, epi, st);
     else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, st);
     else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, epi, st);
