@@ -198,6 +198,32 @@ int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, cons
                                  size_t workspace_bytes, void *stream);
 
 /*
+ * sylvie_aggregate_csr_fwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same operation, same kernels, same results bit for bit; the partial sums of the
+ * long rows' tasks go to a scratch array that is part of the library's device image
+ * (SYLVIE_STATIC_SCRATCH_BYTES per GPU, resident until the process ends) instead of a caller
+ * workspace.  The call allocates and frees nothing.
+ *   - n_tasks * d * 4 must not exceed SYLVIE_STATIC_SCRATCH_BYTES: SYLVIE_ERR_WORKSPACE
+ *     otherwise (nothing is enqueued).  With n_long = 0 the scratch is not used.
+ *   - The scratch needs no clearing: every task writes its whole partial row before the
+ *     reduction reads it, and nothing else is read.  It keeps the last call's contents.
+ *   - All calls on one GPU share that GPU's array: two calls whose work overlaps in time on the
+ *     same GPU (different streams) race.  Calls on one stream are ordered and safe.
+ *   - The device address of the array is looked up on the first call on each device (the
+ *     device current at the call, which must be the stream's).
+ * Other arguments as in sylvie_aggregate_csr_fwd.
+ */
+#define SYLVIE_STATIC_SCRATCH_BYTES (16ull << 20)
+int32_t sylvie_aggregate_csr_fwd_noalloc(const int64_t *rowptr, const int32_t *col, const float *w,
+                                         const float *row_scale, const float *col_scale,
+                                         int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+                                         float *Y, int64_t ld_y, const float *addend,
+                                         int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                         const int32_t *long_rows, const int64_t *long_ptr,
+                                         int64_t n_long, int64_t n_tasks, void *stream);
+
+/*
  * Neighbour aggregation, forward, reading the halo rows straight from the wire
  * (Alg. 1 "dequantize" + "concatenate" + the product A_n * H~ in one pass; Eq. 5
  * is applied to each gathered element): the same result as

@@ -52,6 +52,7 @@ def lib():
                      "sylvie_quantize_bbit_fwd", "sylvie_quantize_bbit_bwd",
                      "sylvie_dequantize_bbit_fwd", "sylvie_dequantize_bbit_bwd",
                      "sylvie_aggregate_csr_fwd", "sylvie_aggregate_csr_bwd",
+                     "sylvie_aggregate_csr_fwd_noalloc",
                      "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
                      "sylvie_aggregate_csr_bwd_integrate",
                      "sylvie_transform_fwd", "sylvie_transform_bwd", "sylvie_softmax_xent",
@@ -191,6 +192,25 @@ def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld
     _aggregate(lib().sylvie_aggregate_csr_fwd, rowptr, col, w, row_scale, col_scale, n_rows, X,
                ld_x, d, Y, ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
                n_long, n_tasks, workspace)
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def sylvie_aggregate_csr_fwd_noalloc(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y,
+                                     addend=None, ld_addend=0, addend_rows=0, chunk=0,
+                                     long_rows=None, long_ptr=None, n_long=0, n_tasks=0):
+    """sylvie_aggregate_csr_fwd with the long-row partial sums in the library's built-in scratch
+    (n_tasks * d * 4 <= STATIC_SCRATCH_BYTES); allocates nothing."""
+    _check(lib().sylvie_aggregate_csr_fwd_noalloc(
+        _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
+        _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
+        _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d),
+        _ptr(Y, torch.float32, "Y"), C.c_int64(ld_y), _ptr(addend, torch.float32, "addend"),
+        C.c_int64(ld_addend), C.c_int64(addend_rows), C.c_int32(chunk),
+        _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+        C.c_int64(n_long), C.c_int64(n_tasks), _stream()))
 
 
 def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,

@@ -26,6 +26,7 @@
 //     columns 64 apart", the layout in which a wave-wide compare is a packed word)
 //     and write only the wire row; or, for the inner block, add the dequantized
 //     wire rows that belong to it (Alg. 2 "integrate") before the one store.
+#include <mutex>
 #include <type_traits>
 
 #include "common.hpp"
@@ -716,7 +717,66 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     return SYLVIE_OK;
 }
 
+// Scratch of the entry point that may not allocate: the partial sums of the long rows'
+// tasks live in this array instead of a caller workspace.  Every GPU the library runs on
+// holds its own copy at its own address for the life of the process; the name below is only
+// the host-side handle of the symbol, the address kernels can use is looked up per device.
+static __device__ __align__(256) unsigned char scratch[SYLVIE_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static float *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up once per device).
+static int32_t static_scratch(const char *name, float **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SYLVIE_ERR_HIP, "%s: hipGetDevice: %s", name, hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(SYLVIE_ERR_UNIMPLEMENTED, "%s: device ordinal %d not supported", name, dev);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(SYLVIE_ERR_HIP, "%s: hipGetSymbolAddress: %s", name, hipGetErrorString(e));
+        g_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SYLVIE_OK;
+}
+
 }  // namespace sylvie
+
+extern "C" int32_t sylvie_aggregate_csr_fwd_noalloc(const int64_t *rowptr, const int32_t *col,
+                                                    const float *w, const float *row_scale,
+                                                    const float *col_scale, int64_t n_rows,
+                                                    const float *X, int64_t ld_x, int32_t d, float *Y,
+                                                    int64_t ld_y, const float *addend,
+                                                    int64_t ld_addend, int64_t addend_rows,
+                                                    int32_t chunk, const int32_t *long_rows,
+                                                    const int64_t *long_ptr, int64_t n_long,
+                                                    int64_t n_tasks, void *stream)
+{
+    const char *name = "sylvie_aggregate_csr_fwd_noalloc";
+    float *ws = nullptr;
+    if (n_long > 0) {
+        // the size is checked before anything else so that the error names the limit
+        if (n_tasks < 0 || d < 1 ||
+            static_cast<uint64_t>(n_tasks) > SYLVIE_STATIC_SCRATCH_BYTES / (4ull * static_cast<uint64_t>(d)))
+            return sylvie::fail(SYLVIE_ERR_WORKSPACE,
+                                "%s: n_tasks * d * 4 = %lld * %d * 4 bytes exceeds the built-in scratch of %llu bytes; "
+                                "use sylvie_aggregate_csr_fwd with a workspace of your own",
+                                name, (long long)n_tasks, d, (unsigned long long)SYLVIE_STATIC_SCRATCH_BYTES);
+        const int32_t rc = sylvie::static_scratch(name, &ws);
+        if (rc != SYLVIE_OK) return rc;
+    }
+    return sylvie::aggregate_common(name, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y,
+                                    ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
+                                    n_long, n_tasks, ws, n_long > 0 ? SYLVIE_STATIC_SCRATCH_BYTES : 0,
+                                    stream);
+}
 
 extern "C" int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col,
                                             const float *w, const float *row_scale,

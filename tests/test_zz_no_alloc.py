@@ -1,0 +1,82 @@
+"""The entry point that allocates nothing (sylvie_aggregate_csr_fwd_noalloc), called through
+the C ABI with raw pointers: two calls in a row, the second on a smaller input, each compared
+bit for bit with sylvie_aggregate_csr_fwd given a caller workspace (same kernels, fixed order
+of additions) and, to 1e-5 * max(|ref|, S), with the oracle."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from synth import CONFIGS, build_workload, scaled
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _case(oracle, n_nodes, d, chunk, seed):
+    from paper_2303_01277_amd import graph_engine as GE
+    wl = build_workload(scaled(CONFIGS["stress"], n_nodes))
+    p = wl.parts[0]
+    rp, cl, w = oracle.gcn_operator(p.rowptr.numpy(), p.col.numpy(), p.deg.numpy(), p.n_in)
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((p.n_in + p.n_halo, d)) *
+         np.exp(2 * rng.standard_normal((p.n_in + p.n_halo, 1)))).astype(np.float32)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    rpd, cld, wd, Xd = t(rp), t(cl), t(w), t(X)
+    lr, lp, nt = GE.long_row_plan(rpd, chunk)
+    assert nt > 0 and lr.numel() > 0, "the case must exercise the scratch"
+    return dict(n=p.n_in, d=d, chunk=chunk, rp=rpd, cl=cld, w=wd, X=Xd, lr=lr, lp=lp, nt=nt,
+                host=(rp, cl, w, X))
+
+
+def _call(fn, c, Y, extra):
+    L_args = [C.c_void_p(c["rp"].data_ptr()), C.c_void_p(c["cl"].data_ptr()),
+              C.c_void_p(c["w"].data_ptr()), C.c_void_p(0), C.c_void_p(0), C.c_int64(c["n"]),
+              C.c_void_p(c["X"].data_ptr()), C.c_int64(c["d"]), C.c_int32(c["d"]),
+              C.c_void_p(Y.data_ptr()), C.c_int64(c["d"]), C.c_void_p(0), C.c_int64(0), C.c_int64(0),
+              C.c_int32(c["chunk"]), C.c_void_p(c["lr"].data_ptr()), C.c_void_p(c["lp"].data_ptr()),
+              C.c_int64(c["lr"].numel()), C.c_int64(c["nt"])]
+    return fn(*L_args, *extra, C.c_void_p(torch.cuda.current_stream().cuda_stream))
+
+
+def test_noalloc_matches_workspace_entry_point(oracle):
+    from paper_2303_01277_amd import binding as B
+    L = B.lib()
+    big = _case(oracle, 40_000, 256, 64, 1)
+    small = _case(oracle, 12_000, 100, 128, 2)       # smaller input, other width, second
+    assert small["nt"] * small["d"] < big["nt"] * big["d"]
+    outs = []
+    # everything is allocated before the two calls under test
+    for c in (big, small):
+        c["Y"] = torch.full((c["n"], c["d"]), float("nan"), device=DEV)
+        c["Yref"] = torch.full((c["n"], c["d"]), float("nan"), device=DEV)
+        c["ws"] = torch.empty(c["nt"] * c["d"], device=DEV)
+    torch.cuda.synchronize()
+    for c in (big, small):                           # two calls in a row on one stream
+        rc = _call(L.sylvie_aggregate_csr_fwd_noalloc, c, c["Y"], [])
+        assert rc == 0, L.sylvie_last_error().decode()
+    for c in (big, small):
+        rc = _call(L.sylvie_aggregate_csr_fwd, c, c["Yref"],
+                   [C.c_void_p(c["ws"].data_ptr()), C.c_size_t(c["ws"].numel() * 4)])
+        assert rc == 0, L.sylvie_last_error().decode()
+    torch.cuda.synchronize()
+    for c in (big, small):
+        got, ref = c["Y"].cpu().numpy(), c["Yref"].cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+        rp, cl, w, X = c["host"]
+        Z, S = oracle.aggregate_fwd(rp, cl, w, X, c["d"], want_S=True)
+        err = np.abs(got.astype(np.float64) - Z)
+        assert (err <= 1e-5 * np.maximum(np.abs(Z), S)).all()
+
+
+def test_noalloc_rejects_oversize(oracle):
+    from paper_2303_01277_amd import binding as B
+    L = B.lib()
+    c = _case(oracle, 12_000, 64, 64, 3)
+    Y = torch.zeros((c["n"], c["d"]), device=DEV)
+    c = dict(c, nt=(B.STATIC_SCRATCH_BYTES // (4 * c["d"])) + 1)
+    rc = _call(L.sylvie_aggregate_csr_fwd_noalloc, c, Y, [])
+    assert rc == -5 and b"scratch" in L.sylvie_last_error()
+    torch.cuda.synchronize()
+    assert (Y == 0).all()                            # nothing was enqueued
