@@ -333,7 +333,7 @@ def lowbit_microbench(torch, B, loop, st, d, iters=10):
                        "frac_hbm_peak": tot_b / (tot_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     out["rows"] = n
     out["d"] = d
-    # the bit-width study (Sec. 5.4): the same four calls at b = 2, 4, 8 and on the
+    # the bit-width study (Sec. 4.3): the same four calls at b = 2, 4, 8 and on the
     # half-precision wire; wire row bytes = 8 * sylvie_wire_row_words_bits(d, bits)
     sweep = {}
     for bits in (2, 4, 8, 16):
@@ -421,7 +421,7 @@ def pipeline_bench(torch, LayerLoop, wl, owner, rows, spec, args, forced):
 
 
 def attention_bench(torch, B, wl, owner, rows, spec, args, forced, heads=4):
-    """The attention model (GAT, Sec. 5.1) on the same partition and widths: whole forward +
+    """The attention model (GAT, Sec. 4) on the same partition and widths: whole forward +
     backward step of the layer loop, and one more step with every entry point bracketed by
     events.  Reported beside the headline; not part of value."""
     from paper_2303_01277_amd.trainer import AttentionLoop

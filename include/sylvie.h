@@ -132,7 +132,7 @@ int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_wire, int64_
 
 /*
  * b-bit Low-bit Module (Sec. 3.2, Eq. 3-5 with B = 2^b - 1 bins; the bit-width study of
- * Sec. 5.4, which also has a half-precision point).  `bits` is 1, 2, 4 or 8 for b-bit
+ * Sec. 4.3, which also has a half-precision point).  `bits` is 1, 2, 4 or 8 for b-bit
  * stochastic rounding, or 16 for IEEE binary16 (round to nearest even, no side channel,
  * seed ignored).  bits = 1 is exactly the 1-bit entry points above.
  *
@@ -363,7 +363,7 @@ int32_t sylvie_sum_gradients(float *dst, const float *const *srcs, int32_t n_src
 int32_t sylvie_sgd_update(float *W, const float *G, int64_t elems, float eta, void *stream);
 
 /*
- * Attention aggregator: the GAT model of the evaluation (Sec. 5.1), i.e. Eq. 1 with learned
+ * Attention aggregator: the GAT model of the evaluation (Sec. 4), i.e. Eq. 1 with learned
  * edge weights.  The paper cites the model without formulas; these are the cited model's:
  *     P = H~ W,  s_dst[v] = P_v . a_dst,  s_src[u] = P_u . a_src,
  *     alpha_v. = softmax over the entries (v, u) of row v of leaky_relu(s_dst[v] + s_src[u]),

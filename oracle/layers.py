@@ -10,7 +10,7 @@ peers.
 
 wire = "1bit": quantize -> (packed, scale, zero) -> dequantize (Sec. 3.2).
 wire = "2bit" / "4bit" / "8bit": the same with B = 2^b - 1 bins; wire = "fp16": rows
-rounded to binary16 (the other points of the bit-width study, Sec. 5.4).
+rounded to binary16 (the other points of the bit-width study, Sec. 4.3).
 Sylvie-A (Sec. 3.3): with `prev` given, every layer computes with the wires of the
 previous epoch found there, while this epoch's wires are still produced (and stored in
 `keep`), to be used by the next epoch.  1-bit wire only.

@@ -183,7 +183,7 @@ void orc_dequantize_1bit_bwd(const uint64_t *packed, const float *scale, const f
 
 /* ------------------------------------------------------------------------- */
 /* b-bit quantizer / dequantizer: Eq. 3, Eq. 4 and Eq. 5 for b in {1, 2, 4, 8}, */
-/* B = 2^b - 1 bins (Sec. 3.2; the bit-width study of Sec. 5.4).               */
+/* B = 2^b - 1 bins (Sec. 3.2; the bit-width study of Sec. 4.3).               */
 /* ------------------------------------------------------------------------- */
 
 int64_t orc_words_per_row_bits(int32_t d, int32_t bits) { return ((int64_t)d * bits + 63) / 64; }
@@ -291,7 +291,7 @@ void orc_dequantize_bbit_bwd(const uint64_t *packed, const float *scale, const f
 }
 
 /* ------------------------------------------------------------------------- */
-/* Half-precision wire (the FP16 point of the bit-width study, Sec. 5.4): each  */
+/* Half-precision wire (the FP16 point of the bit-width study, Sec. 4.3): each  */
 /* element is rounded to IEEE binary16, nearest-even; no side channel.          */
 /* ------------------------------------------------------------------------- */
 
@@ -613,7 +613,7 @@ void orc_transform_bwd(const float *A1, int64_t ld1, int32_t k1, const float *A2
 }
 
 /* ------------------------------------------------------------------------- */
-/* Attention aggregator (the GAT model of Sec. 2.1 / Sec. 5.1; the paper cites   */
+/* Attention aggregator (the GAT model of Sec. 2.1 / Sec. 4; the paper cites   */
 /* the model and gives no formulas, so these are the cited model's):             */
 /*   P = Htilde W,  s_dst[v] = P_v . a_dst,  s_src[u] = P_u . a_src               */
 /*   e_vu = leaky_relu(s_dst[v] + s_src[u]),  alpha_v. = softmax_u e_vu           */

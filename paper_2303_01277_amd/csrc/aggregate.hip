@@ -268,23 +268,23 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         }
         if constexpr (WIRE) {
             if (nd < cnt) {
-                // Wire entries.  Each lane first fetches the two levels of ITS entry
-                // (zero and fl(zero + scale), Eq. 5) so that the per-entry loop has no
-                // dependent scalar fetch; then, entry by entry, the levels and the
-                // weight are broadcast, every lane loads the one dword that holds its
-                // VEC bits, and a bit-field insert picks the level.  Lane groups stay
-                // aligned with the dense loops; an entry before nd is masked with weight
-                // 0 and reads wire row 0.
+                // Wire entries.  Each lane has fetched the two levels of ITS entry (zero and
+                // fl(zero + scale), Eq. 5) and publishes them with its weight as a 16-byte
+                // record; then, entry by entry, the record is broadcast, the row's mask words
+                // arrive by scalar loads and one select + one FMA per word does the rest.
                 const bool mine = lane >= nd && lane < cnt;
                 const float my_zp = __uint_as_float(meta.y);
                 const float my_hi = my_zp + __uint_as_float(meta.x);
                 const float my_ww = mine ? my_w : 0.0f;
-                if constexpr (EP == 1) {
+                static_assert(!WIRE || EP == 1, "rows that read a wire take a whole wavefront");
+                {
                     typedef const __attribute__((address_space(4))) uint64_t *const_words;
                     constexpr int NW = P * VEC;                     // >= words per wire row
                     constexpr int UW = NW <= 4 ? SYLVIE_UW4 : (NW <= 8 ? 2 : 1);
                     const int W = W32 >> 1;
+                    wave_lds_sync();    // the previous batch's records have been read
                     reinterpret_cast<float4 *>(bcast)[lane] = make_float4(my_ww, my_zp, my_hi, 0.0f);
+                    wave_lds_sync();    // every lane reads every record below
                     used_w = true;
                     auto row_of_slot = [&](int slot) -> const_words {
                         const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_lo), slot));
@@ -307,15 +307,39 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                             // registers, otherwise issues them one at a time.
                             typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
                             u32x8 m8[N];
+                            const_words prow[N];
 #pragma unroll
                             for (int u = 0; u < N; ++u) {
-                                const_words prow = row_of_slot(j0 + u);
-                                asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(m8[u]) : "s"(prow));
+                                prow[u] = row_of_slot(j0 + u);
                                 rec[u] = recs[u];
                             }
-                            asm volatile("s_waitcnt lgkmcnt(0)");
-#pragma unroll
-                            for (int u = 0; u < N; ++u) asm volatile("" : "+s"(m8[u]));   // uses come after the wait
+                            // Issue and wait are ONE asm statement: the compiler never sees
+                            // a destination register as defined before its data has arrived,
+                            // so it cannot copy or spill it in between.  Early-clobber outputs
+                            // keep a destination from sharing registers with an address that a
+                            // later load of the block still has to read.
+                            static_assert(N == 8 || N == 1, "scalar wire loads come in blocks of 8 or singly");
+                            if constexpr (N == 8) {
+                                asm volatile(
+                                    "s_load_dwordx8 %0, %8, 0x0\n\t"
+                                    "s_load_dwordx8 %1, %9, 0x0\n\t"
+                                    "s_load_dwordx8 %2, %10, 0x0\n\t"
+                                    "s_load_dwordx8 %3, %11, 0x0\n\t"
+                                    "s_load_dwordx8 %4, %12, 0x0\n\t"
+                                    "s_load_dwordx8 %5, %13, 0x0\n\t"
+                                    "s_load_dwordx8 %6, %14, 0x0\n\t"
+                                    "s_load_dwordx8 %7, %15, 0x0\n\t"
+                                    "s_waitcnt lgkmcnt(0)"
+                                    : "=&s"(m8[0]), "=&s"(m8[1]), "=&s"(m8[2]), "=&s"(m8[3]),
+                                      "=&s"(m8[4]), "=&s"(m8[5]), "=&s"(m8[6]), "=&s"(m8[7])
+                                    : "s"(prow[0]), "s"(prow[1]), "s"(prow[2]), "s"(prow[3]),
+                                      "s"(prow[4]), "s"(prow[5]), "s"(prow[6]), "s"(prow[7])
+                                    : "memory");
+                            } else {
+                                asm volatile("s_load_dwordx8 %0, %1, 0x0\n\t"
+                                             "s_waitcnt lgkmcnt(0)"
+                                             : "=&s"(m8[0]) : "s"(prow[0]) : "memory");
+                            }
 #pragma unroll
                             for (int u = 0; u < N; ++u)
 #pragma unroll
@@ -355,45 +379,6 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                     };
                     if (W == NW) all_entries(std::true_type{});
                     else all_entries(std::false_type{});
-                } else {
-                constexpr int UW = (P >= 4) ? 4 : (16 / P);
-                for (j = nd - nd % EP; j < cnt; j += EP * UW) {
-                    uint32_t dw[UW][P];
-                    float wv[UW], zp[UW], hi[UW];
-#pragma unroll
-                    for (int u = 0; u < UW; ++u) {
-                        const int sl = j + u * EP + sub;
-                        const int src = sl & 63;
-                        const bool ok = sl >= nd && sl < cnt;
-                        // every lane takes part in the lane reads; select afterwards
-                        const int cs = __shfl(my_c, src);
-                        const int64_t wr = ok ? static_cast<int64_t>(cs) - a.n_dense : 0;
-                        wv[u] = __shfl(my_ww, src);
-                        if (!ok) wv[u] = 0.0f;
-                        zp[u] = __shfl(my_zp, src);
-                        hi[u] = __shfl(my_hi, src);
-                        const uint32_t *pr = a.wire32 + wr * (2 * a.ldw);
-#pragma unroll
-                        for (int p = 0; p < P; ++p) dw[u][p] = pr[coff[p] >> 5];
-                    }
-#pragma unroll
-                    for (int u = 0; u < UW; ++u)
-#pragma unroll
-                        for (int p = 0; p < P; ++p) {
-                            const int bits = static_cast<int>(dw[u][p] >> (coff[p] & 31));
-#pragma unroll
-                            for (int t = 0; t < VEC; ++t) {
-                                // all-ones where the bit is set, then (m & hi) | (~m & zp):
-                                // written as the two instructions meant, because the
-                                // compiler turns the C form into and + compare + select
-                                uint32_t m;
-                                float x;
-                                asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(m) : "v"(bits), "n"(t));
-                                asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(x) : "v"(m), "v"(hi[u]), "v"(zp[u]));
-                                acc[p][t] = fmaf(wv[u], x, acc[p][t]);
-                            }
-                        }
-                }
                 }
             }
         }
@@ -415,8 +400,10 @@ template <int VEC, int P>
 __device__ __forceinline__ void merge_wire_sums(float (&acc)[P][VEC], const float (&accw)[P * VEC],
                                                 float *row, int d, int lane)
 {
+    wave_lds_sync();    // `row` shares its memory with the broadcast records read above
 #pragma unroll
     for (int k = 0; k < P * VEC; ++k) row[64 * k + lane] = accw[k];
+    wave_lds_sync();    // a lane now reads columns that other lanes wrote
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const int cc = (p * 64 + lane) * VEC;
@@ -593,8 +580,10 @@ static void launch_shape(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t
     const int64_t nt = a.n_long > 0 ? n_tasks : 0;
     if (epi == kEpiQuantize) launch_kernels<VEC, G, P, false, kEpiQuantize>(a, nt, st);
     else if (epi == kEpiIntegrate) launch_kernels<VEC, G, P, false, kEpiIntegrate>(a, nt, st);
-    else if (a.wire32) launch_kernels<VEC, G, P, true, kEpiStore>(a, nt, st);
-    else launch_kernels<VEC, G, P, false, kEpiStore>(a, nt, st);
+    else if (a.wire32) {
+        // launch_vec gives every wire-reading launch a whole wavefront per row
+        if constexpr (G == 64) launch_kernels<VEC, G, P, true, kEpiStore>(a, nt, st);
+    } else launch_kernels<VEC, G, P, false, kEpiStore>(a, nt, st);
 }
 
 template <int VEC>

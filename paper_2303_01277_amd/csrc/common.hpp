@@ -47,6 +47,16 @@ __device__ __forceinline__ float uniform(float v)
     return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
 }
 
+// Between an LDS write by one lane and the read of that location by another lane of the SAME
+// wavefront: makes the hand-off defined in the memory model (the compiler may not move either
+// access across it).  A wavefront's LDS operations execute in order, so this emits no
+// instruction.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Plain compare-select minimum / maximum (inputs are finite by contract).
 __device__ __forceinline__ float fmin_sel(float a, float b) { return b < a ? b : a; }
 __device__ __forceinline__ float fmax_sel(float a, float b) { return b > a ? b : a; }

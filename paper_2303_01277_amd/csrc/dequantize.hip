@@ -142,8 +142,12 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
         for (int q = 0; q < D; ++q) {
             V accv = *reinterpret_cast<const V *>(orow[q] + c0);
             __builtin_memcpy(acc[q], &accv, sizeof(V));
-            const int64_t jj = j0[q] < j1[q] ? j0[q] : 0;
-            prow[q] = wire + static_cast<int64_t>(seg_rows[jj]) * ldw;
+            // an empty segment reads nothing of seg_rows (which may then have no elements at
+            // all): its load goes to a location that always exists and wire row 0 stands in
+            const bool some = j0[q] < j1[q];
+            const int32_t *pid = some ? seg_rows + j0[q] : dst_ids + k0;
+            const int32_t id = *pid;
+            prow[q] = wire + static_cast<int64_t>(some ? id : 0) * ldw;
         }
 #pragma unroll
         for (int q = 0; q < D; ++q) {

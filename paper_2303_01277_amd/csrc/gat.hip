@@ -1,4 +1,4 @@
-// Attention aggregator (the GAT model evaluated in Sec. 5.1; Eq. 1 with learned edge
+// Attention aggregator (the GAT model evaluated in Sec. 4; Eq. 1 with learned edge
 // weights): scores, edge softmax, the product that differentiates it, and their backward.
 //   s_dst[v] = P_v . a_dst, s_src[u] = P_u . a_src
 //   e_vu = leaky_relu(s_dst[v] + s_src[u]); alpha_v. = softmax over the entries of row v

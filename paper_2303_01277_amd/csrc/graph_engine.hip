@@ -465,8 +465,9 @@ extern "C" int32_t sylvie_graph_local_index(const int32_t *gcol, int64_t nnz, in
                        halo_gid, halo_capacity);
     const int32_t rc = finish(name, status, st, "neighbour id outside [0, n_nodes)", "");
     if (rc != SYLVIE_OK) return rc;
-    uint64_t totals = 0;                                   // the stream has been waited for
-    const hipError_t e = hipMemcpy(&totals, ranks + n_nodes, sizeof(totals), hipMemcpyDeviceToHost);
+    uint64_t totals = 0;                                   // read back on the caller's stream
+    hipError_t e = hipMemcpyAsync(&totals, ranks + n_nodes, sizeof(totals), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) return fail(SYLVIE_ERR_HIP, "%s: %s", name, hipGetErrorString(e));
     counts_host[0] = static_cast<int64_t>(totals & 0xffffffffu);
     counts_host[1] = static_cast<int64_t>(totals >> 32);

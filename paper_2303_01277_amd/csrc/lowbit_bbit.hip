@@ -1,5 +1,5 @@
 // b-bit Low-bit Module (Sec. 3.2, Eq. 3-5 with B = 2^b - 1, b in {2, 4, 8}; the
-// bit-width study of Sec. 5.4) and the half-precision wire of the same study.
+// bit-width study of Sec. 4.3) and the half-precision wire of the same study.
 //
 // Quantizer: one wavefront per wire row, as in the 1-bit kernel, but lane L holds VEC
 // ADJACENT columns per pass, because the codes of adjacent columns are adjacent in the

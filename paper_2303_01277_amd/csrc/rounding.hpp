@@ -53,6 +53,7 @@ __device__ __forceinline__ void quantize_row_lds(const float *row, int d, uint32
 {
     constexpr float kTwoM24 = 1.0f / 16777216.0f;
     const int W = (d + 63) >> 6;
+    wave_lds_sync();    // the row was written by other lanes of this wavefront
     // columns past d re-read column d-1: extrema unchanged, no predicate
     float mn = row[lane < d ? lane : d - 1], mx = mn;
     for (int c = lane + 64; c < d; c += 64) {

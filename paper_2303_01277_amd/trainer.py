@@ -96,7 +96,7 @@ class LayerLoop:
         if wire not in WIRE_BITS and wire != "fp32":
             raise ValueError(f"wire must be one of {sorted(WIRE_BITS)} or 'fp32'")
         # bits per element on the wire: 1 = the paper's default; 2, 4, 8 and 16 (binary16)
-        # are the other points of its bit-width study (Sec. 5.4); None = float rows
+        # are the other points of its bit-width study (Sec. 4.3); None = float rows
         self.bits = WIRE_BITS.get(wire)
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)

@@ -263,7 +263,7 @@ def test_layer_loop_teacher_forced(oracle, cfg, n_nodes, fused):
 @pytest.mark.parametrize("wire", ["2bit", "4bit", "8bit", "fp16"])
 @pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("co_purchase", 12_000), ("dense_social", 5_000)])
 def test_layer_loop_bit_widths(oracle, cfg, n_nodes, wire):
-    """The other wire formats of the bit-width study (Sec. 5.4) through the same
+    """The other wire formats of the bit-width study (Sec. 4.3) through the same
     teacher-forced replay: wires bit-exact, recovered rows and accumulate bit-exact."""
     spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
     wl = build_workload(spec)

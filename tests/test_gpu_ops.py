@@ -282,7 +282,7 @@ def test_transform_strided(oracle, n, k1, k2, h):
             assert bool((dA2[:, k2:] == 7.0).all())
 
 
-@pytest.mark.parametrize("d", [2, 64, 100, 128, 160, 256, 300, 602, 1024])
+@pytest.mark.parametrize("d", [2, 7, 64, 65, 100, 128, 129, 160, 256, 300, 301, 602, 1024])
 @pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 40_000, "gcn"),
                                                ("co_purchase", 30_000, "sage")])
 def test_aggregate_from_wire_parity(oracle, d, cfg, n_nodes, model):

@@ -63,7 +63,7 @@ def test_quantize_and_dequantize_with_row_stride(oracle, d, S):
         B.sylvie_dequantize_1bit_fwd(wired, n, d, b, d + 4, 6, ld_wire=W1 - 1)
 
 
-@pytest.mark.parametrize("d,S", [(7, 2), (64, 4), (100, 4), (256, 8), (256, 13), (602, 16)])
+@pytest.mark.parametrize("d,S", [(7, 2), (64, 4), (65, 3), (100, 4), (129, 4), (256, 8), (256, 13), (301, 8), (602, 16)])
 @pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
 def test_aggregations_with_row_stride(oracle, d, S, cfg, n_nodes, model):
     """Wire-reading forward aggregation and both backward epilogues: strided == packed."""

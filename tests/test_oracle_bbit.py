@@ -1,5 +1,5 @@
 """Pins for the oracle's b-bit quantizer / dequantizer (Sec. 3.2, Eq. 3-5 with
-B = 2^b - 1; bit-width study of Sec. 5.4; Theorem 1) and its half-precision wire.
+B = 2^b - 1; bit-width study of Sec. 4.3; Theorem 1) and its half-precision wire.
 
 The pins are: words packed by hand from the format statement, facts that hold for
 every seed (extreme elements, values on the grid, one-bin error bound), closed-form

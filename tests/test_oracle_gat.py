@@ -1,5 +1,5 @@
 """Pins for the oracle's attention aggregator (the GAT model the paper evaluates, Sec. 2.1 /
-Sec. 5.1): library softmax and autograd on dense masked matrices, dense matmuls, and central
+Sec. 4): library softmax and autograd on dense masked matrices, dense matmuls, and central
 finite differences through the whole two-partition layer loop."""
 import numpy as np
 import pytest

@@ -149,7 +149,7 @@ def test_one_bit_loop_runs_and_is_unbiased_in_the_mean(oracle):
 
 
 def test_more_bits_less_exchange_error(oracle):
-    """Bit-width study (Sec. 5.4): against the full-precision exchange, the error that the
+    """Bit-width study (Sec. 4.3): against the full-precision exchange, the error that the
     wire adds to the layer outputs and to the propagated gradients shrinks as the wire gets
     wider: 1 > 2 > 4 > 8 bits > half precision."""
     import numpy as np
