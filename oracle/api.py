@@ -21,7 +21,7 @@ _lib = None
 __all__ = [
     "build", "words_per_row", "uniform24", "quantize_1bit", "dequantize_1bit_fwd",
     "dequantize_1bit_bwd", "gcn_operator", "mean_weights", "aggregate_fwd", "aggregate_bwd",
-    "aggregate_bwd_rows", "transform_fwd", "transform_bwd", "num_threads",
+    "aggregate_bwd_rows", "transform_fwd", "transform_bwd", "num_threads", "set_num_threads",
     "words_per_row_bits", "quantize_bbit", "dequantize_bbit_fwd", "dequantize_bbit_bwd",
     "words_per_row_fp16", "convert_fp16", "recover_fp16_fwd", "recover_fp16_bwd",
     "softmax_xent", "sum_gradients", "sgd_update",
@@ -82,6 +82,11 @@ def _chk(a, dtype, name):
 
 def num_threads() -> int:
     return int(_L().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads for the row loops from now on (a timing knob; results do not depend on it)."""
+    _L().orc_set_num_threads(C.c_int(int(n)))
 
 
 def words_per_row(d: int) -> int:

@@ -946,6 +946,17 @@ void orc_scatter_segments(const int32_t *dst_row, int64_t n, int64_t n_dst, int6
     free(next);
 }
 
+/* Threads the row loops may use from now on (timing with one thread vs all cores; */
+/* results do not depend on it: rows are independent and the draws are counter-based). */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int orc_num_threads(void)
 {
     int n = 1;
