@@ -17,6 +17,14 @@
  *     thread-local text for the last failing call.
  *   - Sizes of zero rows are valid no-ops.  Inputs must be finite with
  *     |x| < 2^126; row indices must be in range (not checked on the device).
+ *   - Debug mode: with the environment variable SYLVIE_VALIDATE set to 1, the quantizers, the
+ *     backward dequantizer and the aggregations first check those preconditions on the device
+ *     (quantizer source rows finite and below 2^126, gather indices >= 0; CSR row pointers
+ *     ascending, columns >= 0 and, for sylvie_aggregate_csr_fwd_wire, below n_dense + n_wire
+ *     with every dense column before every wire column of its row; segment tables ascending
+ *     with wire rows in range).  Such a call WAITS for `stream`, and returns
+ *     SYLVIE_ERR_INVALID_ARG without enqueueing its work when a check fails.  Upper bounds are
+ *     only checked where the call states the row count of the array an index points into.
  *
  * Wire format of one exchange of n_rows rows of width d (Sec. 3.2, "1-bit
  * integers" plus the scale / zero-point side channel): one contiguous array

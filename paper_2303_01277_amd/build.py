@@ -25,6 +25,7 @@ _SOURCES = {
     "training.hip": ["-ffp-contract=off"],
     "gat.hip": ["-ffp-contract=off"],
     "graph_engine.hip": [],
+    "validate.hip": [],
 }
 
 

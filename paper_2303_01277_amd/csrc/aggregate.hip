@@ -31,6 +31,7 @@
 
 #include "common.hpp"
 #include "rounding.hpp"
+#include "validate.hpp"
 
 #ifndef SYLVIE_UW4
 #define SYLVIE_UW4 8
@@ -688,6 +689,17 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.seg_rows = x.seg_rows;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (validate_enabled()) {
+        // the number of rows of X is not an argument: columns are checked against it only
+        // where the call states it (dense + wire rows of the wire-reading forward)
+        Validator v(name, st);
+        const bool reads_wire = x.epi == kEpiStore && n_wire > 0;
+        v.csr(rowptr, col, x.row_begin, n_rows, reads_wire ? n_dense + n_wire : -1,
+              reads_wire ? n_dense : -1);
+        if (x.epi == kEpiIntegrate) v.segments(x.seg_ptr, x.seg_rows, n_rows, n_wire, nullptr);
+        const int32_t rc = v.finish();
+        if (rc != SYLVIE_OK) return rc;
+    }
     if (x.epi == kEpiQuantize) { Y = const_cast<float *>(X); ld_y = ld_x; }   // Y is unused
     const bool a16 = aligned(X, 16) && aligned(Y, 16) && ld_x % 4 == 0 && ld_y % 4 == 0 &&
                      d % 4 == 0 && (!addend || (aligned(addend, 16) && ld_addend % 4 == 0));

@@ -7,6 +7,7 @@
 // float stores are full-width and contiguous across the wave; the VEC bits it
 // needs sit in one 64-bit word, which neighbouring lanes share through the cache.
 #include "common.hpp"
+#include "validate.hpp"
 
 namespace sylvie {
 
@@ -249,6 +250,12 @@ extern "C" int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_w
     if (!aligned(seg_ptr, 8) || !aligned(seg_rows, 4) || !aligned(dst_ids, 4))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned index array", name);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (validate_enabled()) {
+        Validator v(name, st);
+        v.segments(seg_ptr, seg_rows, n_dst_rows, n_rows, dst_ids);
+        const int32_t rc = v.finish();
+        if (rc != SYLVIE_OK) return rc;
+    }
     const int64_t per_block = kDqWavesPerBlock * kDqDstPerWave;
     const dim3 grid(static_cast<unsigned>((n_dst_rows + per_block - 1) / per_block));
     const dim3 block(kDqWavesPerBlock * kWave);

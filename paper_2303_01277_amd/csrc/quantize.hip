@@ -10,6 +10,7 @@
 
 #include "common.hpp"
 #include "rounding.hpp"
+#include "validate.hpp"
 
 namespace sylvie {
 
@@ -227,6 +228,12 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: wire_out needs 8-byte alignment", name);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (validate_enabled()) {
+        Validator v(name, st);
+        v.rows(src, ld, d, idx, row_offset, n_rows);
+        const int32_t rc = v.finish();
+        if (rc != SYLVIE_OK) return rc;
+    }
     const uint32_t ckey = call_key(seed, stream_id);
     const int P = (d + 63) / 64;
 #define SYLVIE_Q_CASE(p)                                                                       \

@@ -75,7 +75,21 @@ class Run:
                                fused_bwd=True)
         self.fused.record = {}
         self.fused.forward(SEED, OL.pair_seed)
-        self.fused.backward(SEED, OL.pair_seed)
+        # what the fused inner-row call was given, per layer (it is called for l = L .. 2)
+        self.fused_in = {}
+        orig_i = B.sylvie_aggregate_csr_bwd_integrate
+        L = len(spec.dims) - 1
+
+        def hook_i(*a, **kw):
+            l = L - len(self.fused_in)
+            self.fused_in[l] = {"dZ": a[7].clone(), "dself": None if a[12] is None else a[12].clone()}
+            return orig_i(*a, **kw)
+
+        B.sylvie_aggregate_csr_bwd_integrate = hook_i
+        try:
+            self.fused.backward(SEED, OL.pair_seed)
+        finally:
+            B.sylvie_aggregate_csr_bwd_integrate = orig_i
         torch.cuda.synchronize()
         self.st = self.loop.parts[0]
         rp, cl, dg = np_c(p0.rowptr), np_c(p0.col), np_c(p0.deg)
@@ -291,3 +305,74 @@ def test_fused_backward_matches(run):
     for l in range(1, len(run.spec.dims)):
         assert torch.equal(sa.G[l], sb.G[l]), l
     assert torch.equal(sa.out, sb.out)
+
+
+@allruns
+def test_fused_integrate_against_oracle(oracle, run):
+    """The inner-row call of the fused backward (transposed aggregation + received gradients
+    added in its epilogue) against the oracle directly: Alg. 2's feature gradient of sampled
+    inner rows from the call's own dense gradient, then the oracle's ordered accumulate of the
+    wire rows that land on each.  The sum carries the float tolerance, the adds change nothing
+    about it."""
+    st, dims = run.fused.parts[0], run.spec.dims
+    rp, cl, w = run.op
+    L = len(dims) - 1
+    order = np.argsort(run.mirror, kind="stable")
+    sorted_m = run.mirror[order]
+    refs = np.bincount(cl, minlength=st.n_in + st.n_halo)[: st.n_in]
+    for l in range(L, 1, -1):
+        d = dims[l - 1]
+        W1 = (d + 63) // 64 + 1
+        fin = run.fused_in[l]
+        dZ = np_c(fin["dZ"])
+        sel = np.unique(np.concatenate([
+            run.rng.integers(0, st.n_in, 160), np.argsort(refs)[-8:],
+            np.argsort(np.bincount(run.mirror, minlength=st.n_in))[-5:], [0, st.n_in - 1]])).astype(np.int32)
+        out, S = oracle.aggregate_bwd_rows(rp, cl, w, dZ, d, sel)
+        sel_t = torch.from_numpy(sel.astype(np.int64)).to(DEV)
+        ref64 = out.astype(np.float64)
+        if fin["dself"] is not None:
+            ds = np_c(fin["dself"][sel_t])
+            ref64 += ds
+            S = S + np.abs(ds)
+        J = ref64.astype(np.float32)
+        wire2 = run.fused.record[("bwd", l, 0, 0)].view(-1, W1)
+        lo = np.searchsorted(sorted_m, sel, "left")
+        hi = np.searchsorted(sorted_m, sel, "right")
+        for i, (a, b) in enumerate(zip(lo, hi)):
+            js = order[a:b]                                   # ascending wire rows
+            if len(js) == 0:
+                continue
+            pk, sc, zp = split_wire(np_c(wire2[torch.from_numpy(js).to(DEV)]), len(js), d)
+            tgt = J[i: i + 1].copy()
+            oracle.dequantize_1bit_bwd(pk, sc, zp, d, tgt, np.zeros(len(js), np.int32))
+            J[i] = tgt[0]
+            S[i] += (np.abs(zp) + np.abs(sc)).sum()           # magnitudes of the added levels
+        close(np_c(st.dHtil[l - 1][sel_t]), J, S, ("fused integrate", l))
+
+
+@allruns
+def test_fused_step_repeats_bitwise(run):
+    """The same step twice on the same loop object: every wire, gradient and output repeats
+    bit for bit (long rows are cut into tasks and joined in task order, nothing is atomic)."""
+    loop = run.fused
+    st = loop.parts[0]
+    first = {k: v.clone() for k, v in loop.record.items()}
+    out0 = st.out.clone()
+    G0 = [None if g is None else g.clone() for g in st.G]
+    dH0 = [None if (g is None or l == 0) else g.clone() for l, g in enumerate(st.dHtil)]
+    Z0 = [z.clone() for z in st.Z]
+    loop.record = {}
+    loop.forward(SEED, OL.pair_seed)
+    loop.backward(SEED, OL.pair_seed)
+    torch.cuda.synchronize()
+    assert loop.record.keys() == first.keys()
+    for k in first:
+        assert torch.equal(first[k], loop.record[k]), k
+    assert torch.equal(out0, st.out)
+    for a, b in zip(Z0, st.Z):
+        assert torch.equal(a, b)
+    for a, b in zip(G0, st.G):
+        assert a is None or torch.equal(a, b)
+    for a, b in zip(dH0, st.dHtil):
+        assert a is None or torch.equal(a, b)
