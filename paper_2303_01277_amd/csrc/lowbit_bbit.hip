@@ -130,8 +130,14 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_kernel(
             }
         wave_minmax(mn, mx);
         const BbRow rc = bb_row_constants<BITS>(mn, mx);
-        // clear the image (whole 64-bit words of the row), then OR the pieces in
-        for (int k = lane; k < 2 * Wb; k += 64) img[k] = 0u;
+        // A lane's VEC codes are a piece of VEC * BITS bits.  Where that is a whole number of
+        // bytes (VEC = 4) every lane stores its piece with one plain sub-dword write - lanes
+        // past the row store zeros, which are the padding bits - so the image needs neither
+        // clearing nor atomics; otherwise the image is cleared and the pieces are OR-ed in.
+        constexpr int kPieceBits = VEC * BITS;
+        constexpr bool kPlain = kPieceBits % 8 == 0;
+        if constexpr (!kPlain)
+            for (int k = lane; k < 2 * Wb; k += 64) img[k] = 0u;
         const uint32_t rkey = mix32(ckey ^ static_cast<uint32_t>(first + r));
         auto encode = [&](auto tiny_c) {
 #pragma unroll
@@ -142,7 +148,13 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_kernel(
                 for (int t = 0; t < VEC; ++t)
                     piece |= bb_code<BITS, decltype(tiny_c)::value>(cur[p][t], rc, rkey + (c0 + t) * kColStride)
                              << (BITS * t);
-                if (valid[p]) {
+                if constexpr (kPlain) {
+                    const uint32_t v = valid[p] ? piece : 0u;
+                    const int slot = p * 64 + lane;                 // piece index inside the row
+                    if constexpr (kPieceBits == 8) reinterpret_cast<uint8_t *>(img)[slot] = static_cast<uint8_t>(v);
+                    else if constexpr (kPieceBits == 16) reinterpret_cast<uint16_t *>(img)[slot] = static_cast<uint16_t>(v);
+                    else img[slot] = v;
+                } else if (valid[p]) {
                     const uint32_t bit = c0 * BITS;
                     atomicOr(&img[bit >> 5], piece << (bit & 31u));
                 }
