@@ -720,6 +720,8 @@ def main():
                          "attention model and the Graph Engine set-up kernels")
     ap.add_argument("--packed-wire", action="store_true",
                     help="keep the resident 1-bit wire rows back to back instead of at the padded stride")
+    ap.add_argument("--reorder", action="store_true",
+                    help="aggregation launches take their rows longest first instead of in index order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of known size (scales the rocprofv3 "
@@ -768,7 +770,7 @@ def main():
     t0 = time.time()
     loop = LayerLoop(wl.parts, owner, rows, wl.X, wl.J, wl.W, spec.model, spec.dims,
                      chunk=args.chunk, exchange_first_layer=forced, wire=args.wire,
-                     pad_wire=not args.packed_wire)
+                     pad_wire=not args.packed_wire, reorder=args.reorder)
     torch.cuda.synchronize()
     log(f"[bench] set-up (operators, transpose, plans, buffers): {time.time() - t0:.1f} s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated")
@@ -788,7 +790,7 @@ def main():
     ag_ms = sum(o["ms_per_step"] for o in ag)
 
     default_cfg = (args.workload == "stress" and not args.nodes and args.chunk == 1024
-                   and args.wire == "1bit")
+                   and args.wire == "1bit" and not args.reorder and not args.packed_wire)
 
     profile = read_profile() if default_cfg else {}
 
@@ -859,6 +861,7 @@ def main():
                    "n_in": p0.n_in, "n_halo": p0.n_halo, "nnz_adjacency": p0.nnz,
                    "layer_model": spec.model, "dims": list(spec.dims), "chunk": args.chunk,
                    "wire": args.wire,
+                   "row_order": "longest row first" if args.reorder else "index order",
                    "resident_wire_row_stride": "packed" if args.packed_wire else "padded to a power of two words",
                    "value_is": "aggregated edges (fwd+bwd, all layers) per second of the whole "
                                "step, every hot-path kernel inside the timed region"},

@@ -194,13 +194,21 @@ int32_t sylvie_dequantize_bbit_bwd(const uint64_t *wire, int64_t n_rows, int32_t
  * With n_long = 0 these may be NULL / 0 and every row is summed by one wavefront.
  * chunk must be a positive multiple of 64.
  *
+ * Processing order (optional, every aggregation entry point takes it): row_order int32
+ * [n_rows], a permutation of [0, n_rows); wavefront i of the launch sums row
+ * row_begin + row_order[i] (row_begin = 0 where the call has no such argument).  NULL = rows
+ * in index order.  Results do not depend on it bit for bit - every row is still summed by one
+ * wavefront (or its tasks) in entry order - only the traffic between the caches and memory
+ * does: rows handed out longest first reach a higher hit rate in the L2s on power-law
+ * graphs (sylvie_graph_rows_by_length builds that order).
+ *
  *   rowptr int64 [n_rows+1]; col int32 [nnz] in [0, rows of X)
  */
 int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col, const float *w,
                                  const float *row_scale, const float *col_scale,
                                  int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
                                  float *Y, int64_t ld_y, const float *addend,
-                                 int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                 int64_t ld_addend, int64_t addend_rows, const int32_t *row_order, int32_t chunk,
                                  const int32_t *long_rows, const int64_t *long_ptr,
                                  int64_t n_long, int64_t n_tasks, float *workspace,
                                  size_t workspace_bytes, void *stream);
@@ -227,7 +235,7 @@ int32_t sylvie_aggregate_csr_fwd_noalloc(const int64_t *rowptr, const int32_t *c
                                          const float *row_scale, const float *col_scale,
                                          int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
                                          float *Y, int64_t ld_y, const float *addend,
-                                         int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                         int64_t ld_addend, int64_t addend_rows, const int32_t *row_order, int32_t chunk,
                                          const int32_t *long_rows, const int64_t *long_ptr,
                                          int64_t n_long, int64_t n_tasks, void *stream);
 
@@ -247,7 +255,7 @@ int32_t sylvie_aggregate_csr_fwd_wire(const int64_t *rowptr, const int32_t *col,
                                       const float *row_scale, const float *col_scale,
                                       int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
                                       int64_t n_dense, const uint64_t *wire, int64_t ld_wire,
-                                      int64_t n_wire, float *Y, int64_t ld_y, int32_t chunk,
+                                      int64_t n_wire, float *Y, int64_t ld_y, const int32_t *row_order, int32_t chunk,
                                       const int32_t *long_rows,
                                       const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
                                       float *workspace, size_t workspace_bytes, void *stream);
@@ -263,7 +271,7 @@ int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_t *colT, co
                                  const float *row_scale, const float *col_scale,
                                  int64_t n_rowsT, const float *dY, int64_t ld_dy, int32_t d,
                                  float *dX, int64_t ld_dx, const float *addend,
-                                 int64_t ld_addend, int64_t addend_rows, int32_t chunk,
+                                 int64_t ld_addend, int64_t addend_rows, const int32_t *row_order, int32_t chunk,
                                  const int32_t *long_rows, const int64_t *long_ptr,
                                  int64_t n_long, int64_t n_tasks, float *workspace,
                                  size_t workspace_bytes, void *stream);
@@ -284,7 +292,7 @@ int32_t sylvie_aggregate_csr_bwd_quantize(const int64_t *rowptrT, const int32_t 
                                           const float *col_scale, int64_t row_begin,
                                           int64_t n_rows, const float *dY, int64_t ld_dy,
                                           int32_t d, uint64_t seed, uint32_t stream_id,
-                                          uint64_t *wire_out, int64_t ld_wire, int32_t chunk,
+                                          uint64_t *wire_out, int64_t ld_wire, const int32_t *row_order, int32_t chunk,
                                           const int32_t *long_rows, const int64_t *long_ptr,
                                           int64_t n_long, int64_t n_tasks, float *workspace,
                                           size_t workspace_bytes, void *stream);
@@ -308,7 +316,7 @@ int32_t sylvie_aggregate_csr_bwd_integrate(const int64_t *rowptrT, const int32_t
                                            const float *addend, int64_t ld_addend,
                                            int64_t addend_rows, const uint64_t *wire,
                                            int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
-                                           const int32_t *seg_rows, int32_t chunk,
+                                           const int32_t *seg_rows, const int32_t *row_order, int32_t chunk,
                                            const int32_t *long_rows, const int64_t *long_ptr,
                                            int64_t n_long, int64_t n_tasks, float *workspace,
                                            size_t workspace_bytes, void *stream);

@@ -173,14 +173,16 @@ def sylvie_dequantize_1bit_bwd(wire, n_rows, d, dst, ld_dst, seg_ptr, seg_rows, 
 
 
 def _aggregate(fn, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y, addend,
-               ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks, workspace):
+               ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks, workspace,
+               row_order=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(fn(_ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
               _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
               _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
               _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d),
               _ptr(Y, torch.float32, "Y"), C.c_int64(ld_y), _ptr(addend, torch.float32, "addend"),
-              C.c_int64(ld_addend), C.c_int64(addend_rows), C.c_int32(chunk),
+              C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(row_order, torch.int32, "row_order"),
+              C.c_int32(chunk),
               _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
               C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
               C.c_size_t(ws_bytes), _stream()))
@@ -188,10 +190,10 @@ def _aggregate(fn, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, 
 
 def sylvie_aggregate_csr_fwd(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y,
                              addend=None, ld_addend=0, addend_rows=0, chunk=0, long_rows=None,
-                             long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+                             long_ptr=None, n_long=0, n_tasks=0, workspace=None, row_order=None):
     _aggregate(lib().sylvie_aggregate_csr_fwd, rowptr, col, w, row_scale, col_scale, n_rows, X,
                ld_x, d, Y, ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
-               n_long, n_tasks, workspace)
+               n_long, n_tasks, workspace, row_order)
 
 
 STATIC_SCRATCH_BYTES = 16 << 20
@@ -199,7 +201,7 @@ STATIC_SCRATCH_BYTES = 16 << 20
 
 def sylvie_aggregate_csr_fwd_noalloc(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y,
                                      addend=None, ld_addend=0, addend_rows=0, chunk=0,
-                                     long_rows=None, long_ptr=None, n_long=0, n_tasks=0):
+                                     long_rows=None, long_ptr=None, n_long=0, n_tasks=0, row_order=None):
     """sylvie_aggregate_csr_fwd with the long-row partial sums in the library's built-in scratch
     (n_tasks * d * 4 <= STATIC_SCRATCH_BYTES); allocates nothing."""
     _check(lib().sylvie_aggregate_csr_fwd_noalloc(
@@ -208,14 +210,16 @@ def sylvie_aggregate_csr_fwd_noalloc(rowptr, col, w, row_scale, col_scale, n_row
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
         _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d),
         _ptr(Y, torch.float32, "Y"), C.c_int64(ld_y), _ptr(addend, torch.float32, "addend"),
-        C.c_int64(ld_addend), C.c_int64(addend_rows), C.c_int32(chunk),
+        C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(row_order, torch.int32, "row_order"),
+        C.c_int32(chunk),
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _stream()))
 
 
 def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,
                                   wire, n_wire, Y, ld_y, chunk=0, long_rows=None,
-                                  long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
+                                  long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
+                                  row_order=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_fwd_wire(
         _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
@@ -224,22 +228,25 @@ def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, 
         _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), C.c_int64(n_dense),
         _ptr(wire, torch.int64, "wire"), C.c_int64(ld_wire), C.c_int64(n_wire),
         _ptr(Y, torch.float32, "Y"),
-        C.c_int64(ld_y), C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"),
+        C.c_int64(ld_y), _ptr(row_order, torch.int32, "row_order"), C.c_int32(chunk),
+        _ptr(long_rows, torch.int32, "long_rows"),
         _ptr(long_ptr, torch.int64, "long_ptr"), C.c_int64(n_long), C.c_int64(n_tasks),
         _ptr(workspace, torch.float32, "workspace"), C.c_size_t(ws_bytes), _stream()))
 
 
 def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, dY, ld_dy, d, dX,
                              ld_dx, addend=None, ld_addend=0, addend_rows=0, chunk=0,
-                             long_rows=None, long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+                             long_rows=None, long_ptr=None, n_long=0, n_tasks=0, workspace=None,
+                             row_order=None):
     _aggregate(lib().sylvie_aggregate_csr_bwd, rowptrT, colT, wT, row_scale, col_scale, n_rowsT,
                dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows, chunk, long_rows,
-               long_ptr, n_long, n_tasks, workspace)
+               long_ptr, n_long, n_tasks, workspace, row_order)
 
 
 def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
                                       ld_dy, d, seed, stream_id, wire_out, chunk=0, long_rows=None,
-                                      long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
+                                      long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
+                                      row_order=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_bwd_quantize(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
@@ -247,7 +254,8 @@ def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, r
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
         _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
         C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
-        _ptr(wire_out, torch.int64, "wire_out"), C.c_int64(ld_wire), C.c_int32(chunk),
+        _ptr(wire_out, torch.int64, "wire_out"), C.c_int64(ld_wire),
+        _ptr(row_order, torch.int32, "row_order"), C.c_int32(chunk),
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))
@@ -256,7 +264,8 @@ def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, r
 def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows,
                                        dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows,
                                        wire, n_wire, seg_ptr, seg_rows, chunk=0, long_rows=None,
-                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0):
+                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
+                                       row_order=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sylvie_aggregate_csr_bwd_integrate(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
@@ -266,7 +275,8 @@ def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, 
         _ptr(dX, torch.float32, "dX"), C.c_int64(ld_dx), _ptr(addend, torch.float32, "addend"),
         C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(wire, torch.int64, "wire"),
         C.c_int64(ld_wire), C.c_int64(n_wire), _ptr(seg_ptr, torch.int64, "seg_ptr"),
-        _ptr(seg_rows, torch.int32, "seg_rows"), C.c_int32(chunk),
+        _ptr(seg_rows, torch.int32, "seg_rows"), _ptr(row_order, torch.int32, "row_order"),
+        C.c_int32(chunk),
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))

@@ -115,6 +115,9 @@ struct AggArgs {
     // rows handled by this launch are row_begin .. row_begin + n_rows - 1 (absolute
     // indices into rowptr / Y / addend / row_scale)
     int64_t row_begin;
+    // optional processing order: wavefront i of the launch takes row row_begin + row_order[i]
+    // (a permutation of [0, n_rows)); results do not depend on it, the cache traffic does
+    const int32_t *row_order;
     // epilogue "quantize": wire row (v - row_begin) <- quantized row v
     uint64_t *wire_out;
     int64_t ldw_out;            // row stride of wire_out in 64-bit words
@@ -471,8 +474,9 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         return;
     }
 
-    const int64_t local = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
-    if (local >= a.n_rows) return;
+    const int64_t pos = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
+    if (pos >= a.n_rows) return;
+    const int64_t local = a.row_order ? static_cast<int64_t>(uniform(a.row_order[pos])) : pos;
     const int64_t v = a.row_begin + local;
     const int64_t e0 = uniform(a.rowptr[v]);
     const int64_t e1 = uniform(a.rowptr[v + 1]);
@@ -620,6 +624,7 @@ struct AggExtra {
     uint32_t ckey = 0;
     const int64_t *seg_ptr = nullptr;
     const int32_t *seg_rows = nullptr;
+    const int32_t *row_order = nullptr;
 };
 
 static int32_t aggregate_common(const char *name, const int64_t *rowptr, const int32_t *col,
@@ -687,6 +692,7 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.ckey = x.ckey;
     a.seg_ptr = x.seg_ptr;
     a.seg_rows = x.seg_rows;
+    a.row_order = x.row_order;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (validate_enabled()) {
@@ -756,7 +762,7 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_noalloc(const int64_t *rowptr, const
                                                     const float *X, int64_t ld_x, int32_t d, float *Y,
                                                     int64_t ld_y, const float *addend,
                                                     int64_t ld_addend, int64_t addend_rows,
-                                                    int32_t chunk, const int32_t *long_rows,
+                                                    const int32_t *row_order, int32_t chunk, const int32_t *long_rows,
                                                     const int64_t *long_ptr, int64_t n_long,
                                                     int64_t n_tasks, void *stream)
 {
@@ -773,10 +779,12 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_noalloc(const int64_t *rowptr, const
         const int32_t rc = sylvie::static_scratch(name, &ws);
         if (rc != SYLVIE_OK) return rc;
     }
+    sylvie::AggExtra x;
+    x.row_order = row_order;
     return sylvie::aggregate_common(name, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y,
                                     ld_y, addend, ld_addend, addend_rows, chunk, long_rows, long_ptr,
                                     n_long, n_tasks, ws, n_long > 0 ? SYLVIE_STATIC_SCRATCH_BYTES : 0,
-                                    stream);
+                                    stream, x);
 }
 
 extern "C" int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t *col,
@@ -784,15 +792,17 @@ extern "C" int32_t sylvie_aggregate_csr_fwd(const int64_t *rowptr, const int32_t
                                             const float *col_scale, int64_t n_rows,
                                             const float *X, int64_t ld_x, int32_t d, float *Y,
                                             int64_t ld_y, const float *addend, int64_t ld_addend,
-                                            int64_t addend_rows, int32_t chunk,
+                                            int64_t addend_rows, const int32_t *row_order, int32_t chunk,
                                             const int32_t *long_rows, const int64_t *long_ptr,
                                             int64_t n_long, int64_t n_tasks, float *workspace,
                                             size_t workspace_bytes, void *stream)
 {
+    sylvie::AggExtra x;
+    x.row_order = row_order;
     return sylvie::aggregate_common("sylvie_aggregate_csr_fwd", rowptr, col, w, row_scale,
                                     col_scale, n_rows, X, ld_x, d, Y, ld_y, addend, ld_addend,
                                     addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
-                                    workspace, workspace_bytes, stream);
+                                    workspace, workspace_bytes, stream, x);
 }
 
 extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_t *colT,
@@ -800,22 +810,24 @@ extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_
                                             const float *col_scale, int64_t n_rowsT,
                                             const float *dY, int64_t ld_dy, int32_t d, float *dX,
                                             int64_t ld_dx, const float *addend, int64_t ld_addend,
-                                            int64_t addend_rows, int32_t chunk,
+                                            int64_t addend_rows, const int32_t *row_order, int32_t chunk,
                                             const int32_t *long_rows, const int64_t *long_ptr,
                                             int64_t n_long, int64_t n_tasks, float *workspace,
                                             size_t workspace_bytes, void *stream)
 {
+    sylvie::AggExtra x;
+    x.row_order = row_order;
     return sylvie::aggregate_common("sylvie_aggregate_csr_bwd", rowptrT, colT, wT, row_scale,
                                     col_scale, n_rowsT, dY, ld_dy, d, dX, ld_dx, addend, ld_addend,
                                     addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
-                                    workspace, workspace_bytes, stream);
+                                    workspace, workspace_bytes, stream, x);
 }
 
 extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
     const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
     const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
     int64_t n_dense, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
-    int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
     float *workspace, size_t workspace_bytes, void *stream)
 {
     sylvie::AggExtra x;
@@ -823,6 +835,7 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
     x.wire = wire;
     x.ld_wire = ld_wire;
     x.n_wire = n_wire;
+    x.row_order = row_order;
     return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
                                     col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
                                     long_rows, long_ptr, n_long, n_tasks, workspace,
@@ -832,7 +845,7 @@ extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
 extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
     const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
-    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire, int32_t chunk,
+    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire, const int32_t *row_order, int32_t chunk,
     const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
     float *workspace, size_t workspace_bytes, void *stream)
 {
@@ -842,6 +855,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
     x.wire_out = wire_out;
     x.ld_wire = ld_wire;
     x.ckey = sylvie::call_key(seed, stream_id);
+    x.row_order = row_order;
     return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_quantize", rowptrT, colT, wT,
                                     row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr, ld_dy,
                                     nullptr, 0, 0, chunk, long_rows, long_ptr, n_long, n_tasks,
@@ -853,7 +867,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
     int32_t d, float *dX, int64_t ld_dx, const float *addend, int64_t ld_addend,
     int64_t addend_rows, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
-    const int32_t *seg_rows, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    const int32_t *seg_rows, const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
     int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
 {
     sylvie::AggExtra x;
@@ -864,6 +878,7 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
     x.n_wire = n_wire;
     x.seg_ptr = seg_ptr;
     x.seg_rows = seg_rows;
+    x.row_order = row_order;
     return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_integrate", rowptrT, colT, wT,
                                     row_scale, col_scale, n_rows, dY, ld_dy, d, dX, ld_dx, addend,
                                     ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long,

@@ -130,6 +130,16 @@ def long_row_plan(rowptr, chunk, row_begin=0, row_end=None):
     return long_rows.to(torch.int32), long_ptr, int(long_ptr[-1])
 
 
+def rows_by_length(rowptr, row_begin=0, row_end=None):
+    """Processing order of the rows [row_begin, row_end) of a CSR for the aggregation kernels:
+    longest row first, ties in index order.  Returns int32 [row_end - row_begin], a permutation
+    of [0, row_end - row_begin) (indices relative to row_begin)."""
+    n = int(rowptr.numel()) - 1
+    hi = n if row_end is None else row_end
+    counts = rowptr[row_begin + 1: hi + 1] - rowptr[row_begin: hi]
+    return torch.argsort(counts, descending=True, stable=True).to(torch.int32)
+
+
 def scatter_segments_dense(dst_row, n_dst):
     """Wire rows grouped by destination row, one (possibly empty) segment for every
     destination row 0 .. n_dst - 1: returns (seg_ptr int64 [n_dst + 1], seg_rows int32 [n]);

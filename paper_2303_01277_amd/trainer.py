@@ -36,6 +36,7 @@ class Block:
     seg_rows: torch.Tensor
     dst_ids: torch.Tensor
     planT: tuple = None         # long-row plan of the transposed operator on these halo rows
+    orderT: Optional[torch.Tensor] = None   # processing order of these halo rows (longest first)
     inb_off: int = 0            # first row of this block in the owner's inbound wire
 
 
@@ -67,6 +68,11 @@ class PartState:
     inb_seg_ptr: Optional[torch.Tensor] = None                # int64 [n_in + 1]
     inb_seg_rows: Optional[torch.Tensor] = None               # int32 [n_inbound]
     planT_inner: tuple = None
+    # processing orders (longest row first) of the operator's rows, of all rows of its transpose
+    # and of the transpose's inner rows; None = index order
+    order: Optional[torch.Tensor] = None
+    orderT: Optional[torch.Tensor] = None
+    orderT_inner: Optional[torch.Tensor] = None
     # pipeline mode: one wire per layer and two generations of each (this epoch / previous)
     fwd_wires: Optional[list] = None                          # [gen][l] int64 words
     inb_wires: Optional[list] = None                          # [gen][l] int64 words
@@ -82,7 +88,8 @@ class LayerLoop:
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, model: str, dims, chunk: int = 1024,
                  exchange_first_layer: bool = False, wire: str = "1bit", fused: bool = True,
-                 fused_bwd: bool = True, pipeline: bool = False, pad_wire: bool = True):
+                 fused_bwd: bool = True, pipeline: bool = False, pad_wire: bool = True,
+                 reorder: bool = False):
         """parts: synth Partition objects already on the GPU; halo_owner / halo_row: per
         partition int32 tensors naming the owner partition and owner-local inner row of
         each halo row (grouped by owner, ascending).  pad_wire: keep the resident 1-bit wire
@@ -93,6 +100,11 @@ class LayerLoop:
         self.exchange_first_layer = exchange_first_layer
         self.wire = wire
         self.pad_wire = pad_wire
+        # reorder: every aggregation launch hands its rows out longest first (same results bit
+        # for bit).  Off by default: an L2 model predicts 11-15 % less traffic for it on the
+        # stress partition, the chip's counters show none and the scattered row pointers cost
+        # 5-28 % time; the hook stays for graphs whose own structure gives a better order.
+        self.reorder = reorder
         if wire not in WIRE_BITS and wire != "fp32":
             raise ValueError(f"wire must be one of {sorted(WIRE_BITS)} or 'fp32'")
         # bits per element on the wire: 1 = the paper's default; 2, 4, 8 and 16 (binary16)
@@ -127,6 +139,8 @@ class LayerLoop:
             opT = tuple(opT)
             plan = GE.long_row_plan(op[0], chunk)
             planT = GE.long_row_plan(opT[0], chunk)
+            order = GE.rows_by_length(op[0]) if reorder else None
+            orderT = GE.rows_by_length(opT[0]) if reorder else None
             blocks = []
             if part.n_halo:
                 own, cnt = torch.unique_consecutive(halo_owner[p], return_counts=True)
@@ -138,6 +152,7 @@ class LayerLoop:
                     j += c
             st = PartState(part.n_in, part.n_halo, op, opT, plan, planT, blocks, X[p], J[p])
             st.perm = perm              # entry i of opT is entry perm[i] of op
+            st.order, st.orderT = order, orderT
             Wd = max(self._stride(d) for d in dims[:-1])
             st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
@@ -174,12 +189,15 @@ class LayerLoop:
                         b.inb_off = sq.n_inbound
                         b.planT = GE.long_row_plan(sp_.opT[0], chunk, sp_.n_in + b.j0,
                                                    sp_.n_in + b.j1)
+                        b.orderT = GE.rows_by_length(sp_.opT[0], sp_.n_in + b.j0,
+                                                     sp_.n_in + b.j1) if reorder else None
                         sq.n_inbound += b.j1 - b.j0
                         dst.append(b.rows)
                 dst = torch.cat(dst) if dst else torch.zeros(0, dtype=torch.int32, device=dev)
                 sq.inb_seg_ptr, sq.inb_seg_rows = GE.scatter_segments_dense(dst, sq.n_in)
                 sq.inbound = torch.empty(max(1, sq.n_inbound) * Wd, dtype=torch.int64, device=dev)
                 sq.planT_inner = GE.long_row_plan(sq.opT[0], chunk, 0, sq.n_in)
+                sq.orderT_inner = GE.rows_by_length(sq.opT[0], 0, sq.n_in) if reorder else None
         if pipeline:
             self.side = torch.cuda.Stream()        # default priority
             lo = 1 if exchange_first_layer else 2  # layers whose backward exchanges gradients
@@ -227,14 +245,14 @@ class LayerLoop:
             return B.sylvie_wire_row_words(d)
         return B.sylvie_wire_row_words_bits(d, self.bits)
 
-    def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0):
+    def _aggregate(self, fn, op, plan, ws, n_rows, X, d, Y, addend=None, addend_rows=0, order=None):
         rp, cl, w = op
         lr, lp, nt = plan
         fn(rp, cl, w, None, None, n_rows, X, X.stride(0), d, Y, Y.stride(0),
            addend=addend, ld_addend=0 if addend is None else addend.stride(0),
            addend_rows=addend_rows, chunk=self.chunk, long_rows=lr if nt else None,
            long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-           workspace=ws if nt else None)
+           workspace=ws if nt else None, row_order=order)
 
     def _exchange_forward(self, l, d, Wd, seed, pair_seed):
         """Alg. 1, the exchange of layer l: every owner quantizes the rows its peers need; the
@@ -314,10 +332,11 @@ class LayerLoop:
                         st.n_halo, Z, Z.stride(0), chunk=self.chunk,
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                        workspace=st.ws_agg if nt else None, ld_wire=self._stride(d))
+                        workspace=st.ws_agg if nt else None, ld_wire=self._stride(d),
+                        row_order=st.order)
                 else:
                     self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
-                                    st.n_in, ht, d, Z)
+                                    st.n_in, ht, d, Z, order=st.order)
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
                 h = self.dims[l]
@@ -360,7 +379,7 @@ class LayerLoop:
                     g = st.dHtil[l - 1]
                     self._aggregate(B.sylvie_aggregate_csr_bwd, st.opT, st.planT, st.ws_aggT,
                                     st.n_in + st.n_halo, dZ, d, g, addend=dself,
-                                    addend_rows=st.n_in)
+                                    addend_rows=st.n_in, order=st.orderT)
             if not need_dx:
                 continue
             if self.fused_bwd:
@@ -383,7 +402,7 @@ class LayerLoop:
                     pair_seed(seed, me, b.owner), 2 * l + 1, wire, chunk=self.chunk,
                     long_rows=lr if nt else None, long_ptr=lp if nt else None,
                     n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                    workspace=st.ws_aggT if nt else None)
+                    workspace=st.ws_aggT if nt else None, row_order=b.orderT)
                 self._keep(("bwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
         for st in self.parts:
             rpT, clT, wT = st.opT
@@ -398,7 +417,7 @@ class LayerLoop:
                 0 if dself is None else d, st.n_in, st.inbound, st.n_inbound, st.inb_seg_ptr,
                 st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
                 long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                workspace=st.ws_aggT if nt else None)
+                workspace=st.ws_aggT if nt else None, row_order=st.orderT_inner)
 
     # -- Sylvie-A (Sec. 3.3): pipeline mode ------------------------------------------
     def _gen(self, which):
@@ -448,13 +467,13 @@ class LayerLoop:
                         st.n_halo, Z, Z.stride(0), chunk=self.chunk,
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                        workspace=st.ws_agg if nt else None, ld_wire=S)
+                        workspace=st.ws_agg if nt else None, ld_wire=S, row_order=st.order)
                 else:
                     if st.n_halo:
                         B.sylvie_dequantize_1bit_fwd(wire, st.n_halo, d, ht, ht.stride(0), st.n_in,
                                                      ld_wire=S)
                     self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
-                                    st.n_in, ht, d, Z)
+                                    st.n_in, ht, d, Z, order=st.order)
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
                 h = self.dims[l]
@@ -496,7 +515,7 @@ class LayerLoop:
                     g = st.dHtil[l - 1]
                     self._aggregate(B.sylvie_aggregate_csr_bwd, st.opT, st.planT, st.ws_aggT,
                                     st.n_in + st.n_halo, dZ, d, g, addend=dself,
-                                    addend_rows=st.n_in)
+                                    addend_rows=st.n_in, order=st.orderT)
             if not need_dx:
                 continue
             # this epoch's gradient wires, written into the owners' inbound buffers
@@ -516,7 +535,7 @@ class LayerLoop:
                                 pair_seed(seed, me, b.owner), 2 * l + 1, wire, chunk=self.chunk,
                                 long_rows=lr if nt else None, long_ptr=lp if nt else None,
                                 n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                                workspace=ws if nt else None)
+                                workspace=ws if nt else None, row_order=b.orderT)
                         else:
                             B.sylvie_quantize_1bit_bwd(g, g.stride(0), d, None, st.n_in + b.j0,
                                                        b.j1 - b.j0, pair_seed(seed, me, b.owner),
@@ -538,7 +557,8 @@ class LayerLoop:
                         0 if dself is None else d, st.n_in, inb, st.n_inbound, st.inb_seg_ptr,
                         st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
                         long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0,
-                        n_tasks=nt, workspace=st.ws_aggT if nt else None)
+                        n_tasks=nt, workspace=st.ws_aggT if nt else None,
+                        row_order=st.orderT_inner)
             if not self.fused_bwd:
                 for sp_ in self.parts:
                     for b in sp_.blocks:

@@ -97,10 +97,10 @@ def test_bad_arguments_are_rejected_without_gpu(lib):
     base = [p, p, None, None, None, C.c_int64(4), p, C.c_int64(64), C.c_int32(64), p,
             C.c_int64(64), None, C.c_int64(0), C.c_int64(0)]
     # long rows announced but chunk not a multiple of 64
-    assert ag(*base, C.c_int32(100), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(1 << 20),
+    assert ag(*base, None, C.c_int32(100), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(1 << 20),
               None) == -1
     # workspace too small for the announced tasks
-    assert ag(*base, C.c_int32(128), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(16),
+    assert ag(*base, None, C.c_int32(128), p, p, C.c_int64(1), C.c_int64(2), p, C.c_size_t(16),
               None) == -5
     tf = lib.sylvie_transform_fwd
     tf.restype = C.c_int32

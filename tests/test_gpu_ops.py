@@ -401,3 +401,66 @@ def test_loop_without_halo(oracle):
         assert np.abs(st.dHtil[1].cpu().numpy()[: p.n_in] - ref.Jin[1]).max() <= \
             2e-5 * np.abs(ref.Jin[1]).max()
         assert np.abs(st.G[1].cpu().numpy() - ref.G[1]).max() <= 2e-5 * np.abs(ref.G[1]).max()
+
+
+@pytest.mark.parametrize("d", [64, 100, 256])
+def test_row_order_changes_nothing(oracle, d):
+    """A processing order (any permutation of the launch's rows) leaves every aggregation entry
+    point's result bit for bit what it is in index order."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    p, (rp, cl, w) = _operator(oracle, "stress", 30_000, "gcn")
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + 11)
+    X = make_rows(rng, n_loc, d, "heavy")
+    pk, sc, zp = oracle.quantize_1bit(X, d, p.n_halo, 5, 2, row_offset=p.n_in)
+    rpd, cld, wd = dev(rp), dev(cl), dev(w)
+    wired = dev(join_wire(pk, sc, zp))
+    Xin, Xfull = dev(X[: p.n_in]), dev(X)
+    chunk = 128
+    lr, lp, nt = GE.long_row_plan(rpd, chunk)
+    kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+              workspace=torch.empty(max(1, nt) * d, device=DEV))
+    orders = [None, GE.rows_by_length(rpd), dev(rng.permutation(p.n_in).astype(np.int32))]
+    outs = []
+    for o in orders:
+        Y1 = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, Y1, d, row_order=o, **kw)
+        Y2 = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd_wire(rpd, cld, wd, None, None, p.n_in, Xin, d, d, p.n_in, wired,
+                                        p.n_halo, Y2, d, row_order=o, **kw)
+        outs.append((Y1, Y2))
+    torch.cuda.synchronize()
+    for Y1, Y2 in outs[1:]:
+        assert torch.equal(Y1, outs[0][0]) and torch.equal(Y2, outs[0][1])
+    # backward epilogues on a row range of the transposed operator
+    rpT, clT, wT = GE.transpose_csr(rpd, cld, wd, n_loc)
+    dZ = dev(make_rows(rng, p.n_in, d, "heavy"))
+    mirror = dev(rng.integers(0, p.n_in, p.n_halo).astype(np.int32))
+    sp_, sr = GE.scatter_segments_dense(mirror, p.n_in)
+    W1 = (d + 63) // 64 + 1
+    res = []
+    for kind in ("index", "length", "random"):
+        def order(r0, r1):
+            if kind == "index":
+                return None
+            if kind == "length":
+                return GE.rows_by_length(rpT, r0, r1)
+            return dev(rng.permutation(r1 - r0).astype(np.int32))
+        lrq, lpq, ntq = GE.long_row_plan(rpT, chunk, p.n_in, n_loc)
+        wire = torch.full((p.n_halo * W1,), -1, dtype=torch.int64, device=DEV)
+        B.sylvie_aggregate_csr_bwd_quantize(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, 99, 7, wire,
+                                            chunk=chunk, long_rows=lrq, long_ptr=lpq, n_long=int(lrq.numel()),
+                                            n_tasks=ntq, workspace=torch.empty(max(1, ntq) * d, device=DEV),
+                                            row_order=order(p.n_in, n_loc))
+        lri, lpi, nti = GE.long_row_plan(rpT, chunk, 0, p.n_in)
+        G = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_bwd_integrate(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, G, d, None, 0, 0,
+                                             wire, p.n_halo, sp_, sr, chunk=chunk, long_rows=lri, long_ptr=lpi,
+                                             n_long=int(lri.numel()), n_tasks=nti,
+                                             workspace=torch.empty(max(1, nti) * d, device=DEV),
+                                             row_order=order(0, p.n_in))
+        res.append((wire, G))
+    torch.cuda.synchronize()
+    for wire, G in res[1:]:
+        assert torch.equal(wire, res[0][0]) and torch.equal(G, res[0][1])

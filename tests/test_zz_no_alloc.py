@@ -35,7 +35,7 @@ def _call(fn, c, Y, extra):
               C.c_void_p(c["w"].data_ptr()), C.c_void_p(0), C.c_void_p(0), C.c_int64(c["n"]),
               C.c_void_p(c["X"].data_ptr()), C.c_int64(c["d"]), C.c_int32(c["d"]),
               C.c_void_p(Y.data_ptr()), C.c_int64(c["d"]), C.c_void_p(0), C.c_int64(0), C.c_int64(0),
-              C.c_int32(c["chunk"]), C.c_void_p(c["lr"].data_ptr()), C.c_void_p(c["lp"].data_ptr()),
+              C.c_void_p(0), C.c_int32(c["chunk"]), C.c_void_p(c["lr"].data_ptr()), C.c_void_p(c["lp"].data_ptr()),
               C.c_int64(c["lr"].numel()), C.c_int64(c["nt"])]
     return fn(*L_args, *extra, C.c_void_p(torch.cuda.current_stream().cuda_stream))
 
