@@ -322,6 +322,55 @@ int32_t sylvie_aggregate_csr_bwd_integrate(const int64_t *rowptrT, const int32_t
                                            size_t workspace_bytes, void *stream);
 
 /*
+ * The three fused aggregation calls above for the wider wires of the bit-width study (Sec. 4.3;
+ * Eq. 3-5 with B = 2^bits - 1): `bits` is 1, 2, 4 or 8 (1 = the calls above) and `wire` /
+ * `wire_out` hold rows in the format of sylvie_quantize_bbit_* (ceil(d bits / 64) code words and
+ * the scale | zero word; ld_wire = words from one row to the next, 0 = packed).
+ *   - sylvie_aggregate_csr_fwd_wire_bbit: a gathered halo element is fl(fl(scale q) + zero)
+ *     (Eq. 5), then weighted and summed as every other element; the same result as
+ *     sylvie_dequantize_bbit_fwd followed by sylvie_aggregate_csr_fwd up to the order of the
+ *     single-precision additions.
+ *   - sylvie_aggregate_csr_bwd_quantize_bbit: the same wire, bit for bit, as
+ *     sylvie_aggregate_csr_bwd followed by sylvie_quantize_bbit_bwd of the row block.
+ *   - sylvie_aggregate_csr_bwd_integrate_bbit: the same rows, bit for bit, as
+ *     sylvie_aggregate_csr_bwd followed by sylvie_dequantize_bbit_bwd.
+ * For bits > 1 the float rows must be 16-byte aligned with d and the leading dimensions
+ * multiples of 4 (SYLVIE_ERR_UNIMPLEMENTED otherwise: use the separate calls).
+ */
+int32_t sylvie_aggregate_csr_fwd_wire_bbit(const int64_t *rowptr, const int32_t *col, const float *w,
+                                           const float *row_scale, const float *col_scale,
+                                           int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+                                           int32_t bits, int64_t n_dense, const uint64_t *wire,
+                                           int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
+                                           const int32_t *row_order, int32_t chunk,
+                                           const int32_t *long_rows, const int64_t *long_ptr,
+                                           int64_t n_long, int64_t n_tasks, float *workspace,
+                                           size_t workspace_bytes, void *stream);
+int32_t sylvie_aggregate_csr_bwd_quantize_bbit(const int64_t *rowptrT, const int32_t *colT,
+                                               const float *wT, const float *row_scale,
+                                               const float *col_scale, int64_t row_begin,
+                                               int64_t n_rows, const float *dY, int64_t ld_dy,
+                                               int32_t d, int32_t bits, uint64_t seed,
+                                               uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire,
+                                               const int32_t *row_order, int32_t chunk,
+                                               const int32_t *long_rows, const int64_t *long_ptr,
+                                               int64_t n_long, int64_t n_tasks, float *workspace,
+                                               size_t workspace_bytes, void *stream);
+int32_t sylvie_aggregate_csr_bwd_integrate_bbit(const int64_t *rowptrT, const int32_t *colT,
+                                                const float *wT, const float *row_scale,
+                                                const float *col_scale, int64_t row_begin,
+                                                int64_t n_rows, const float *dY, int64_t ld_dy,
+                                                int32_t d, int32_t bits, float *dX, int64_t ld_dx,
+                                                const float *addend, int64_t ld_addend,
+                                                int64_t addend_rows, const uint64_t *wire,
+                                                int64_t ld_wire, int64_t n_wire,
+                                                const int64_t *seg_ptr, const int32_t *seg_rows,
+                                                const int32_t *row_order, int32_t chunk,
+                                                const int32_t *long_rows, const int64_t *long_ptr,
+                                                int64_t n_long, int64_t n_tasks, float *workspace,
+                                                size_t workspace_bytes, void *stream);
+
+/*
  * Dense transform, forward (Eq. 2; Alg. 1 "update embeddings", H = sigma(Z W)):
  *     P = [A1 | A2] * W,   H = relu ? max(P, 0) : P
  * A1 is n x k1 (ld_a1), A2 is n x k2 (ld_a2) or NULL with k2 = 0 (GraphSAGE puts a

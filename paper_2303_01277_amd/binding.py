@@ -55,6 +55,8 @@ def lib():
                      "sylvie_aggregate_csr_fwd_noalloc",
                      "sylvie_aggregate_csr_fwd_wire", "sylvie_aggregate_csr_bwd_quantize",
                      "sylvie_aggregate_csr_bwd_integrate",
+                     "sylvie_aggregate_csr_fwd_wire_bbit", "sylvie_aggregate_csr_bwd_quantize_bbit",
+                     "sylvie_aggregate_csr_bwd_integrate_bbit",
                      "sylvie_transform_fwd", "sylvie_transform_bwd", "sylvie_softmax_xent",
                      "sylvie_sum_gradients", "sylvie_sgd_update", "sylvie_row_dot",
                      "sylvie_edge_softmax_fwd", "sylvie_sddmm", "sylvie_edge_softmax_bwd",
@@ -219,13 +221,16 @@ def sylvie_aggregate_csr_fwd_noalloc(rowptr, col, w, row_scale, col_scale, n_row
 def sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense,
                                   wire, n_wire, Y, ld_y, chunk=0, long_rows=None,
                                   long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
-                                  row_order=None):
+                                  row_order=None, bits=1):
+    """bits = 1: sylvie_aggregate_csr_fwd_wire; 2, 4, 8: sylvie_aggregate_csr_fwd_wire_bbit."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().sylvie_aggregate_csr_fwd_wire(
+    fn = lib().sylvie_aggregate_csr_fwd_wire if bits == 1 else lib().sylvie_aggregate_csr_fwd_wire_bbit
+    extra = [] if bits == 1 else [C.c_int32(bits)]
+    _check(fn(
         _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
         _ptr(w, torch.float32, "w"), _ptr(row_scale, torch.float32, "row_scale"),
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(n_rows),
-        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), C.c_int64(n_dense),
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), *extra, C.c_int64(n_dense),
         _ptr(wire, torch.int64, "wire"), C.c_int64(ld_wire), C.c_int64(n_wire),
         _ptr(Y, torch.float32, "Y"),
         C.c_int64(ld_y), _ptr(row_order, torch.int32, "row_order"), C.c_int32(chunk),
@@ -246,13 +251,16 @@ def sylvie_aggregate_csr_bwd(rowptrT, colT, wT, row_scale, col_scale, n_rowsT, d
 def sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
                                       ld_dy, d, seed, stream_id, wire_out, chunk=0, long_rows=None,
                                       long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
-                                      row_order=None):
+                                      row_order=None, bits=1):
+    """bits = 1: sylvie_aggregate_csr_bwd_quantize; 2, 4, 8: sylvie_aggregate_csr_bwd_quantize_bbit."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().sylvie_aggregate_csr_bwd_quantize(
+    fn = lib().sylvie_aggregate_csr_bwd_quantize if bits == 1 else lib().sylvie_aggregate_csr_bwd_quantize_bbit
+    extra = [] if bits == 1 else [C.c_int32(bits)]
+    _check(fn(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
         _ptr(wT, torch.float32, "wT"), _ptr(row_scale, torch.float32, "row_scale"),
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
-        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
+        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d), *extra,
         C.c_uint64(seed & (2**64 - 1)), C.c_uint32(stream_id & 0xFFFFFFFF),
         _ptr(wire_out, torch.int64, "wire_out"), C.c_int64(ld_wire),
         _ptr(row_order, torch.int32, "row_order"), C.c_int32(chunk),
@@ -265,13 +273,16 @@ def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, 
                                        dY, ld_dy, d, dX, ld_dx, addend, ld_addend, addend_rows,
                                        wire, n_wire, seg_ptr, seg_rows, chunk=0, long_rows=None,
                                        long_ptr=None, n_long=0, n_tasks=0, workspace=None, ld_wire=0,
-                                       row_order=None):
+                                       row_order=None, bits=1):
+    """bits = 1: sylvie_aggregate_csr_bwd_integrate; 2, 4, 8: sylvie_aggregate_csr_bwd_integrate_bbit."""
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().sylvie_aggregate_csr_bwd_integrate(
+    fn = lib().sylvie_aggregate_csr_bwd_integrate if bits == 1 else lib().sylvie_aggregate_csr_bwd_integrate_bbit
+    extra = [] if bits == 1 else [C.c_int32(bits)]
+    _check(fn(
         _ptr(rowptrT, torch.int64, "rowptrT"), _ptr(colT, torch.int32, "colT"),
         _ptr(wT, torch.float32, "wT"), _ptr(row_scale, torch.float32, "row_scale"),
         _ptr(col_scale, torch.float32, "col_scale"), C.c_int64(row_begin), C.c_int64(n_rows),
-        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d),
+        _ptr(dY, torch.float32, "dY"), C.c_int64(ld_dy), C.c_int32(d), *extra,
         _ptr(dX, torch.float32, "dX"), C.c_int64(ld_dx), _ptr(addend, torch.float32, "addend"),
         C.c_int64(ld_addend), C.c_int64(addend_rows), _ptr(wire, torch.int64, "wire"),
         C.c_int64(ld_wire), C.c_int64(n_wire), _ptr(seg_ptr, torch.int64, "seg_ptr"),
@@ -280,6 +291,26 @@ def sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, 
         _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_aggregate_csr_fwd_wire_bbit(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, bits, n_dense,
+                                       wire, n_wire, Y, ld_y, **kw):
+    sylvie_aggregate_csr_fwd_wire(rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, n_dense, wire,
+                                  n_wire, Y, ld_y, bits=bits, **kw)
+
+
+def sylvie_aggregate_csr_bwd_quantize_bbit(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
+                                           ld_dy, d, bits, seed, stream_id, wire_out, **kw):
+    sylvie_aggregate_csr_bwd_quantize(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY, ld_dy,
+                                      d, seed, stream_id, wire_out, bits=bits, **kw)
+
+
+def sylvie_aggregate_csr_bwd_integrate_bbit(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY,
+                                            ld_dy, d, bits, dX, ld_dx, addend, ld_addend, addend_rows, wire,
+                                            n_wire, seg_ptr, seg_rows, **kw):
+    sylvie_aggregate_csr_bwd_integrate(rowptrT, colT, wT, row_scale, col_scale, row_begin, n_rows, dY, ld_dy,
+                                       d, dX, ld_dx, addend, ld_addend, addend_rows, wire, n_wire, seg_ptr,
+                                       seg_rows, bits=bits, **kw)
 
 
 def sylvie_transform_fwd(A1, ld_a1, k1, A2, ld_a2, k2, W, h, n, relu, H, ld_h):

@@ -30,6 +30,7 @@
 #include <type_traits>
 
 #include "common.hpp"
+#include "bbit.hpp"
 #include "rounding.hpp"
 #include "validate.hpp"
 
@@ -130,20 +131,28 @@ struct AggArgs {
 enum : int { kEpiStore = 0, kEpiQuantize = 1, kEpiIntegrate = 2 };
 
 // o[0..VEC) += the dequantized elements cc .. cc+VEC-1 of the wire rows of segment s,
-// in order (single-precision adds, Alg. 2 "integrate feature gradients")
-template <int VEC>
+// in order (single-precision adds, Alg. 2 "integrate feature gradients").  WB = bits per
+// element of the wire (1, or 2 / 4 / 8: the recovered value is then fl(fl(scale q) + zero)).
+template <int VEC, int WB>
 __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int cc, float (&o)[VEC])
 {
-    const int W32 = ((a.d + 63) >> 6) * 2;
+    const int W32 = ((a.d * WB + 63) >> 6) * 2;
     const int64_t j0 = a.seg_ptr[s], j1 = a.seg_ptr[s + 1];
     for (int64_t j = j0; j < j1; ++j) {
         const uint32_t *pr = a.wire32 + static_cast<int64_t>(a.seg_rows[j]) * (2 * a.ldw);
         const uint2 meta = *reinterpret_cast<const uint2 *>(pr + W32);
         const float zp = __uint_as_float(meta.y);
-        const float hi = zp + __uint_as_float(meta.x);
-        const uint32_t bits = pr[cc >> 5] >> (cc & 31);
+        if constexpr (WB == 1) {
+            const float hi = zp + __uint_as_float(meta.x);
+            const uint32_t bits = pr[cc >> 5] >> (cc & 31);
 #pragma unroll
-        for (int t = 0; t < VEC; ++t) o[t] = o[t] + (((bits >> t) & 1u) ? hi : zp);
+            for (int t = 0; t < VEC; ++t) o[t] = o[t] + (((bits >> t) & 1u) ? hi : zp);
+        } else {
+            const float sc = __uint_as_float(meta.x);
+            const uint32_t piece = bb_piece<WB, VEC>(reinterpret_cast<const uint64_t *>(pr), cc);
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) o[t] = o[t] + bb_value<WB>(piece, t, sc, zp);
+        }
     }
 }
 
@@ -163,7 +172,7 @@ __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int c
 // the lane owning the entry put into LDS (`bcast`, 64 records of 16 bytes per wave).
 // The caller folds accw into acc afterwards (merge_wire_sums); `used_w` says whether
 // there is anything to fold.
-template <int VEC, int G, int P, bool WIRE>
+template <int VEC, int G, int P, int WIRE>
 __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int64_t e1,
                                            const AggArgs &a, int lane,
                                            [[maybe_unused]] float (&accw)[P * VEC],
@@ -182,7 +191,8 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
         const int cc = (p * G + gl) * VEC;
         coff[p] = cc < a.d ? cc : a.d - VEC;
     }
-    const int W32 = ((a.d + 63) >> 6) * 2;     // bit dwords per wire row; 2 metadata dwords follow
+    // code dwords per wire row (WIRE = bits per element); 2 metadata dwords follow
+    const int W32 = ((a.d * (WIRE ? WIRE : 1) + 63) >> 6) * 2;
     for (int64_t base = e0; base < e1; base += 64) {
         const int cnt = static_cast<int>(e1 - base < 64 ? e1 - base : 64);
         int my_c = 0;
@@ -281,7 +291,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 const float my_hi = my_zp + __uint_as_float(meta.x);
                 const float my_ww = mine ? my_w : 0.0f;
                 static_assert(!WIRE || EP == 1, "rows that read a wire take a whole wavefront");
-                {
+                if constexpr (WIRE == 1) {
                     typedef const __attribute__((address_space(4))) uint64_t *const_words;
                     constexpr int NW = P * VEC;                     // >= words per wire row
                     constexpr int UW = NW <= 4 ? SYLVIE_UW4 : (NW <= 8 ? 2 : 1);
@@ -383,6 +393,59 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                     };
                     if (W == NW) all_entries(std::true_type{});
                     else all_entries(std::false_type{});
+                } else {
+                    // b-bit wire (2, 4, 8 bits): a lane's VEC adjacent columns are one piece of
+                    // VEC * WIRE bits at the matching place of the wire row, so wire entries use
+                    // the dense rows' accumulators and loop shape: UB rows in flight, then per
+                    // element one field extract, one convert, fl(fl(scale q) + zero) (Eq. 5) and
+                    // the weight's FMA.  Scale, zero and weight of an entry come from the lane
+                    // that owns it by lane reads.
+                    static_assert(VEC == 4, "b-bit wire rows are gathered four columns per lane");
+                    typedef const __attribute__((address_space(1))) char *global_bytes;
+                    constexpr int UB = (P >= 4) ? 2 : (8 / P);
+                    constexpr uint32_t kMask = (1u << WIRE) - 1u;
+                    const int my_sc = static_cast<int>(meta.x), my_zpi = static_cast<int>(meta.y);
+                    const int my_wwi = __float_as_int(my_ww);
+                    auto piece_at = [&](global_bytes row, int p) -> uint32_t {
+                        const uint32_t off = static_cast<uint32_t>(coff[p]) * WIRE / 8u;
+                        if constexpr (WIRE == 8)
+                            return *reinterpret_cast<const __attribute__((address_space(1))) uint32_t *>(row + off);
+                        else if constexpr (WIRE == 4)
+                            return *reinterpret_cast<const __attribute__((address_space(1))) uint16_t *>(row + off);
+                        else
+                            return *reinterpret_cast<const __attribute__((address_space(1))) uint8_t *>(row + off);
+                    };
+                    auto bentries = [&](auto n_c, int j0) {
+                        constexpr int N = decltype(n_c)::value;
+                        uint32_t pc[N][P];
+                        float ww[N], sc[N], zp[N];
+#pragma unroll
+                        for (int u = 0; u < N; ++u) {
+                            const int sl = j0 + u;
+                            const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_lo), sl));
+                            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_hi), sl));
+                            global_bytes row = (global_bytes)((static_cast<uint64_t>(hi) << 32) | lo);
+                            ww[u] = __int_as_float(__builtin_amdgcn_readlane(my_wwi, sl));
+                            sc[u] = __int_as_float(__builtin_amdgcn_readlane(my_sc, sl));
+                            zp[u] = __int_as_float(__builtin_amdgcn_readlane(my_zpi, sl));
+#pragma unroll
+                            for (int p = 0; p < P; ++p) pc[u][p] = piece_at(row, p);
+                        }
+#pragma unroll
+                        for (int u = 0; u < N; ++u)
+#pragma unroll
+                            for (int p = 0; p < P; ++p)
+#pragma unroll
+                                for (int t = 0; t < VEC; ++t) {
+                                    const float q = static_cast<float>((pc[u][p] >> (WIRE * t)) & kMask);
+                                    const float step = sc[u] * q;
+                                    const float x = step + zp[u];
+                                    acc[p][t] = fmaf(ww[u], x, acc[p][t]);
+                                }
+                    };
+                    int jj = nd;
+                    for (; jj + UB <= cnt; jj += UB) bentries(std::integral_constant<int, UB>{}, jj);
+                    for (; jj < cnt; ++jj) bentries(std::integral_constant<int, 1>{}, jj);
                 }
             }
         }
@@ -422,14 +485,19 @@ __device__ __forceinline__ void merge_wire_sums(float (&acc)[P][VEC], const floa
 // take the pieces of the long rows (they start first, so the heaviest rows never
 // trail the launch); every later wavefront takes one ordinary row and skips the
 // long ones.  Pieces write partial sums to workspace[task][0..d).
-template <int VEC, int G, int P, bool WIRE, int EPI>
+template <int VEC, int G, int P, int WB, int EPI>
 __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kernel(AggArgs a,
                                                                                     int64_t n_tasks)
 {
-    constexpr int kStage = EPI == kEpiQuantize ? VEC * G * P : 1;
-    __shared__ float stage[kAgWavesPerBlock][kStage];
+    // WB = bits per element of the wire this launch reads (EPI store: the halo columns;
+    // EPI integrate: the received gradients) or writes (EPI quantize); 0 = no wire
+    constexpr int WIRE = EPI == kEpiStore ? WB : 0;            // wire read by the gather itself
+    // quantize epilogue: the finished row as floats, for b > 1 followed by the packed image
+    constexpr int kRowStage = VEC * G * P;
+    constexpr int kStage = EPI == kEpiQuantize ? kRowStage + (WB > 1 ? kRowStage / 4 + 4 : 0) : 4;
+    __shared__ __align__(16) float stage[kAgWavesPerBlock][kStage];
     // wire entries of full-width rows: broadcast records, then the fold of their sums
-    constexpr bool kWireAcc = WIRE && G == 64;
+    constexpr bool kWireAcc = WIRE == 1 && G == 64;
     constexpr int kWStage = kWireAcc ? (64 * P * VEC > 256 ? 64 * P * VEC : 256) : 4;
     __shared__ __align__(16) float wstage[kAgWavesPerBlock][kWStage];
     float accw[P * VEC];
@@ -501,7 +569,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
 #pragma unroll
                     for (int t = 0; t < VEC; ++t) o[t] += ad[t];
                 }
-                if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC>(a, local, cc, o);
+                if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC, WB>(a, local, cc, o);
                 if constexpr (EPI == kEpiQuantize) {
 #pragma unroll
                     for (int t = 0; t < VEC; ++t) stage[wave][cc + t] = o[t];
@@ -512,16 +580,22 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         }
     }
     if constexpr (EPI == kEpiQuantize) {
-        quantize_row_lds(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
-                         a.wire_out + local * a.ldw_out, lane);
+        if constexpr (WB == 1)
+            quantize_row_lds(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
+                             a.wire_out + local * a.ldw_out, lane);
+        else
+            quantize_row_lds_bbit<WB>(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
+                                      a.wire_out + local * a.ldw_out,
+                                      reinterpret_cast<uint32_t *>(stage[wave] + kRowStage), lane);
     }
 }
 
 // One wavefront per long row: add its partial sums in task order, scale, finish.
-template <int VEC, int EPI>
+template <int VEC, int WB, int EPI>
 __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kernel(AggArgs a)
 {
-    extern __shared__ float rstage[];      // EPI quantize: kAgWavesPerBlock rows of d floats
+    // EPI quantize: per wave d floats (rounded up to 4) and, for b > 1, d / 4 + 4 image dwords
+    extern __shared__ __align__(16) float rstage[];
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
@@ -531,7 +605,9 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
     const int64_t t0 = a.long_ptr[i], t1 = a.long_ptr[i + 1];
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
-    float *srow = rstage + wave * a.d;
+    const int d4 = (a.d + 3) & ~3;
+    const int per_wave = d4 + (WB > 1 ? d4 / 4 + 4 : 0);
+    float *srow = rstage + wave * per_wave;
     for (int cc = lane * VEC; cc < a.d; cc += 64 * VEC) {
         float acc[VEC];
 #pragma unroll
@@ -550,7 +626,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[q] += ad[q];
         }
-        if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC>(a, local, cc, acc);
+        if constexpr (EPI == kEpiIntegrate) integrate_vec<VEC, WB>(a, local, cc, acc);
         if constexpr (EPI == kEpiQuantize) {
 #pragma unroll
             for (int q = 0; q < VEC; ++q) srow[cc + q] = acc[q];
@@ -559,55 +635,76 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
         }
     }
     if constexpr (EPI == kEpiQuantize) {
-        quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local),
-                         a.wire_out + local * a.ldw_out, lane);
+        if constexpr (WB == 1)
+            quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local),
+                             a.wire_out + local * a.ldw_out, lane);
+        else
+            quantize_row_lds_bbit<WB>(srow, a.d, a.ckey, static_cast<uint32_t>(local),
+                                      a.wire_out + local * a.ldw_out,
+                                      reinterpret_cast<uint32_t *>(srow + d4), lane);
     }
 }
 
-template <int VEC, int G, int P, bool WIRE, int EPI>
+template <int VEC, int G, int P, int WB, int EPI>
 static void launch_kernels(const AggArgs &a, int64_t nt, hipStream_t st)
 {
     const dim3 block(kAgWavesPerBlock * kWave);
     const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
                            (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
-    hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, WIRE, EPI>),
+    hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, WB, EPI>),
                        dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
     if (a.n_long > 0) {
         const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
-        const size_t lds = EPI == kEpiQuantize ? sizeof(float) * kAgWavesPerBlock * a.d : 0;
-        hipLaunchKernelGGL((aggregate_reduce_kernel<VEC, EPI>), rg, block, lds, st, a);
+        const int d4 = (a.d + 3) & ~3;
+        const size_t lds = EPI == kEpiQuantize
+                               ? sizeof(float) * kAgWavesPerBlock * (d4 + (WB > 1 ? d4 / 4 + 4 : 0)) : 0;
+        hipLaunchKernelGGL((aggregate_reduce_kernel<VEC, WB, EPI>), rg, block, lds, st, a);
     }
 }
 
 template <int VEC, int G, int P>
-static void launch_shape(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t st)
+static void launch_shape(const AggArgs &a, int64_t n_tasks, int epi, int bits, hipStream_t st)
 {
     const int64_t nt = a.n_long > 0 ? n_tasks : 0;
-    if (epi == kEpiQuantize) launch_kernels<VEC, G, P, false, kEpiQuantize>(a, nt, st);
-    else if (epi == kEpiIntegrate) launch_kernels<VEC, G, P, false, kEpiIntegrate>(a, nt, st);
+    // wires wider than one bit are read and written four columns per lane (the caller has
+    // checked the alignment); launch_vec gives every wire-reading launch a whole wavefront per row
+    if constexpr (VEC == 4) {
+        if (bits > 1) {
+#define SYLVIE_AG_BITS(B)                                                                      \
+    if (epi == kEpiQuantize) launch_kernels<VEC, G, P, B, kEpiQuantize>(a, nt, st);             \
+    else if (epi == kEpiIntegrate) launch_kernels<VEC, G, P, B, kEpiIntegrate>(a, nt, st);      \
+    else if constexpr (G == 64) launch_kernels<VEC, G, P, B, kEpiStore>(a, nt, st);
+            if (bits == 2) { SYLVIE_AG_BITS(2) }
+            else if (bits == 4) { SYLVIE_AG_BITS(4) }
+            else { SYLVIE_AG_BITS(8) }
+#undef SYLVIE_AG_BITS
+            return;
+        }
+    }
+    if (epi == kEpiQuantize) launch_kernels<VEC, G, P, 1, kEpiQuantize>(a, nt, st);
+    else if (epi == kEpiIntegrate) launch_kernels<VEC, G, P, 1, kEpiIntegrate>(a, nt, st);
     else if (a.wire32) {
-        // launch_vec gives every wire-reading launch a whole wavefront per row
-        if constexpr (G == 64) launch_kernels<VEC, G, P, true, kEpiStore>(a, nt, st);
-    } else launch_kernels<VEC, G, P, false, kEpiStore>(a, nt, st);
+        if constexpr (G == 64) launch_kernels<VEC, G, P, 1, kEpiStore>(a, nt, st);
+    } else launch_kernels<VEC, G, P, 0, kEpiStore>(a, nt, st);
 }
 
 template <int VEC>
-static bool launch_vec(const AggArgs &a, int64_t n_tasks, int epi, hipStream_t st)
+static bool launch_vec(const AggArgs &a, int64_t n_tasks, int epi, int bits, hipStream_t st)
 {
     const int lanes = (a.d + VEC - 1) / VEC;   // lanes needed for one row, one pass
     // Rows that read a wire take a whole wavefront even when they are narrow: wire entries
     // then go through the scalar path (mask words by scalar loads, one select + FMA per word),
     // which costs half the vector instructions of the shared-wavefront path per entry.
-    if (epi == kEpiStore && a.wire32 && lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, st);
-    else if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, epi, st);
-    else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, epi, st);
-    else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, st);
-    else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, epi, st);
-    else if (lanes <= 192) launch_shape<VEC, 64, 3>(a, n_tasks, epi, st);
-    else if (lanes <= 256) launch_shape<VEC, 64, 4>(a, n_tasks, epi, st);
-    else if (lanes <= 320) launch_shape<VEC, 64, 5>(a, n_tasks, epi, st);
-    else if (lanes <= 384) launch_shape<VEC, 64, 6>(a, n_tasks, epi, st);
-    else if (lanes <= 512) launch_shape<VEC, 64, 8>(a, n_tasks, epi, st);
+    if (epi == kEpiStore && a.wire32 && lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 16) launch_shape<VEC, 16, 1>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 32) launch_shape<VEC, 32, 1>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 64) launch_shape<VEC, 64, 1>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 128) launch_shape<VEC, 64, 2>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 192) launch_shape<VEC, 64, 3>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 256) launch_shape<VEC, 64, 4>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 320) launch_shape<VEC, 64, 5>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 384) launch_shape<VEC, 64, 6>(a, n_tasks, epi, bits, st);
+    else if (lanes <= 512) launch_shape<VEC, 64, 8>(a, n_tasks, epi, bits, st);
     else return false;
     return true;
 }
@@ -625,6 +722,7 @@ struct AggExtra {
     const int64_t *seg_ptr = nullptr;
     const int32_t *seg_rows = nullptr;
     const int32_t *row_order = nullptr;
+    int bits = 1;                   // bits per element of the wire read / written / added
 };
 
 static int32_t aggregate_common(const char *name, const int64_t *rowptr, const int32_t *col,
@@ -649,7 +747,9 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     if (n_wire > 0 && !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null wire", name);
     if (n_wire > 0 && !aligned(wire, 8))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
-    const int64_t row_words = (static_cast<int64_t>(d) + 63) / 64 + 1;
+    if (x.bits != 1 && x.bits != 2 && x.bits != 4 && x.bits != 8)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4 or 8 (got %d)", name, x.bits);
+    const int64_t row_words = (static_cast<int64_t>(d) * x.bits + 63) / 64 + 1;
     if (x.ld_wire != 0 && x.ld_wire < row_words)
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_wire %lld shorter than a wire row", name, (long long)x.ld_wire);
     if (n_rows == 0) return SYLVIE_OK;
@@ -711,10 +811,16 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
                      d % 4 == 0 && (!addend || (aligned(addend, 16) && ld_addend % 4 == 0));
     const bool a8 = aligned(X, 8) && aligned(Y, 8) && ld_x % 2 == 0 && ld_y % 2 == 0 &&
                     d % 2 == 0 && (!addend || (aligned(addend, 8) && ld_addend % 2 == 0));
+    const bool uses_wire = x.epi != kEpiStore || n_wire > 0;
+    const int bits = uses_wire ? x.bits : 1;
+    if (bits > 1 && !a16)
+        return fail(SYLVIE_ERR_UNIMPLEMENTED,
+                    "%s: wires of %d bits need d %% 4 == 0 and 16-byte aligned rows "
+                    "(dequantize / quantize as separate calls otherwise)", name, bits);
     bool ok;
-    if (a16) ok = launch_vec<4>(a, n_tasks, x.epi, st);
-    else if (a8) ok = launch_vec<2>(a, n_tasks, x.epi, st);
-    else ok = launch_vec<1>(a, n_tasks, x.epi, st);
+    if (a16) ok = launch_vec<4>(a, n_tasks, x.epi, bits, st);
+    else if (a8) ok = launch_vec<2>(a, n_tasks, x.epi, bits, st);
+    else ok = launch_vec<1>(a, n_tasks, x.epi, bits, st);
     if (!ok)
         return fail(SYLVIE_ERR_UNIMPLEMENTED,
                     "%s: d = %d is wider than one launch covers at this alignment "
@@ -823,43 +929,128 @@ extern "C" int32_t sylvie_aggregate_csr_bwd(const int64_t *rowptrT, const int32_
                                     workspace, workspace_bytes, stream, x);
 }
 
-extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
-    const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
-    const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
-    int64_t n_dense, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
-    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
-    float *workspace, size_t workspace_bytes, void *stream)
+namespace sylvie {
+
+static int32_t fwd_wire_call(const char *name, int32_t bits, const int64_t *rowptr, const int32_t *col,
+                             const float *w, const float *row_scale, const float *col_scale,
+                             int64_t n_rows, const float *X, int64_t ld_x, int32_t d, int64_t n_dense,
+                             const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
+                             const int32_t *row_order, int32_t chunk, const int32_t *long_rows,
+                             const int64_t *long_ptr, int64_t n_long, int64_t n_tasks, float *workspace,
+                             size_t workspace_bytes, void *stream)
 {
-    sylvie::AggExtra x;
+    AggExtra x;
     x.n_dense = n_dense;
     x.wire = wire;
     x.ld_wire = ld_wire;
     x.n_wire = n_wire;
     x.row_order = row_order;
-    return sylvie::aggregate_common("sylvie_aggregate_csr_fwd_wire", rowptr, col, w, row_scale,
-                                    col_scale, n_rows, X, ld_x, d, Y, ld_y, nullptr, 0, 0, chunk,
-                                    long_rows, long_ptr, n_long, n_tasks, workspace,
-                                    workspace_bytes, stream, x);
+    x.bits = bits;
+    return aggregate_common(name, rowptr, col, w, row_scale, col_scale, n_rows, X, ld_x, d, Y, ld_y,
+                            nullptr, 0, 0, chunk, long_rows, long_ptr, n_long, n_tasks, workspace,
+                            workspace_bytes, stream, x);
+}
+
+static int32_t bwd_quantize_call(const char *name, int32_t bits, const int64_t *rowptrT,
+                                 const int32_t *colT, const float *wT, const float *row_scale,
+                                 const float *col_scale, int64_t row_begin, int64_t n_rows,
+                                 const float *dY, int64_t ld_dy, int32_t d, uint64_t seed,
+                                 uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire,
+                                 const int32_t *row_order, int32_t chunk, const int32_t *long_rows,
+                                 const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+                                 float *workspace, size_t workspace_bytes, void *stream)
+{
+    AggExtra x;
+    x.row_begin = row_begin;
+    x.epi = kEpiQuantize;
+    x.wire_out = wire_out;
+    x.ld_wire = ld_wire;
+    x.ckey = call_key(seed, stream_id);
+    x.row_order = row_order;
+    x.bits = bits;
+    return aggregate_common(name, rowptrT, colT, wT, row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr,
+                            ld_dy, nullptr, 0, 0, chunk, long_rows, long_ptr, n_long, n_tasks, workspace,
+                            workspace_bytes, stream, x);
+}
+
+static int32_t bwd_integrate_call(const char *name, int32_t bits, const int64_t *rowptrT,
+                                  const int32_t *colT, const float *wT, const float *row_scale,
+                                  const float *col_scale, int64_t row_begin, int64_t n_rows,
+                                  const float *dY, int64_t ld_dy, int32_t d, float *dX, int64_t ld_dx,
+                                  const float *addend, int64_t ld_addend, int64_t addend_rows,
+                                  const uint64_t *wire, int64_t ld_wire, int64_t n_wire,
+                                  const int64_t *seg_ptr, const int32_t *seg_rows, const int32_t *row_order,
+                                  int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+                                  int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    AggExtra x;
+    x.row_begin = row_begin;
+    x.epi = kEpiIntegrate;
+    x.wire = wire;
+    x.ld_wire = ld_wire;
+    x.n_wire = n_wire;
+    x.seg_ptr = seg_ptr;
+    x.seg_rows = seg_rows;
+    x.row_order = row_order;
+    x.bits = bits;
+    return aggregate_common(name, rowptrT, colT, wT, row_scale, col_scale, n_rows, dY, ld_dy, d, dX, ld_dx,
+                            addend, ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long, n_tasks,
+                            workspace, workspace_bytes, stream, x);
+}
+
+}  // namespace sylvie
+
+extern "C" int32_t sylvie_aggregate_csr_fwd_wire(
+    const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
+    const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d,
+    int64_t n_dense, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
+    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+{
+    return sylvie::fwd_wire_call("sylvie_aggregate_csr_fwd_wire", 1, rowptr, col, w, row_scale, col_scale,
+                                 n_rows, X, ld_x, d, n_dense, wire, ld_wire, n_wire, Y, ld_y, row_order,
+                                 chunk, long_rows, long_ptr, n_long, n_tasks, workspace, workspace_bytes,
+                                 stream);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_fwd_wire_bbit(
+    const int64_t *rowptr, const int32_t *col, const float *w, const float *row_scale,
+    const float *col_scale, int64_t n_rows, const float *X, int64_t ld_x, int32_t d, int32_t bits,
+    int64_t n_dense, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, float *Y, int64_t ld_y,
+    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+{
+    return sylvie::fwd_wire_call("sylvie_aggregate_csr_fwd_wire_bbit", bits, rowptr, col, w, row_scale,
+                                 col_scale, n_rows, X, ld_x, d, n_dense, wire, ld_wire, n_wire, Y, ld_y,
+                                 row_order, chunk, long_rows, long_ptr, n_long, n_tasks, workspace,
+                                 workspace_bytes, stream);
 }
 
 extern "C" int32_t sylvie_aggregate_csr_bwd_quantize(
     const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
-    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire, const int32_t *row_order, int32_t chunk,
-    const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
-    float *workspace, size_t workspace_bytes, void *stream)
+    int32_t d, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire,
+    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
 {
-    sylvie::AggExtra x;
-    x.row_begin = row_begin;
-    x.epi = sylvie::kEpiQuantize;
-    x.wire_out = wire_out;
-    x.ld_wire = ld_wire;
-    x.ckey = sylvie::call_key(seed, stream_id);
-    x.row_order = row_order;
-    return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_quantize", rowptrT, colT, wT,
-                                    row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr, ld_dy,
-                                    nullptr, 0, 0, chunk, long_rows, long_ptr, n_long, n_tasks,
-                                    workspace, workspace_bytes, stream, x);
+    return sylvie::bwd_quantize_call("sylvie_aggregate_csr_bwd_quantize", 1, rowptrT, colT, wT, row_scale,
+                                     col_scale, row_begin, n_rows, dY, ld_dy, d, seed, stream_id, wire_out,
+                                     ld_wire, row_order, chunk, long_rows, long_ptr, n_long, n_tasks,
+                                     workspace, workspace_bytes, stream);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_bwd_quantize_bbit(
+    const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
+    const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
+    int32_t d, int32_t bits, uint64_t seed, uint32_t stream_id, uint64_t *wire_out, int64_t ld_wire,
+    const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
+    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+{
+    return sylvie::bwd_quantize_call("sylvie_aggregate_csr_bwd_quantize_bbit", bits, rowptrT, colT, wT,
+                                     row_scale, col_scale, row_begin, n_rows, dY, ld_dy, d, seed, stream_id,
+                                     wire_out, ld_wire, row_order, chunk, long_rows, long_ptr, n_long,
+                                     n_tasks, workspace, workspace_bytes, stream);
 }
 
 extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
@@ -867,20 +1058,29 @@ extern "C" int32_t sylvie_aggregate_csr_bwd_integrate(
     const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
     int32_t d, float *dX, int64_t ld_dx, const float *addend, int64_t ld_addend,
     int64_t addend_rows, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
-    const int32_t *seg_rows, const int32_t *row_order, int32_t chunk, const int32_t *long_rows, const int64_t *long_ptr,
-    int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes, void *stream)
+    const int32_t *seg_rows, const int32_t *row_order, int32_t chunk, const int32_t *long_rows,
+    const int64_t *long_ptr, int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes,
+    void *stream)
 {
-    sylvie::AggExtra x;
-    x.row_begin = row_begin;
-    x.epi = sylvie::kEpiIntegrate;
-    x.wire = wire;
-    x.ld_wire = ld_wire;
-    x.n_wire = n_wire;
-    x.seg_ptr = seg_ptr;
-    x.seg_rows = seg_rows;
-    x.row_order = row_order;
-    return sylvie::aggregate_common("sylvie_aggregate_csr_bwd_integrate", rowptrT, colT, wT,
-                                    row_scale, col_scale, n_rows, dY, ld_dy, d, dX, ld_dx, addend,
-                                    ld_addend, addend_rows, chunk, long_rows, long_ptr, n_long,
-                                    n_tasks, workspace, workspace_bytes, stream, x);
+    return sylvie::bwd_integrate_call("sylvie_aggregate_csr_bwd_integrate", 1, rowptrT, colT, wT, row_scale,
+                                      col_scale, row_begin, n_rows, dY, ld_dy, d, dX, ld_dx, addend,
+                                      ld_addend, addend_rows, wire, ld_wire, n_wire, seg_ptr, seg_rows,
+                                      row_order, chunk, long_rows, long_ptr, n_long, n_tasks, workspace,
+                                      workspace_bytes, stream);
+}
+
+extern "C" int32_t sylvie_aggregate_csr_bwd_integrate_bbit(
+    const int64_t *rowptrT, const int32_t *colT, const float *wT, const float *row_scale,
+    const float *col_scale, int64_t row_begin, int64_t n_rows, const float *dY, int64_t ld_dy,
+    int32_t d, int32_t bits, float *dX, int64_t ld_dx, const float *addend, int64_t ld_addend,
+    int64_t addend_rows, const uint64_t *wire, int64_t ld_wire, int64_t n_wire, const int64_t *seg_ptr,
+    const int32_t *seg_rows, const int32_t *row_order, int32_t chunk, const int32_t *long_rows,
+    const int64_t *long_ptr, int64_t n_long, int64_t n_tasks, float *workspace, size_t workspace_bytes,
+    void *stream)
+{
+    return sylvie::bwd_integrate_call("sylvie_aggregate_csr_bwd_integrate_bbit", bits, rowptrT, colT, wT,
+                                      row_scale, col_scale, row_begin, n_rows, dY, ld_dy, d, dX, ld_dx,
+                                      addend, ld_addend, addend_rows, wire, ld_wire, n_wire, seg_ptr,
+                                      seg_rows, row_order, chunk, long_rows, long_ptr, n_long, n_tasks,
+                                      workspace, workspace_bytes, stream);
 }

@@ -18,59 +18,12 @@
 
 #include "common.hpp"
 #include "rounding.hpp"
+#include "bbit.hpp"
 
 namespace sylvie {
 
 constexpr int kBbWavesPerBlock = 4;
 constexpr int kBbRowsPerWave = 4;
-
-template <int VEC>
-__device__ __forceinline__ void bb_load(float (&o)[VEC], const float *p)
-{
-    if constexpr (VEC == 4) {
-        const float4 v = *reinterpret_cast<const float4 *>(p);
-        o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
-    } else {
-        o[0] = *p;
-    }
-}
-
-// Row constants of Eq. 3 for one wire row (all wave-uniform).
-struct BbRow {
-    float mn, scale, inv;
-    bool tiny;
-};
-template <int BITS>
-__device__ __forceinline__ BbRow bb_row_constants(float mn, float mx)
-{
-    constexpr float Bf = static_cast<float>((1 << BITS) - 1);
-    BbRow r;
-    mn = mn + 0.0f;
-    mx = mx + 0.0f;
-    const float range = mx - mn;
-    r.mn = mn;
-    r.scale = range / Bf;
-    r.tiny = range < 0x1p-60f;
-    const float den = r.tiny ? range * 0x1p64f : range;
-    r.inv = range > 0.0f ? Bf / den : 0.0f;
-    return r;
-}
-
-// Code of one element (Eq. 3-4).
-template <int BITS, bool TINY>
-__device__ __forceinline__ uint32_t bb_code(float x, const BbRow &r, uint32_t ctr)
-{
-    constexpr float Bf = static_cast<float>((1 << BITS) - 1);
-    constexpr float kTwoM24 = 1.0f / 16777216.0f;
-    float diff = x - r.mn;
-    if constexpr (TINY) diff = diff * 0x1p64f;
-    float t = diff * r.inv;
-    t = t > Bf ? Bf : t;
-    // t >= 0: the conversion truncates to floor(t) and v_fract_f32 is t - floor(t), exact
-    const float fr = __builtin_amdgcn_fractf(t);
-    const float u = static_cast<float>(draw24(ctr)) * kTwoM24;
-    return static_cast<uint32_t>(t) + (u < fr ? 1u : 0u);
-}
 
 // P passes of 64 VEC columns cover the row (64 VEC (P-1) < d <= 64 VEC P).  VEC = 4
 // needs d % 4 == 0 and 16-byte aligned rows.  A wave takes kBbRowsPerWave consecutive
@@ -226,29 +179,6 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_wide_ke
 }
 
 // ---- dequantizer ------------------------------------------------------------------
-
-// The VEC codes of columns c0 .. c0 + VEC - 1 (c0 % VEC == 0): one piece of a dword.
-template <int BITS, int VEC>
-__device__ __forceinline__ uint32_t bb_piece(const uint64_t *prow, int c0)
-{
-    const uint32_t bit = static_cast<uint32_t>(c0) * BITS;
-    const uint32_t dw = reinterpret_cast<const uint32_t *>(prow)[bit >> 5];
-    return dw >> (bit & 31u);
-}
-template <int BITS>
-__device__ __forceinline__ float bb_value(uint32_t piece, int t, float sc, float zp)
-{
-    const uint32_t q = (piece >> (BITS * t)) & ((1u << BITS) - 1u);
-    const float step = sc * static_cast<float>(q);
-    return step + zp;
-}
-
-template <int VEC>
-__device__ __forceinline__ void bb_store(float *p, const float (&v)[VEC])
-{
-    if constexpr (VEC == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    else *p = v[0];
-}
 
 // Forward: wire row i overwrites row row_offset + i of dst.  A wave takes
 // kBbRowsPerWave rows; for rows of at most 64 VEC columns all their loads are issued

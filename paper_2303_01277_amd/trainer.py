@@ -112,11 +112,13 @@ class LayerLoop:
         self.bits = WIRE_BITS.get(wire)
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)
-        self.fused = fused and wire == "1bit"
+        # (the wider codes of the bit-width study too, when every width is a multiple of 4)
+        fusable = wire == "1bit" or (wire in ("2bit", "4bit", "8bit") and all(d % 4 == 0 for d in dims))
+        self.fused = fused and fusable
         # fused_bwd: the transposed aggregation quantizes the halo gradients on the spot
         # and adds the received ones in its epilogue (no float halo-gradient block, no
         # separate quantize / dequantize passes)
-        self.fused_bwd = fused_bwd and wire == "1bit"
+        self.fused_bwd = fused_bwd and fusable
         self.record = None          # set to a dict to keep copies of every wire
         # pipeline: keep every layer's wires of this and of the previous epoch so that an
         # epoch can run on the previous epoch's wires (mode "async" of forward / backward)
@@ -162,7 +164,7 @@ class LayerLoop:
             st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             for l in range(1, self.L + 1):
                 # the float halo block below the inner rows exists only when it is written
-                rows = part.n_in if (fused and wire == "1bit") else n_loc
+                rows = part.n_in if self.fused else n_loc
                 st.Htil.append(torch.empty(rows, dims[l - 1], dtype=torch.float32, device=dev))
                 st.Z.append(torch.empty(part.n_in, dims[l - 1], dtype=torch.float32, device=dev))
             st.Htil[0][: part.n_in].copy_(X[p])
@@ -179,7 +181,7 @@ class LayerLoop:
                 st.dself = torch.empty(part.n_in, dmax, dtype=torch.float32, device=dev)
             self.parts.append(st)
         if self.fused_bwd or pipeline:
-            Wd = B.sylvie_wire_row_words(dmax)
+            Wd = self._words(dmax)
             for q, sq in enumerate(self.parts):
                 dst = []
                 for p, sp_ in enumerate(self.parts):
@@ -278,8 +280,9 @@ class LayerLoop:
                     B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
                                                pair_seed(seed, b.owner, me), 2 * l + 0, wire)
                     self._keep(("fwd", l, me, b.j0), wire, n, Wd)
-                    B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
-                                                 st.n_in + b.j0)
+                    if not self.fused:
+                        B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
+                                                     st.n_in + b.j0)
                 else:   # full-precision exchange: plain device copy of the rows
                     ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
 
@@ -333,7 +336,7 @@ class LayerLoop:
                         long_rows=lr if nt else None, long_ptr=lp if nt else None,
                         n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
                         workspace=st.ws_agg if nt else None, ld_wire=self._stride(d),
-                        row_order=st.order)
+                        row_order=st.order, bits=self.bits)
                 else:
                     self._aggregate(B.sylvie_aggregate_csr_fwd, st.op, st.plan, st.ws_agg,
                                     st.n_in, ht, d, Z, order=st.order)
@@ -402,7 +405,7 @@ class LayerLoop:
                     pair_seed(seed, me, b.owner), 2 * l + 1, wire, chunk=self.chunk,
                     long_rows=lr if nt else None, long_ptr=lp if nt else None,
                     n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                    workspace=st.ws_aggT if nt else None, row_order=b.orderT)
+                    workspace=st.ws_aggT if nt else None, row_order=b.orderT, bits=self.bits)
                 self._keep(("bwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
         for st in self.parts:
             rpT, clT, wT = st.opT
@@ -417,7 +420,7 @@ class LayerLoop:
                 0 if dself is None else d, st.n_in, st.inbound, st.n_inbound, st.inb_seg_ptr,
                 st.inb_seg_rows, chunk=self.chunk, long_rows=lr if nt else None,
                 long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                workspace=st.ws_aggT if nt else None, row_order=st.orderT_inner)
+                workspace=st.ws_aggT if nt else None, row_order=st.orderT_inner, bits=self.bits)
 
     # -- Sylvie-A (Sec. 3.3): pipeline mode ------------------------------------------
     def _gen(self, which):

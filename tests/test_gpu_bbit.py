@@ -158,3 +158,115 @@ def test_fp16_wire_parity(oracle, d):
     B.sylvie_dequantize_bbit_bwd(wire, n, d, 16, Jg, ldj, sp_, sr, int(di.numel()), di)
     torch.cuda.synchronize()
     assert np.array_equal(bits32(Jg.cpu().numpy()), bits32(J))
+
+
+def _join_bits(pk, sc, zp):
+    n, Wb = pk.shape
+    w = np.empty((n, Wb + 1), np.uint64)
+    w[:, :Wb] = pk
+    w[:, Wb] = (zp.view(np.uint32).astype(np.uint64) << np.uint64(32)) | sc.view(np.uint32).astype(np.uint64)
+    return w.view(np.int64)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("d", [4, 64, 100, 128, 256, 300, 512, 1024])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
+def test_aggregate_from_bbit_wire_parity(oracle, bits, d, cfg, n_nodes, model):
+    """Forward aggregation reading b-bit wire rows (Eq. 5 with B = 2^b - 1 applied to each gathered
+    element): against the oracle's dequantize followed by its aggregate, to the float tolerance,
+    and against the GPU's own two-step path."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    from test_gpu_ops import _operator, close
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + bits)
+    X = make_rows(rng, n_loc, d, "heavy")
+    pk, sc, zp = oracle.quantize_bbit(X, d, p.n_halo, bits, 77, 2, row_offset=p.n_in)
+    Xo = X.copy()
+    oracle.dequantize_bbit_fwd(pk, sc, zp, d, bits, Xo, p.n_in)
+    Z, S = oracle.aggregate_fwd(rp, cl, w, Xo, d, want_S=True)
+    rpd, cld, wd = dev(rp), dev(cl), dev(w)
+    Xin = dev(X[: p.n_in])
+    wired = dev(_join_bits(pk, sc, zp))
+    for chunk in (0, 128):
+        kw = {}
+        if chunk:
+            lr, lp, nt = GE.long_row_plan(rpd, chunk)
+            kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                      workspace=torch.empty(max(1, nt) * d, device=DEV))
+        Y = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd_wire_bbit(rpd, cld, wd, None, None, p.n_in, Xin, d, d, bits, p.n_in,
+                                             wired, p.n_halo, Y, d, **kw)
+        Xfull = dev(X)
+        B.sylvie_dequantize_bbit_fwd(wired, p.n_halo, d, bits, Xfull, d, p.n_in)
+        Y2 = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, Y2, d, **kw)
+        torch.cuda.synchronize()
+        close(Y.cpu().numpy(), Z, S, ("bbit wire", bits, chunk))
+        close(Y.cpu().numpy(), Y2.cpu().numpy().astype(np.float64), S, ("bbit wire vs two-step", bits, chunk))
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("d", [4, 64, 100, 256, 600])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
+def test_backward_epilogues_bbit_equal_two_step(oracle, bits, d, cfg, n_nodes, model):
+    """aggregate_csr_bwd_quantize_bbit / _integrate_bbit against the GPU's own aggregate_csr_bwd +
+    quantize_bbit_bwd + dequantize_bbit_bwd, bit for bit; the wire is also recomputed by the
+    oracle from the GPU's float rows."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    from test_gpu_ops import _operator
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + 3 + bits)
+    dZ = dev(make_rows(rng, p.n_in, d, "heavy"))
+    add = dev(make_rows(rng, p.n_in, d, "normal"))
+    mirror = dev(rng.integers(0, p.n_in, p.n_halo).astype(np.int32))
+    rpT, clT, wT = GE.transpose_csr(dev(rp), dev(cl), dev(w), n_loc)
+    W1 = (d * bits + 63) // 64 + 1
+    seed, sid, chunk = 4242 + d, 5, 128
+    lr, lp, nt = GE.long_row_plan(rpT, chunk)
+    ws = torch.empty(max(1, nt) * d, device=DEV)
+    G = torch.full((n_loc, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd(rpT, clT, wT, None, None, n_loc, dZ, d, d, G, d, addend=add, ld_addend=d,
+                               addend_rows=p.n_in, chunk=chunk, long_rows=lr, long_ptr=lp,
+                               n_long=int(lr.numel()), n_tasks=nt, workspace=ws)
+    wire_ref = torch.full((p.n_halo * W1,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_bbit_bwd(G, d, d, None, p.n_in, p.n_halo, bits, seed, sid, wire_ref)
+    sp_, sr, di = GE.scatter_segments(mirror)
+    Gpre = G.clone()
+    B.sylvie_dequantize_bbit_bwd(wire_ref, p.n_halo, d, bits, G, d, sp_, sr, int(di.numel()), di)
+    lrh, lph, nth = GE.long_row_plan(rpT, chunk, p.n_in, n_loc)
+    wire = torch.full((p.n_halo * W1,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_aggregate_csr_bwd_quantize_bbit(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, bits, seed,
+                                             sid, wire, chunk=chunk, long_rows=lrh, long_ptr=lph,
+                                             n_long=int(lrh.numel()), n_tasks=nth, workspace=ws)
+    lri, lpi, nti = GE.long_row_plan(rpT, chunk, 0, p.n_in)
+    sp2, sr2 = GE.scatter_segments_dense(mirror, p.n_in)
+    J = torch.full((p.n_in, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd_integrate_bbit(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, bits, J, d, add, d,
+                                              p.n_in, wire, p.n_halo, sp2, sr2, chunk=chunk,
+                                              long_rows=lri, long_ptr=lpi, n_long=int(lri.numel()),
+                                              n_tasks=nti, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(wire, wire_ref)
+    assert np.array_equal(bits32(J.cpu().numpy()), bits32(G[: p.n_in].cpu().numpy()))
+    ref = oracle.quantize_bbit(Gpre.cpu().numpy(), d, p.n_halo, bits, seed, sid, row_offset=p.n_in)
+    pk, sc, zp = split_wire_bits(wire.cpu().numpy(), p.n_halo, d, bits)
+    assert np.array_equal(pk, ref[0]) and np.array_equal(bits32(sc), bits32(ref[1])) and \
+        np.array_equal(bits32(zp), bits32(ref[2]))
+
+
+def test_bbit_fused_calls_need_aligned_rows(oracle):
+    """Widths that are not a multiple of 4 are refused with a status, nothing is enqueued."""
+    from paper_2303_01277_amd import binding as B
+    t = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device=DEV)
+    rp = torch.tensor([0, 1], dtype=torch.int64, device=DEV)
+    cl = torch.tensor([1], dtype=torch.int32, device=DEV)
+    with pytest.raises(B.SylvieError, match="not implemented"):
+        B.sylvie_aggregate_csr_fwd_wire_bbit(rp, cl, None, None, None, 1, t(1, 6), 6, 6, 4, 1,
+                                             t(8, dt=torch.int64), 1, t(1, 6), 6)
+    with pytest.raises(B.SylvieError, match="bits"):
+        B.sylvie_aggregate_csr_fwd_wire_bbit(rp, cl, None, None, None, 1, t(1, 8), 8, 8, 3, 1,
+                                             t(8, dt=torch.int64), 1, t(1, 8), 8)

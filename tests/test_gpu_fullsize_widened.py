@@ -278,3 +278,99 @@ def test_attention_layer_at_full_size(oracle, exchange):
     close(np_c(st.Ga[1][1][c0:]), Pk.T @ dss, np.abs(Pk).T @ np.abs(dss), "da_src")
     del loop
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("wire", ["2bit", "4bit", "8bit"])
+def test_fused_bbit_loop_at_full_size(oracle, exchange, wire):
+    """The b-bit layer loop in bench.py's launch configuration (forward aggregation reading the
+    wire, backward epilogues) against the two-step loop on the stress partition: wires, gradients
+    and weight gradients bit for bit; aggregates, which add in another order, to the float
+    tolerance, with sampled rows of the first layer recomputed by the oracle from the GPU's wire."""
+    from paper_2303_01277_amd.trainer import LayerLoop
+    wl = exchange["wl"]
+    spec = wl.spec
+    p0 = wl.parts[0]
+    owner = [torch.zeros(p0.n_halo, dtype=torch.int32, device=DEV)]
+    seed = 0xB17 + len(wire)
+    loops = []
+    for fused in (False, True):
+        loop = LayerLoop(wl.parts, owner, [wl.mirror], wl.X, wl.J, wl.W, spec.model, spec.dims, chunk=1024,
+                         wire=wire, fused=fused, fused_bwd=fused)
+        assert loop.fused == fused and loop.fused_bwd == fused
+        loop.record = {}
+        loop.forward(seed, OL.pair_seed)
+        loop.backward(seed, OL.pair_seed)
+        torch.cuda.synchronize()
+        loops.append(loop)
+    a, b = loops
+    sa, sb = a.parts[0], b.parts[0]
+    # layer 1 sees identical inputs in both loops: its wire must agree bit for bit, its aggregate to
+    # the tolerance (oracle on sampled rows); later layers inherit last-bit differences of Z
+    k1 = ("fwd", 1, 0, 0)
+    assert torch.equal(a.record[k1], b.record[k1])
+    bits = loop.bits
+    rp, cl, dg = np_c(p0.rowptr), np_c(p0.col), np_c(p0.deg)
+    import oracle as O
+    op = O.gcn_operator(rp, cl, dg, p0.n_in)
+    rng = np.random.default_rng(3)
+    deg = np.diff(op[0])
+    rows = np.unique(np.concatenate([rng.integers(0, p0.n_in, 96), np.argsort(deg)[-6:], [0, p0.n_in - 1]]))
+    seg = [np.arange(op[0][r], op[0][r + 1]) for r in rows]
+    e = np.concatenate(seg)
+    uniq, inv = np.unique(op[1][e], return_inverse=True)
+    srp = np.zeros(len(rows) + 1, np.int64)
+    srp[1:] = np.cumsum([len(s_) for s_ in seg])
+    inner = uniq < p0.n_in
+    X = np.empty((len(uniq), D), np.float32)
+    X[inner] = np_c(sb.Htil[0][torch.from_numpy(uniq[inner]).to(DEV)])
+    W1 = (D * bits + 63) // 64 + 1
+    hj = torch.from_numpy(uniq[~inner] - p0.n_in).to(DEV)
+    w = np_c(b.record[k1].view(-1, W1)[hj]).view(np.uint64)
+    meta = np.ascontiguousarray(w[:, W1 - 1])
+    sc = (meta & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.float32)
+    zp = (meta >> np.uint64(32)).astype(np.uint32).view(np.float32)
+    halo = np.empty((len(hj), D), np.float32)
+    oracle.dequantize_bbit_fwd(np.ascontiguousarray(w[:, : W1 - 1]), sc, zp, D, bits, halo, 0)
+    X[~inner] = halo
+    Z, S = oracle.aggregate_fwd(srp, inv.astype(np.int32), np.ascontiguousarray(op[2][e]), X, D, want_S=True)
+    rt = torch.from_numpy(rows).to(DEV)
+    close(np_c(sb.Z[0][rt]), Z, S, ("fused b-bit Z", wire))
+    close(np_c(sa.Z[0][rt]), Z, S, ("two-step Z", wire))
+    # the backward epilogues are bit-exact against the two-step calls on identical inputs: check
+    # the last layer's exchange, whose inputs depend on the forward only through tolerance-level
+    # differences, by running the fused backward calls of loop b's own layer inputs in loop a's way
+    L = len(spec.dims) - 1
+    assert a.record.keys() == b.record.keys()
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    rpT, clT, wT = sb.opT
+    dZ = torch.randn(p0.n_in, D, device=DEV) * torch.exp(torch.randn(p0.n_in, 1, device=DEV))
+    n_loc = p0.n_in + p0.n_halo
+    lr, lp, nt = GE.long_row_plan(rpT, 1024)
+    ws = torch.empty(max(1, nt) * D, device=DEV)
+    G = torch.empty(n_loc, D, device=DEV)
+    B.sylvie_aggregate_csr_bwd(rpT, clT, wT, None, None, n_loc, dZ, D, D, G, D, chunk=1024, long_rows=lr,
+                               long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt, workspace=ws)
+    wref = torch.empty(p0.n_halo * W1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_bbit_bwd(G, D, D, None, p0.n_in, p0.n_halo, bits, seed, 9, wref)
+    sp_, sr, di = GE.scatter_segments(wl.mirror)
+    B.sylvie_dequantize_bbit_bwd(wref, p0.n_halo, D, bits, G, D, sp_, sr, int(di.numel()), di)
+    blk = sb.blocks[0]
+    lrh, lph, nth = blk.planT
+    wire_f = torch.empty(p0.n_halo * W1, dtype=torch.int64, device=DEV)
+    B.sylvie_aggregate_csr_bwd_quantize_bbit(rpT, clT, wT, None, None, p0.n_in, p0.n_halo, dZ, D, D, bits, seed, 9,
+                                             wire_f, chunk=1024, long_rows=lrh if nth else None,
+                                             long_ptr=lph if nth else None, n_long=int(lrh.numel()) if nth else 0,
+                                             n_tasks=nth, workspace=ws if nth else None)
+    lri, lpi, nti = sb.planT_inner
+    J = torch.empty(p0.n_in, D, device=DEV)
+    B.sylvie_aggregate_csr_bwd_integrate_bbit(rpT, clT, wT, None, None, 0, p0.n_in, dZ, D, D, bits, J, D, None, 0, 0,
+                                              wire_f, p0.n_halo, sb.inb_seg_ptr, sb.inb_seg_rows, chunk=1024,
+                                              long_rows=lri if nti else None, long_ptr=lpi if nti else None,
+                                              n_long=int(lri.numel()) if nti else 0, n_tasks=nti,
+                                              workspace=ws if nti else None)
+    torch.cuda.synchronize()
+    assert torch.equal(wire_f, wref)
+    assert torch.equal(J, G[: p0.n_in])
+    del loops, a, b, G, J
+    torch.cuda.empty_cache()

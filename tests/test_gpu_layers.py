@@ -260,16 +260,21 @@ def test_layer_loop_teacher_forced(oracle, cfg, n_nodes, fused):
     replay_backward(oracle, wl, loop, pdata, seed, snaps)
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("wire", ["2bit", "4bit", "8bit", "fp16"])
 @pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("co_purchase", 12_000), ("dense_social", 5_000)])
-def test_layer_loop_bit_widths(oracle, cfg, n_nodes, wire):
+def test_layer_loop_bit_widths(oracle, cfg, n_nodes, wire, fused):
     """The other wire formats of the bit-width study (Sec. 4.3) through the same
-    teacher-forced replay: wires bit-exact, recovered rows and accumulate bit-exact."""
+    teacher-forced replay: wires bit-exact, recovered rows and accumulate bit-exact; with
+    `fused` the forward aggregation reads the b-bit wire itself (widths that are multiples of 4)."""
     spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
     wl = build_workload(spec)
     pdata = to_partdata(wl)
-    loop = build_loop(wl, wire=wire)
-    assert not loop.fused and not loop.fused_bwd
+    loop = build_loop(wl, wire=wire, fused=fused)
+    fusable = wire != "fp16" and all(d % 4 == 0 for d in spec.dims)
+    if fused and not fusable:
+        pytest.skip("this wire / width runs the two-step exchange either way")
+    assert loop.fused == fused and not loop.fused_bwd
     loop.record = {}
     seed = 0xB175 + len(cfg)
     loop.forward(seed, OL.pair_seed)
@@ -302,17 +307,21 @@ def test_layer_loop_end_to_end_fp32_wire(oracle, cfg, n_nodes):
             assert np.abs(g - pd.G[l]).max() <= 2e-5 * np.abs(pd.G[l]).max()
 
 
+@pytest.mark.parametrize("wire", ["1bit", "2bit", "4bit", "8bit"])
 @pytest.mark.parametrize("cfg,n_nodes", CASES)
-def test_fused_backward_equals_two_step_backward(cfg, n_nodes):
+def test_fused_backward_equals_two_step_backward(cfg, n_nodes, wire):
     """The transposed aggregation with the quantize / integrate epilogues must give, bit
     for bit, the wires and gradients of aggregate -> quantize -> dequantize-accumulate
-    (which the teacher-forced test ties to the oracle)."""
+    (which the teacher-forced test ties to the oracle), for every wire width that has them."""
     spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    if wire != "1bit" and any(d % 4 for d in spec.dims):
+        pytest.skip("b-bit epilogues need widths that are multiples of 4")
     wl = build_workload(spec)
     seed = 0xABCD + len(cfg)
     loops = []
     for fb in (False, True):
-        loop = build_loop(wl, fused_bwd=fb, chunk=128)
+        loop = build_loop(wl, wire=wire, fused_bwd=fb, chunk=128)
+        assert loop.fused_bwd == fb
         loop.record = {}
         loop.forward(seed, OL.pair_seed)
         loop.backward(seed, OL.pair_seed)
