@@ -140,9 +140,10 @@ int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_wire, int64_
 
 /*
  * b-bit Low-bit Module (Sec. 3.2, Eq. 3-5 with B = 2^b - 1 bins; the bit-width study of
- * Sec. 4.3, which also has a half-precision point).  `bits` is 1, 2, 4 or 8 for b-bit
- * stochastic rounding, or 16 for IEEE binary16 (round to nearest even, no side channel,
- * seed ignored).  bits = 1 is exactly the 1-bit entry points above.
+ * Sec. 4.3, which also has a half-precision and a full-precision point).  `bits` is 1, 2, 4 or
+ * 8 for b-bit stochastic rounding, 16 for IEEE binary16 (round to nearest even, no side channel,
+ * seed ignored), or 32 for the vanilla exchange: the float rows themselves, unchanged (seed
+ * ignored).  bits = 1 is exactly the 1-bit entry points above.
  *
  * Arithmetic for bits in {2, 4, 8}, single precision, one operation each:
  *   mn, mx as for 1 bit;  range = mx - mn;  zero = mn;  scale = range / B;
@@ -154,7 +155,8 @@ int32_t sylvie_dequantize_1bit_bwd(const uint64_t *wire, int64_t ld_wire, int64_
  * Wire row for bits in {2, 4, 8}: uint64 [ceil(d * bits / 64) + 1]; the code of column
  * c is bits [bits * (c mod 64/bits), + bits) of word c / (64/bits), unused high codes
  * are 0; the last word is scale | zero << 32 as for 1 bit.  Wire row for bits = 16:
- * uint64 [ceil(d / 4)] holding d binary16 values in column order, zero padded.
+ * uint64 [ceil(d / 4)] holding d binary16 values in column order, zero padded; for bits = 32:
+ * uint64 [ceil(d / 2)] holding the d floats, zero padded.
  * sylvie_wire_row_words_bits returns that word count (0 for an invalid argument).
  *
  * All other arguments, row selection, destinations, ordering and error behaviour are
@@ -556,6 +558,54 @@ int32_t sylvie_graph_transpose_csr(const int64_t *rowptr, const int32_t *col, co
  * Workspace n = n. */
 int32_t sylvie_graph_scatter_segments(const int32_t *dst_row, int64_t n, int64_t n_dst, int64_t *seg_ptr,
                                       int32_t *seg_rows, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The normalised operator of a partition (Sec. 3.4: A_n = D^-1/2 (A + I) D^-1/2 restricted to
+ * the partition's inner rows; Eq. 1's aggregation weights for GCN).  rowptr / col: adjacency of
+ * the n_in inner rows over all n_cols local rows, no self loops, columns ascending; deg int32
+ * [n_cols]: degree of every local row in the WHOLE graph, self loop not counted.  Writes
+ * rowptr_out int64 [n_in + 1] (= rowptr[r] + r), col_out int32 and w_out float [nnz + n_in]:
+ * every row with its self loop (r, r) merged in column order and
+ * w = 1 / sqrt((deg_r + 1)(deg_c + 1)) evaluated in double precision, rounded once to float.
+ * Fails on a column outside [0, n_cols) or a self loop in the input.  Workspace: 256 bytes.
+ */
+int32_t sylvie_graph_gcn_operator(const int64_t *rowptr, const int32_t *col, const int32_t *deg, int64_t n_in,
+                                  int64_t n_cols, int64_t nnz, int64_t *rowptr_out, int32_t *col_out, float *w_out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* GraphSAGE mean aggregator (Sec. 2.1 / Sec. 4): w_out[e] = 1 / len(row of e), evaluated in
+ * double precision, rounded once to float.  Workspace: 256 bytes. */
+int32_t sylvie_graph_mean_weights(const int64_t *rowptr, int64_t n_rows, int64_t nnz, float *w_out, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
+ * Launch plans of the aggregation kernels (no counterpart in the paper: how this library cuts
+ * the work of Eq. 1).  All three wait for `stream`.  Workspace n = n_rows.
+ *
+ * sylvie_graph_long_row_plan: the rows of [row_begin, row_begin + n_rows) longer than `chunk`
+ * entries, ascending, as absolute row indices in long_rows int32 [<= capacity], and long_ptr
+ * int64 [n_long + 1] = prefix sum of ceil(len / chunk) over them (what the aggregation calls take);
+ * counts_host int64 [2] (host) receives n_long and n_tasks.  Fails if n_long > capacity
+ * (counts_host is valid then).  nnz / chunk + 1 is always room enough.
+ *
+ * sylvie_graph_piece_table: every row cut into pieces of at most `chunk` consecutive entries
+ * (the attention kernels' work units): row_piece int64 [n_rows + 1], piece_ptr int64
+ * [n_pieces + 1], piece_row int32 [n_pieces] as described above; n_pieces_host (host) receives
+ * the count; capacity = room in piece_row (piece_ptr has one more).  n_rows + nnz / chunk is
+ * always room enough.
+ *
+ * sylvie_graph_rows_by_length: order int32 [n_rows] = the rows of the range, longest first,
+ * ties in index order, as indices relative to row_begin: a row_order argument of the
+ * aggregation calls.
+ */
+int32_t sylvie_graph_long_row_plan(const int64_t *rowptr, int64_t row_begin, int64_t n_rows, int32_t chunk,
+                                   int32_t *long_rows, int64_t *long_ptr, int64_t capacity, int64_t *counts_host,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+int32_t sylvie_graph_piece_table(const int64_t *rowptr, int64_t n_rows, int32_t chunk, int64_t *row_piece,
+                                 int64_t *piece_ptr, int32_t *piece_row, int64_t capacity, int64_t *n_pieces_host,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+int32_t sylvie_graph_rows_by_length(const int64_t *rowptr, int64_t row_begin, int64_t n_rows, int32_t *order,
+                                    void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -65,7 +65,10 @@ def lib():
                      "sylvie_relu_fwd", "sylvie_relu_bwd",
                      "sylvie_graph_local_index", "sylvie_graph_relabel_columns",
                      "sylvie_graph_rows_in_owner", "sylvie_graph_recv_sets",
-                     "sylvie_graph_transpose_csr", "sylvie_graph_scatter_segments"):
+                     "sylvie_graph_transpose_csr", "sylvie_graph_scatter_segments",
+                     "sylvie_graph_gcn_operator", "sylvie_graph_mean_weights",
+                     "sylvie_graph_long_row_plan", "sylvie_graph_piece_table",
+                     "sylvie_graph_rows_by_length"):
             getattr(L, name).restype = C.c_int32
         _lib = L
     return _lib
@@ -487,3 +490,41 @@ def sylvie_graph_scatter_segments(dst_row, n, n_dst, seg_ptr, seg_rows, workspac
     _check(lib().sylvie_graph_scatter_segments(_ptr(dst_row, torch.int32, "dst_row"), C.c_int64(n), C.c_int64(n_dst),
                                                _ptr(seg_ptr, torch.int64, "seg_ptr"),
                                                _ptr(seg_rows, torch.int32, "seg_rows"), *_ws(workspace), _stream()))
+
+
+def sylvie_graph_gcn_operator(rowptr, col, deg, n_in, n_cols, nnz, rowptr_out, col_out, w_out, workspace):
+    _check(lib().sylvie_graph_gcn_operator(_ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"),
+                                           _ptr(deg, torch.int32, "deg"), C.c_int64(n_in), C.c_int64(n_cols),
+                                           C.c_int64(nnz), _ptr(rowptr_out, torch.int64, "rowptr_out"),
+                                           _ptr(col_out, torch.int32, "col_out"), _ptr(w_out, torch.float32, "w_out"),
+                                           *_ws(workspace), _stream()))
+
+
+def sylvie_graph_mean_weights(rowptr, n_rows, nnz, w_out, workspace):
+    _check(lib().sylvie_graph_mean_weights(_ptr(rowptr, torch.int64, "rowptr"), C.c_int64(n_rows), C.c_int64(nnz),
+                                           _ptr(w_out, torch.float32, "w_out"), *_ws(workspace), _stream()))
+
+
+def sylvie_graph_long_row_plan(rowptr, row_begin, n_rows, chunk, long_rows, long_ptr, capacity, workspace):
+    """Returns (n_long, n_tasks) as the library reported them."""
+    counts = (C.c_int64 * 2)(0, 0)
+    _check(lib().sylvie_graph_long_row_plan(_ptr(rowptr, torch.int64, "rowptr"), C.c_int64(row_begin), C.c_int64(n_rows),
+                                            C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"),
+                                            _ptr(long_ptr, torch.int64, "long_ptr"), C.c_int64(capacity), counts,
+                                            *_ws(workspace), _stream()))
+    return int(counts[0]), int(counts[1])
+
+
+def sylvie_graph_piece_table(rowptr, n_rows, chunk, row_piece, piece_ptr, piece_row, capacity, workspace):
+    """Returns the number of pieces."""
+    count = (C.c_int64 * 1)(0)
+    _check(lib().sylvie_graph_piece_table(_ptr(rowptr, torch.int64, "rowptr"), C.c_int64(n_rows), C.c_int32(chunk),
+                                          _ptr(row_piece, torch.int64, "row_piece"), _ptr(piece_ptr, torch.int64, "piece_ptr"),
+                                          _ptr(piece_row, torch.int32, "piece_row"), C.c_int64(capacity), count,
+                                          *_ws(workspace), _stream()))
+    return int(count[0])
+
+
+def sylvie_graph_rows_by_length(rowptr, row_begin, n_rows, order, workspace):
+    _check(lib().sylvie_graph_rows_by_length(_ptr(rowptr, torch.int64, "rowptr"), C.c_int64(row_begin), C.c_int64(n_rows),
+                                             _ptr(order, torch.int32, "order"), *_ws(workspace), _stream()))

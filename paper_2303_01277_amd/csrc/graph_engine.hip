@@ -408,7 +408,156 @@ __global__ __launch_bounds__(kBlock) void copy_u32_to_i32_kernel(const uint32_t 
     if (i < n) dst[i] = static_cast<int32_t>(src[i]);
 }
 
+
+// ---- operator weights and launch plans ------------------------------------------------------
+
+// One wavefront per inner row r of the adjacency (no self loops, columns ascending): writes row r
+// of D^-1/2 (A + I) D^-1/2 with the self loop merged in column order.  The weight of entry
+// (r, c) is 1 / sqrt((deg_r + 1)(deg_c + 1)) evaluated in double (multiplication, square root
+// and division are each correctly rounded) and rounded once to float.
+__global__ __launch_bounds__(kBlock) void gcn_operator_kernel(const int64_t *rowptr, const int32_t *col,
+                                                             const int32_t *deg, int64_t n_in, int64_t n_cols,
+                                                             int64_t *rowptr_out, int32_t *col_out, float *w_out,
+                                                             int32_t *status)
+{
+    const int lane = lane_id();
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + static_cast<int>(threadIdx.x) / kWave;
+    if (r > n_in) return;
+    const int64_t e0 = rowptr[r < n_in ? r : n_in];
+    if (lane == 0) rowptr_out[r] = e0 + r;
+    if (r == n_in) return;
+    const int64_t e1 = rowptr[r + 1];
+    if (e1 < e0) {
+        if (lane == 0) status[0] = 2;
+        return;
+    }
+    const double dr = static_cast<double>(deg[r]) + 1.0;
+    const int64_t o0 = e0 + r;
+    int64_t below = 0;                                   // columns < r seen so far
+    for (int64_t base = e0; base < e1; base += kWave) {
+        const int64_t e = base + lane;
+        const bool have = e < e1;
+        int64_t c = have ? static_cast<int64_t>(col[e]) : n_cols;
+        if (have && (c < 0 || c >= n_cols || c == r)) {
+            status[0] = 1;
+            c = 0;                                       // keeps every access below in range
+        }
+        const bool lt = have && c < r;
+        const uint64_t m = __ballot(lt);
+        if (have) {
+            const int64_t k = e - e0;                    // position inside the input row
+            const int64_t o = o0 + k + (lt ? 0 : 1);     // the self loop sits after the columns < r
+            col_out[o] = static_cast<int32_t>(c);
+            w_out[o] = static_cast<float>(1.0 / sqrt(dr * (static_cast<double>(deg[c]) + 1.0)));
+        }
+        below += __popcll(m);
+    }
+    if (lane == 0) {
+        col_out[o0 + below] = static_cast<int32_t>(r);
+        w_out[o0 + below] = static_cast<float>(1.0 / sqrt(dr * dr));
+    }
+}
+
+// Mean aggregator: every entry of row r weighs 1 / len(r), evaluated in double, rounded once.
+__global__ __launch_bounds__(kBlock) void mean_weights_kernel(const int64_t *rowptr, int64_t n_rows, float *w,
+                                                             int32_t *status)
+{
+    const int lane = lane_id();
+    const int64_t r = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + static_cast<int>(threadIdx.x) / kWave;
+    if (r >= n_rows) return;
+    const int64_t e0 = rowptr[r], e1 = rowptr[r + 1];
+    if (e1 < e0) {
+        if (lane == 0) status[0] = 2;
+        return;
+    }
+    const float v = static_cast<float>(1.0 / static_cast<double>(e1 - e0));
+    for (int64_t e = e0 + lane; e < e1; e += kWave) w[e] = v;
+}
+
+// item i = row row_begin + i: low half 1 if the row is longer than chunk, high half its number of
+// chunk-sized tasks (0 for a row that is not long).  One more item (zeros) closes the scan.
+__global__ __launch_bounds__(kBlock) void long_row_items_kernel(const int64_t *rowptr, int64_t row_begin, int64_t n,
+                                                               int64_t chunk, uint64_t *items, int32_t *status)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i > n) return;
+    uint64_t v = 0;
+    if (i < n) {
+        const int64_t len = rowptr[row_begin + i + 1] - rowptr[row_begin + i];
+        if (len < 0) status[0] = 2;
+        if (len > chunk) v = 1ull | (static_cast<uint64_t>((len + chunk - 1) / chunk) << 32);
+    }
+    items[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void long_row_fill_kernel(const uint64_t *items, const uint64_t *ranks, int64_t n,
+                                                              int64_t row_begin, int32_t *long_rows, int64_t *long_ptr,
+                                                              int64_t capacity)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i > n) return;
+    const uint64_t rk = ranks[i];
+    const int64_t slot = static_cast<int64_t>(rk & 0xffffffffu);
+    const bool is_long = i < n && (items[i] & 1ull);
+    if ((is_long || i == n) && slot <= capacity) {
+        if (is_long && slot < capacity) long_rows[slot] = static_cast<int32_t>(row_begin + i);
+        long_ptr[slot] = static_cast<int64_t>(rk >> 32);     // tasks before this row; the total at i == n
+    }
+}
+
+// pieces of every row: per[i] = ceil(len_i / chunk)
+__global__ __launch_bounds__(kBlock) void piece_counts_kernel(const int64_t *rowptr, int64_t n_rows, int64_t chunk,
+                                                             uint64_t *per, int32_t *status)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i > n_rows) return;
+    uint64_t v = 0;
+    if (i < n_rows) {
+        const int64_t len = rowptr[i + 1] - rowptr[i];
+        if (len < 0) status[0] = 2;
+        else v = static_cast<uint64_t>((len + chunk - 1) / chunk);
+    }
+    per[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void piece_fill_kernel(const int64_t *rowptr, const uint64_t *first, int64_t n_rows,
+                                                           int64_t chunk, int64_t *row_piece, int64_t *piece_ptr,
+                                                           int32_t *piece_row, int64_t capacity)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i > n_rows) return;
+    const int64_t k0 = static_cast<int64_t>(first[i]);
+    row_piece[i] = k0;
+    if (i == n_rows) {
+        if (k0 <= capacity) piece_ptr[k0] = rowptr[n_rows];
+        return;
+    }
+    const int64_t e0 = rowptr[i], e1 = rowptr[i + 1];
+    int64_t k = k0;
+    for (int64_t e = e0; e < e1 && k < capacity; e += chunk, ++k) {
+        piece_ptr[k] = e;
+        piece_row[k] = static_cast<int32_t>(i);
+    }
+}
+
+// keys that sort rows longest first: 2^32 - 1 - min(len, 2^32 - 1); value = row index in the range
+__global__ __launch_bounds__(kBlock) void length_keys_kernel(const int64_t *rowptr, int64_t row_begin, int64_t n,
+                                                            uint32_t *keys, uint32_t *vals, int32_t *status)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n) return;
+    int64_t len = rowptr[row_begin + i + 1] - rowptr[row_begin + i];
+    if (len < 0) {
+        status[0] = 2;
+        len = 0;
+    }
+    if (len > 0xffffffffll) len = 0xffffffffll;
+    keys[i] = 0xffffffffu - static_cast<uint32_t>(len);
+    vals[i] = static_cast<uint32_t>(i);
+}
+
 inline unsigned blocks_for(int64_t n) { return static_cast<unsigned>((n + kBlock - 1) / kBlock); }
+inline unsigned wave_blocks_for(int64_t n) { return static_cast<unsigned>((n + kWavesPerBlock - 1) / kWavesPerBlock); }
 
 // Waits for the stream and reports what the kernels' range checks found.
 int32_t finish(const char *name, int32_t *status, hipStream_t st, const char *what1, const char *what2)
@@ -604,4 +753,143 @@ extern "C" int32_t sylvie_graph_scatter_segments(const int32_t *dst_row, int64_t
     if (n > 0)
         hipLaunchKernelGGL(copy_u32_to_i32_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, st, b.vals[cur], n, seg_rows);
     return finish(name, status, st, "destination row outside [0, n_dst)", "");
+}
+
+extern "C" int32_t sylvie_graph_gcn_operator(const int64_t *rowptr, const int32_t *col, const int32_t *deg, int64_t n_in,
+                                             int64_t n_cols, int64_t nnz, int64_t *rowptr_out, int32_t *col_out,
+                                             float *w_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_graph_gcn_operator";
+    if (n_in < 0 || n_in > kMaxItems || n_cols < n_in || n_cols > kMaxItems || nnz < 0 || nnz + n_in > kMaxItems)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (!rowptr || !rowptr_out || (n_cols > 0 && !deg) || (nnz > 0 && !col) || (nnz + n_in > 0 && (!col_out || !w_out)))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!workspace || workspace_bytes < 256) return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t *status = static_cast<int32_t *>(workspace);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+    hipLaunchKernelGGL(gcn_operator_kernel, dim3(wave_blocks_for(n_in + 1)), dim3(kBlock), 0, st, rowptr, col, deg, n_in,
+                       n_cols, rowptr_out, col_out, w_out, status);
+    return finish(name, status, st, "column outside [0, n_cols) or a self loop in the adjacency",
+                  "row pointer does not ascend");
+}
+
+extern "C" int32_t sylvie_graph_mean_weights(const int64_t *rowptr, int64_t n_rows, int64_t nnz, float *w_out,
+                                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_graph_mean_weights";
+    if (n_rows < 0 || n_rows > kMaxItems || nnz < 0 || nnz > kMaxItems) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (!rowptr || (nnz > 0 && !w_out)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!workspace || workspace_bytes < 256) return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t *status = static_cast<int32_t *>(workspace);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+    if (n_rows > 0)
+        hipLaunchKernelGGL(mean_weights_kernel, dim3(wave_blocks_for(n_rows)), dim3(kBlock), 0, st, rowptr, n_rows, w_out,
+                           status);
+    return finish(name, status, st, "", "row pointer does not ascend");
+}
+
+extern "C" int32_t sylvie_graph_long_row_plan(const int64_t *rowptr, int64_t row_begin, int64_t n_rows, int32_t chunk,
+                                              int32_t *long_rows, int64_t *long_ptr, int64_t capacity,
+                                              int64_t *counts_host, void *workspace, size_t workspace_bytes,
+                                              void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_graph_long_row_plan";
+    if (row_begin < 0 || n_rows < 0 || n_rows > kMaxItems || capacity < 0)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (chunk <= 0 || chunk % 64 != 0)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: chunk must be a positive multiple of 64", name);
+    if (!rowptr || !long_ptr || !counts_host || (capacity > 0 && !long_rows))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!workspace || workspace_bytes < sylvie_graph_workspace_bytes(n_rows))
+        return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Arena a{static_cast<char *>(workspace), 0, workspace_bytes};
+    int32_t *status = a.take<int32_t>(1);
+    uint64_t *items = a.take<uint64_t>(n_rows + 1);
+    uint64_t *ranks = a.take<uint64_t>(n_rows + 1);
+    uint64_t *scratch = a.take<uint64_t>(scan_scratch_elems(n_rows + 1) + 64);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+    hipLaunchKernelGGL(long_row_items_kernel, dim3(blocks_for(n_rows + 1)), dim3(kBlock), 0, st, rowptr, row_begin, n_rows,
+                       static_cast<int64_t>(chunk), items, status);
+    exclusive_scan<uint64_t>(items, ranks, n_rows + 1, scratch, st);
+    hipLaunchKernelGGL(long_row_fill_kernel, dim3(blocks_for(n_rows + 1)), dim3(kBlock), 0, st, items, ranks, n_rows,
+                       row_begin, long_rows, long_ptr, capacity);
+    const int32_t rc = finish(name, status, st, "", "row pointer does not ascend");
+    if (rc != SYLVIE_OK) return rc;
+    uint64_t totals = 0;
+    hipError_t e = hipMemcpyAsync(&totals, ranks + n_rows, sizeof(totals), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(SYLVIE_ERR_HIP, "%s: %s", name, hipGetErrorString(e));
+    counts_host[0] = static_cast<int64_t>(totals & 0xffffffffu);
+    counts_host[1] = static_cast<int64_t>(totals >> 32);
+    if (counts_host[0] > capacity)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: %lld long rows, room for %lld", name,
+                    static_cast<long long>(counts_host[0]), static_cast<long long>(capacity));
+    return SYLVIE_OK;
+}
+
+extern "C" int32_t sylvie_graph_piece_table(const int64_t *rowptr, int64_t n_rows, int32_t chunk, int64_t *row_piece,
+                                            int64_t *piece_ptr, int32_t *piece_row, int64_t capacity,
+                                            int64_t *n_pieces_host, void *workspace, size_t workspace_bytes,
+                                            void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_graph_piece_table";
+    if (n_rows < 0 || n_rows > kMaxItems || capacity < 0 || chunk <= 0)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (!rowptr || !row_piece || !piece_ptr || !n_pieces_host || (capacity > 0 && !piece_row))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!workspace || workspace_bytes < sylvie_graph_workspace_bytes(n_rows))
+        return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Arena a{static_cast<char *>(workspace), 0, workspace_bytes};
+    int32_t *status = a.take<int32_t>(1);
+    uint64_t *per = a.take<uint64_t>(n_rows + 1);
+    uint64_t *first = a.take<uint64_t>(n_rows + 1);
+    uint64_t *scratch = a.take<uint64_t>(scan_scratch_elems(n_rows + 1) + 64);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+    hipLaunchKernelGGL(piece_counts_kernel, dim3(blocks_for(n_rows + 1)), dim3(kBlock), 0, st, rowptr, n_rows,
+                       static_cast<int64_t>(chunk), per, status);
+    exclusive_scan<uint64_t>(per, first, n_rows + 1, scratch, st);
+    hipLaunchKernelGGL(piece_fill_kernel, dim3(blocks_for(n_rows + 1)), dim3(kBlock), 0, st, rowptr, first, n_rows,
+                       static_cast<int64_t>(chunk), row_piece, piece_ptr, piece_row, capacity);
+    const int32_t rc = finish(name, status, st, "", "row pointer does not ascend");
+    if (rc != SYLVIE_OK) return rc;
+    uint64_t total = 0;
+    hipError_t e = hipMemcpyAsync(&total, first + n_rows, sizeof(total), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return fail(SYLVIE_ERR_HIP, "%s: %s", name, hipGetErrorString(e));
+    n_pieces_host[0] = static_cast<int64_t>(total);
+    if (n_pieces_host[0] > capacity)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: %lld pieces, room for %lld", name,
+                    static_cast<long long>(n_pieces_host[0]), static_cast<long long>(capacity));
+    return SYLVIE_OK;
+}
+
+extern "C" int32_t sylvie_graph_rows_by_length(const int64_t *rowptr, int64_t row_begin, int64_t n_rows,
+                                               int32_t *order, void *workspace, size_t workspace_bytes, void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_graph_rows_by_length";
+    if (row_begin < 0 || n_rows < 0 || n_rows > kMaxItems) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (!rowptr || (n_rows > 0 && !order)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    if (!workspace || workspace_bytes < sylvie_graph_workspace_bytes(n_rows))
+        return fail(SYLVIE_ERR_WORKSPACE, "%s: workspace too small", name);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Arena a{static_cast<char *>(workspace), 0, workspace_bytes};
+    int32_t *status = a.take<int32_t>(1);
+    SortBuffers b = take_sort(a, n_rows);
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
+    if (n_rows > 0)
+        hipLaunchKernelGGL(length_keys_kernel, dim3(blocks_for(n_rows)), dim3(kBlock), 0, st, rowptr, row_begin, n_rows,
+                           b.keys[0], b.vals[0], status);
+    const int cur = radix_sort_pairs(b, n_rows, 32, st);
+    if (n_rows > 0)
+        hipLaunchKernelGGL(copy_u32_to_i32_kernel, dim3(blocks_for(n_rows)), dim3(kBlock), 0, st, b.vals[cur], n_rows, order);
+    return finish(name, status, st, "", "row pointer does not ascend");
 }

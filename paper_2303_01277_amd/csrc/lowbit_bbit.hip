@@ -374,9 +374,93 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void recover_fp16_bwd_kern
     }
 }
 
+// ---- full-precision wire (the vanilla exchange the bit-width study compares with) ---------
+
+// Wire row: the d floats of the source row unchanged, one zero float of padding when d is odd
+// (rows are whole 64-bit words).  Sending is a row gather, receiving a row copy or, in the
+// backward direction, the ordered accumulate of the other wires.
+template <int VEC>
+__global__ __launch_bounds__(kBbWavesPerBlock *kWave) void copy_rows_out_kernel(
+    const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
+    int64_t row_offset, int64_t n_rows, float *__restrict__ wire)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t first = (static_cast<int64_t>(blockIdx.x) * kBbWavesPerBlock + wave) * kBbRowsPerWave;
+    const int dp = ((d + 1) >> 1) << 1;
+#pragma unroll 1
+    for (int r = 0; r < kBbRowsPerWave; ++r) {
+        const int64_t i = first + r;
+        if (i >= n_rows) break;
+        const int64_t srow = idx ? static_cast<int64_t>(uniform(idx[i])) : row_offset + i;
+        const float *row = src + srow * ld;
+        float *out = wire + i * dp;
+        for (int c0 = lane * VEC; c0 < dp; c0 += 64 * VEC) {
+            if constexpr (VEC == 4) {
+                float v[4];
+                bb_load<4>(v, row + c0);                 // d % 4 == 0: never ragged
+                bb_store<4>(out + c0, v);
+            } else {
+                out[c0] = c0 < d ? row[c0] : 0.0f;
+            }
+        }
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kBbWavesPerBlock *kWave) void copy_rows_in_kernel(
+    const float *__restrict__ wire, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
+    int64_t row_offset)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t first = (static_cast<int64_t>(blockIdx.x) * kBbWavesPerBlock + wave) * kBbRowsPerWave;
+    const int dp = ((d + 1) >> 1) << 1;
+#pragma unroll 1
+    for (int r = 0; r < kBbRowsPerWave; ++r) {
+        const int64_t i = first + r;
+        if (i >= n_rows) break;
+        for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
+            float v[VEC];
+            bb_load<VEC>(v, wire + i * dp + c0);
+            bb_store<VEC>(dst + (row_offset + i) * ld + c0, v);
+        }
+    }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kBbWavesPerBlock *kWave) void add_rows_bwd_kernel(
+    const float *__restrict__ wire, int d, float *__restrict__ dst, int64_t ld,
+    const int64_t *__restrict__ seg_ptr, const int32_t *__restrict__ seg_rows,
+    int64_t n_dst_rows, const int32_t *__restrict__ dst_ids)
+{
+    const int lane = lane_id();
+    const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * kBbWavesPerBlock + wave;
+    if (k >= n_dst_rows) return;
+    const int dp = ((d + 1) >> 1) << 1;
+    const int64_t j0 = uniform(seg_ptr[k]), j1 = uniform(seg_ptr[k + 1]);
+    if (j0 >= j1) return;
+    float *orow = dst + static_cast<int64_t>(uniform(dst_ids[k])) * ld;
+    for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
+        float acc[VEC];
+        bb_load<VEC>(acc, orow + c0);
+        for (int64_t j = j0; j < j1; ++j) {
+            float v[VEC];
+            bb_load<VEC>(v, wire + static_cast<int64_t>(uniform(seg_rows[j])) * dp + c0);
+#pragma unroll
+            for (int t = 0; t < VEC; ++t) acc[t] = acc[t] + v[t];
+        }
+        bb_store<VEC>(orow + c0, acc);
+    }
+}
+
 // ---- host side ----------------------------------------------------------------------
 
-static bool bits_ok(int32_t bits) { return bits == 1 || bits == 2 || bits == 4 || bits == 8 || bits == 16; }
+static bool bits_ok(int32_t bits)
+{
+    return bits == 1 || bits == 2 || bits == 4 || bits == 8 || bits == 16 || bits == 32;
+}
 
 template <int BITS, int VEC>
 static void launch_quantize(const float *src, int64_t ld, int d, const int32_t *idx, int64_t row_offset,
@@ -419,7 +503,7 @@ static int32_t quantize_bbit_common(const char *name, const float *src, int64_t 
                                     int32_t bits, uint64_t seed, uint32_t stream_id, uint64_t *wire,
                                     void *stream, bool fwd)
 {
-    if (!bits_ok(bits)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8 or 16 (got %d)", name, bits);
+    if (!bits_ok(bits)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8, 16 or 32 (got %d)", name, bits);
     if (bits == 1)
         return fwd ? sylvie_quantize_1bit_fwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, 0, stream)
                    : sylvie_quantize_1bit_bwd(src, ld, d, idx, row_offset, n_rows, seed, stream_id, wire, 0, stream);
@@ -444,6 +528,15 @@ static int32_t quantize_bbit_common(const char *name, const float *src, int64_t 
             hipLaunchKernelGGL(convert_fp16_kernel<4>, grid, block, 0, st, src, ld, d, idx, row_offset, n_rows, w16);
         else
             hipLaunchKernelGGL(convert_fp16_kernel<1>, grid, block, 0, st, src, ld, d, idx, row_offset, n_rows, w16);
+    } else if (bits == 32) {
+        const int64_t per_block = kBbWavesPerBlock * kBbRowsPerWave;
+        const dim3 grid(static_cast<unsigned>((n_rows + per_block - 1) / per_block));
+        const dim3 block(kBbWavesPerBlock * kWave);
+        float *w32 = reinterpret_cast<float *>(wire);
+        if (d % 4 == 0 && ld % 4 == 0 && aligned(src, 16) && aligned(wire, 16))
+            hipLaunchKernelGGL(copy_rows_out_kernel<4>, grid, block, 0, st, src, ld, d, idx, row_offset, n_rows, w32);
+        else
+            hipLaunchKernelGGL(copy_rows_out_kernel<1>, grid, block, 0, st, src, ld, d, idx, row_offset, n_rows, w32);
     } else {
         const uint32_t ckey = call_key(seed, stream_id);
         if (bits == 2) launch_quantize_bits<2>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);
@@ -457,7 +550,7 @@ static int32_t quantize_bbit_common(const char *name, const float *src, int64_t 
 static int32_t check_bb_wire(const char *name, const uint64_t *wire, int64_t n_rows, int32_t d,
                              int32_t bits, const float *dst, int64_t ld)
 {
-    if (!bits_ok(bits)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8 or 16 (got %d)", name, bits);
+    if (!bits_ok(bits)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8, 16 or 32 (got %d)", name, bits);
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31))
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: n_rows %lld out of range", name, (long long)n_rows);
     if (d < 1 || d > 65536) return fail(SYLVIE_ERR_INVALID_ARG, "%s: d %d out of range", name, d);
@@ -475,6 +568,7 @@ extern "C" size_t sylvie_wire_row_words_bits(int32_t d, int32_t bits)
 {
     if (d < 1 || !sylvie::bits_ok(bits)) return 0;
     if (bits == 16) return (static_cast<size_t>(d) + 3) / 4;
+    if (bits == 32) return (static_cast<size_t>(d) + 1) / 2;
     return (static_cast<size_t>(d) * bits + 63) / 64 + 1;
 }
 
@@ -518,7 +612,11 @@ extern "C" int32_t sylvie_dequantize_bbit_fwd(const uint64_t *wire, int64_t n_ro
     if (bits == 2) { SYLVIE_BB_DQ(2); }
     else if (bits == 4) { SYLVIE_BB_DQ(4); }
     else if (bits == 8) { SYLVIE_BB_DQ(8); }
-    else {
+    else if (bits == 32) {
+        const float *w32 = reinterpret_cast<const float *>(wire);
+        if (v4 && aligned(wire, 16)) hipLaunchKernelGGL(copy_rows_in_kernel<4>, grid, block, 0, st, w32, n_rows, d, dst, ld_dst, row_offset);
+        else hipLaunchKernelGGL(copy_rows_in_kernel<1>, grid, block, 0, st, w32, n_rows, d, dst, ld_dst, row_offset);
+    } else {
         const uint16_t *w16 = reinterpret_cast<const uint16_t *>(wire);
         if (v4) hipLaunchKernelGGL(recover_fp16_fwd_kernel<4>, grid, block, 0, st, w16, n_rows, d, dst, ld_dst, row_offset);
         else hipLaunchKernelGGL(recover_fp16_fwd_kernel<1>, grid, block, 0, st, w16, n_rows, d, dst, ld_dst, row_offset);
@@ -555,7 +653,11 @@ extern "C" int32_t sylvie_dequantize_bbit_bwd(const uint64_t *wire, int64_t n_ro
     if (bits == 2) { SYLVIE_BB_DQB(2); }
     else if (bits == 4) { SYLVIE_BB_DQB(4); }
     else if (bits == 8) { SYLVIE_BB_DQB(8); }
-    else {
+    else if (bits == 32) {
+        const float *w32 = reinterpret_cast<const float *>(wire);
+        if (v4 && aligned(wire, 16)) hipLaunchKernelGGL(add_rows_bwd_kernel<4>, grid, block, 0, st, w32, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
+        else hipLaunchKernelGGL(add_rows_bwd_kernel<1>, grid, block, 0, st, w32, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
+    } else {
         const uint16_t *w16 = reinterpret_cast<const uint16_t *>(wire);
         if (v4) hipLaunchKernelGGL(recover_fp16_bwd_kernel<4>, grid, block, 0, st, w16, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);
         else hipLaunchKernelGGL(recover_fp16_bwd_kernel<1>, grid, block, 0, st, w16, d, dst, ld_dst, seg_ptr, seg_rows, n_dst_rows, dst_ids);

@@ -3,10 +3,9 @@
 Builds, once per graph, the index structures the kernels consume: the HALO set and the
 local numbering of a partition, its receive / send sets, the normalised operator
 (Sec. 3.4), its transpose as a CSR of its own, the plan that cuts long rows into tasks,
-and the scatter segments of the backward dequantizer.  The set constructions, the
-transpose and the segments run in the library's own kernels (GPU tensors only); the
-operator weights and the small plans are tensor arithmetic on whatever device the
-inputs live on.  None of this is on the per-layer hot path.
+and the scatter segments of the backward dequantizer.  Everything runs in the library's own
+kernels (GPU tensors only); this module allocates the outputs and the workspaces and slices
+them to the counts the library reports.  None of this is on the per-layer hot path.
 """
 from __future__ import annotations
 
@@ -65,35 +64,30 @@ def recv_sets(halo_gid, owner, row_of, n_parts):
 
 
 def gcn_operator(rowptr, col, deg, n_in):
-    """Rows of D^-1/2 (A + I) D^-1/2 for the inner nodes of a partition.
+    """Rows of D^-1/2 (A + I) D^-1/2 for the inner nodes of a partition (Sec. 3.4).
 
     rowptr/col: adjacency of the inner rows over all local rows (inner + halo), no
     self loops, columns ascending.  deg[r]: degree of local row r in the whole
     graph, self loop not counted.  Returns (rowptr', col', w) with the self loop
     (r, r) merged in column order and w = 1/sqrt((deg_r + 1)(deg_c + 1)) evaluated
-    in float64, rounded once to float32.
+    in float64, rounded once to float32 (sylvie_graph_gcn_operator).
     """
     dev = rowptr.device
-    counts = rowptr[1:] - rowptr[:-1]
-    rows = torch.repeat_interleave(torch.arange(n_in, device=dev), counts)
-    self_rows = torch.arange(n_in, device=dev)
-    all_rows = torch.cat([rows, self_rows])
-    all_cols = torch.cat([col.to(torch.int64), self_rows])
-    n_cols = int(deg.numel())
-    order = torch.argsort(all_rows * n_cols + all_cols)
-    all_rows, all_cols = all_rows[order], all_cols[order]
-    new_rowptr = rowptr + torch.arange(n_in + 1, device=dev, dtype=torch.int64)
-    d1 = deg.to(torch.float64) + 1.0
-    w = (1.0 / torch.sqrt(d1[all_rows] * d1[all_cols])).to(torch.float32)
-    return new_rowptr, all_cols.to(torch.int32), w
+    nnz, n_cols = int(col.numel()), int(deg.numel())
+    rowptr_out = torch.empty(n_in + 1, dtype=torch.int64, device=dev)
+    col_out = torch.empty(max(1, nnz + n_in), dtype=torch.int32, device=dev)
+    w_out = torch.empty(max(1, nnz + n_in), dtype=torch.float32, device=dev)
+    B.sylvie_graph_gcn_operator(rowptr, col if nnz else None, deg, n_in, n_cols, nnz, rowptr_out, col_out, w_out,
+                                _workspace(1, dev))
+    return rowptr_out, col_out[: nnz + n_in], w_out[: nnz + n_in]
 
 
 def mean_operator(rowptr, col, n_in):
-    """GraphSAGE mean aggregator: every entry of row r weighs 1/len(r)."""
-    counts = rowptr[1:] - rowptr[:-1]
-    inv = (1.0 / counts.to(torch.float64)).to(torch.float32)
-    w = torch.repeat_interleave(inv, counts)
-    return rowptr, col, w
+    """GraphSAGE mean aggregator: every entry of row r weighs 1/len(r) (sylvie_graph_mean_weights)."""
+    nnz = int(col.numel())
+    w = torch.empty(max(1, nnz), dtype=torch.float32, device=rowptr.device)
+    B.sylvie_graph_mean_weights(rowptr, n_in, nnz, w, _workspace(1, rowptr.device))
+    return rowptr, col, w[:nnz]
 
 
 def transpose_csr(rowptr, col, w, n_cols, want_perm=False):
@@ -113,31 +107,36 @@ def transpose_csr(rowptr, col, w, n_cols, want_perm=False):
     return (rowptrT, colT, wT, perm) if want_perm else (rowptrT, colT, wT)
 
 
-def long_row_plan(rowptr, chunk, row_begin=0, row_end=None):
+def long_row_plan(rowptr, chunk, row_begin=0, row_end=None, nnz=None):
     """Rows longer than `chunk` entries (absolute indices, optionally only those in
-    [row_begin, row_end)) and the prefix sum of their task counts.
-    Returns (long_rows int32 [n_long], long_ptr int64 [n_long + 1], n_tasks)."""
+    [row_begin, row_end)) and the prefix sum of their task counts (sylvie_graph_long_row_plan).
+    Returns (long_rows int32 [n_long], long_ptr int64 [n_long + 1], n_tasks).  nnz: entries of
+    the row range if the caller knows them (bounds the number of long rows without a read-back)."""
     if chunk <= 0 or chunk % 64:
         raise ValueError("chunk must be a positive multiple of 64")
-    counts = rowptr[1:] - rowptr[:-1]
-    long_rows = torch.nonzero(counts > chunk).flatten()
-    if row_end is not None or row_begin:
-        hi = counts.numel() if row_end is None else row_end
-        long_rows = long_rows[(long_rows >= row_begin) & (long_rows < hi)]
-    tasks = (counts[long_rows] + chunk - 1) // chunk
-    long_ptr = torch.zeros(long_rows.numel() + 1, dtype=torch.int64, device=rowptr.device)
-    long_ptr[1:] = torch.cumsum(tasks, 0)
-    return long_rows.to(torch.int32), long_ptr, int(long_ptr[-1])
+    dev = rowptr.device
+    n = int(rowptr.numel()) - 1
+    hi = n if row_end is None else row_end
+    n_rows = hi - row_begin
+    cap = n_rows if nnz is None else min(n_rows, nnz // chunk + 1)
+    long_rows = torch.empty(max(1, cap), dtype=torch.int32, device=dev)
+    long_ptr = torch.empty(cap + 1, dtype=torch.int64, device=dev)
+    n_long, n_tasks = B.sylvie_graph_long_row_plan(rowptr, row_begin, n_rows, chunk, long_rows, long_ptr, cap,
+                                                   _workspace(n_rows, dev))
+    return long_rows[:n_long], long_ptr[: n_long + 1], n_tasks
 
 
 def rows_by_length(rowptr, row_begin=0, row_end=None):
     """Processing order of the rows [row_begin, row_end) of a CSR for the aggregation kernels:
-    longest row first, ties in index order.  Returns int32 [row_end - row_begin], a permutation
-    of [0, row_end - row_begin) (indices relative to row_begin)."""
+    longest row first, ties in index order (sylvie_graph_rows_by_length).  Returns int32
+    [row_end - row_begin], a permutation of [0, row_end - row_begin) (indices relative to row_begin)."""
+    dev = rowptr.device
     n = int(rowptr.numel()) - 1
     hi = n if row_end is None else row_end
-    counts = rowptr[row_begin + 1: hi + 1] - rowptr[row_begin: hi]
-    return torch.argsort(counts, descending=True, stable=True).to(torch.int32)
+    n_rows = hi - row_begin
+    order = torch.empty(max(1, n_rows), dtype=torch.int32, device=dev)
+    B.sylvie_graph_rows_by_length(rowptr, row_begin, n_rows, order, _workspace(n_rows, dev))
+    return order[:n_rows]
 
 
 def scatter_segments_dense(dst_row, n_dst):
@@ -169,22 +168,21 @@ def scatter_segments(dst_row, n_dst=None):
     return seg_ptr, seg_rows, dst_ids.to(torch.int32)
 
 
-def piece_table(rowptr, chunk):
+def piece_table(rowptr, chunk, nnz=None):
     """Cuts every row's entries into pieces of at most `chunk` consecutive entries (rows without
-    entries get none).  Returns (piece_ptr int64 [n_pieces + 1], piece_row int32 [n_pieces],
-    row_piece int64 [n_rows + 1])."""
+    entries get none; sylvie_graph_piece_table).  Returns (piece_ptr int64 [n_pieces + 1], piece_row
+    int32 [n_pieces], row_piece int64 [n_rows + 1]).  nnz: the number of entries, if the caller
+    knows it (otherwise it is read back from the row pointer)."""
     if chunk <= 0:
         raise ValueError("chunk must be positive")
     dev = rowptr.device
-    counts = rowptr[1:] - rowptr[:-1]
-    per_row = (counts + (chunk - 1)) // chunk
-    row_piece = torch.zeros(rowptr.numel(), dtype=torch.int64, device=dev)
-    row_piece[1:] = torch.cumsum(per_row, 0)
-    n_pieces = int(row_piece[-1])
-    piece_row = torch.repeat_interleave(torch.arange(counts.numel(), device=dev), per_row)
-    k_in_row = torch.arange(n_pieces, device=dev) - row_piece[:-1][piece_row]
-    start = rowptr[:-1][piece_row] + k_in_row * chunk
-    piece_ptr = torch.empty(n_pieces + 1, dtype=torch.int64, device=dev)
-    piece_ptr[:-1] = start
-    piece_ptr[-1] = rowptr[-1]
-    return piece_ptr, piece_row.to(torch.int32), row_piece
+    n_rows = int(rowptr.numel()) - 1
+    if nnz is None:
+        nnz = int(rowptr[-1])
+    cap = n_rows + nnz // chunk
+    row_piece = torch.empty(n_rows + 1, dtype=torch.int64, device=dev)
+    piece_ptr = torch.empty(cap + 1, dtype=torch.int64, device=dev)
+    piece_row = torch.empty(max(1, cap), dtype=torch.int32, device=dev)
+    n_pieces = B.sylvie_graph_piece_table(rowptr, n_rows, chunk, row_piece, piece_ptr, piece_row, cap,
+                                          _workspace(n_rows, dev))
+    return piece_ptr[: n_pieces + 1], piece_row[:n_pieces], row_piece

@@ -79,7 +79,7 @@ class PartState:
     ws_aggT2: Optional[torch.Tensor] = None                   # long-row workspace of the side stream
 
 
-WIRE_BITS = {"1bit": 1, "2bit": 2, "4bit": 4, "8bit": 8, "fp16": 16}
+WIRE_BITS = {"1bit": 1, "2bit": 2, "4bit": 4, "8bit": 8, "fp16": 16, "fp32": 32}
 
 
 class LayerLoop:
@@ -105,10 +105,10 @@ class LayerLoop:
         # stress partition, the chip's counters show none and the scattered row pointers cost
         # 5-28 % time; the hook stays for graphs whose own structure gives a better order.
         self.reorder = reorder
-        if wire not in WIRE_BITS and wire != "fp32":
-            raise ValueError(f"wire must be one of {sorted(WIRE_BITS)} or 'fp32'")
+        if wire not in WIRE_BITS:
+            raise ValueError(f"wire must be one of {sorted(WIRE_BITS)}")
         # bits per element on the wire: 1 = the paper's default; 2, 4, 8 and 16 (binary16)
-        # are the other points of its bit-width study (Sec. 4.3); None = float rows
+        # are the other points of its bit-width study (Sec. 4.3); 32 = float rows, unchanged
         self.bits = WIRE_BITS.get(wire)
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)
@@ -232,7 +232,7 @@ class LayerLoop:
         multiple of 16.  The rows still travel packed: the padding is never written or read.
         Other wires (wider codes, gradient wires, which are read once in order) stay packed."""
         W = self._words(d)
-        if self.bits not in (None, 1) or self.wire != "1bit" or not self.pad_wire:
+        if self.bits != 1 or not self.pad_wire:
             return W
         if W > 16:
             return (W + 15) // 16 * 16
@@ -243,7 +243,7 @@ class LayerLoop:
 
     def _words(self, d):
         """64-bit words of one wire row of width d."""
-        if self.bits in (None, 1):
+        if self.bits == 1:
             return B.sylvie_wire_row_words(d)
         return B.sylvie_wire_row_words_bits(d, self.bits)
 
@@ -275,7 +275,7 @@ class LayerLoop:
                     if not self.fused:
                         B.sylvie_dequantize_1bit_fwd(wire, n, d, ht, ht.stride(0),
                                                      st.n_in + b.j0, ld_wire=S)
-                elif self.bits:
+                else:   # wider codes, half precision, or the float rows themselves (bits = 32)
                     wire = st.wire[b.j0 * Wd:]
                     B.sylvie_quantize_bbit_fwd(src, src.stride(0), d, b.rows, 0, n, self.bits,
                                                pair_seed(seed, b.owner, me), 2 * l + 0, wire)
@@ -283,8 +283,6 @@ class LayerLoop:
                     if not self.fused:
                         B.sylvie_dequantize_bbit_fwd(wire, n, d, self.bits, ht, ht.stride(0),
                                                      st.n_in + b.j0)
-                else:   # full-precision exchange: plain device copy of the rows
-                    ht[st.n_in + b.j0: st.n_in + b.j1] = src[b.rows.long()]
 
     def _exchange_backward(self, l, d, Wd, seed, pair_seed):
         """Alg. 2, the exchange of layer l in two steps: quantize the halo block of every
@@ -303,7 +301,7 @@ class LayerLoop:
                     self._keep(("bwd", l, me, b.j0), st.wire, n, Wd)
                     B.sylvie_dequantize_1bit_bwd(st.wire, n, d, tgt, tgt.stride(0), b.seg_ptr,
                                                  b.seg_rows, int(b.dst_ids.numel()), b.dst_ids)
-                elif self.bits:
+                else:
                     B.sylvie_quantize_bbit_bwd(g, g.stride(0), d, None, st.n_in + b.j0, n,
                                                self.bits, pair_seed(seed, me, b.owner),
                                                2 * l + 1, st.wire)
@@ -311,8 +309,6 @@ class LayerLoop:
                     B.sylvie_dequantize_bbit_bwd(st.wire, n, d, self.bits, tgt, tgt.stride(0),
                                                  b.seg_ptr, b.seg_rows,
                                                  int(b.dst_ids.numel()), b.dst_ids)
-                else:
-                    tgt.index_add_(0, b.rows.long(), g[st.n_in + b.j0: st.n_in + b.j1].clone())
 
     # -- Alg. 1 ------------------------------------------------------------------
     def forward(self, seed: int, pair_seed: Callable[[int, int, int], int] = default_pair_seed,

@@ -151,31 +151,3 @@ def test_widened_entry_points_reject_bad_arguments_without_gpu(lib):
     sgd = lib.sylvie_sgd_update
     sgd.restype = i32
     assert sgd(p, p, i64(-1), C.c_float(0.1), None) == -1 and sgd(p, p, i64(0), C.c_float(0.1), None) == 0
-
-
-def test_graph_engine_host_logic(oracle):
-    """Host-side set-up arithmetic of the product against the oracle's operator and plain counts
-    (the transpose, the sets and the segments run in the library: GPU tests cover them)."""
-    import numpy as np
-    import scipy.sparse as sp
-    import torch
-    from synth import CONFIGS, build_workload, scaled
-    from paper_2303_01277_amd import graph_engine as GE
-    wl = build_workload(scaled(CONFIGS["citation"], 4000))
-    p = wl.parts[0]
-    rp, cl, w = GE.gcn_operator(p.rowptr, p.col, p.deg, p.n_in)
-    orp, ocl, ow = oracle.gcn_operator(p.rowptr.numpy(), p.col.numpy(), p.deg.numpy(), p.n_in)
-    assert np.array_equal(rp.numpy(), orp) and np.array_equal(cl.numpy(), ocl)
-    assert np.array_equal(w.numpy().view(np.uint32), ow.view(np.uint32))
-    _, _, wm = GE.mean_operator(p.rowptr, p.col, p.n_in)
-    assert np.array_equal(wm.numpy().view(np.uint32),
-                          oracle.mean_weights(p.rowptr.numpy(), p.n_in).view(np.uint32))
-    lr, lp, nt = GE.long_row_plan(rp, 64)
-    cnt = np.diff(rp.numpy())
-    assert np.array_equal(lr.numpy(), np.nonzero(cnt > 64)[0])
-    assert nt == int(np.ceil(cnt[cnt > 64] / 64).sum()) and lp[0] == 0 and lp[-1] == nt
-    pp, pr, rpc = GE.piece_table(rp, 16)
-    sizes = np.diff(pp.numpy())
-    assert sizes.min() >= 1 and sizes.max() <= 16 and pp[-1] == rp[-1]
-    assert np.array_equal(np.diff(rpc.numpy()), -(-cnt // 16))
-    assert np.array_equal(pr.numpy(), np.repeat(np.arange(cnt.size), -(-cnt // 16)))

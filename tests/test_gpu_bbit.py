@@ -270,3 +270,40 @@ def test_bbit_fused_calls_need_aligned_rows(oracle):
     with pytest.raises(B.SylvieError, match="bits"):
         B.sylvie_aggregate_csr_fwd_wire_bbit(rp, cl, None, None, None, 1, t(1, 8), 8, 8, 3, 1,
                                              t(8, dt=torch.int64), 1, t(1, 8), 8)
+
+
+@pytest.mark.parametrize("d", [1, 3, 64, 100, 255, 256, 602])
+def test_full_precision_wire(d):
+    """bits = 32, the vanilla exchange of the bit-width study: the rows themselves travel.  Sending
+    is a row gather, receiving a copy, the backward direction the ordered accumulate; checked
+    against plain indexing and numpy's unbuffered in-order add."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    rng = np.random.default_rng(d)
+    n_src, n, n_dst = 300, 517, 200
+    ld = d + (5 if d % 2 else 0)
+    x = make_rows(rng, n_src, ld, "heavy")
+    idx = rng.integers(0, n_src, n).astype(np.int32)
+    W = B.sylvie_wire_row_words_bits(d, 32)
+    assert W == (d + 1) // 2
+    wire = torch.full((n * W + 3,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_bbit_fwd(dev(x), ld, d, dev(idx), 0, n, 32, 0, 0, wire)
+    torch.cuda.synchronize()
+    gw = wire.cpu().numpy()
+    rows = gw[: n * W].view(np.float32).reshape(n, 2 * W)
+    assert np.array_equal(bits32(rows[:, :d]), bits32(x[idx][:, :d])) and (gw[n * W:] == -1).all()
+    assert not rows[:, d:].any()
+    out = torch.full((n + 7, ld), float("nan"), device=DEV)
+    B.sylvie_dequantize_bbit_fwd(wire, n, d, 32, out, ld, 5)
+    J = rng.standard_normal((n_dst, ld)).astype(np.float32)
+    Jg = dev(J)
+    dst = rng.integers(0, n_dst - 20, n).astype(np.int32)
+    dst[:30] = 11
+    sp_, sr, di = GE.scatter_segments(dev(dst))
+    B.sylvie_dequantize_bbit_bwd(wire, n, d, 32, Jg, ld, sp_, sr, int(di.numel()), di)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert np.array_equal(bits32(o[5: 5 + n, :d]), bits32(x[idx][:, :d])) and np.isnan(o[:5]).all()
+    ref = J.copy()
+    np.add.at(ref[:, :d], dst, x[idx][:, :d])
+    assert np.array_equal(bits32(Jg.cpu().numpy()), bits32(ref))

@@ -203,3 +203,55 @@ def test_partitions_rebuilt_by_the_library_match_the_input_generator(oracle):
             want = oracle.send_set(wl.parts[k].halo_gid.to(torch.int32).cpu().numpy(), owner.cpu().numpy(),
                                    row_of.cpu().numpy(), n)
             assert np.array_equal(S, want)
+
+
+@pytest.mark.parametrize("cfg,n_nodes", [("citation", 4000), ("stress", 30_000), ("co_purchase", 12_000)])
+def test_operator_weights_and_launch_plans(oracle, cfg, n_nodes):
+    """The normalised operator (Sec. 3.4) and the mean weights against the oracle bit for bit, and
+    the launch plans (long rows, pieces, longest-first order) against plain counts."""
+    from synth import CONFIGS, build_workload, scaled
+    from paper_2303_01277_amd import graph_engine as GE
+    wl = build_workload(scaled(CONFIGS[cfg], n_nodes))
+    p = wl.parts[0]
+    rpd, cld, dgd = p.rowptr.to(DEV), p.col.to(DEV), p.deg.to(DEV)
+    rp, cl, w = GE.gcn_operator(rpd, cld, dgd, p.n_in)
+    orp, ocl, ow = oracle.gcn_operator(p.rowptr.numpy(), p.col.numpy(), p.deg.numpy(), p.n_in)
+    assert np.array_equal(rp.cpu().numpy(), orp) and np.array_equal(cl.cpu().numpy(), ocl)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), ow.view(np.uint32))
+    _, _, wm = GE.mean_operator(rpd, cld, p.n_in)
+    assert np.array_equal(wm.cpu().numpy().view(np.uint32),
+                          oracle.mean_weights(p.rowptr.numpy(), p.n_in).view(np.uint32))
+    cnt = np.diff(orp)
+    for chunk in (64, 1024):
+        lr, lp, nt = GE.long_row_plan(rp, chunk)
+        assert np.array_equal(lr.cpu().numpy(), np.nonzero(cnt > chunk)[0])
+        tasks = -(-cnt[cnt > chunk] // chunk)
+        assert nt == int(tasks.sum()) and np.array_equal(lp.cpu().numpy(), np.concatenate([[0], np.cumsum(tasks)]))
+    lo, hi = p.n_in // 3, p.n_in - 5
+    lr, lp, nt = GE.long_row_plan(rp, 64, lo, hi, nnz=int(orp[hi] - orp[lo]))
+    sel = np.nonzero(cnt[lo:hi] > 64)[0] + lo
+    assert np.array_equal(lr.cpu().numpy(), sel) and nt == int((-(-cnt[sel] // 64)).sum())
+    for chunk in (16, 1000):
+        pp, pr, rpc = GE.piece_table(rp, chunk)
+        per = -(-cnt // chunk)
+        assert np.array_equal(np.diff(rpc.cpu().numpy()), per) and int(rpc[0]) == 0
+        assert np.array_equal(pr.cpu().numpy(), np.repeat(np.arange(cnt.size), per))
+        starts = np.concatenate([orp[r] + chunk * np.arange(per[r]) for r in range(cnt.size)] + [[orp[-1]]])
+        assert np.array_equal(pp.cpu().numpy(), starts)
+    for r0, r1 in ((0, p.n_in), (lo, hi)):
+        order = GE.rows_by_length(rp, r0, r1).cpu().numpy()
+        assert np.array_equal(order, np.argsort(-cnt[r0:r1], kind="stable"))
+
+
+def test_operator_rejects_bad_adjacency():
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    rp = torch.tensor([0, 2, 3], dtype=torch.int64, device=DEV)
+    deg = torch.tensor([2, 1, 1], dtype=torch.int32, device=DEV)
+    with pytest.raises(B.SylvieError, match="self loop"):
+        GE.gcn_operator(rp, torch.tensor([0, 2, 2], dtype=torch.int32, device=DEV), deg, 2)
+    with pytest.raises(B.SylvieError, match="self loop"):
+        GE.gcn_operator(rp, torch.tensor([1, 7, 2], dtype=torch.int32, device=DEV), deg, 2)
+    with pytest.raises(B.SylvieError, match="ascend"):
+        GE.gcn_operator(torch.tensor([0, 3, 2], dtype=torch.int64, device=DEV),
+                        torch.tensor([1, 2, 2], dtype=torch.int32, device=DEV), deg, 2)
