@@ -30,7 +30,8 @@ _SOURCES = {
 
 
 def library_path() -> str:
-    return _SO
+    """The built library; SYLVIE_LIBRARY names another build of it (same ABI) to load instead."""
+    return os.environ.get("SYLVIE_LIBRARY") or _SO
 
 
 def _stale() -> bool:

@@ -34,13 +34,18 @@
 #include "rounding.hpp"
 #include "validate.hpp"
 
-#ifndef SYLVIE_UW4
-#define SYLVIE_UW4 8
-#endif
 
 namespace sylvie {
 
-constexpr int kAgWavesPerBlock = 4;
+// Wavefronts per workgroup.  A workgroup keeps its slots until its last wavefront ends, and row
+// lengths vary widely, so small workgroups keep more wavefronts in flight: one per workgroup for
+// the wire-reading forward launch, whose rows walk the longest chain of dependent fetches
+// (measured on the four large workloads: -8 to -14 %), two for the others (-1 %; one is slower
+// for the backward halo launch).
+constexpr int kAgWavesPerBlock = 2;
+constexpr int kAgWavesPerBlockWire = 1;
+template <int WB, int EPI>
+constexpr int waves_per_block() { return (EPI == 0 && WB > 0) ? kAgWavesPerBlockWire : kAgWavesPerBlock; }
 
 template <int VEC>
 struct Vec;
@@ -153,6 +158,82 @@ __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int c
 #pragma unroll
             for (int t = 0; t < VEC; ++t) o[t] = o[t] + bb_value<WB>(piece, t, sc, zp);
         }
+    }
+}
+
+// N scalar loads of LW dwords each (one wire row's mask words per load) and the wait for all of
+// them, as ONE asm statement: the compiler never sees a destination register as defined before
+// its data has arrived, so it cannot copy or spill it in between; early-clobber outputs keep a
+// destination from sharing registers with an address that a later load still has to read.
+typedef const __attribute__((address_space(4))) uint64_t *const_words;
+template <int LW>
+struct SVec { typedef uint32_t type __attribute__((ext_vector_type(LW))); };
+template <int LW, int N>
+__device__ __forceinline__ void scalar_rows(typename SVec<LW>::type (&m)[N], const const_words (&p)[N])
+{
+    static_assert((LW == 8 && (N == 8 || N == 1)) || (LW == 4 && (N == 12 || N == 1)) ||
+                  (LW == 2 && (N == 16 || N == 1)), "block sizes the wire loops use");
+    if constexpr (N == 1) {
+        if constexpr (LW == 8)
+            asm volatile("s_load_dwordx8 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(m[0]) : "s"(p[0]) : "memory");
+        else if constexpr (LW == 4)
+            asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(m[0]) : "s"(p[0]) : "memory");
+        else
+            asm volatile("s_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=&s"(m[0]) : "s"(p[0]) : "memory");
+    } else if constexpr (LW == 8) {
+            asm volatile(
+                "s_load_dwordx8 %0, %8, 0x0\n\t"
+                "s_load_dwordx8 %1, %9, 0x0\n\t"
+                "s_load_dwordx8 %2, %10, 0x0\n\t"
+                "s_load_dwordx8 %3, %11, 0x0\n\t"
+                "s_load_dwordx8 %4, %12, 0x0\n\t"
+                "s_load_dwordx8 %5, %13, 0x0\n\t"
+                "s_load_dwordx8 %6, %14, 0x0\n\t"
+                "s_load_dwordx8 %7, %15, 0x0\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&s"(m[0]), "=&s"(m[1]), "=&s"(m[2]), "=&s"(m[3]), "=&s"(m[4]), "=&s"(m[5]), "=&s"(m[6]), "=&s"(m[7])
+                : "s"(p[0]), "s"(p[1]), "s"(p[2]), "s"(p[3]), "s"(p[4]), "s"(p[5]), "s"(p[6]), "s"(p[7])
+                : "memory");
+    } else if constexpr (LW == 4) {
+            asm volatile(
+                "s_load_dwordx4 %0, %12, 0x0\n\t"
+                "s_load_dwordx4 %1, %13, 0x0\n\t"
+                "s_load_dwordx4 %2, %14, 0x0\n\t"
+                "s_load_dwordx4 %3, %15, 0x0\n\t"
+                "s_load_dwordx4 %4, %16, 0x0\n\t"
+                "s_load_dwordx4 %5, %17, 0x0\n\t"
+                "s_load_dwordx4 %6, %18, 0x0\n\t"
+                "s_load_dwordx4 %7, %19, 0x0\n\t"
+                "s_load_dwordx4 %8, %20, 0x0\n\t"
+                "s_load_dwordx4 %9, %21, 0x0\n\t"
+                "s_load_dwordx4 %10, %22, 0x0\n\t"
+                "s_load_dwordx4 %11, %23, 0x0\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&s"(m[0]), "=&s"(m[1]), "=&s"(m[2]), "=&s"(m[3]), "=&s"(m[4]), "=&s"(m[5]), "=&s"(m[6]), "=&s"(m[7]), "=&s"(m[8]), "=&s"(m[9]), "=&s"(m[10]), "=&s"(m[11])
+                : "s"(p[0]), "s"(p[1]), "s"(p[2]), "s"(p[3]), "s"(p[4]), "s"(p[5]), "s"(p[6]), "s"(p[7]), "s"(p[8]), "s"(p[9]), "s"(p[10]), "s"(p[11])
+                : "memory");
+    } else {
+            asm volatile(
+                "s_load_dwordx2 %0, %16, 0x0\n\t"
+                "s_load_dwordx2 %1, %17, 0x0\n\t"
+                "s_load_dwordx2 %2, %18, 0x0\n\t"
+                "s_load_dwordx2 %3, %19, 0x0\n\t"
+                "s_load_dwordx2 %4, %20, 0x0\n\t"
+                "s_load_dwordx2 %5, %21, 0x0\n\t"
+                "s_load_dwordx2 %6, %22, 0x0\n\t"
+                "s_load_dwordx2 %7, %23, 0x0\n\t"
+                "s_load_dwordx2 %8, %24, 0x0\n\t"
+                "s_load_dwordx2 %9, %25, 0x0\n\t"
+                "s_load_dwordx2 %10, %26, 0x0\n\t"
+                "s_load_dwordx2 %11, %27, 0x0\n\t"
+                "s_load_dwordx2 %12, %28, 0x0\n\t"
+                "s_load_dwordx2 %13, %29, 0x0\n\t"
+                "s_load_dwordx2 %14, %30, 0x0\n\t"
+                "s_load_dwordx2 %15, %31, 0x0\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&s"(m[0]), "=&s"(m[1]), "=&s"(m[2]), "=&s"(m[3]), "=&s"(m[4]), "=&s"(m[5]), "=&s"(m[6]), "=&s"(m[7]), "=&s"(m[8]), "=&s"(m[9]), "=&s"(m[10]), "=&s"(m[11]), "=&s"(m[12]), "=&s"(m[13]), "=&s"(m[14]), "=&s"(m[15])
+                : "s"(p[0]), "s"(p[1]), "s"(p[2]), "s"(p[3]), "s"(p[4]), "s"(p[5]), "s"(p[6]), "s"(p[7]), "s"(p[8]), "s"(p[9]), "s"(p[10]), "s"(p[11]), "s"(p[12]), "s"(p[13]), "s"(p[14]), "s"(p[15])
+                : "memory");
     }
 }
 
@@ -292,9 +373,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 const float my_ww = mine ? my_w : 0.0f;
                 static_assert(!WIRE || EP == 1, "rows that read a wire take a whole wavefront");
                 if constexpr (WIRE == 1) {
-                    typedef const __attribute__((address_space(4))) uint64_t *const_words;
                     constexpr int NW = P * VEC;                     // >= words per wire row
-                    constexpr int UW = NW <= 4 ? SYLVIE_UW4 : (NW <= 8 ? 2 : 1);
                     const int W = W32 >> 1;
                     wave_lds_sync();    // the previous batch's records have been read
                     reinterpret_cast<float4 *>(bcast)[lane] = make_float4(my_ww, my_zp, my_hi, 0.0f);
@@ -305,67 +384,58 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                         const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_hi), slot));
                         return (const_words)((static_cast<uint64_t>(hi) << 32) | lo);
                     };
-                    // N entries starting at batch slot j0 (all valid): their mask words by
-                    // scalar loads, their records by broadcast reads, then select + FMA.
-                    // FULLW: the row has exactly NW words; otherwise the words past the last
-                    // one re-read the metadata word and feed accumulators nobody reads.
-                    auto entries = [&](auto n_c, auto full_c, int j0) {
-                        constexpr int N = decltype(n_c)::value;
-                        constexpr bool FULLW = decltype(full_c)::value;
-                        float4 rec[N];
-                        const float4 *recs = reinterpret_cast<const float4 *>(bcast) + j0;
-                        if constexpr (FULLW && NW == 4) {
-                            // the four words of each entry in one scalar load; all N loads are
-                            // issued before the first use so that N rows are in flight.  The
-                            // loads are written out because the compiler, short of scalar
-                            // registers, otherwise issues them one at a time.
-                            typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-                            u32x8 m8[N];
+                    if constexpr (NW == 4) {
+                        // Rows of up to 256 columns: 1 to 4 mask words.  One scalar load brings an
+                        // entry's words (2, 4 or 8 dwords: a row of 3 words is loaded with its
+                        // metadata word, which feeds an accumulator nobody reads), and the narrower
+                        // the row, the more entries are in flight before the one wait: the row's
+                        // dependent fetches, not bandwidth, bound these launches.
+                        auto entries = [&](auto lw_c, auto n_c, int j0) {
+                            constexpr int LW = decltype(lw_c)::value;   // dwords per load
+                            constexpr int N = decltype(n_c)::value;
+                            constexpr int WU = LW / 2;                  // words used per entry
+                            typename SVec<LW>::type m[N];
                             const_words prow[N];
+                            float4 rec[N];
+                            const float4 *recs = reinterpret_cast<const float4 *>(bcast) + j0;
 #pragma unroll
                             for (int u = 0; u < N; ++u) {
                                 prow[u] = row_of_slot(j0 + u);
                                 rec[u] = recs[u];
                             }
-                            // Issue and wait are ONE asm statement: the compiler never sees
-                            // a destination register as defined before its data has arrived,
-                            // so it cannot copy or spill it in between.  Early-clobber outputs
-                            // keep a destination from sharing registers with an address that a
-                            // later load of the block still has to read.
-                            static_assert(N == 8 || N == 1, "scalar wire loads come in blocks of 8 or singly");
-                            if constexpr (N == 8) {
-                                asm volatile(
-                                    "s_load_dwordx8 %0, %8, 0x0\n\t"
-                                    "s_load_dwordx8 %1, %9, 0x0\n\t"
-                                    "s_load_dwordx8 %2, %10, 0x0\n\t"
-                                    "s_load_dwordx8 %3, %11, 0x0\n\t"
-                                    "s_load_dwordx8 %4, %12, 0x0\n\t"
-                                    "s_load_dwordx8 %5, %13, 0x0\n\t"
-                                    "s_load_dwordx8 %6, %14, 0x0\n\t"
-                                    "s_load_dwordx8 %7, %15, 0x0\n\t"
-                                    "s_waitcnt lgkmcnt(0)"
-                                    : "=&s"(m8[0]), "=&s"(m8[1]), "=&s"(m8[2]), "=&s"(m8[3]),
-                                      "=&s"(m8[4]), "=&s"(m8[5]), "=&s"(m8[6]), "=&s"(m8[7])
-                                    : "s"(prow[0]), "s"(prow[1]), "s"(prow[2]), "s"(prow[3]),
-                                      "s"(prow[4]), "s"(prow[5]), "s"(prow[6]), "s"(prow[7])
-                                    : "memory");
-                            } else {
-                                asm volatile("s_load_dwordx8 %0, %1, 0x0\n\t"
-                                             "s_waitcnt lgkmcnt(0)"
-                                             : "=&s"(m8[0]) : "s"(prow[0]) : "memory");
-                            }
+                            scalar_rows<LW, N>(m, prow);
 #pragma unroll
                             for (int u = 0; u < N; ++u)
 #pragma unroll
-                                for (int k = 0; k < NW; ++k) {
-                                    const uint64_t mk = (static_cast<uint64_t>(m8[u][2 * k + 1]) << 32) | m8[u][2 * k];
+                                for (int k = 0; k < WU; ++k) {
+                                    const uint64_t mk = (static_cast<uint64_t>(m[u][2 * k + 1]) << 32) | m[u][2 * k];
                                     float x;
                                     asm("v_cndmask_b32_e64 %0, %1, %2, %3"
                                         : "=v"(x)
                                         : "v"(rec[u].y), "v"(rec[u].z), "s"(mk));
                                     accw[k] = fmaf(rec[u].x, x, accw[k]);
                                 }
-                        } else {
+                        };
+                        auto all_entries = [&](auto lw_c, auto n_c) {
+                            constexpr int N = decltype(n_c)::value;
+                            int jj = nd;
+                            for (; jj + N <= cnt; jj += N) entries(lw_c, n_c, jj);
+                            for (; jj < cnt; ++jj) entries(lw_c, std::integral_constant<int, 1>{}, jj);
+                        };
+                        if (W == 1) all_entries(std::integral_constant<int, 2>{}, std::integral_constant<int, 16>{});
+                        else if (W == 2) all_entries(std::integral_constant<int, 4>{}, std::integral_constant<int, 12>{});
+                        else all_entries(std::integral_constant<int, 8>{}, std::integral_constant<int, 8>{});
+                    } else {
+                        // wider rows: word by word.  FULLW: the row has exactly NW words, so the
+                        // loads have constant offsets and merge into wide ones; otherwise the
+                        // words past the row's last one re-read the metadata word and feed
+                        // accumulators nobody reads.
+                        constexpr int UW = NW <= 8 ? 2 : 1;
+                        auto entries = [&](auto n_c, auto full_c, int j0) {
+                            constexpr int N = decltype(n_c)::value;
+                            constexpr bool FULLW = decltype(full_c)::value;
+                            float4 rec[N];
+                            const float4 *recs = reinterpret_cast<const float4 *>(bcast) + j0;
                             uint64_t m[N][NW];
 #pragma unroll
                             for (int u = 0; u < N; ++u) {
@@ -384,15 +454,15 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                                         : "v"(rec[u].y), "v"(rec[u].z), "s"(m[u][k]));
                                     accw[k] = fmaf(rec[u].x, x, accw[k]);
                                 }
-                        }
-                    };
-                    auto all_entries = [&](auto full_c) {
-                        int jj = nd;
-                        for (; jj + UW <= cnt; jj += UW) entries(std::integral_constant<int, UW>{}, full_c, jj);
-                        for (; jj < cnt; ++jj) entries(std::integral_constant<int, 1>{}, full_c, jj);
-                    };
-                    if (W == NW) all_entries(std::true_type{});
-                    else all_entries(std::false_type{});
+                        };
+                        auto all_entries = [&](auto full_c) {
+                            int jj = nd;
+                            for (; jj + UW <= cnt; jj += UW) entries(std::integral_constant<int, UW>{}, full_c, jj);
+                            for (; jj < cnt; ++jj) entries(std::integral_constant<int, 1>{}, full_c, jj);
+                        };
+                        if (W == NW) all_entries(std::true_type{});
+                        else all_entries(std::false_type{});
+                    }
                 } else {
                     // b-bit wire (2, 4, 8 bits): a lane's VEC adjacent columns are one piece of
                     // VEC * WIRE bits at the matching place of the wire row, so wire entries use
@@ -481,32 +551,33 @@ __device__ __forceinline__ void merge_wire_sums(float (&acc)[P][VEC], const floa
     }
 }
 
-// One launch covers everything that gathers.  The first ceil(n_tasks/4) workgroups
+// One launch covers everything that gathers.  The first workgroups
 // take the pieces of the long rows (they start first, so the heaviest rows never
 // trail the launch); every later wavefront takes one ordinary row and skips the
 // long ones.  Pieces write partial sums to workspace[task][0..d).
 template <int VEC, int G, int P, int WB, int EPI>
-__global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kernel(AggArgs a,
-                                                                                    int64_t n_tasks)
+__global__ __launch_bounds__((waves_per_block<WB, EPI>() * kWave)) void aggregate_gather_kernel(AggArgs a,
+                                                                                              int64_t n_tasks)
 {
+    constexpr int kWPB = waves_per_block<WB, EPI>();
     // WB = bits per element of the wire this launch reads (EPI store: the halo columns;
     // EPI integrate: the received gradients) or writes (EPI quantize); 0 = no wire
     constexpr int WIRE = EPI == kEpiStore ? WB : 0;            // wire read by the gather itself
     // quantize epilogue: the finished row as floats, for b > 1 followed by the packed image
     constexpr int kRowStage = VEC * G * P;
     constexpr int kStage = EPI == kEpiQuantize ? kRowStage + (WB > 1 ? kRowStage / 4 + 4 : 0) : 4;
-    __shared__ __align__(16) float stage[kAgWavesPerBlock][kStage];
+    __shared__ __align__(16) float stage[kWPB][kStage];
     // wire entries of full-width rows: broadcast records, then the fold of their sums
     constexpr bool kWireAcc = WIRE == 1 && G == 64;
     constexpr int kWStage = kWireAcc ? (64 * P * VEC > 256 ? 64 * P * VEC : 256) : 4;
-    __shared__ __align__(16) float wstage[kAgWavesPerBlock][kWStage];
+    __shared__ __align__(16) float wstage[kWPB][kWStage];
     float accw[P * VEC];
 #pragma unroll
     for (int k = 0; k < P * VEC; ++k) accw[k] = 0.0f;
     bool used_w = false;
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
-    const int64_t task_blocks = (n_tasks + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
+    const int64_t task_blocks = (n_tasks + kWPB - 1) / kWPB;
     float acc[P][VEC];
 #pragma unroll
     for (int p = 0; p < P; ++p)
@@ -514,7 +585,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         for (int t = 0; t < VEC; ++t) acc[p][t] = 0.0f;
 
     if (static_cast<int64_t>(blockIdx.x) < task_blocks) {
-        const int64_t t = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
+        const int64_t t = static_cast<int64_t>(blockIdx.x) * kWPB + wave;
         if (t >= n_tasks) return;
         // long row that owns task t: last i with long_ptr[i] <= t
         int64_t lo = 0, hi = a.n_long;
@@ -542,7 +613,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_gather_kern
         return;
     }
 
-    const int64_t pos = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kAgWavesPerBlock + wave;
+    const int64_t pos = (static_cast<int64_t>(blockIdx.x) - task_blocks) * kWPB + wave;
     if (pos >= a.n_rows) return;
     const int64_t local = a.row_order ? static_cast<int64_t>(uniform(a.row_order[pos])) : pos;
     const int64_t v = a.row_begin + local;
@@ -648,12 +719,12 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
 template <int VEC, int G, int P, int WB, int EPI>
 static void launch_kernels(const AggArgs &a, int64_t nt, hipStream_t st)
 {
-    const dim3 block(kAgWavesPerBlock * kWave);
-    const int64_t blocks = (nt + kAgWavesPerBlock - 1) / kAgWavesPerBlock +
-                           (a.n_rows + kAgWavesPerBlock - 1) / kAgWavesPerBlock;
+    constexpr int kWPB = waves_per_block<WB, EPI>();
+    const int64_t blocks = (nt + kWPB - 1) / kWPB + (a.n_rows + kWPB - 1) / kWPB;
     hipLaunchKernelGGL((aggregate_gather_kernel<VEC, G, P, WB, EPI>),
-                       dim3(static_cast<unsigned>(blocks)), block, 0, st, a, nt);
+                       dim3(static_cast<unsigned>(blocks)), dim3(kWPB * kWave), 0, st, a, nt);
     if (a.n_long > 0) {
+        const dim3 block(kAgWavesPerBlock * kWave);
         const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
         const int d4 = (a.d + 3) & ~3;
         const size_t lds = EPI == kEpiQuantize
