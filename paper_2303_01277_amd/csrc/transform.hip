@@ -473,6 +473,28 @@ __device__ __forceinline__ void store_block(const floatx16 &acc, __amdgpu_buffer
     _Pragma("unroll") for (int j_ = 0; j_ < 2; ++j_)           \
     _Pragma("unroll") for (int r_ = 0; r_ < 16; ++r_) acc[i_][j_][r_] = 0.0f
 
+// Tile coordinates of workgroup b of a one-dimensional launch over n_major x n_minor tiles.
+// Consecutive workgroups go to the chip's 8 XCDs in turn, each with an L2 of its own, and tiles
+// that share an operand block (the column tiles of one row block; the tiles of one row slab)
+// should meet in ONE L2 shortly after each other: workgroups b and b + 8 (same XCD, consecutive
+// there) get the same `major` and consecutive `minor`.  Any n_major works (the last n_major % 8
+// majors are laid out plainly); the map is a bijection of [0, n_major n_minor).
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ void xcd_tile(uint32_t b, uint32_t n_major, uint32_t n_minor, uint32_t &major,
+                                         uint32_t &minor)
+{
+    const uint32_t group = kXcds * n_minor, full = n_major / kXcds;
+    if (b < full * group) {
+        const uint32_t g = b / group, r = b % group;
+        major = g * kXcds + r % kXcds;
+        minor = r / kXcds;
+    } else {
+        const uint32_t rem = n_major - full * kXcds, bb = b - full * group;
+        major = full * kXcds + bb % rem;
+        minor = bb / rem;
+    }
+}
+
 // H = relu?([A1|A2] W); K % BK == 0, k1 % BK == 0, h % 4 == 0.
 __global__ __launch_bounds__(kGemmThreads, 3) void transform_fwd_fast_kernel(CatA a, const float *__restrict__ Wm,
                                                                          int h, int relu,
@@ -481,8 +503,10 @@ __global__ __launch_bounds__(kGemmThreads, 3) void transform_fwd_fast_kernel(Cat
     __shared__ __align__(16) float As[2][kTileKC];
     __shared__ __align__(16) float Bs[2][kTileXC];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
-    const int n0 = blockIdx.y * BN;
+    uint32_t row_blk, col_tile;
+    xcd_tile(blockIdx.x, static_cast<uint32_t>((a.n + BM - 1) / BM), static_cast<uint32_t>((h + BN - 1) / BN), row_blk, col_tile);
+    const int64_t m0 = static_cast<int64_t>(row_blk) * BM;
+    const int n0 = static_cast<int>(col_tile) * BN;
     const int K = a.k1 + a.k2;
     const int half_m = wave >> 1, half_n = wave & 1;
     const int rows = a.n - m0 < BM ? static_cast<int>(a.n - m0) : BM;
@@ -573,9 +597,11 @@ __global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_da_fast_kernel(
     __shared__ __align__(16) float As[2][kTileKC];
     __shared__ __align__(16) float Bs[2][kTileKC];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
-    const int n0 = blockIdx.y * BN;                 // output column = row of W
     const int K = k1 + k2, h = m.h;
+    uint32_t row_blk, col_tile;
+    xcd_tile(blockIdx.x, static_cast<uint32_t>((m.n + BM - 1) / BM), static_cast<uint32_t>((K + BN - 1) / BN), row_blk, col_tile);
+    const int64_t m0 = static_cast<int64_t>(row_blk) * BM;
+    const int n0 = static_cast<int>(col_tile) * BN;       // output column = row of W
     const int half_m = wave >> 1, half_n = wave & 1;
     const int rows = m.n - m0 < BM ? static_cast<int>(m.n - m0) : BM;
     const int wrows = K - n0 < BN ? K - n0 : BN;
@@ -661,21 +687,24 @@ __global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_da_fast_kernel(
 // part[slab] = [A1|A2]^T M over one slab of rows; k1 % 128 == 0 or k2 == 0 (a tile of
 // 128 operand columns lies in one of the two matrices), widths % 4 == 0.
 __global__ __launch_bounds__(kGemmThreads, 3) void transform_bwd_g_fast_kernel(CatA a, MaskedJ m,
-                                                                           int64_t rows_per_slab,
+                                                                           int64_t rows_per_slab, int n_slabs,
                                                                            float *__restrict__ part)
 {
     __shared__ __align__(16) float As[2][kTileXC];
     __shared__ __align__(16) float Bs[2][kTileXC];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int K = a.k1 + a.k2, h = m.h;
-    const int m0 = blockIdx.x * BM;                 // row of G = column of [A1|A2]
-    const int n0 = blockIdx.y * BN;                 // column of G
-    const int64_t r_begin = static_cast<int64_t>(blockIdx.z) * rows_per_slab;
+    const uint32_t tiles_m = static_cast<uint32_t>((K + BM - 1) / BM), tiles_n = static_cast<uint32_t>((h + BN - 1) / BN);
+    uint32_t slab, tile;
+    xcd_tile(blockIdx.x, static_cast<uint32_t>(n_slabs), tiles_m * tiles_n, slab, tile);
+    const int m0 = static_cast<int>(tile % tiles_m) * BM;   // row of G = column of [A1|A2]
+    const int n0 = static_cast<int>(tile / tiles_m) * BN;   // column of G
+    const int64_t r_begin = static_cast<int64_t>(slab) * rows_per_slab;
     const int64_t r_end = r_begin + rows_per_slab < a.n ? r_begin + rows_per_slab : a.n;
     const int half_m = wave >> 1, half_n = wave & 1;
     floatx16 acc[2][2];
     SYLVIE_ZERO_ACC(acc);
-    float *out = part + static_cast<int64_t>(blockIdx.z) * K * h;
+    float *out = part + static_cast<int64_t>(slab) * K * h;
     const int nr = static_cast<int>(r_end - r_begin);      // rows of this slab (may be <= 0)
     if (nr > 0) {
         const bool first = m0 < a.k1;
@@ -817,7 +846,7 @@ extern "C" int32_t sylvie_transform_fwd(const float *A1, int64_t ld_a1, int32_t 
     const bool fast = v4 && K % BK == 0 && k1 % BK == 0 && ld_a1 < kMaxFastLd && ld_a2 < kMaxFastLd &&
                       ld_h < kMaxFastLd && static_cast<int64_t>(K) * h < (int64_t(1) << 29);
     if (fast)
-        hipLaunchKernelGGL(transform_fwd_fast_kernel, grid, dim3(kGemmThreads), 0, st, a, W, h, relu, H, ld_h);
+        hipLaunchKernelGGL(transform_fwd_fast_kernel, dim3(grid.x * grid.y), dim3(kGemmThreads), 0, st, a, W, h, relu, H, ld_h);
     else if (v4)
         hipLaunchKernelGGL(transform_fwd_kernel<4>, grid, dim3(kGemmThreads), 0, st, a, W, h, relu, H, ld_h);
     else
@@ -868,7 +897,8 @@ extern "C" int32_t sylvie_transform_bwd(const float *A1, int64_t ld_a1, int32_t 
         const int64_t ldmax = std::max(std::max(ld_a1, k2 > 0 ? ld_a2 : 0), std::max(ld_j, relu ? ld_h : 0));
         const bool fast = v4 && (k2 == 0 || k1 % BM == 0) && rps * ldmax < (int64_t(1) << 29);
         if (fast)
-            hipLaunchKernelGGL(transform_bwd_g_fast_kernel, grid, dim3(kGemmThreads), 0, st, a, m, rps, workspace);
+            hipLaunchKernelGGL(transform_bwd_g_fast_kernel, dim3(grid.x * grid.y * grid.z), dim3(kGemmThreads), 0, st, a, m,
+                               rps, slabs, workspace);
         else if (v4)
             hipLaunchKernelGGL(transform_bwd_g_kernel<4>, grid, dim3(kGemmThreads), 0, st, a, m, rps, workspace);
         else
@@ -882,7 +912,8 @@ extern "C" int32_t sylvie_transform_bwd(const float *A1, int64_t ld_a1, int32_t 
         const bool fast = v4 && h % BK == 0 && ld_j < kMaxFastLd && (!relu || ld_h < kMaxFastLd) &&
                           ld_da1 < kMaxFastLd && (k2 == 0 || ld_da2 < kMaxFastLd);
         if (fast)
-            hipLaunchKernelGGL(transform_bwd_da_fast_kernel, grid, dim3(kGemmThreads), 0, st, m, W, k1, k2, dA1, ld_da1, dA2, ld_da2);
+            hipLaunchKernelGGL(transform_bwd_da_fast_kernel, dim3(grid.x * grid.y), dim3(kGemmThreads), 0, st, m, W, k1, k2,
+                               dA1, ld_da1, dA2, ld_da2);
         else if (v4)
             hipLaunchKernelGGL(transform_bwd_da_kernel<4>, grid, dim3(kGemmThreads), 0, st, m, W, k1, k2, dA1, ld_da1, dA2, ld_da2);
         else
