@@ -73,11 +73,11 @@ __device__ __forceinline__ float bb_value(uint32_t piece, int t, float sc, float
     return step + zp;
 }
 
+// Output rows are written once and read by a later launch: streaming stores.
 template <int VEC>
 __device__ __forceinline__ void bb_store(float *p, const float (&v)[VEC])
 {
-    if constexpr (VEC == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    else *p = v[0];
+    stream_store<VEC>(p, v);
 }
 
 // Quantize one row of d floats that this wavefront holds in LDS (row[0..d), d % 4 == 0, 16-byte

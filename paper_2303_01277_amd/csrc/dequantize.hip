@@ -26,21 +26,10 @@ struct VecT<1> { using type = float; };
 template <int VEC>
 __device__ __forceinline__ void select_store(float *p, uint32_t bits, float lo, float hi)
 {
-    if constexpr (VEC == 4) {
-        float4 o;
-        o.x = (bits & 1u) ? hi : lo;
-        o.y = (bits & 2u) ? hi : lo;
-        o.z = (bits & 4u) ? hi : lo;
-        o.w = (bits & 8u) ? hi : lo;
-        *reinterpret_cast<float4 *>(p) = o;
-    } else if constexpr (VEC == 2) {
-        float2 o;
-        o.x = (bits & 1u) ? hi : lo;
-        o.y = (bits & 2u) ? hi : lo;
-        *reinterpret_cast<float2 *>(p) = o;
-    } else {
-        *p = (bits & 1u) ? hi : lo;
-    }
+    float o[VEC];
+#pragma unroll
+    for (int t = 0; t < VEC; ++t) o[t] = ((bits >> t) & 1u) ? hi : lo;
+    stream_store<VEC>(p, o);            // recovered rows are written once and read by a later launch
 }
 
 // ONEPASS: d <= 64 VEC, every lane owns at most one vector of a row.  Then the loads
@@ -141,8 +130,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
         uint64_t meta[D], word[D];
 #pragma unroll
         for (int q = 0; q < D; ++q) {
-            V accv = *reinterpret_cast<const V *>(orow[q] + c0);
-            __builtin_memcpy(acc[q], &accv, sizeof(V));
+            stream_load<VEC>(acc[q], orow[q] + c0);   // read-modify-write rows: touched once
             // an empty segment reads nothing of seg_rows (which may then have no elements at
             // all): its load goes to a location that always exists and wire row 0 stands in
             const bool some = j0[q] < j1[q];
@@ -169,9 +157,7 @@ __global__ __launch_bounds__(kDqWavesPerBlock *kWave) void dequantize_bwd_kernel
                 meta[q] = pr[W];
                 word[q] = pr[c0 >> 6];
             }
-            V accv;
-            __builtin_memcpy(&accv, acc[q], sizeof(V));
-            *reinterpret_cast<V *>(orow[q] + c0) = accv;
+            stream_store<VEC>(orow[q] + c0, acc[q]);
         }
     }
 }

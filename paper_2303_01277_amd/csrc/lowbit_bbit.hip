@@ -258,7 +258,7 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void dequantize_bbit_bwd_k
     float *orow = dst + static_cast<int64_t>(uniform(dst_ids[k])) * ld;
     for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
         float acc[VEC];
-        bb_load<VEC>(acc, orow + c0);
+        stream_load<VEC>(acc, orow + c0);      // read-modify-write row: touched once
         for (int64_t j = j0; j < j1; ++j) {
             const uint64_t *prow = wire + static_cast<int64_t>(uniform(seg_rows[j])) * (Wb + 1);
             const uint64_t meta = prow[Wb];
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void recover_fp16_bwd_kern
     float *orow = dst + static_cast<int64_t>(uniform(dst_ids[k])) * ld;
     for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
         float acc[VEC];
-        bb_load<VEC>(acc, orow + c0);
+        stream_load<VEC>(acc, orow + c0);      // read-modify-write row: touched once
         for (int64_t j = j0; j < j1; ++j) {
             float v[VEC];
             fp16_load<VEC>(v, wire + static_cast<int64_t>(uniform(seg_rows[j])) * dp + c0);
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void add_rows_bwd_kernel(
     float *orow = dst + static_cast<int64_t>(uniform(dst_ids[k])) * ld;
     for (int c0 = lane * VEC; c0 < d; c0 += 64 * VEC) {
         float acc[VEC];
-        bb_load<VEC>(acc, orow + c0);
+        stream_load<VEC>(acc, orow + c0);      // read-modify-write row: touched once
         for (int64_t j = j0; j < j1; ++j) {
             float v[VEC];
             bb_load<VEC>(v, wire + static_cast<int64_t>(uniform(seg_rows[j])) * dp + c0);
