@@ -479,18 +479,24 @@ def attention_bench(torch, B, wl, owner, rows, spec, args, forced, heads=4):
         for n in names:
             setattr(B, n, orig[n])
     nnz = sum(int(st.op[0][-1]) for st in loop.parts)
-    # gather count of the three kernels that fetch one float row slice per operator entry
-    # (index + weight or result per entry, 4 F bytes of the gathered row, the rows written)
+    # gather bytes of the calls that fetch one float row (all heads' slices) per operator entry:
+    # index, the entry's K weights or results, 4 K F bytes of the gathered row, the rows written;
+    # the aggregation is called twice per layer (forward; backward through the transposed
+    # operator, whose weights come through the 8-byte entry map)
     F = spec.dims[1] // heads
-    calls = heads * loop.L
+    h = F * heads
     n_in = sum(st.n_in for st in loop.parts)
     n_loc = sum(st.n_in + st.n_halo for st in loop.parts)
+    per_layer = {
+        "sylvie_sddmm_heads": nnz * (4 + 4 * heads + 4 * h) + n_in * 4 * h,
+        "sylvie_aggregate_csr_attention": (nnz * (4 + 4 * heads + 4 * h) + n_in * (4 * h + 8)) +
+                                          (nnz * (12 + 4 * heads + 4 * h) + n_loc * (4 * h + 8 + 8 * heads)),
+    }
     gathers = {}
-    for name, rows_out in (("sylvie_sddmm", 0), ("sylvie_aggregate_csr_fwd", n_in), ("sylvie_aggregate_csr_bwd", n_loc)):
+    for name, nbytes in per_layer.items():
         if name in acc:
-            per_call = nnz * (8 + 4 * F) + rows_out * (4 * F + 8) + (n_in * 4 * F if not rows_out else 0)
-            gbps = per_call * calls / (acc[name] * 1e-3) / 1e9
-            gathers[name] = {"gather_bytes_per_call": per_call, "gather_GBps": gbps,
+            gbps = nbytes * loop.L / (acc[name] * 1e-3) / 1e9
+            gathers[name] = {"gather_bytes_per_layer": nbytes, "gather_GBps": gbps,
                              "frac_hbm_peak": gbps / HBM_PEAK_GBS}
     return {"model": f"attention, {heads} heads, {loop.L} layers", "ms_per_step": ms,
             "gather_kernels": gathers,

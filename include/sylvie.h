@@ -492,6 +492,94 @@ int32_t sylvie_relu_bwd(const float *H, int64_t ld_h, const float *J, int64_t ld
                         float *dZ, int64_t ld_dz, void *stream);
 
 /*
+ * The same attention aggregator (GAT, Sec. 4) for `heads` = K attention heads at once.  The
+ * heads share the projection column-wise: head k owns columns [k F, (k+1) F) of P and of the
+ * attention vectors a_dst / a_src (each K F long).  Per-node arrays hold a node's K values side
+ * by side (s_dst, ds_dst: [n_rows][K]; s_src: [number of columns][K]), per-entry arrays an
+ * entry's K values (alpha, dalpha, de: [entries][K]), so an entry's column index and its
+ * node's scores are fetched once for all heads.  Per head the arithmetic and its order are
+ * those of the single-head calls above, which are these with K = 1: results agree bit for bit
+ * with K single-head calls on the head's own slices (tested).
+ *
+ * K is 1, 2, 4 or 8 (sylvie_row_dot_heads, sylvie_sddmm_heads and sylvie_scaled_column_sum_heads:
+ * any K); per-node and per-entry arrays of a K-head call must be 4 K-byte aligned
+ * (SYLVIE_ERR_BAD_ALIGNMENT otherwise).
+ *
+ *   sylvie_row_dot_heads           out[i][k] = P[i][k F .. (k+1) F) . a[k F .. (k+1) F), i < n; with a2
+ *                                  (may be NULL) also out2[i][k] with a2 for i < n2, from the same
+ *                                  pass over P (s_dst over the inner rows and s_src over all rows)
+ *   sylvie_edge_softmax_fwd_heads  alpha[e][k]; workspace sylvie_edge_softmax_heads_workspace_bytes
+ *   sylvie_sddmm_heads             out[e][k] = A_v[k F ..) . B_u[k F ..) for entry e = (v, u)
+ *   sylvie_edge_softmax_bwd_heads  de[e][k]; if ds_dst is not NULL also ds_dst[v][k] = the row sums
+ *                                  of de (what sylvie_segment_sum_heads would return, bit for bit);
+ *                                  workspace (n_pieces + n_rows) K floats, 4 K-byte aligned
+ *   sylvie_segment_sum_heads       out[v][k] = sum over the entries e of row v of vals[i_e][k],
+ *                                  i_e = e, or index[e] when `index` (int64 [entries]) is given:
+ *                                  with the pieces of the TRANSPOSED operator and the
+ *                                  transposition's entry map as index these are the column sums of
+ *                                  values left in forward entry order (ds_src from de);
+ *                                  workspace n_pieces K floats
+ *   sylvie_scaled_column_sum_heads out[c] = sum_{i < n} s[i][c / (F / K)] X[i][c], c < F (F = all
+ *                                  K heads' columns here); with s2 (may be NULL) also out2 from s2
+ *                                  over i < n2 in the same pass over X; each sum has the value and
+ *                                  bits it has alone.  Workspace: the single-head query for
+ *                                  max(n, n2) rows, twice that with s2
+ */
+int32_t sylvie_row_dot_heads(const float *P, int64_t ld_p, int64_t n, int32_t F, int32_t heads,
+                             const float *a, float *out, const float *a2, int64_t n2, float *out2,
+                             void *stream);
+size_t sylvie_edge_softmax_heads_workspace_bytes(int64_t n_pieces, int64_t n_rows, int32_t heads);
+int32_t sylvie_edge_softmax_fwd_heads(const int64_t *piece_ptr, const int32_t *piece_row,
+                                      const int64_t *row_piece, int64_t n_pieces, int64_t n_rows,
+                                      const int32_t *col, const float *s_dst, const float *s_src,
+                                      int32_t heads, float slope, float *alpha, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+int32_t sylvie_sddmm_heads(const int64_t *piece_ptr, const int32_t *piece_row, const int64_t *row_piece,
+                           int64_t n_pieces, int64_t n_rows, const int32_t *col, const float *A,
+                           int64_t ld_a, const float *B, int64_t ld_b, int32_t F, int32_t heads,
+                           float *out, void *stream);
+int32_t sylvie_edge_softmax_bwd_heads(const int64_t *piece_ptr, const int32_t *piece_row,
+                                      const int64_t *row_piece, int64_t n_pieces, int64_t n_rows,
+                                      const int32_t *col, const float *alpha, const float *dalpha,
+                                      const float *s_dst, const float *s_src, int32_t heads, float slope,
+                                      float *de, float *ds_dst, void *workspace, size_t workspace_bytes,
+                                      void *stream);
+int32_t sylvie_segment_sum_heads(const int64_t *piece_ptr, const int32_t *piece_row,
+                                 const int64_t *row_piece, int64_t n_pieces, int64_t n_rows,
+                                 const float *vals, const int64_t *index, int32_t heads, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+int32_t sylvie_scaled_column_sum_heads(const float *X, int64_t ld_x, int64_t n, int32_t F, int32_t heads,
+                                       const float *s, float *out, const float *s2, int64_t n2,
+                                       float *out2, void *workspace, size_t workspace_bytes,
+                                       void *stream);
+
+/*
+ * Aggregation of the attention model (GAT, Sec. 4; Eq. 1 with learned edge weights), all heads
+ * in one launch:
+ *     Y[v][c] = act( sum_e w[i_e][c / F] X[col_e][c]  +  s1[v][c / F] a1[c]  +  s2[v][c / F] a2[c] )
+ * over the entries e of row v of the CSR (rowptr, col); F = d / heads; i_e = e, or w_index[e]
+ * when w_index (int64 [entries]) is given.  Forward: w = alpha, Y = Z (relu != 0: Y = max(Z, 0),
+ * the hidden layers' activation).  Backward: (rowptr, col) is the transposed operator, w still
+ * alpha in forward entry order, w_index the transposition's entry map, X = dZ, and the two
+ * rank-1 terms add the gradient that reaches P through the scores (s1 = ds_src [n1][heads] with
+ * a1 = a_src on rows [0, n1), s2 = ds_dst with a2 = a_dst on rows [0, n2)); each term is a
+ * single-precision product and add, term 1 first, as two sylvie_rank1_add calls would do.
+ * Either term may be NULL.  heads is 1 .. 8 and divides d; the sums are accumulated entry by
+ * entry in ascending order with one FMA per element; long rows, chunk, the task plan and the
+ * workspace (n_tasks * d floats, 16-byte aligned) are those of sylvie_aggregate_csr_fwd.
+ * SYLVIE_ERR_UNIMPLEMENTED if d is wider than one launch covers (2048 columns for 16-byte
+ * aligned rows whose F is a multiple of 4).
+ */
+int32_t sylvie_aggregate_csr_attention(const int64_t *rowptr, const int32_t *col, const float *w,
+                                       const int64_t *w_index, int32_t heads, int64_t n_rows,
+                                       const float *X, int64_t ld_x, int32_t d, float *Y, int64_t ld_y,
+                                       const float *s1, const float *a1, int64_t n1, const float *s2,
+                                       const float *a2, int64_t n2, int32_t relu, int32_t chunk,
+                                       const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long,
+                                       int64_t n_tasks, float *workspace, size_t workspace_bytes,
+                                       void *stream);
+
+/*
  * Graph Engine set-up on the device (Sec. 3.2; Alg. 1, the lines before the epoch loop).
  * Not on the per-layer path: each call waits for `stream` before it returns, because it
  * reports counts and the result of the kernels' own range checks (a bad id gives

@@ -42,6 +42,8 @@ def lib():
         L.sylvie_scaled_column_sum_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
         L.sylvie_edge_softmax_workspace_bytes.restype = C.c_size_t
         L.sylvie_edge_softmax_workspace_bytes.argtypes = [C.c_int64, C.c_int64]
+        L.sylvie_edge_softmax_heads_workspace_bytes.restype = C.c_size_t
+        L.sylvie_edge_softmax_heads_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int32]
         L.sylvie_graph_workspace_bytes.restype = C.c_size_t
         L.sylvie_graph_workspace_bytes.argtypes = [C.c_int64]
         L.sylvie_transform_bwd_workspace_bytes.restype = C.c_size_t
@@ -63,6 +65,9 @@ def lib():
                      "sylvie_segment_sum", "sylvie_permute_f32", "sylvie_rank1_add",
                      "sylvie_scaled_column_sum",
                      "sylvie_relu_fwd", "sylvie_relu_bwd",
+                     "sylvie_row_dot_heads", "sylvie_edge_softmax_fwd_heads", "sylvie_sddmm_heads",
+                     "sylvie_edge_softmax_bwd_heads", "sylvie_segment_sum_heads",
+                     "sylvie_scaled_column_sum_heads", "sylvie_aggregate_csr_attention",
                      "sylvie_graph_local_index", "sylvie_graph_relabel_columns",
                      "sylvie_graph_rows_in_owner", "sylvie_graph_recv_sets",
                      "sylvie_graph_transpose_csr", "sylvie_graph_scatter_segments",
@@ -440,6 +445,70 @@ def sylvie_scaled_column_sum(X, ld_x, n, F, s, out, workspace):
     _check(lib().sylvie_scaled_column_sum(_ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int64(n),
                                           C.c_int32(F), _ptr(s, torch.float32, "s"),
                                           _ptr(out, torch.float32, "out"), *_ws(workspace), _stream()))
+
+
+# ---- the attention aggregator for K heads at once ([.][K] arrays) -------------------------
+
+def sylvie_row_dot_heads(P, ld_p, n, F, heads, a, out, a2=None, n2=0, out2=None):
+    _check(lib().sylvie_row_dot_heads(_ptr(P, torch.float32, "P"), C.c_int64(ld_p), C.c_int64(n), C.c_int32(F),
+                                      C.c_int32(heads), _ptr(a, torch.float32, "a"),
+                                      _ptr(out, torch.float32, "out"), _ptr(a2, torch.float32, "a2"),
+                                      C.c_int64(n2), _ptr(out2, torch.float32, "out2"), _stream()))
+
+
+def sylvie_edge_softmax_heads_workspace_bytes(n_pieces, n_rows, heads) -> int:
+    return int(lib().sylvie_edge_softmax_heads_workspace_bytes(int(n_pieces), int(n_rows), int(heads)))
+
+
+def sylvie_edge_softmax_fwd_heads(pieces, col, s_dst, s_src, heads, slope, alpha, workspace):
+    _check(lib().sylvie_edge_softmax_fwd_heads(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(s_dst, torch.float32, "s_dst"),
+        _ptr(s_src, torch.float32, "s_src"), C.c_int32(heads), C.c_float(slope),
+        _ptr(alpha, torch.float32, "alpha"), *_ws(workspace), _stream()))
+
+
+def sylvie_sddmm_heads(pieces, col, A, ld_a, Bm, ld_b, F, heads, out):
+    _check(lib().sylvie_sddmm_heads(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(A, torch.float32, "A"), C.c_int64(ld_a),
+        _ptr(Bm, torch.float32, "B"), C.c_int64(ld_b), C.c_int32(F), C.c_int32(heads),
+        _ptr(out, torch.float32, "out"), _stream()))
+
+
+def sylvie_edge_softmax_bwd_heads(pieces, col, alpha, dalpha, s_dst, s_src, heads, slope, de, ds_dst,
+                                  workspace):
+    _check(lib().sylvie_edge_softmax_bwd_heads(
+        *_pieces(pieces), _ptr(col, torch.int32, "col"), _ptr(alpha, torch.float32, "alpha"),
+        _ptr(dalpha, torch.float32, "dalpha"), _ptr(s_dst, torch.float32, "s_dst"),
+        _ptr(s_src, torch.float32, "s_src"), C.c_int32(heads), C.c_float(slope),
+        _ptr(de, torch.float32, "de"), _ptr(ds_dst, torch.float32, "ds_dst"), *_ws(workspace), _stream()))
+
+
+def sylvie_segment_sum_heads(pieces, vals, index, heads, out, workspace):
+    _check(lib().sylvie_segment_sum_heads(
+        *_pieces(pieces), _ptr(vals, torch.float32, "vals"), _ptr(index, torch.int64, "index"),
+        C.c_int32(heads), _ptr(out, torch.float32, "out"), *_ws(workspace), _stream()))
+
+
+def sylvie_scaled_column_sum_heads(X, ld_x, n, F, heads, s, out, workspace, s2=None, n2=0, out2=None):
+    _check(lib().sylvie_scaled_column_sum_heads(
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int64(n), C.c_int32(F), C.c_int32(heads),
+        _ptr(s, torch.float32, "s"), _ptr(out, torch.float32, "out"), _ptr(s2, torch.float32, "s2"),
+        C.c_int64(n2), _ptr(out2, torch.float32, "out2"), *_ws(workspace), _stream()))
+
+
+def sylvie_aggregate_csr_attention(rowptr, col, w, w_index, heads, n_rows, X, ld_x, d, Y, ld_y, s1=None,
+                                   a1=None, n1=0, s2=None, a2=None, n2=0, relu=False, chunk=0,
+                                   long_rows=None, long_ptr=None, n_long=0, n_tasks=0, workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_aggregate_csr_attention(
+        _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"), _ptr(w, torch.float32, "w"),
+        _ptr(w_index, torch.int64, "w_index"), C.c_int32(heads), C.c_int64(n_rows),
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), _ptr(Y, torch.float32, "Y"),
+        C.c_int64(ld_y), _ptr(s1, torch.float32, "s1"), _ptr(a1, torch.float32, "a1"), C.c_int64(n1),
+        _ptr(s2, torch.float32, "s2"), _ptr(a2, torch.float32, "a2"), C.c_int64(n2), C.c_int32(int(relu)),
+        C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+        C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
+        C.c_size_t(ws_bytes), _stream()))
 
 
 # ---- Graph Engine set-up (each call waits for the current stream) ------------------------

@@ -24,6 +24,7 @@ _SOURCES = {
     "transform.hip": [],
     "training.hip": ["-ffp-contract=off"],
     "gat.hip": ["-ffp-contract=off"],
+    "gat_aggregate.hip": ["-ffp-contract=off"],
     "graph_engine.hip": [],
     "validate.hip": [],
 }

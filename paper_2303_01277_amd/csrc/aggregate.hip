@@ -47,53 +47,6 @@ constexpr int kAgWavesPerBlockWire = 1;
 template <int WB, int EPI>
 constexpr int waves_per_block() { return (EPI == 0 && WB > 0) ? kAgWavesPerBlockWire : kAgWavesPerBlock; }
 
-template <int VEC>
-struct Vec;
-template <>
-struct Vec<4> { using type = float4; };
-template <>
-struct Vec<2> { using type = float2; };
-template <>
-struct Vec<1> { using type = float; };
-
-template <int VEC>
-struct NativeVec {
-    typedef float type __attribute__((ext_vector_type(VEC)));
-};
-template <>
-struct NativeVec<1> {
-    typedef float type;
-};
-
-// Every operand read through load_vec is device (global) memory; saying so keeps the load a
-// global one where the pointer was reassembled from lane reads and its origin is no longer visible.
-template <int VEC>
-__device__ __forceinline__ void load_vec(float (&o)[VEC], const float *p)
-{
-    typedef typename NativeVec<VEC>::type V;
-    typedef const __attribute__((address_space(1))) V *global_ptr;
-    const V v = *(global_ptr)(p);
-    __builtin_memcpy(o, &v, sizeof(v));
-}
-// The same through a wave-uniform row address and a lane's own byte offset inside the row
-// (an unsigned 32-bit offset lets the load take the row address from scalar registers).
-template <int VEC>
-__device__ __forceinline__ void load_vec_at(float (&o)[VEC], const float *row, uint32_t byte_off)
-{
-    typedef typename NativeVec<VEC>::type V;
-    typedef const __attribute__((address_space(1))) char *global_bytes;
-    typedef const __attribute__((address_space(1))) V *global_ptr;
-    const V v = *(global_ptr)((global_bytes)(row) + byte_off);
-    __builtin_memcpy(o, &v, sizeof(v));
-}
-template <int VEC>
-__device__ __forceinline__ void store_vec(float *p, const float (&o)[VEC])
-{
-    typename Vec<VEC>::type v;
-    __builtin_memcpy(&v, o, sizeof(v));
-    *reinterpret_cast<typename Vec<VEC>::type *>(p) = v;
-}
-
 struct AggArgs {
     const int64_t *rowptr;
     const int32_t *col;

@@ -637,6 +637,7 @@ class AttentionLoop(LayerLoop):
     normalises the scores of each row with a softmax and aggregates Z = sum alpha P_u;
     H = relu(Z) except on the last layer.  `heads` attention heads share W column-wise: head k
     owns columns [k F, (k+1) F) of P, F = d_l / heads, and its own slices of a_dst / a_src.
+    All heads go through one call per step: scores and per-entry values are [.][heads] arrays.
     The exchange is the two-step one (the transform needs the halo rows as floats)."""
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, att, dims, heads: int = 1,
@@ -647,9 +648,12 @@ class AttentionLoop(LayerLoop):
                          fused_bwd=False)
         self.model = "gat"
         self.att, self.heads, self.slope = att, heads, slope
+        if heads not in (1, 2, 4, 8):
+            raise ValueError("heads must be 1, 2, 4 or 8")
         if any(d % heads for d in dims[1:]):
             raise ValueError("every layer width must be a multiple of heads")
         dev = self.dev
+        K = heads
         for st in self.parts:
             n_loc = st.n_in + st.n_halo
             nnz = int(st.op[0][-1])
@@ -657,28 +661,23 @@ class AttentionLoop(LayerLoop):
             st.piecesT = GE.piece_table(st.opT[0], chunk)
             st.P = [None] + [torch.empty(n_loc, dims[l], dtype=torch.float32, device=dev)
                              for l in range(1, self.L + 1)]
-            st.Zg = [None] + [torch.empty(st.n_in, dims[l], dtype=torch.float32, device=dev)
-                              for l in range(1, self.L + 1)]
-            st.alpha = [None] + [[torch.empty(nnz, dtype=torch.float32, device=dev) for _ in range(heads)]
-                                 for _ in range(self.L)]
-            st.s_dst = [None] + [[torch.empty(st.n_in, dtype=torch.float32, device=dev) for _ in range(heads)]
-                                 for _ in range(self.L)]
-            st.s_src = [None] + [[torch.empty(n_loc, dtype=torch.float32, device=dev) for _ in range(heads)]
-                                 for _ in range(self.L)]
-            st.edge = [torch.empty(nnz, dtype=torch.float32, device=dev) for _ in range(4)]
-            st.ds_dst = torch.empty(st.n_in, dtype=torch.float32, device=dev)
-            st.ds_src = torch.empty(n_loc, dtype=torch.float32, device=dev)
+            st.alpha = [None] + [torch.empty(nnz * K, dtype=torch.float32, device=dev) for _ in range(self.L)]
+            st.s_dst = [None] + [torch.empty(st.n_in * K, dtype=torch.float32, device=dev) for _ in range(self.L)]
+            st.s_src = [None] + [torch.empty(n_loc * K, dtype=torch.float32, device=dev) for _ in range(self.L)]
+            st.edge = [torch.empty(nnz * K, dtype=torch.float32, device=dev) for _ in range(2)]
+            st.ds_dst = torch.empty(st.n_in * K, dtype=torch.float32, device=dev)
+            st.ds_src = torch.empty(n_loc * K, dtype=torch.float32, device=dev)
             st.dP = torch.empty(n_loc, max(dims[1:]), dtype=torch.float32, device=dev)
             st.dZg = torch.empty(st.n_in, max(dims[1:]), dtype=torch.float32, device=dev)
-            n_ws = max(B.sylvie_edge_softmax_workspace_bytes(st.pieces[1].numel(), st.n_in) // 4,
-                       st.piecesT[1].numel() + n_loc, 1)
+            n_ws = max(B.sylvie_edge_softmax_heads_workspace_bytes(st.pieces[1].numel(), st.n_in, K) // 4,
+                       (st.piecesT[1].numel() + n_loc) * K, 1)
             st.ws_att = torch.empty(n_ws, dtype=torch.float32, device=dev)
             nbytes = B.sylvie_transform_bwd_workspace_bytes(max(dims), 0, max(dims[1:]), n_loc)
             st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             st.Ga = [None] + [(torch.empty(dims[l], dtype=torch.float32, device=dev),
                                torch.empty(dims[l], dtype=torch.float32, device=dev))
                               for l in range(1, self.L + 1)]
-            st.ws_col = torch.empty(max(1, B.sylvie_scaled_column_sum_workspace_bytes(n_loc, max(dims[1:])) // 4),
+            st.ws_col = torch.empty(max(1, 2 * B.sylvie_scaled_column_sum_workspace_bytes(n_loc, max(dims[1:])) // 4),
                                     dtype=torch.float32, device=dev)
 
     def forward(self, seed, pair_seed=default_pair_seed, mode="sync"):
@@ -693,25 +692,20 @@ class AttentionLoop(LayerLoop):
             for st in self.parts:
                 n_loc = st.n_in + st.n_halo
                 ht, P = st.Htil[l - 1], st.P[l]
-                Z = st.Zg[l] if l < self.L else st.out       # no activation after the last layer
+                # the hidden layers' activation is the aggregation's last step
+                Y = st.Htil[l] if l < self.L else st.out
                 B.sylvie_transform_fwd(ht, ht.stride(0), d, None, 0, 0, self.W[l - 1], h, n_loc, False,
                                        P, P.stride(0))
                 rp, cl, _ = st.op
                 lr, lp, nt = st.plan
-                for k in range(K):
-                    Pk, Zk = P[:, k * F:], Z[:, k * F:]
-                    sd, ss, al = st.s_dst[l][k], st.s_src[l][k], st.alpha[l][k]
-                    B.sylvie_row_dot(Pk, h, st.n_in, F, a_dst[k * F:], sd)
-                    B.sylvie_row_dot(Pk, h, n_loc, F, a_src[k * F:], ss)
-                    B.sylvie_edge_softmax_fwd(st.pieces, cl, sd, ss, self.slope, al, st.ws_att)
-                    B.sylvie_aggregate_csr_fwd(rp, cl, al, None, None, st.n_in, Pk, h, F, Zk, h,
-                                               chunk=self.chunk, long_rows=lr if nt else None,
-                                               long_ptr=lp if nt else None,
-                                               n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                                               workspace=st.ws_agg if nt else None)
-                if l != self.L:
-                    Hout = st.Htil[l]
-                    B.sylvie_relu_fwd(Z, h, st.n_in, h, Hout, Hout.stride(0))
+                sd, ss, al = st.s_dst[l], st.s_src[l], st.alpha[l]
+                B.sylvie_row_dot_heads(P, h, st.n_in, F, K, a_dst, sd, a2=a_src, n2=n_loc, out2=ss)
+                B.sylvie_edge_softmax_fwd_heads(st.pieces, cl, sd, ss, K, self.slope, al, st.ws_att)
+                B.sylvie_aggregate_csr_attention(rp, cl, al, None, K, st.n_in, P, h, h, Y, Y.stride(0),
+                                                 relu=l != self.L, chunk=self.chunk,
+                                                 long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                                                 n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                                                 workspace=st.ws_agg if nt else None)
 
     def backward(self, seed, pair_seed=default_pair_seed, mode="sync"):
         if mode != "sync":
@@ -724,7 +718,6 @@ class AttentionLoop(LayerLoop):
             a_dst, a_src = self.att[l - 1]
             for st in self.parts:
                 n_loc = st.n_in + st.n_halo
-                nnz = st.alpha[l][0].numel()
                 Hout = st.Htil[l] if l < self.L else st.out
                 Jl = st.J if l == self.L else st.dHtil[l]
                 P, dP = st.P[l], st.dP
@@ -734,29 +727,26 @@ class AttentionLoop(LayerLoop):
                 else:
                     dZ = Jl
                 ldz, ldp = dZ.stride(0), dP.stride(0)
-                rp, cl, _ = st.op
+                _, cl, _ = st.op
                 rpT, clT, _ = st.opT
                 lr, lp, nt = st.planT
-                dal, de, deT, alT = st.edge
+                dal, de = st.edge
                 da_dst, da_src = st.Ga[l]
-                for k in range(K):
-                    Pk, dZk, dPk = P[:, k * F:], dZ[:, k * F:], dP[:, k * F:]
-                    sd, ss, al = st.s_dst[l][k], st.s_src[l][k], st.alpha[l][k]
-                    B.sylvie_sddmm(st.pieces, cl, dZk, ldz, Pk, h, F, dal)
-                    B.sylvie_edge_softmax_bwd(st.pieces, cl, al, dal, sd, ss, self.slope, de, st.ws_att)
-                    B.sylvie_segment_sum(st.pieces, de, st.ds_dst, st.ws_att)
-                    B.sylvie_permute_f32(de, st.perm, nnz, deT)
-                    B.sylvie_segment_sum(st.piecesT, deT, st.ds_src, st.ws_att)
-                    B.sylvie_permute_f32(al, st.perm, nnz, alT)
-                    B.sylvie_aggregate_csr_bwd(rpT, clT, alT, None, None, n_loc, dZk, ldz, F, dPk, ldp,
-                                               chunk=self.chunk, long_rows=lr if nt else None,
-                                               long_ptr=lp if nt else None,
-                                               n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                                               workspace=st.ws_aggT if nt else None)
-                    B.sylvie_rank1_add(dPk, ldp, n_loc, F, st.ds_src, a_src[k * F:])
-                    B.sylvie_rank1_add(dPk, ldp, st.n_in, F, st.ds_dst, a_dst[k * F:])
-                    B.sylvie_scaled_column_sum(Pk, h, st.n_in, F, st.ds_dst, da_dst[k * F:], st.ws_col)
-                    B.sylvie_scaled_column_sum(Pk, h, n_loc, F, st.ds_src, da_src[k * F:], st.ws_col)
+                sd, ss, al = st.s_dst[l], st.s_src[l], st.alpha[l]
+                B.sylvie_sddmm_heads(st.pieces, cl, dZ, ldz, P, h, F, K, dal)
+                B.sylvie_edge_softmax_bwd_heads(st.pieces, cl, al, dal, sd, ss, K, self.slope, de, st.ds_dst,
+                                                st.ws_att)
+                # column sums of de and the transposed aggregation read de / alpha in forward
+                # entry order through the transposition's entry map
+                B.sylvie_segment_sum_heads(st.piecesT, de, st.perm, K, st.ds_src, st.ws_att)
+                B.sylvie_aggregate_csr_attention(rpT, clT, al, st.perm, K, n_loc, dZ, ldz, h, dP, ldp,
+                                                 s1=st.ds_src, a1=a_src, n1=n_loc,
+                                                 s2=st.ds_dst, a2=a_dst, n2=st.n_in, chunk=self.chunk,
+                                                 long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                                                 n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                                                 workspace=st.ws_aggT if nt else None)
+                B.sylvie_scaled_column_sum_heads(P, h, st.n_in, h, K, st.ds_dst, da_dst, st.ws_col,
+                                                 s2=st.ds_src, n2=n_loc, out2=da_src)
                 ht = st.Htil[l - 1]
                 g = st.dHtil[l - 1] if need_dx else None
                 B.sylvie_transform_bwd(ht, ht.stride(0), d, None, 0, 0, self.W[l - 1], h, n_loc, False,

@@ -154,3 +154,187 @@ def test_scaled_column_sum_parity(F, n):
     got = out.cpu().numpy()
     close(got[:F], (X64.T @ s64).astype(np.float32), np.abs(X64).T @ np.abs(s64), "column sum")
     assert (got[F:] == 7.0).all()
+
+
+def _heads_setup(oracle, K, F, chunk, seed):
+    from paper_2303_01277_amd import graph_engine as GE
+    p, rp, cl, rpd, cld, pieces = setup(oracle, 20_000, chunk)
+    n_in, n_loc, nnz = p.n_in, p.n_in + p.n_halo, int(rp[-1])
+    rng = np.random.default_rng(seed)
+    h = K * F
+    ld = h + (3 if h % 2 else 4)
+    P = make_rows(rng, n_loc, ld, "normal")
+    dZ = make_rows(rng, n_in, ld, "normal")
+    a_dst = (rng.standard_normal(h) / np.sqrt(F)).astype(np.float32)
+    a_src = (rng.standard_normal(h) / np.sqrt(F)).astype(np.float32)
+    *opT, perm = GE.transpose_csr(rpd, cld, torch.ones(nnz, device=DEV), n_loc, want_perm=True)
+    piecesT = GE.piece_table(opT[0], chunk)
+    return dict(p=p, rp=rp, cl=cl, rpd=rpd, cld=cld, pieces=pieces, piecesT=piecesT, opT=opT, perm=perm,
+                n_in=n_in, n_loc=n_loc, nnz=nnz, h=h, ld=ld, P=P, dZ=dZ, a_dst=a_dst, a_src=a_src)
+
+
+@pytest.mark.parametrize("chunk", [64, 1024])
+@pytest.mark.parametrize("K,F", [(2, 7), (2, 64), (4, 16), (4, 64), (4, 100), (8, 32), (8, 128), (3, 7)])
+def test_heads_calls_equal_single_head_calls(oracle, K, F, chunk):
+    """Every K-head call against K single-head calls on the heads' own slices: bit for bit (the
+    single-head calls are checked against the oracle above)."""
+    from paper_2303_01277_amd import binding as B
+    s = _heads_setup(oracle, K, F, chunk, 17 * K + F + chunk)
+    n_in, n_loc, nnz, h, ld = s["n_in"], s["n_loc"], s["nnz"], s["h"], s["ld"]
+    Pd, dZd, a_dst, a_src = dev(s["P"]), dev(s["dZ"]), dev(s["a_dst"]), dev(s["a_src"])
+    pieces, piecesT, cld, perm = s["pieces"], s["piecesT"], s["cld"], s["perm"]
+    new = lambda n: torch.full((n,), float("nan"), device=DEV)
+    col = lambda t, k: t.view(-1, K)[:, k].contiguous()
+    same = lambda a, b: torch.equal(a.view(torch.int32), b.view(torch.int32))
+    # scores
+    sd, ss = new(n_in * K), new(n_loc * K)
+    B.sylvie_row_dot_heads(Pd, ld, n_in, F, K, a_dst, sd, a2=a_src, n2=n_loc, out2=ss)
+    sd_alone = new(n_in * K)
+    B.sylvie_row_dot_heads(Pd, ld, n_in, F, K, a_dst, sd_alone)
+    assert same(sd, sd_alone)
+    sd1, ss1 = [new(n_in) for _ in range(K)], [new(n_loc) for _ in range(K)]
+    for k in range(K):
+        B.sylvie_row_dot(Pd[:, k * F:], ld, n_in, F, a_dst[k * F:], sd1[k])
+        B.sylvie_row_dot(Pd[:, k * F:], ld, n_loc, F, a_src[k * F:], ss1[k])
+        assert same(col(sd, k), sd1[k]) and same(col(ss, k), ss1[k]), ("row_dot", k)
+    # sampled product: any K; the other per-entry calls: K = 1, 2, 4, 8
+    dal = new(nnz * K)
+    B.sylvie_sddmm_heads(pieces, cld, dZd, ld, Pd, ld, F, K, dal)
+    dal1 = [new(nnz) for _ in range(K)]
+    for k in range(K):
+        B.sylvie_sddmm(pieces, cld, dZd[:, k * F:], ld, Pd[:, k * F:], ld, F, dal1[k])
+        assert same(col(dal, k), dal1[k]), ("sddmm", k)
+    # attention-vector gradients: any K that divides the width
+    sc = torch.randn(n_loc * K, device=DEV)
+    ws_col = torch.empty(max(2 * B.sylvie_scaled_column_sum_workspace_bytes(n_loc, h) // 4, 1), device=DEV)
+    out = torch.full((h + 2,), 7.0, device=DEV)
+    B.sylvie_scaled_column_sum_heads(Pd, ld, n_loc, h, K, sc, out, ws_col)
+    # two sums in one pass (the shorter one over the inner rows) keep the bits they have alone
+    sc2 = torch.randn(n_in * K, device=DEV)
+    o_a, o_b, o_b1 = new(h), new(h), new(h)
+    B.sylvie_scaled_column_sum_heads(Pd, ld, n_in, h, K, sc2, o_b, ws_col, s2=sc, n2=n_loc, out2=o_a)
+    B.sylvie_scaled_column_sum_heads(Pd, ld, n_in, h, K, sc2, o_b1, ws_col)
+    assert same(o_a, out[:h].contiguous()) and same(o_b, o_b1)
+    for k in range(K):
+        o1 = new(F)
+        B.sylvie_scaled_column_sum(Pd[:, k * F:], ld, n_loc, F, col(sc, k), o1, ws_col)
+        assert same(out[k * F:(k + 1) * F], o1), ("column sum", k)
+    assert bool((out[h:] == 7.0).all())
+    if K == 3:
+        with pytest.raises(B.SylvieError):
+            B.sylvie_edge_softmax_fwd_heads(pieces, cld, sd, ss, K, 0.2, new(nnz * K), new(16))
+        return
+    ws = torch.empty(max(B.sylvie_edge_softmax_heads_workspace_bytes(pieces[1].numel(), n_in, K) // 4,
+                         (piecesT[1].numel() + n_loc) * K), device=DEV)
+    al = new(nnz * K)
+    B.sylvie_edge_softmax_fwd_heads(pieces, cld, sd, ss, K, 0.2, al, ws)
+    al1 = [new(nnz) for _ in range(K)]
+    for k in range(K):
+        B.sylvie_edge_softmax_fwd(pieces, cld, sd1[k], ss1[k], 0.2, al1[k], ws)
+        assert same(col(al, k), al1[k]), ("alpha", k)
+    de, dsd = new(nnz * K), new(n_in * K)
+    B.sylvie_edge_softmax_bwd_heads(pieces, cld, al, dal, sd, ss, K, 0.2, de, dsd, ws)
+    de_only = new(nnz * K)
+    B.sylvie_edge_softmax_bwd_heads(pieces, cld, al, dal, sd, ss, K, 0.2, de_only, None, ws)
+    assert same(de, de_only)
+    dss = new(n_loc * K)
+    B.sylvie_segment_sum_heads(piecesT, de, perm, K, dss, ws)
+    dsd2 = new(n_in * K)
+    B.sylvie_segment_sum_heads(pieces, de, None, K, dsd2, ws)
+    assert same(dsd, dsd2)
+    for k in range(K):
+        de1, o1, oT, deT = new(nnz), new(n_in), new(n_loc), new(nnz)
+        B.sylvie_edge_softmax_bwd(pieces, cld, al1[k], dal1[k], sd1[k], ss1[k], 0.2, de1, ws)
+        assert same(col(de, k), de1), ("de", k)
+        B.sylvie_segment_sum(pieces, de1, o1, ws)
+        assert same(col(dsd, k), o1), ("ds_dst", k)
+        B.sylvie_permute_f32(de1, perm, nnz, deT)
+        B.sylvie_segment_sum(piecesT, deT, oT, ws)
+        assert same(col(dss, k), oT), ("ds_src", k)
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("chunk", [0, 64])
+@pytest.mark.parametrize("K,F", [(1, 256), (2, 7), (2, 50), (4, 16), (4, 64), (4, 100), (8, 64), (3, 20), (5, 1)])
+def test_attention_aggregation_parity(oracle, K, F, chunk):
+    """sylvie_aggregate_csr_attention, forward (with and without the activation) and through the
+    transposed operator with the entry map and the two rank-1 terms, per head against the oracle;
+    the options against each other bit for bit."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    s = _heads_setup(oracle, K, F, 64, 31 * K + F)
+    rp, cl, n_in, n_loc, nnz, h, ld = s["rp"], s["cl"], s["n_in"], s["n_loc"], s["nnz"], s["h"], s["ld"]
+    rng = np.random.default_rng(K * 1000 + F)
+    al = rng.random((nnz, K)).astype(np.float32)
+    ald, Pd, dZd = dev(al.reshape(-1)), dev(s["P"]), dev(s["dZ"])
+    rpT, clT, _ = s["opT"]
+    perm = s["perm"]
+    same = lambda a, b: torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+    def plan(rowptr):
+        if not chunk:
+            return {}
+        lr, lp, nt = GE.long_row_plan(rowptr, chunk)
+        assert nt > 0
+        return dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                    workspace=torch.empty(max(1, nt) * h, device=DEV))
+
+    # forward
+    kw = plan(s["rpd"])
+    Z = torch.full((n_in, ld), 5.0, device=DEV)
+    B.sylvie_aggregate_csr_attention(s["rpd"], s["cld"], ald, None, K, n_in, Pd, ld, h, Z, ld, **kw)
+    Zr = torch.full((n_in, ld), 5.0, device=DEV)
+    B.sylvie_aggregate_csr_attention(s["rpd"], s["cld"], ald, None, K, n_in, Pd, ld, h, Zr, ld, relu=True, **kw)
+    torch.cuda.synchronize()
+    assert same(Zr[:, :h].contiguous(), torch.where(Z[:, :h] > 0, Z[:, :h], torch.zeros_like(Z[:, :h])).contiguous())
+    assert bool((Z[:, h:] == 5.0).all()) and bool((Zr[:, h:] == 5.0).all())
+    Zh = Z.cpu().numpy()
+    for k in range(K):
+        sl = slice(k * F, (k + 1) * F)
+        ref, S = oracle.aggregate_fwd(rp, cl, np.ascontiguousarray(al[:, k]), np.ascontiguousarray(s["P"][:, sl]), F,
+                                      want_S=True)
+        close(Zh[:, sl], ref, S, ("Z", k))
+    # backward: transposed operator, weights through the entry map, rank-1 terms
+    kwT = plan(rpT)
+    ds_src, ds_dst = torch.randn(n_loc * K, device=DEV), torch.randn(n_in * K, device=DEV)
+    a_src, a_dst = dev(s["a_src"]), dev(s["a_dst"])
+    dP = torch.full((n_loc, ld), 5.0, device=DEV)
+    B.sylvie_aggregate_csr_attention(rpT, clT, ald, perm, K, n_loc, dZd, ld, h, dP, ld, s1=ds_src, a1=a_src,
+                                     n1=n_loc, s2=ds_dst, a2=a_dst, n2=n_in, **kwT)
+    # the same without the options: weights permuted beforehand, rank-1 terms as separate calls
+    alT = ald.view(nnz, K)[perm].contiguous().view(-1)
+    dP2 = torch.full((n_loc, ld), 5.0, device=DEV)
+    B.sylvie_aggregate_csr_attention(rpT, clT, alT, None, K, n_loc, dZd, ld, h, dP2, ld, **kwT)
+    plain = dP2.clone()
+    for k in range(K):
+        B.sylvie_rank1_add(dP2[:, k * F:], ld, n_loc, F, ds_src.view(-1, K)[:, k].contiguous(), a_src[k * F:])
+        B.sylvie_rank1_add(dP2[:, k * F:], ld, n_in, F, ds_dst.view(-1, K)[:, k].contiguous(), a_dst[k * F:])
+    torch.cuda.synchronize()
+    assert same(dP, dP2)
+    ph = plain.cpu().numpy()
+    for k in range(K):
+        sl = slice(k * F, (k + 1) * F)
+        ref, S = oracle.aggregate_bwd(rp, cl, np.ascontiguousarray(al[:, k]), n_loc,
+                                      np.ascontiguousarray(s["dZ"][:, sl]), F, want_S=True)
+        close(ph[:, sl], ref, S, ("dP", k))
+    # one head, 256 columns: the plain aggregation's own order of additions
+    if K == 1 and F == 256:
+        Y = torch.full((n_in, ld), 5.0, device=DEV)
+        B.sylvie_aggregate_csr_fwd(s["rpd"], s["cld"], ald, None, None, n_in, Pd, ld, h, Y, ld, **kw)
+        torch.cuda.synchronize()
+        assert same(Y, Z)
+
+
+def test_attention_aggregation_rejects_bad_arguments():
+    from paper_2303_01277_amd import binding as B
+    rp = dev(np.array([0, 1, 2], np.int64)); cl = dev(np.array([0, 1], np.int32))
+    w = torch.ones(2 * 9, device=DEV); X = torch.ones(2, 72, device=DEV); Y = torch.empty(2, 72, device=DEV)
+    with pytest.raises(B.SylvieError):      # more heads than the weight table holds
+        B.sylvie_aggregate_csr_attention(rp, cl, w, None, 9, 2, X, 72, 72, Y, 72)
+    with pytest.raises(B.SylvieError):      # heads must divide d
+        B.sylvie_aggregate_csr_attention(rp, cl, w, None, 5, 2, X, 72, 72, Y, 72)
+    with pytest.raises(B.SylvieError):      # a rank-1 term without its vector
+        B.sylvie_aggregate_csr_attention(rp, cl, w, None, 2, 2, X, 72, 72, Y, 72, s1=w)
+    B.sylvie_aggregate_csr_attention(rp, cl, w, None, 2, 2, X, 72, 72, Y, 72)
+    torch.cuda.synchronize()
+    assert bool((Y == 1.0).all())

@@ -112,7 +112,7 @@ def oracle_layer(oracle, rp, cl, n_in, ht, W, a_dst, a_src, heads, slope, relu, 
             "S_dst": S_dst, "S_src": S_src}
 
 
-@pytest.mark.parametrize("heads,wire", [(1, "1bit"), (2, "1bit"), (2, "4bit")])
+@pytest.mark.parametrize("heads,wire", [(1, "1bit"), (2, "1bit"), (2, "4bit"), (4, "1bit"), (8, "1bit")])
 @pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("stress", 12_000)])
 def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire):
     wl = workload(cfg, n_nodes)
@@ -149,10 +149,10 @@ def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire):
             o = oracle_layer(oracle, rp, cl, st.n_in, ht, W[l - 1], a_dst, a_src, heads, 0.2, l != L, J, Hg,
                              np_c(st.P[l]))
             assert rel(np_c(st.P[l]), o["P"]) < 2e-5
-            Zg = np_c(st.Zg[l]) if l < L else Hg
-            assert rel(Zg, o["Z"]) < 5e-5
+            # the hidden layers' activation is applied by the aggregation itself
+            assert rel(Hg, np.maximum(o["Z"], 0) if l < L else o["Z"]) < 5e-5
             if l < L:
-                assert np.array_equal(Hg, np.maximum(Zg, 0))
+                assert (Hg >= 0).all() and ((Hg == 0) == (o["Z"] <= 0))[np.abs(o["Z"]) > 1e-4].all()
             assert rel(np_c(st.G[l]), o["G"]) < 1e-4
             for got, ref, S in ((st.Ga[l][0], o["da_dst"], o["S_dst"]), (st.Ga[l][1], o["da_src"], o["S_src"])):
                 err = np.abs(np_c(got).astype(np.float64) - ref)
