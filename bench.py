@@ -480,18 +480,21 @@ def attention_bench(torch, B, wl, owner, rows, spec, args, forced, heads=4):
             setattr(B, n, orig[n])
     nnz = sum(int(st.op[0][-1]) for st in loop.parts)
     # gather bytes of the calls that fetch one float row (all heads' slices) per operator entry:
-    # index, the entry's K weights or results, 4 K F bytes of the gathered row, the rows written;
-    # the aggregation is called twice per layer (forward; backward through the transposed
-    # operator, whose weights come through the 8-byte entry map)
+    # index, the entry's K weights, 4 K F bytes of the gathered row, the rows written; the
+    # backward call goes through the transposed operator (weights and the sampled products it
+    # also writes go through the 8-byte entry map, and it reads its own row of P)
     F = spec.dims[1] // heads
     h = F * heads
     n_in = sum(st.n_in for st in loop.parts)
     n_loc = sum(st.n_in + st.n_halo for st in loop.parts)
-    per_layer = {
-        "sylvie_sddmm_heads": nnz * (4 + 4 * heads + 4 * h) + n_in * 4 * h,
-        "sylvie_aggregate_csr_attention": (nnz * (4 + 4 * heads + 4 * h) + n_in * (4 * h + 8)) +
-                                          (nnz * (12 + 4 * heads + 4 * h) + n_loc * (4 * h + 8 + 8 * heads)),
-    }
+    fwd = nnz * (4 + 4 * heads + 4 * h) + n_in * (4 * h + 8)
+    bwd = nnz * (12 + 4 * heads + 4 * h) + n_loc * (4 * h + 8)
+    if all(loop.fused_sddmm[1:]):
+        per_layer = {"sylvie_aggregate_csr_attention": fwd,
+                     "sylvie_aggregate_csr_attention_sddmm": bwd + nnz * 4 * heads + n_loc * 4 * h}
+    else:
+        per_layer = {"sylvie_sddmm_heads": nnz * (4 + 4 * heads + 4 * h) + n_in * 4 * h,
+                     "sylvie_aggregate_csr_attention": fwd + bwd + n_loc * 8 * heads}
     gathers = {}
     for name, nbytes in per_layer.items():
         if name in acc:

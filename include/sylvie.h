@@ -570,6 +570,14 @@ int32_t sylvie_scaled_column_sum_heads(const float *X, int64_t ld_x, int64_t n, 
  * SYLVIE_ERR_UNIMPLEMENTED if d is wider than one launch covers (2048 columns for 16-byte
  * aligned rows whose F is a multiple of 4).
  */
+/* X[i][c] = fl(fl(X[i][c] + fl(s1[i][c / (F / K)] a1[c])) + fl(s2[i][c / (F / K)] a2[c])): the two
+ * rank-1 terms of the attention backward (dP += ds_src (x) a_src + ds_dst (x) a_dst) for K heads in
+ * one pass, term 1 on rows [0, n1), term 2 on rows [0, n2); F = all heads' columns; either term
+ * may be NULL.  Equal bit for bit to sylvie_rank1_add per head and term, term 1 first. */
+int32_t sylvie_rank1_add_heads(float *X, int64_t ld_x, int32_t F, int32_t heads, const float *s1,
+                               const float *a1, int64_t n1, const float *s2, const float *a2, int64_t n2,
+                               void *stream);
+
 int32_t sylvie_aggregate_csr_attention(const int64_t *rowptr, const int32_t *col, const float *w,
                                        const int64_t *w_index, int32_t heads, int64_t n_rows,
                                        const float *X, int64_t ld_x, int32_t d, float *Y, int64_t ld_y,
@@ -578,6 +586,31 @@ int32_t sylvie_aggregate_csr_attention(const int64_t *rowptr, const int32_t *col
                                        const int32_t *long_rows, const int64_t *long_ptr, int64_t n_long,
                                        int64_t n_tasks, float *workspace, size_t workspace_bytes,
                                        void *stream);
+
+/*
+ * The transposed aggregation of the attention backward together with the sampled product of the
+ * softmax backward (GAT, Sec. 4): over the rows u of the transposed operator (rowptr, col),
+ *     Y[u][c]        = sum_e w[i_e][c / F] X[col_e][c]                    (dP without its rank-1 terms)
+ *     dalpha[i_e][k] = X[col_e][k F .. (k+1) F) . B[u][k F .. (k+1) F)    (dalpha_vu = dZ_v . P_u)
+ * with X = dZ, B = P and i_e = w_index[e] (the forward entry of transposed entry e; i_e = e when
+ * w_index is NULL).  The wavefront of row u gathers the rows dZ_v once for both results; the
+ * product is what sylvie_sddmm_heads computes over the forward pattern, entry by entry, with the
+ * additions of a dot product in another order (four adjacent columns per lane, then the lanes of
+ * the head pairwise).  Every entry of dalpha named by the pattern is written, once.  Follow it
+ * with sylvie_edge_softmax_bwd_heads and sylvie_rank1_add_heads.
+ * Shapes: d <= 256 and F = d / heads one of 16, 32, 64, 128, 256 (ask
+ * sylvie_aggregate_csr_attention_sddmm_supported, which returns 1 or 0; otherwise
+ * SYLVIE_ERR_UNIMPLEMENTED); rows of X, Y and B 16-byte aligned with leading dimensions that are
+ * multiples of 4.  Long rows, chunk, plan and workspace as for sylvie_aggregate_csr_attention.
+ */
+int32_t sylvie_aggregate_csr_attention_sddmm_supported(int32_t d, int32_t heads);
+int32_t sylvie_aggregate_csr_attention_sddmm(const int64_t *rowptr, const int32_t *col, const float *w,
+                                             const int64_t *w_index, int32_t heads, int64_t n_rows,
+                                             const float *X, int64_t ld_x, int32_t d, float *Y,
+                                             int64_t ld_y, const float *B, int64_t ld_b, float *dalpha,
+                                             int32_t chunk, const int32_t *long_rows,
+                                             const int64_t *long_ptr, int64_t n_long, int64_t n_tasks,
+                                             float *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Graph Engine set-up on the device (Sec. 3.2; Alg. 1, the lines before the epoch loop).

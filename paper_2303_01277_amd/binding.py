@@ -68,6 +68,8 @@ def lib():
                      "sylvie_row_dot_heads", "sylvie_edge_softmax_fwd_heads", "sylvie_sddmm_heads",
                      "sylvie_edge_softmax_bwd_heads", "sylvie_segment_sum_heads",
                      "sylvie_scaled_column_sum_heads", "sylvie_aggregate_csr_attention",
+                     "sylvie_rank1_add_heads", "sylvie_aggregate_csr_attention_sddmm",
+                     "sylvie_aggregate_csr_attention_sddmm_supported",
                      "sylvie_graph_local_index", "sylvie_graph_relabel_columns",
                      "sylvie_graph_rows_in_owner", "sylvie_graph_recv_sets",
                      "sylvie_graph_transpose_csr", "sylvie_graph_scatter_segments",
@@ -506,6 +508,31 @@ def sylvie_aggregate_csr_attention(rowptr, col, w, w_index, heads, n_rows, X, ld
         _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), _ptr(Y, torch.float32, "Y"),
         C.c_int64(ld_y), _ptr(s1, torch.float32, "s1"), _ptr(a1, torch.float32, "a1"), C.c_int64(n1),
         _ptr(s2, torch.float32, "s2"), _ptr(a2, torch.float32, "a2"), C.c_int64(n2), C.c_int32(int(relu)),
+        C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
+        C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
+        C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_rank1_add_heads(X, ld_x, F, heads, s1, a1, n1, s2=None, a2=None, n2=0):
+    _check(lib().sylvie_rank1_add_heads(
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(F), C.c_int32(heads),
+        _ptr(s1, torch.float32, "s1"), _ptr(a1, torch.float32, "a1"), C.c_int64(n1),
+        _ptr(s2, torch.float32, "s2"), _ptr(a2, torch.float32, "a2"), C.c_int64(n2), _stream()))
+
+
+def sylvie_aggregate_csr_attention_sddmm_supported(d, heads) -> bool:
+    return bool(lib().sylvie_aggregate_csr_attention_sddmm_supported(C.c_int32(d), C.c_int32(heads)))
+
+
+def sylvie_aggregate_csr_attention_sddmm(rowptr, col, w, w_index, heads, n_rows, X, ld_x, d, Y, ld_y, Bm, ld_b,
+                                         dalpha, chunk=0, long_rows=None, long_ptr=None, n_long=0, n_tasks=0,
+                                         workspace=None):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sylvie_aggregate_csr_attention_sddmm(
+        _ptr(rowptr, torch.int64, "rowptr"), _ptr(col, torch.int32, "col"), _ptr(w, torch.float32, "w"),
+        _ptr(w_index, torch.int64, "w_index"), C.c_int32(heads), C.c_int64(n_rows),
+        _ptr(X, torch.float32, "X"), C.c_int64(ld_x), C.c_int32(d), _ptr(Y, torch.float32, "Y"),
+        C.c_int64(ld_y), _ptr(Bm, torch.float32, "B"), C.c_int64(ld_b), _ptr(dalpha, torch.float32, "dalpha"),
         C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))

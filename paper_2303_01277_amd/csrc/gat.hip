@@ -547,6 +547,41 @@ __global__ void rank1_add_kernel(float *__restrict__ X, int64_t ld, int64_t n, i
     X[i * ld + c] = X[i * ld + c] + step;
 }
 
+// The two rank-1 terms of the attention backward in one pass over X, K heads side by side:
+// X[i][c] = fl(fl(X[i][c] + fl(s1[i][c / Fh] a1[c])) + fl(s2[i][c / Fh] a2[c])), term 1 on rows
+// [0, n1), term 2 on rows [0, n2).  One thread per VEC adjacent columns (VEC divides Fh).
+template <int VEC>
+__global__ void rank1_pair_kernel(float *__restrict__ X, int64_t ld, int64_t rows, int F, int Fh, int K,
+                                  const float *__restrict__ s1, const float *__restrict__ a1, int64_t n1,
+                                  const float *__restrict__ s2, const float *__restrict__ a2, int64_t n2)
+{
+    const int per_row = F / VEC;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (t >= rows * per_row) return;
+    const int64_t i = t / per_row;
+    const int c = static_cast<int>(t - i * per_row) * VEC;
+    const int hk = c / Fh;
+    float x[VEC];
+    stream_load<VEC>(x, X + i * ld + c);
+    if (s1 && i < n1) {
+        const float u = s1[i * K + hk];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+            const float step = u * a1[c + q];
+            x[q] = x[q] + step;
+        }
+    }
+    if (s2 && i < n2) {
+        const float u = s2[i * K + hk];
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+            const float step = u * a2[c + q];
+            x[q] = x[q] + step;
+        }
+    }
+    stream_store<VEC>(X + i * ld + c, x);
+}
+
 // FWD: out = max(in, 0); otherwise out = gate > 0 ? in : 0.
 template <bool FWD>
 __global__ void relu_kernel(const float *__restrict__ in, int64_t ld_in, const float *__restrict__ gate,
@@ -935,6 +970,37 @@ extern "C" int32_t sylvie_rank1_add(float *X, int64_t ld_x, int64_t n, int32_t F
     const int64_t total = n * F;
     hipLaunchKernelGGL(rank1_add_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), X, ld_x, n, F, s, a);
+    SYLVIE_HIP_LAUNCH_CHECK(name);
+    return SYLVIE_OK;
+}
+
+extern "C" int32_t sylvie_rank1_add_heads(float *X, int64_t ld_x, int32_t F, int32_t heads, const float *s1,
+                                          const float *a1, int64_t n1, const float *s2, const float *a2,
+                                          int64_t n2, void *stream)
+{
+    using namespace sylvie;
+    const char *name = "sylvie_rank1_add_heads";
+    if (!s1) n1 = 0;
+    if (!s2) n2 = 0;
+    const int64_t rows = n1 > n2 ? n1 : n2;
+    if (n1 < 0 || n2 < 0 || rows >= (int64_t(1) << 31) || F < 1 || F > 65536 || ld_x < F)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
+    if (heads < 1 || F % heads != 0)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: heads must divide F (got %d, F = %d)", name, heads, F);
+    if (rows == 0) return SYLVIE_OK;
+    if (!X || (s1 && !a1) || (s2 && !a2)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
+    const int Fh = F / heads;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (Fh % 4 == 0 && ld_x % 4 == 0 && aligned(X, 16)) {
+        const int64_t total = rows * (F / 4);
+        hipLaunchKernelGGL(rank1_pair_kernel<4>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
+                           X, ld_x, rows, F, Fh, heads, s1, a1, n1, s2, a2, n2);
+    } else {
+        const int64_t total = rows * F;
+        if (total >= (int64_t(1) << 39)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: too many elements", name);
+        hipLaunchKernelGGL(rank1_pair_kernel<1>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
+                           X, ld_x, rows, F, Fh, heads, s1, a1, n1, s2, a2, n2);
+    }
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }

@@ -642,12 +642,15 @@ class AttentionLoop(LayerLoop):
 
     def __init__(self, parts, halo_owner, halo_row, X, J, W, att, dims, heads: int = 1,
                  slope: float = 0.2, chunk: int = 1024, exchange_first_layer: bool = False,
-                 wire: str = "1bit"):
+                 wire: str = "1bit", fused_sddmm: bool = True):
         super().__init__(parts, halo_owner, halo_row, X, J, W, "gcn", dims, chunk=chunk,
                          exchange_first_layer=exchange_first_layer, wire=wire, fused=False,
                          fused_bwd=False)
         self.model = "gat"
         self.att, self.heads, self.slope = att, heads, slope
+        # layers whose transposed aggregation also forms the sampled product dalpha = dZ_v . P_u
+        self.fused_sddmm = [False] + [fused_sddmm and B.sylvie_aggregate_csr_attention_sddmm_supported(dims[l], heads)
+                                      and max(dims[1:]) % 4 == 0 for l in range(1, len(dims))]
         if heads not in (1, 2, 4, 8):
             raise ValueError("heads must be 1, 2, 4 or 8")
         if any(d % heads for d in dims[1:]):
@@ -733,18 +736,27 @@ class AttentionLoop(LayerLoop):
                 dal, de = st.edge
                 da_dst, da_src = st.Ga[l]
                 sd, ss, al = st.s_dst[l], st.s_src[l], st.alpha[l]
-                B.sylvie_sddmm_heads(st.pieces, cl, dZ, ldz, P, h, F, K, dal)
-                B.sylvie_edge_softmax_bwd_heads(st.pieces, cl, al, dal, sd, ss, K, self.slope, de, st.ds_dst,
-                                                st.ws_att)
+                planT = dict(chunk=self.chunk, long_rows=lr if nt else None, long_ptr=lp if nt else None,
+                             n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
+                             workspace=st.ws_aggT if nt else None)
                 # column sums of de and the transposed aggregation read de / alpha in forward
                 # entry order through the transposition's entry map
-                B.sylvie_segment_sum_heads(st.piecesT, de, st.perm, K, st.ds_src, st.ws_att)
-                B.sylvie_aggregate_csr_attention(rpT, clT, al, st.perm, K, n_loc, dZ, ldz, h, dP, ldp,
-                                                 s1=st.ds_src, a1=a_src, n1=n_loc,
-                                                 s2=st.ds_dst, a2=a_dst, n2=st.n_in, chunk=self.chunk,
-                                                 long_rows=lr if nt else None, long_ptr=lp if nt else None,
-                                                 n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
-                                                 workspace=st.ws_aggT if nt else None)
+                if self.fused_sddmm[l]:
+                    # the transposed aggregation gathers dZ_v per entry anyway: it also forms dalpha
+                    B.sylvie_aggregate_csr_attention_sddmm(rpT, clT, al, st.perm, K, n_loc, dZ, ldz, h, dP, ldp,
+                                                           P, h, dal, **planT)
+                    B.sylvie_edge_softmax_bwd_heads(st.pieces, cl, al, dal, sd, ss, K, self.slope, de,
+                                                    st.ds_dst, st.ws_att)
+                    B.sylvie_segment_sum_heads(st.piecesT, de, st.perm, K, st.ds_src, st.ws_att)
+                    B.sylvie_rank1_add_heads(dP, ldp, h, K, st.ds_src, a_src, n_loc, st.ds_dst, a_dst, st.n_in)
+                else:
+                    B.sylvie_sddmm_heads(st.pieces, cl, dZ, ldz, P, h, F, K, dal)
+                    B.sylvie_edge_softmax_bwd_heads(st.pieces, cl, al, dal, sd, ss, K, self.slope, de,
+                                                    st.ds_dst, st.ws_att)
+                    B.sylvie_segment_sum_heads(st.piecesT, de, st.perm, K, st.ds_src, st.ws_att)
+                    B.sylvie_aggregate_csr_attention(rpT, clT, al, st.perm, K, n_loc, dZ, ldz, h, dP, ldp,
+                                                     s1=st.ds_src, a1=a_src, n1=n_loc,
+                                                     s2=st.ds_dst, a2=a_dst, n2=st.n_in, **planT)
                 B.sylvie_scaled_column_sum_heads(P, h, st.n_in, h, K, st.ds_dst, da_dst, st.ws_col,
                                                  s2=st.ds_src, n2=n_loc, out2=da_src)
                 ht = st.Htil[l - 1]

@@ -325,6 +325,70 @@ def test_attention_aggregation_parity(oracle, K, F, chunk):
         assert same(Y, Z)
 
 
+@pytest.mark.parametrize("chunk", [0, 64])
+@pytest.mark.parametrize("K,F", [(1, 16), (1, 64), (1, 256), (2, 32), (2, 128), (4, 16), (4, 64), (8, 16), (8, 32)])
+def test_attention_aggregation_with_sampled_product(oracle, K, F, chunk):
+    """The transposed aggregation that also forms dalpha = dZ_v . P_u: the aggregate equals the
+    plain call's bit for bit, the product agrees with the oracle's sampled product over the
+    forward pattern per head, and every entry is written."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    s = _heads_setup(oracle, K, F, 64, 7 * K + F)
+    rp, cl, n_in, n_loc, nnz, h, ld = s["rp"], s["cl"], s["n_in"], s["n_loc"], s["nnz"], s["h"], s["ld"]
+    assert B.sylvie_aggregate_csr_attention_sddmm_supported(h, K)
+    rng = np.random.default_rng(K * 100 + F)
+    al = rng.random((nnz, K)).astype(np.float32)
+    ald, Pd, dZd = dev(al.reshape(-1)), dev(s["P"]), dev(s["dZ"])
+    rpT, clT, _ = s["opT"]
+    perm = s["perm"]
+    kw = {}
+    if chunk:
+        lr, lp, nt = GE.long_row_plan(rpT, chunk)
+        assert nt > 0
+        kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                  workspace=torch.empty(max(1, nt) * h, device=DEV))
+    dP = torch.full((n_loc, ld), 5.0, device=DEV)
+    dal = torch.full((nnz * K + 3,), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_attention_sddmm(rpT, clT, ald, perm, K, n_loc, dZd, ld, h, dP, ld, Pd, ld, dal, **kw)
+    dP0 = torch.full((n_loc, ld), 5.0, device=DEV)
+    B.sylvie_aggregate_csr_attention(rpT, clT, ald, perm, K, n_loc, dZd, ld, h, dP0, ld, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(dP.view(torch.int32), dP0.view(torch.int32))
+    assert bool(torch.isnan(dal[nnz * K:]).all())
+    got = dal[: nnz * K].cpu().numpy().reshape(nnz, K)
+    assert not np.isnan(got).any()
+    for k in range(K):
+        sl = slice(k * F, (k + 1) * F)
+        ref, S = oracle.sddmm(rp, cl, np.ascontiguousarray(s["dZ"][:, sl]), np.ascontiguousarray(s["P"][:, sl]), F,
+                              want_S=True)
+        close(got[:, k], ref, S, ("dalpha", k))
+    # shapes without such a launch are refused, not mis-computed
+    assert not B.sylvie_aggregate_csr_attention_sddmm_supported(24, 3)
+    assert not B.sylvie_aggregate_csr_attention_sddmm_supported(512, 2)
+    with pytest.raises(B.SylvieError):
+        B.sylvie_aggregate_csr_attention_sddmm(rpT, clT, ald, perm, 1, n_loc, dZd, ld, 24, dP, ld, Pd, ld, dal)
+
+
+def test_rank1_add_heads_equals_single_calls():
+    from paper_2303_01277_amd import binding as B
+    rng = np.random.default_rng(3)
+    for K, F, n1, n2 in ((4, 64, 1000, 700), (2, 7, 333, 333), (1, 5, 10, 0), (8, 4, 64, 100)):
+        h = K * F
+        ld = h + (3 if h % 2 else 4)
+        n = max(n1, n2)
+        X = dev(make_rows(rng, n + 2, ld, "normal"))
+        s1, s2 = torch.randn(n1 * K, device=DEV), torch.randn(max(n2, 1) * K, device=DEV)
+        a1, a2 = torch.randn(h, device=DEV), torch.randn(h, device=DEV)
+        want = X.clone()
+        for k in range(K):
+            B.sylvie_rank1_add(want[:, k * F:], ld, n1, F, s1.view(-1, K)[:, k].contiguous(), a1[k * F:])
+            if n2:
+                B.sylvie_rank1_add(want[:, k * F:], ld, n2, F, s2.view(-1, K)[:, k].contiguous(), a2[k * F:])
+        B.sylvie_rank1_add_heads(X, ld, h, K, s1, a1, n1, s2 if n2 else None, a2 if n2 else None, n2)
+        torch.cuda.synchronize()
+        assert torch.equal(X.view(torch.int32), want.view(torch.int32)), (K, F)
+
+
 def test_attention_aggregation_rejects_bad_arguments():
     from paper_2303_01277_amd import binding as B
     rp = dev(np.array([0, 1, 2], np.int64)); cl = dev(np.array([0, 1], np.int32))

@@ -22,7 +22,7 @@ def make_att(wl, seed):
              torch.randn(w.shape[1], generator=g) / w.shape[1] ** 0.5) for w in wl.W]
 
 
-def build_attention_loop(wl, att, heads, wire, chunk=128):
+def build_attention_loop(wl, att, heads, wire, chunk=128, fused_sddmm=True):
     from paper_2303_01277_amd.trainer import AttentionLoop
     parts = wl.parts
     for p in parts:
@@ -36,7 +36,8 @@ def build_attention_loop(wl, att, heads, wire, chunk=128):
         rows = [p.halo_row for p in parts]
     return AttentionLoop(parts, owner, rows, [x.to(DEV) for x in wl.X], [j.to(DEV) for j in wl.J],
                          [w.to(DEV) for w in wl.W], [(a.to(DEV), b.to(DEV)) for a, b in att],
-                         wl.spec.dims, heads=heads, chunk=chunk, exchange_first_layer=True, wire=wire)
+                         wl.spec.dims, heads=heads, chunk=chunk, exchange_first_layer=True, wire=wire,
+                         fused_sddmm=fused_sddmm)
 
 
 def rel(got, ref):
@@ -113,14 +114,19 @@ def oracle_layer(oracle, rp, cl, n_in, ht, W, a_dst, a_src, heads, slope, relu, 
 
 
 @pytest.mark.parametrize("heads,wire", [(1, "1bit"), (2, "1bit"), (2, "4bit"), (4, "1bit"), (8, "1bit")])
+@pytest.mark.parametrize("fused_sddmm", [True, False])
 @pytest.mark.parametrize("cfg,n_nodes", [("tiny", None), ("stress", 12_000)])
-def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire):
+def test_attention_loop_teacher_forced(oracle, cfg, n_nodes, heads, wire, fused_sddmm):
+    """fused_sddmm: the transposed aggregation also forms the sampled product (shapes that have
+    such a launch: all but tiny's 8 heads of 8 columns); otherwise the separate call."""
     wl = workload(cfg, n_nodes)
     att = make_att(wl, 5)
     pdata = to_partdata(wl)
     for pd in pdata:
         OL.build_operator(pd, "gat")
-    loop = build_attention_loop(wl, att, heads, wire)
+    loop = build_attention_loop(wl, att, heads, wire, fused_sddmm=fused_sddmm)
+    assert not any(loop.fused_sddmm) if not fused_sddmm else \
+        all(loop.fused_sddmm[1:]) == (loop.dims[1] // heads >= 16)
     bits = loop.bits
     loop.record = {}
     seed = 0x6A7
