@@ -223,6 +223,13 @@ class SnapLoop:
                             st.dself.view(-1)[: st.n_in * dd].view(st.n_in, dd)),
                         "dHtil_pre": np_c(st.dHtil[l - 1]),
                     }
+                    if getattr(loop, "model", "") == "gat":
+                        # the attention backward's per-layer scratch, still holding layer l
+                        h, n_loc = loop.dims[l], st.n_in + st.n_halo
+                        snaps[(l, me)].update(
+                            dal=np_c(st.edge[0]), de=np_c(st.edge[1]), ds_dst=np_c(st.ds_dst),
+                            ds_src=np_c(st.ds_src), dP=np_c(st.dP[:, :h]),
+                            dZ_att=np_c(st.dZg[:, :h]) if l < loop.L else np_c(Jl))
 
         B.sylvie_quantize_1bit_bwd = hook
         B.sylvie_quantize_bbit_bwd = hook_b
