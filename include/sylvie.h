@@ -64,6 +64,20 @@ const char *sylvie_status_string(int32_t status);
 /* Thread-local detail of the last error returned on this thread ("" if none). */
 const char *sylvie_last_error(void);
 
+/*
+ * Seed offset in device memory, for launches recorded in a HIP graph.  The quantizing entry
+ * points take their seed by value, so a recorded launch would draw the same bits on every
+ * replay.  After sylvie_seed_offset_source(p), p a DEVICE pointer to one uint64, every quantizing
+ * call made by this thread (sylvie_quantize_1bit_*, sylvie_quantize_bbit_*,
+ * sylvie_aggregate_csr_bwd_quantize*) uses the seed `seed + *p` (wrapping), with *p read by the
+ * kernel when it runs: advance *p between replays (any kernel or copy on the same stream) and
+ * each replay is the call with the next seed, bit for bit what the call with that seed passed
+ * by value writes.  p must stay valid while such work is pending; NULL (the initial state)
+ * turns the offset off.  This is the one pointer the library keeps between calls; it is
+ * thread-local, like the error text.
+ */
+int32_t sylvie_seed_offset_source(const uint64_t *offset);
+
 /* uint64 words of one wire row: ceil(d / 64) + 1 (the smallest ld_wire). */
 int64_t sylvie_wire_row_words(int32_t d);
 

@@ -69,6 +69,7 @@ def lib():
                      "sylvie_edge_softmax_bwd_heads", "sylvie_segment_sum_heads",
                      "sylvie_scaled_column_sum_heads", "sylvie_aggregate_csr_attention",
                      "sylvie_rank1_add_heads", "sylvie_aggregate_csr_attention_sddmm",
+                     "sylvie_seed_offset_source",
                      "sylvie_aggregate_csr_attention_sddmm_supported",
                      "sylvie_graph_local_index", "sylvie_graph_relabel_columns",
                      "sylvie_graph_rows_in_owner", "sylvie_graph_recv_sets",
@@ -511,6 +512,11 @@ def sylvie_aggregate_csr_attention(rowptr, col, w, w_index, heads, n_rows, X, ld
         C.c_int32(chunk), _ptr(long_rows, torch.int32, "long_rows"), _ptr(long_ptr, torch.int64, "long_ptr"),
         C.c_int64(n_long), C.c_int64(n_tasks), _ptr(workspace, torch.float32, "workspace"),
         C.c_size_t(ws_bytes), _stream()))
+
+
+def sylvie_seed_offset_source(offset):
+    """offset: a one-element int64 GPU tensor (kept alive by the caller) or None."""
+    _check(lib().sylvie_seed_offset_source(_ptr(offset, torch.int64, "offset")))
 
 
 def sylvie_rank1_add_heads(X, ld_x, F, heads, s1, a1, n1, s2=None, a2=None, n2=0):

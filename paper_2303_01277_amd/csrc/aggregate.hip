@@ -80,7 +80,7 @@ struct AggArgs {
     // epilogue "quantize": wire row (v - row_begin) <- quantized row v
     uint64_t *wire_out;
     int64_t ldw_out;            // row stride of wire_out in 64-bit words
-    uint32_t ckey;
+    CallKey ck;
     // epilogue "integrate": row v += dequantized wire rows seg_rows[seg_ptr[v - row_begin] ..)
     const int64_t *seg_ptr;
     const int32_t *seg_rows;
@@ -517,6 +517,7 @@ __global__ __launch_bounds__((waves_per_block<WB, EPI>() * kWave)) void aggregat
                                                                                               int64_t n_tasks)
 {
     constexpr int kWPB = waves_per_block<WB, EPI>();
+    [[maybe_unused]] const uint32_t ckey = EPI == kEpiQuantize ? call_key_of(a.ck) : 0u;
     // WB = bits per element of the wire this launch reads (EPI store: the halo columns;
     // EPI integrate: the received gradients) or writes (EPI quantize); 0 = no wire
     constexpr int WIRE = EPI == kEpiStore ? WB : 0;            // wire read by the gather itself
@@ -609,10 +610,10 @@ __global__ __launch_bounds__((waves_per_block<WB, EPI>() * kWave)) void aggregat
     }
     if constexpr (EPI == kEpiQuantize) {
         if constexpr (WB == 1)
-            quantize_row_lds(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
+            quantize_row_lds(stage[wave], a.d, ckey, static_cast<uint32_t>(local),
                              a.wire_out + local * a.ldw_out, lane);
         else
-            quantize_row_lds_bbit<WB>(stage[wave], a.d, a.ckey, static_cast<uint32_t>(local),
+            quantize_row_lds_bbit<WB>(stage[wave], a.d, ckey, static_cast<uint32_t>(local),
                                       a.wire_out + local * a.ldw_out,
                                       reinterpret_cast<uint32_t *>(stage[wave] + kRowStage), lane);
     }
@@ -624,6 +625,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
 {
     // EPI quantize: per wave d floats (rounded up to 4) and, for b > 1, d / 4 + 4 image dwords
     extern __shared__ __align__(16) float rstage[];
+    [[maybe_unused]] const uint32_t ckey = EPI == kEpiQuantize ? call_key_of(a.ck) : 0u;
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kAgWavesPerBlock + wave;
@@ -664,10 +666,10 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
     }
     if constexpr (EPI == kEpiQuantize) {
         if constexpr (WB == 1)
-            quantize_row_lds(srow, a.d, a.ckey, static_cast<uint32_t>(local),
+            quantize_row_lds(srow, a.d, ckey, static_cast<uint32_t>(local),
                              a.wire_out + local * a.ldw_out, lane);
         else
-            quantize_row_lds_bbit<WB>(srow, a.d, a.ckey, static_cast<uint32_t>(local),
+            quantize_row_lds_bbit<WB>(srow, a.d, ckey, static_cast<uint32_t>(local),
                                       a.wire_out + local * a.ldw_out,
                                       reinterpret_cast<uint32_t *>(srow + d4), lane);
     }
@@ -746,7 +748,7 @@ struct AggExtra {
     int64_t row_begin = 0;
     int epi = kEpiStore;
     uint64_t *wire_out = nullptr;   // quantize epilogue
-    uint32_t ckey = 0;
+    CallKey ck = {0u, 0u, 0ull, nullptr};
     const int64_t *seg_ptr = nullptr;
     const int32_t *seg_rows = nullptr;
     const int32_t *row_order = nullptr;
@@ -817,7 +819,7 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     a.ldw = a.ldw_out = x.ld_wire ? x.ld_wire : row_words;
     a.row_begin = x.row_begin;
     a.wire_out = x.wire_out;
-    a.ckey = x.ckey;
+    a.ck = x.ck;
     a.seg_ptr = x.seg_ptr;
     a.seg_rows = x.seg_rows;
     a.row_order = x.row_order;
@@ -993,7 +995,7 @@ static int32_t bwd_quantize_call(const char *name, int32_t bits, const int64_t *
     x.epi = kEpiQuantize;
     x.wire_out = wire_out;
     x.ld_wire = ld_wire;
-    x.ckey = call_key(seed, stream_id);
+    x.ck = make_call_key(seed, stream_id);
     x.row_order = row_order;
     x.bits = bits;
     return aggregate_common(name, rowptrT, colT, wT, row_scale, col_scale, n_rows, dY, ld_dy, d, nullptr,

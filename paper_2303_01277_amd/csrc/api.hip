@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include "common.hpp"
+#include "rounding.hpp"
 
 namespace sylvie {
 
@@ -25,7 +26,23 @@ int32_t fail(int32_t code, const char *fmt, ...)
     return code;
 }
 
+// Device-resident seed offset of this thread's quantizing calls (sylvie_seed_offset_source).
+static thread_local const uint64_t *g_seed_offset = nullptr;
+
+CallKey make_call_key(uint64_t seed, uint32_t stream_id)
+{
+    return CallKey{call_key(seed, stream_id), stream_id, seed, g_seed_offset};
+}
+
 }  // namespace sylvie
+
+extern "C" int32_t sylvie_seed_offset_source(const uint64_t *offset)
+{
+    if (offset && !sylvie::aligned(offset, 8))
+        return sylvie::fail(SYLVIE_ERR_BAD_ALIGNMENT, "sylvie_seed_offset_source: the offset needs 8-byte alignment");
+    sylvie::g_seed_offset = offset;
+    return SYLVIE_OK;
+}
 
 extern "C" int32_t sylvie_version(void) { return 100; }
 

@@ -31,8 +31,9 @@ constexpr int kBbRowsPerWave = 4;
 template <int BITS, int VEC, int P>
 __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
+    int64_t row_offset, int64_t n_rows, CallKey ck, uint64_t *__restrict__ wire)
 {
+    const uint32_t ckey = call_key_of(ck);
     constexpr int R = kBbRowsPerWave;
     constexpr int kDwords = P * 64 * VEC * BITS / 32;          // packed codes of a full-width row
     __shared__ __align__(8) uint32_t image[kBbWavesPerBlock][kDwords + 2];
@@ -136,8 +137,9 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_kernel(
 template <int BITS>
 __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void quantize_bbit_wide_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire)
+    int64_t row_offset, int64_t n_rows, CallKey ck, uint64_t *__restrict__ wire)
 {
+    const uint32_t ckey = call_key_of(ck);
     __shared__ __align__(8) uint32_t image[kBbWavesPerBlock][2 * BITS];   // 64 codes
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
@@ -464,7 +466,7 @@ static bool bits_ok(int32_t bits)
 
 template <int BITS, int VEC>
 static void launch_quantize(const float *src, int64_t ld, int d, const int32_t *idx, int64_t row_offset,
-                            int64_t n_rows, uint32_t ckey, uint64_t *wire, hipStream_t st)
+                            int64_t n_rows, const CallKey &ckey, uint64_t *wire, hipStream_t st)
 {
     const int P = (d + 64 * VEC - 1) / (64 * VEC);
     const int64_t per_block = kBbWavesPerBlock * kBbRowsPerWave;
@@ -490,7 +492,7 @@ static void launch_quantize(const float *src, int64_t ld, int d, const int32_t *
 
 template <int BITS>
 static void launch_quantize_bits(const float *src, int64_t ld, int d, const int32_t *idx,
-                                 int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *wire,
+                                 int64_t row_offset, int64_t n_rows, const CallKey &ckey, uint64_t *wire,
                                  hipStream_t st)
 {
     const bool v4 = d % 4 == 0 && ld % 4 == 0 && aligned(src, 16);
@@ -538,7 +540,7 @@ static int32_t quantize_bbit_common(const char *name, const float *src, int64_t 
         else
             hipLaunchKernelGGL(copy_rows_out_kernel<1>, grid, block, 0, st, src, ld, d, idx, row_offset, n_rows, w32);
     } else {
-        const uint32_t ckey = call_key(seed, stream_id);
+        const CallKey ckey = make_call_key(seed, stream_id);
         if (bits == 2) launch_quantize_bits<2>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);
         else if (bits == 4) launch_quantize_bits<4>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);
         else launch_quantize_bits<8>(src, ld, d, idx, row_offset, n_rows, ckey, wire, st);

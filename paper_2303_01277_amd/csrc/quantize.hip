@@ -60,8 +60,9 @@ constexpr int rows_per_wave(int P) { return 64 / (P + 1) < 4 ? 64 / (P + 1) : 4;
 template <int P, bool FULL>
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire, int64_t ldw)
+    int64_t row_offset, int64_t n_rows, CallKey ck, uint64_t *__restrict__ wire, int64_t ldw)
 {
+    const uint32_t ckey = call_key_of(ck);
     constexpr int R = rows_per_wave(P);
     static_assert(R >= 1 && R * (P + 1) <= 64, "one store must hold all words of a wave");
     const int lane = lane_id();
@@ -160,8 +161,9 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_kernel(
 // Any width: the row is read twice (the second read hits the cache).
 __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kernel(
     const float *__restrict__ src, int64_t ld, int d, const int32_t *__restrict__ idx,
-    int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *__restrict__ wire, int64_t ldw)
+    int64_t row_offset, int64_t n_rows, CallKey ck, uint64_t *__restrict__ wire, int64_t ldw)
 {
+    const uint32_t ckey = call_key_of(ck);
     const int lane = lane_id();
     const int wave = uniform(static_cast<int>(threadIdx.x) >> 6);
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(kWavesPerBlock *kWave) void quantize_rows_wide_kern
 
 template <int P, bool FULL>
 static void launch_rows(const float *src, int64_t ld, int d, const int32_t *idx,
-                        int64_t row_offset, int64_t n_rows, uint32_t ckey, uint64_t *wire,
+                        int64_t row_offset, int64_t n_rows, const CallKey &ckey, uint64_t *wire,
                         int64_t ldw, hipStream_t st)
 {
     const int64_t rows_per_block = rows_per_wave(P) * kWavesPerBlock;
@@ -234,7 +236,7 @@ static int32_t quantize_common(const char *name, const float *src, int64_t ld, i
         const int32_t rc = v.finish();
         if (rc != SYLVIE_OK) return rc;
     }
-    const uint32_t ckey = call_key(seed, stream_id);
+    const CallKey ckey = make_call_key(seed, stream_id);
     const int P = (d + 63) / 64;
 #define SYLVIE_Q_CASE(p)                                                                       \
     case p:                                                                                    \

@@ -24,11 +24,30 @@ __host__ __device__ __forceinline__ uint32_t mix32(uint32_t x)
     return x;
 }
 
-static uint32_t call_key(uint64_t seed, uint32_t stream_id)
+__host__ __device__ __forceinline__ uint32_t call_key(uint64_t seed, uint32_t stream_id)
 {
     uint32_t k = mix32(static_cast<uint32_t>(seed) ^ kDomain);
     k = mix32(k ^ static_cast<uint32_t>(seed >> 32));
     return mix32(k ^ stream_id);
+}
+
+// The key of one quantizing call as its kernels receive it.  Normally the host has hashed
+// (seed, stream) into `key`.  When the caller has named a device-resident seed offset
+// (sylvie_seed_offset_source), `offset` points at it and the kernel hashes
+// (seed + *offset, stream) itself, on the scalar unit, once per wavefront: a launch recorded in
+// a graph then draws the bits of a new seed on every replay.
+struct CallKey {
+    uint32_t key;
+    uint32_t stream_id;
+    uint64_t seed;
+    const uint64_t *offset;
+};
+CallKey make_call_key(uint64_t seed, uint32_t stream_id);   // api.hip
+__device__ __forceinline__ uint32_t call_key_of(const CallKey &k)
+{
+    if (!k.offset) return k.key;
+    const uint64_t s = k.seed + *k.offset;
+    return call_key(s, k.stream_id);
 }
 
 // Top 24 bits of the second product: the draw for one element.  Both xor-shifts

@@ -802,9 +802,17 @@ __global__ void transform_bwd_g_reduce_kernel(const float *__restrict__ part, in
 
 // Row slabs of the weight-gradient product: enough of them to fill the chip even when
 // the output is a single tile, at most 256 (the partial products go through a workspace).
-static int g_slabs(int64_t n)
+// Slabs of 512 rows by default; a small partition whose output has few tiles gets shorter slabs
+// (down to 64 rows) until about 512 workgroups exist: with one 64 x 64 output tile and 10 000
+// rows, 20 workgroups walked 512 rows each (38 us) where 155 now walk 64 (the launch is then as
+// short as the other launches of such a step).
+static int g_slabs(int64_t n, int K, int h)
 {
-    const int64_t s = (n + 511) / 512;
+    const int64_t tiles = static_cast<int64_t>((K + BM - 1) / BM) * ((h + BN - 1) / BN);
+    int64_t s = (n + 511) / 512;
+    const int64_t fill = (512 + tiles - 1) / tiles, shortest = n / 64;
+    const int64_t more = fill < shortest ? fill : shortest;
+    if (more > s) s = more;
     return static_cast<int>(s < 1 ? 1 : (s > 256 ? 256 : s));
 }
 
@@ -857,7 +865,7 @@ extern "C" int32_t sylvie_transform_fwd(const float *A1, int64_t ld_a1, int32_t 
 
 extern "C" size_t sylvie_transform_bwd_workspace_bytes(int32_t k1, int32_t k2, int32_t h, int64_t n)
 {
-    return static_cast<size_t>(sylvie::g_slabs(n)) * static_cast<size_t>(k1 + k2) *
+    return static_cast<size_t>(sylvie::g_slabs(n, k1 + k2, h)) * static_cast<size_t>(k1 + k2) *
            static_cast<size_t>(h) * sizeof(float);
 }
 
@@ -889,7 +897,7 @@ extern "C" int32_t sylvie_transform_bwd(const float *A1, int64_t ld_a1, int32_t 
     const int K = k1 + k2;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (G) {
-        const int slabs = g_slabs(n);
+        const int slabs = g_slabs(n, K, h);
         int64_t rps = (n + slabs - 1) / slabs;
         rps = (rps + BK - 1) / BK * BK;
         const dim3 grid(static_cast<unsigned>((K + BM - 1) / BM), static_cast<unsigned>((h + BN - 1) / BN),

@@ -159,8 +159,10 @@ class LayerLoop:
             st.wire = torch.empty(max(1, part.n_halo) * Wd, dtype=torch.int64, device=dev)
             st.ws_agg = torch.empty(max(1, plan[2]) * dmax, dtype=torch.float32, device=dev)
             st.ws_aggT = torch.empty(max(1, planT[2]) * dmax, dtype=torch.float32, device=dev)
-            kmax = max(dims[l - 1] * (2 if model == "sage" else 1) for l in range(1, self.L + 1))
-            nbytes = B.sylvie_transform_bwd_workspace_bytes(kmax, 0, max(dims[1:]), part.n_in)
+            # per layer: the slab count, hence the size, depends on the layer's own widths
+            nbytes = max(B.sylvie_transform_bwd_workspace_bytes(dims[l - 1] * (2 if model == "sage" else 1), 0,
+                                                                dims[l], part.n_in)
+                         for l in range(1, self.L + 1))
             st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             for l in range(1, self.L + 1):
                 # the float halo block below the inner rows exists only when it is written
@@ -256,10 +258,30 @@ class LayerLoop:
            long_ptr=lp if nt else None, n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
            workspace=ws if nt else None, row_order=order)
 
+    def _each(self):
+        """The partitions of one phase whose launches are independent of each other (each
+        writes only its own buffers, or disjoint parts of a peer's).  Normally all on the
+        caller's stream; with `part_streams` set (a step being recorded as a graph) partition p's
+        launches go to stream p, forked from the caller's stream at the start of the phase and
+        joined to it at the end, so that the recorded graph runs the partitions side by side."""
+        streams = getattr(self, "part_streams", None)
+        if not streams:
+            yield from enumerate(self.parts)
+            return
+        cur = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(cur)
+        for me, st in enumerate(self.parts):
+            streams[me].wait_event(fork)
+            with torch.cuda.stream(streams[me]):
+                yield me, st
+        for s in streams:
+            cur.wait_stream(s)
+
     def _exchange_forward(self, l, d, Wd, seed, pair_seed):
         """Alg. 1, the exchange of layer l: every owner quantizes the rows its peers need; the
         receiver keeps the wire (fused aggregation) or recovers the rows into its halo block."""
-        for me, st in enumerate(self.parts):
+        for me, st in self._each():
             ht = st.Htil[l - 1]
             for b in st.blocks:
                 n = b.j1 - b.j0
@@ -321,7 +343,7 @@ class LayerLoop:
             d = self.dims[l - 1]
             Wd = self._words(d)
             self._exchange_forward(l, d, Wd, seed, pair_seed)
-            for st in self.parts:
+            for _, st in self._each():
                 ht, Z = st.Htil[l - 1], st.Z[l - 1]
                 if self.fused:
                     rp, cl, w = st.op
@@ -357,7 +379,7 @@ class LayerLoop:
             d, h = self.dims[l - 1], self.dims[l]
             need_dx = l > 1 or self.exchange_first_layer
             Wd = self._words(d)
-            for st in self.parts:
+            for _, st in self._each():
                 relu = l != self.L
                 Hout = st.Htil[l] if l < self.L else st.out
                 Jl = st.J if l == self.L else st.dHtil[l]
@@ -389,7 +411,7 @@ class LayerLoop:
     def _backward_exchange_fused(self, l, d, Wd, seed, pair_seed):
         """Halo gradients: aggregate + quantize straight into the owner's inbound wire;
         then inner gradients: aggregate + add the inbound wire rows, one store per row."""
-        for me, st in enumerate(self.parts):
+        for me, st in self._each():
             rpT, clT, wT = st.opT
             dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
             for b in st.blocks:
@@ -403,7 +425,7 @@ class LayerLoop:
                     n_long=int(lr.numel()) if nt else 0, n_tasks=nt,
                     workspace=st.ws_aggT if nt else None, row_order=b.orderT, bits=self.bits)
                 self._keep(("bwd", l, me, b.j0), wire, b.j1 - b.j0, Wd)
-        for st in self.parts:
+        for _, st in self._each():
             rpT, clT, wT = st.opT
             dZ = st.dZ.view(-1)[: st.n_in * d].view(st.n_in, d)
             dself = None
@@ -631,6 +653,47 @@ class LayerLoop:
         return loss
 
 
+class StepGraph:
+    """One epoch of a layer loop (forward + backward, sequential mode) recorded once as a HIP
+    graph and replayed: for small partitions the step is bound by its launches, not its kernels.
+    The quantizing calls take their seed by value, so the graph is recorded with the library's
+    device-resident seed offset switched on and ends with a kernel that advances it: replay k
+    (k = 0, 1, ...) is the step with pair seeds pair_seed(seed, a, b) + k, bit for bit."""
+
+    def __init__(self, loop: "LayerLoop", seed: int,
+                 pair_seed: Callable[[int, int, int], int] = default_pair_seed):
+        if loop.pipeline:
+            raise ValueError("a recorded step runs in sequential mode")
+        self.loop = loop
+        self.epoch = torch.zeros(1, dtype=torch.int64, device=loop.dev)
+        cur = torch.cuda.current_stream()
+        side = torch.cuda.Stream()
+        B.sylvie_seed_offset_source(self.epoch)
+        if len(loop.parts) > 1 and not isinstance(loop, AttentionLoop):
+            loop.part_streams = [torch.cuda.Stream() for _ in loop.parts]
+        try:
+            # one eager step on a side stream first, as the tensor library asks before a capture
+            side.wait_stream(cur)
+            with torch.cuda.stream(side):
+                loop.step(seed, pair_seed)
+            cur.wait_stream(side)
+            torch.cuda.synchronize()
+            self.graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.graph):
+                loop.step(seed, pair_seed)
+                self.epoch.add_(1)          # an ordinary kernel: no memset node in the graph
+        finally:
+            B.sylvie_seed_offset_source(None)
+            loop.part_streams = None
+
+    def replay(self):
+        self.graph.replay()
+
+    def reset(self, k: int = 0):
+        """The next replay is replay number k."""
+        self.epoch.fill_(k)
+
+
 class AttentionLoop(LayerLoop):
     """The attention model (GAT) under the same exchange: layer l transforms inner and recovered
     halo rows, P = Htilde W, scores every operator entry with leaky_relu(P_v . a_dst + P_u . a_src),
@@ -675,7 +738,8 @@ class AttentionLoop(LayerLoop):
             n_ws = max(B.sylvie_edge_softmax_heads_workspace_bytes(st.pieces[1].numel(), st.n_in, K) // 4,
                        (st.piecesT[1].numel() + n_loc) * K, 1)
             st.ws_att = torch.empty(n_ws, dtype=torch.float32, device=dev)
-            nbytes = B.sylvie_transform_bwd_workspace_bytes(max(dims), 0, max(dims[1:]), n_loc)
+            nbytes = max(B.sylvie_transform_bwd_workspace_bytes(dims[l - 1], 0, dims[l], n_loc)
+                         for l in range(1, self.L + 1))
             st.ws_g = torch.empty(nbytes // 4, dtype=torch.float32, device=dev)
             st.Ga = [None] + [(torch.empty(dims[l], dtype=torch.float32, device=dev),
                                torch.empty(dims[l], dtype=torch.float32, device=dev))

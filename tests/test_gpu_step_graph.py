@@ -1,0 +1,95 @@
+"""The layer loop's step recorded as a HIP graph: every replay must equal the eager step with
+the matching seed bit for bit, with eager work and synchronisations between the replays; and the
+library's device-resident seed offset must equal a seed passed by value."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layers as OL
+from synth import CONFIGS, build_workload, scaled
+from test_gpu_layers import build_loop, o_quantize
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def outputs(loop):
+    out = []
+    for st in loop.parts:
+        out += [st.out.clone(), st.dHtil[0][: st.n_in].clone()] + [g.clone() for g in st.G[1:]]
+        out += [st.wire.clone()]
+    return out
+
+
+def same(a, b):
+    return all(torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x,
+                           y.view(torch.int32) if y.dtype == torch.float32 else y) for x, y in zip(a, b))
+
+
+def test_seed_offset_equals_seed_by_value(oracle):
+    """Wire rows written with (seed, offset in device memory) are those of seed + offset passed
+    by value, and of the oracle with that seed; the offset is read when the kernel runs."""
+    from paper_2303_01277_amd import binding as B
+    rng = np.random.default_rng(5)
+    n, d = 3000, 200
+    X = rng.standard_normal((n, d)).astype(np.float32)
+    Xd = torch.from_numpy(X).to(DEV)
+    W1 = B.sylvie_wire_row_words(d)
+    seed, sid = 0x1234_5678_9ABC, 7
+    off = torch.zeros(1, dtype=torch.int64, device=DEV)
+    B.sylvie_seed_offset_source(off)
+    try:
+        for k in (0, 1, 5, 2 ** 33 + 3):
+            off.fill_(k)
+            w_off = torch.full((n * W1,), -1, dtype=torch.int64, device=DEV)
+            B.sylvie_quantize_1bit_fwd(Xd, d, d, None, 0, n, seed, sid, w_off)
+            w4 = torch.full((n * B.sylvie_wire_row_words_bits(d, 4),), -1, dtype=torch.int64, device=DEV)
+            B.sylvie_quantize_bbit_fwd(Xd, d, d, None, 0, n, 4, seed, sid, w4)
+            torch.cuda.synchronize()
+            ref = o_quantize(oracle, 1, X, d, n, seed + k, sid)
+            assert np.array_equal(w_off.cpu().numpy().view(np.uint64).reshape(n, W1), ref), k
+            ref4 = o_quantize(oracle, 4, X, d, n, seed + k, sid)
+            assert np.array_equal(w4.cpu().numpy().view(np.uint64).reshape(ref4.shape), ref4), k
+    finally:
+        B.sylvie_seed_offset_source(None)
+    # switched off again: the seed alone
+    w = torch.full((n * W1,), -1, dtype=torch.int64, device=DEV)
+    off.fill_(9)
+    B.sylvie_quantize_1bit_fwd(Xd, d, d, None, 0, n, seed, sid, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(w.cpu().numpy().view(np.uint64).reshape(n, W1), o_quantize(oracle, 1, X, d, n, seed, sid))
+
+
+@pytest.mark.parametrize("cfg,n_nodes,wire,fused_bwd", [("tiny", None, "1bit", True), ("tiny", None, "1bit", False),
+                                                      ("co_purchase", 12_000, "1bit", True),
+                                                      ("citation", 12_000, "4bit", True)])
+def test_recorded_step_replays_equal_eager_steps(cfg, n_nodes, wire, fused_bwd):
+    from paper_2303_01277_amd.trainer import StepGraph
+    spec = CONFIGS[cfg] if n_nodes is None else scaled(CONFIGS[cfg], n_nodes)
+    wl = build_workload(spec)
+    loop = build_loop(wl, wire=wire, fused=True, fused_bwd=fused_bwd)
+    seed = 0xC0FFEE
+    graph = StepGraph(loop, seed, OL.pair_seed)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for k in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = outputs(loop)
+        # eager work of the program's own between the replays: the same step with the seeds of
+        # replay k passed by value, and an unrelated kernel
+        scratch.add_(1.0)
+        for st in loop.parts:
+            st.out.fill_(float("nan"))
+        loop.step(seed, lambda s, a, b, k=k: OL.pair_seed(s, a, b) + k)
+        torch.cuda.synchronize()
+        want = outputs(loop)
+        assert same(got, want), (cfg, "replay", k)
+        if k:
+            assert not same(got[-1:], first_wire), "every replay draws new bits"
+        else:
+            first_wire = got[-1:]
+    # start over: replay 0 again
+    graph.reset(0)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert same(outputs(loop)[-1:], first_wire)
