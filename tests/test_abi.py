@@ -151,3 +151,44 @@ def test_widened_entry_points_reject_bad_arguments_without_gpu(lib):
     sgd = lib.sylvie_sgd_update
     sgd.restype = i32
     assert sgd(p, p, i64(-1), C.c_float(0.1), None) == -1 and sgd(p, p, i64(0), C.c_float(0.1), None) == 0
+
+
+def test_attention_heads_and_seed_offset_reject_bad_arguments_without_gpu(lib):
+    """The all-heads attention entry points and the seed offset: host-side validation only."""
+    p = C.c_void_p(4096)
+    i64, i32, sz = C.c_int64, C.c_int32, C.c_size_t
+    lib.sylvie_last_error.restype = C.c_char_p
+    so = lib.sylvie_seed_offset_source
+    so.restype = i32
+    assert so(C.c_void_p(4100)) == -2 and so(None) == 0                     # 8-byte alignment; off again
+    pieces = [p, p, p, i64(3), i64(2)]
+    sf = lib.sylvie_edge_softmax_fwd_heads
+    sf.restype = i32
+    assert sf(*pieces, p, p, p, i32(3), C.c_float(0.2), p, p, sz(1 << 20), None) == -1 and \
+        b"heads" in lib.sylvie_last_error()
+    assert sf(*pieces, p, C.c_void_p(4100), p, i32(4), C.c_float(0.2), p, p, sz(1 << 20), None) == -2
+    assert sf(*pieces, p, p, p, i32(4), C.c_float(0.2), p, p, sz(8), None) == -5
+    lib.sylvie_edge_softmax_heads_workspace_bytes.restype = sz
+    assert lib.sylvie_edge_softmax_heads_workspace_bytes(i64(3), i64(2), i32(4)) == (3 + 2) * 4 * 8
+    ag = lib.sylvie_aggregate_csr_attention
+    ag.restype = i32
+    agargs = lambda heads=4, d=256, s1=None, a1=None: [
+        p, p, p, None, i32(heads), i64(10), p, i64(256), i32(d), p, i64(256), s1, a1, i64(0), None, None, i64(0),
+        i32(0), i32(0), None, None, i64(0), i64(0), None, sz(0), None]
+    assert ag(*agargs(heads=9)) == -1 and ag(*agargs(heads=3)) == -1 and ag(*agargs(d=0)) == -1
+    assert ag(*agargs(s1=p)) == -1 and b"rank-1" in lib.sylvie_last_error()
+    sup = lib.sylvie_aggregate_csr_attention_sddmm_supported
+    sup.restype = i32
+    assert [sup(i32(d), i32(k)) for d, k in ((256, 4), (256, 1), (64, 4), (64, 8), (512, 4), (24, 3), (100, 1))] == \
+        [1, 1, 1, 0, 0, 0, 0]
+    sd = lib.sylvie_aggregate_csr_attention_sddmm
+    sd.restype = i32
+    sdargs = lambda d=256, heads=4, out=p: [p, p, p, None, i32(heads), i64(10), p, i64(d), i32(d), p, i64(d), p,
+                                            i64(d), out, i32(0), None, None, i64(0), i64(0), None, sz(0), None]
+    assert sd(*sdargs(out=None)) == -1
+    assert sd(*sdargs(d=512)) == -4 and b"sylvie_sddmm_heads" in lib.sylvie_last_error()
+    r1 = lib.sylvie_rank1_add_heads
+    r1.restype = i32
+    assert r1(p, i64(8), i32(16), i32(4), p, p, i64(5), None, None, i64(0), None) == -1       # ld < F
+    assert r1(p, i64(16), i32(16), i32(3), p, p, i64(5), None, None, i64(0), None) == -1      # heads must divide F
+    assert r1(p, i64(16), i32(16), i32(4), None, None, i64(5), None, None, i64(0), None) == 0  # no term: nothing to do
