@@ -6,7 +6,8 @@
  *
  * Conventions (all entry points)
  *   - Every pointer is DEVICE memory owned by the caller unless the parameter
- *     says "host".  The library never allocates, frees or keeps a pointer.
+ *     says "host".  The library never allocates, frees or keeps a pointer (one exception,
+ *     switched on by the caller: sylvie_seed_offset_source).
  *   - Matrices are row-major float32; `ld_*` is the distance between rows in
  *     elements (>= the number of columns used).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
