@@ -120,6 +120,7 @@ class LayerLoop:
         # separate quantize / dequantize passes)
         self.fused_bwd = fused_bwd and fusable
         self.record = None          # set to a dict to keep copies of every wire
+        self.part_streams = None    # one stream per partition while a step is being recorded (StepGraph)
         # pipeline: keep every layer's wires of this and of the previous epoch so that an
         # epoch can run on the previous epoch's wires (mode "async" of forward / backward)
         self.pipeline = pipeline
@@ -264,7 +265,7 @@ class LayerLoop:
         caller's stream; with `part_streams` set (a step being recorded as a graph) partition p's
         launches go to stream p, forked from the caller's stream at the start of the phase and
         joined to it at the end, so that the recorded graph runs the partitions side by side."""
-        streams = getattr(self, "part_streams", None)
+        streams = self.part_streams
         if not streams:
             yield from enumerate(self.parts)
             return

@@ -101,3 +101,23 @@ def test_backward_dequantizer_rejects_bad_segments(validate):
         B.sylvie_dequantize_1bit_bwd(wire, n, d, J, d, dev(np.array([0, 2, 2, 7], np.int64)),
                                      dev(np.array([0, 4, 1, 2, 3, 5], np.int32)), 3, ids)
     torch.cuda.synchronize()
+
+
+def test_attention_aggregation_rejects_bad_operators(validate):
+    from paper_2303_01277_amd import binding as B
+    d, K, n = 64, 4, 3
+    X = dev(np.random.default_rng(2).standard_normal((6, d)).astype(np.float32))
+    Y = torch.zeros((n, d), device=DEV)
+    w = dev(np.ones(8 * K, np.float32))
+    good = dev(np.array([0, 3, 5, 8], np.int64))
+
+    def call(cols, rp=good):
+        B.sylvie_aggregate_csr_attention(rp, dev(np.array(cols, np.int32)), w, None, K, n, X, d, d, Y, d)
+
+    call([0, 2, 5, 1, 4, 3, 4, 5])
+    torch.cuda.synchronize()
+    assert bool((Y[0] == X[0] + X[2] + X[5]).all())
+    with pytest.raises(B.SylvieError, match="index out of range"):
+        call([0, 2, -1, 1, 4, 3, 4, 5])
+    with pytest.raises(B.SylvieError, match="SYLVIE_VALIDATE"):
+        call([0, 2, 5, 1, 4, 3, 4, 5], rp=dev(np.array([0, 3, 2, 8], np.int64)))       # row pointers descend
