@@ -340,9 +340,11 @@ int32_t sylvie_aggregate_csr_bwd_integrate(const int64_t *rowptrT, const int32_t
 
 /*
  * The three fused aggregation calls above for the wider wires of the bit-width study (Sec. 4.3;
- * Eq. 3-5 with B = 2^bits - 1): `bits` is 1, 2, 4 or 8 (1 = the calls above) and `wire` /
+ * Eq. 3-5 with B = 2^bits - 1): `bits` is 1, 2, 4, 8 (1 = the calls above) or 16 (the study's
+ * half-precision point: binary16 rows, no rounding draws, no metadata word) and `wire` /
  * `wire_out` hold rows in the format of sylvie_quantize_bbit_* (ceil(d bits / 64) code words and
- * the scale | zero word; ld_wire = words from one row to the next, 0 = packed).
+ * the scale | zero word, or ceil(d / 4) words of halves; ld_wire = words from one row to the
+ * next, 0 = packed).
  *   - sylvie_aggregate_csr_fwd_wire_bbit: a gathered halo element is fl(fl(scale q) + zero)
  *     (Eq. 5), then weighted and summed as every other element; the same result as
  *     sylvie_dequantize_bbit_fwd followed by sylvie_aggregate_csr_fwd up to the order of the

@@ -90,26 +90,34 @@ enum : int { kEpiStore = 0, kEpiQuantize = 1, kEpiIntegrate = 2 };
 
 // o[0..VEC) += the dequantized elements cc .. cc+VEC-1 of the wire rows of segment s,
 // in order (single-precision adds, Alg. 2 "integrate feature gradients").  WB = bits per
-// element of the wire (1, or 2 / 4 / 8: the recovered value is then fl(fl(scale q) + zero)).
+// element of the wire (1, or 2 / 4 / 8: the recovered value is then fl(fl(scale q) + zero); 16: the
+// rows are binary16 values).
 template <int VEC, int WB>
 __device__ __forceinline__ void integrate_vec(const AggArgs &a, int64_t s, int cc, float (&o)[VEC])
 {
-    const int W32 = ((a.d * WB + 63) >> 6) * 2;
     const int64_t j0 = a.seg_ptr[s], j1 = a.seg_ptr[s + 1];
     for (int64_t j = j0; j < j1; ++j) {
         const uint32_t *pr = a.wire32 + static_cast<int64_t>(a.seg_rows[j]) * (2 * a.ldw);
-        const uint2 meta = *reinterpret_cast<const uint2 *>(pr + W32);
-        const float zp = __uint_as_float(meta.y);
-        if constexpr (WB == 1) {
-            const float hi = zp + __uint_as_float(meta.x);
-            const uint32_t bits = pr[cc >> 5] >> (cc & 31);
+        if constexpr (WB == 16) {       // half-precision rows carry no metadata
+            float v[VEC];
+            fp16_load<VEC>(v, reinterpret_cast<const uint16_t *>(pr) + cc);
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) o[t] = o[t] + (((bits >> t) & 1u) ? hi : zp);
+            for (int t = 0; t < VEC; ++t) o[t] = o[t] + v[t];
         } else {
-            const float sc = __uint_as_float(meta.x);
-            const uint32_t piece = bb_piece<WB, VEC>(reinterpret_cast<const uint64_t *>(pr), cc);
+            const int W32 = ((a.d * WB + 63) >> 6) * 2;
+            const uint2 meta = *reinterpret_cast<const uint2 *>(pr + W32);
+            const float zp = __uint_as_float(meta.y);
+            if constexpr (WB == 1) {
+                const float hi = zp + __uint_as_float(meta.x);
+                const uint32_t bits = pr[cc >> 5] >> (cc & 31);
 #pragma unroll
-            for (int t = 0; t < VEC; ++t) o[t] = o[t] + bb_value<WB>(piece, t, sc, zp);
+                for (int t = 0; t < VEC; ++t) o[t] = o[t] + (((bits >> t) & 1u) ? hi : zp);
+            } else {
+                const float sc = __uint_as_float(meta.x);
+                const uint32_t piece = bb_piece<WB, VEC>(reinterpret_cast<const uint64_t *>(pr), cc);
+#pragma unroll
+                for (int t = 0; t < VEC; ++t) o[t] = o[t] + bb_value<WB>(piece, t, sc, zp);
+            }
         }
     }
 }
@@ -264,7 +272,7 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                 const bool mine = lane >= nd && lane < cnt;
                 const int64_t my_wr = mine ? static_cast<int64_t>(my_c) - a.n_dense : 0;
                 const uint32_t *my_row = a.wire32 + my_wr * (2 * a.ldw);
-                meta = *reinterpret_cast<const uint2 *>(my_row + W32);
+                if constexpr (WIRE != 16) meta = *reinterpret_cast<const uint2 *>(my_row + W32);
                 my_row_lo = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(my_row));
                 my_row_hi = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(my_row) >> 32);
             }
@@ -420,6 +428,47 @@ __device__ __forceinline__ void gather_sum(float (&acc)[P][VEC], int64_t e0, int
                         if (W == NW) all_entries(std::true_type{});
                         else all_entries(std::false_type{});
                     }
+                } else if constexpr (WIRE == 16) {
+                    // half-precision wire: a lane's four adjacent columns are eight bytes at the
+                    // matching place of the wire row; UB rows in flight, four conversions and the
+                    // weight's FMAs per entry.
+                    static_assert(VEC == 4, "half-precision wire rows are gathered four columns per lane");
+                    typedef const __attribute__((address_space(1))) char *global_bytes;
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    typedef const __attribute__((address_space(1))) u32x2 *global_u2;
+                    constexpr int UB = (P >= 4) ? 2 : (8 / P);
+                    const int my_wwi = __float_as_int(my_ww);
+                    auto hentries = [&](auto n_c, int j0) {
+                        constexpr int N = decltype(n_c)::value;
+                        u32x2 pc[N][P];
+                        float ww[N];
+#pragma unroll
+                        for (int u = 0; u < N; ++u) {
+                            const int sl = j0 + u;
+                            const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_lo), sl));
+                            const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(my_row_hi), sl));
+                            global_bytes row = (global_bytes)((static_cast<uint64_t>(hi) << 32) | lo);
+                            ww[u] = __int_as_float(__builtin_amdgcn_readlane(my_wwi, sl));
+#pragma unroll
+                            for (int p = 0; p < P; ++p) pc[u][p] = *(global_u2)(row + static_cast<uint32_t>(coff[p]) * 2u);
+                        }
+#pragma unroll
+                        for (int u = 0; u < N; ++u)
+#pragma unroll
+                            for (int p = 0; p < P; ++p) {
+                                const float x0 = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(pc[u][p].x & 0xffffu)));
+                                const float x1 = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(pc[u][p].x >> 16)));
+                                const float x2 = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(pc[u][p].y & 0xffffu)));
+                                const float x3 = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(pc[u][p].y >> 16)));
+                                acc[p][0] = fmaf(ww[u], x0, acc[p][0]);
+                                acc[p][1] = fmaf(ww[u], x1, acc[p][1]);
+                                acc[p][2] = fmaf(ww[u], x2, acc[p][2]);
+                                acc[p][3] = fmaf(ww[u], x3, acc[p][3]);
+                            }
+                    };
+                    int jj = nd;
+                    for (; jj + UB <= cnt; jj += UB) hentries(std::integral_constant<int, UB>{}, jj);
+                    for (; jj < cnt; ++jj) hentries(std::integral_constant<int, 1>{}, jj);
                 } else {
                     // b-bit wire (2, 4, 8 bits): a lane's VEC adjacent columns are one piece of
                     // VEC * WIRE bits at the matching place of the wire row, so wire entries use
@@ -523,7 +572,7 @@ __global__ __launch_bounds__((waves_per_block<WB, EPI>() * kWave)) void aggregat
     constexpr int WIRE = EPI == kEpiStore ? WB : 0;            // wire read by the gather itself
     // quantize epilogue: the finished row as floats, for b > 1 followed by the packed image
     constexpr int kRowStage = VEC * G * P;
-    constexpr int kStage = EPI == kEpiQuantize ? kRowStage + (WB > 1 ? kRowStage / 4 + 4 : 0) : 4;
+    constexpr int kStage = EPI == kEpiQuantize ? kRowStage + (WB > 1 && WB < 16 ? kRowStage / 4 + 4 : 0) : 4;
     __shared__ __align__(16) float stage[kWPB][kStage];
     // wire entries of full-width rows: broadcast records, then the fold of their sums
     constexpr bool kWireAcc = WIRE == 1 && G == 64;
@@ -612,6 +661,8 @@ __global__ __launch_bounds__((waves_per_block<WB, EPI>() * kWave)) void aggregat
         if constexpr (WB == 1)
             quantize_row_lds(stage[wave], a.d, ckey, static_cast<uint32_t>(local),
                              a.wire_out + local * a.ldw_out, lane);
+        else if constexpr (WB == 16)
+            convert_row_lds_fp16(stage[wave], a.d, a.wire_out + local * a.ldw_out, lane);
         else
             quantize_row_lds_bbit<WB>(stage[wave], a.d, ckey, static_cast<uint32_t>(local),
                                       a.wire_out + local * a.ldw_out,
@@ -636,7 +687,7 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
     const float rs = a.row_scale ? a.row_scale[v] : 1.0f;
     const bool add = a.addend && v < a.addend_rows;
     const int d4 = (a.d + 3) & ~3;
-    const int per_wave = d4 + (WB > 1 ? d4 / 4 + 4 : 0);
+    const int per_wave = d4 + (WB > 1 && WB < 16 ? d4 / 4 + 4 : 0);
     float *srow = rstage + wave * per_wave;
     for (int cc = lane * VEC; cc < a.d; cc += 64 * VEC) {
         float acc[VEC];
@@ -668,6 +719,8 @@ __global__ __launch_bounds__(kAgWavesPerBlock *kWave) void aggregate_reduce_kern
         if constexpr (WB == 1)
             quantize_row_lds(srow, a.d, ckey, static_cast<uint32_t>(local),
                              a.wire_out + local * a.ldw_out, lane);
+        else if constexpr (WB == 16)
+            convert_row_lds_fp16(srow, a.d, a.wire_out + local * a.ldw_out, lane);
         else
             quantize_row_lds_bbit<WB>(srow, a.d, ckey, static_cast<uint32_t>(local),
                                       a.wire_out + local * a.ldw_out,
@@ -687,7 +740,7 @@ static void launch_kernels(const AggArgs &a, int64_t nt, hipStream_t st)
         const dim3 rg(static_cast<unsigned>((a.n_long + kAgWavesPerBlock - 1) / kAgWavesPerBlock));
         const int d4 = (a.d + 3) & ~3;
         const size_t lds = EPI == kEpiQuantize
-                               ? sizeof(float) * kAgWavesPerBlock * (d4 + (WB > 1 ? d4 / 4 + 4 : 0)) : 0;
+                               ? sizeof(float) * kAgWavesPerBlock * (d4 + (WB > 1 && WB < 16 ? d4 / 4 + 4 : 0)) : 0;
         hipLaunchKernelGGL((aggregate_reduce_kernel<VEC, WB, EPI>), rg, block, lds, st, a);
     }
 }
@@ -706,7 +759,8 @@ static void launch_shape(const AggArgs &a, int64_t n_tasks, int epi, int bits, h
     else if constexpr (G == 64) launch_kernels<VEC, G, P, B, kEpiStore>(a, nt, st);
             if (bits == 2) { SYLVIE_AG_BITS(2) }
             else if (bits == 4) { SYLVIE_AG_BITS(4) }
-            else { SYLVIE_AG_BITS(8) }
+            else if (bits == 8) { SYLVIE_AG_BITS(8) }
+            else { SYLVIE_AG_BITS(16) }
 #undef SYLVIE_AG_BITS
             return;
         }
@@ -777,9 +831,11 @@ static int32_t aggregate_common(const char *name, const int64_t *rowptr, const i
     if (n_wire > 0 && !wire) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null wire", name);
     if (n_wire > 0 && !aligned(wire, 8))
         return fail(SYLVIE_ERR_BAD_ALIGNMENT, "%s: misaligned wire", name);
-    if (x.bits != 1 && x.bits != 2 && x.bits != 4 && x.bits != 8)
-        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4 or 8 (got %d)", name, x.bits);
-    const int64_t row_words = (static_cast<int64_t>(d) * x.bits + 63) / 64 + 1;
+    if (x.bits != 1 && x.bits != 2 && x.bits != 4 && x.bits != 8 && x.bits != 16)
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: bits must be 1, 2, 4, 8 or 16 (got %d)", name, x.bits);
+    // half-precision rows (16) have no metadata word
+    const int64_t row_words = x.bits == 16 ? (static_cast<int64_t>(d) + 3) / 4
+                                           : (static_cast<int64_t>(d) * x.bits + 63) / 64 + 1;
     if (x.ld_wire != 0 && x.ld_wire < row_words)
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: ld_wire %lld shorter than a wire row", name, (long long)x.ld_wire);
     if (n_rows == 0) return SYLVIE_OK;

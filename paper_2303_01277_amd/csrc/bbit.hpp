@@ -131,4 +131,46 @@ __device__ __forceinline__ void quantize_row_lds_bbit(const float *row, int d, u
     wave_lds_sync();
 }
 
+// ---- half-precision wire rows (d binary16 values, zero halves up to a multiple of four) --------
+
+template <int VEC>
+__device__ __forceinline__ void fp16_load(float (&o)[VEC], const uint16_t *p)
+{
+    if constexpr (VEC == 4) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        o[0] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.x & 0xffffu)));
+        o[1] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.x >> 16)));
+        o[2] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.y & 0xffffu)));
+        o[3] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.y >> 16)));
+    } else {
+        o[0] = static_cast<float>(__builtin_bit_cast(_Float16, *p));
+    }
+}
+
+// Four floats -> four binary16 values (round to nearest even) as two dwords.
+__device__ __forceinline__ uint2 fp16_pack4(const float (&v)[4])
+{
+    const _Float16 h0 = static_cast<_Float16>(v[0]), h1 = static_cast<_Float16>(v[1]);
+    const _Float16 h2 = static_cast<_Float16>(v[2]), h3 = static_cast<_Float16>(v[3]);
+    uint2 o;
+    o.x = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, h0)) |
+          (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, h1)) << 16);
+    o.y = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, h2)) |
+          (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, h3)) << 16);
+    return o;
+}
+
+// Convert one row of d floats that this wavefront holds in LDS (d % 4 == 0, 16-byte aligned)
+// into the half-precision wire row `out`: the arithmetic of convert_fp16_kernel.  All 64 lanes call.
+__device__ __forceinline__ void convert_row_lds_fp16(const float *row, int d, uint64_t *out, int lane)
+{
+    wave_lds_sync();    // the row was written by other lanes of this wavefront
+    for (int c0 = lane * 4; c0 < d; c0 += 256) {
+        const float4 x = *reinterpret_cast<const float4 *>(row + c0);
+        const float v[4] = {x.x, x.y, x.z, x.w};
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(out) + c0) = fp16_pack4(v);
+    }
+    wave_lds_sync();
+}
+
 }  // namespace sylvie

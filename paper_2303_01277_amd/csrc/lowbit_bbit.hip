@@ -315,20 +315,6 @@ __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void convert_fp16_kernel(
 }
 
 template <int VEC>
-__device__ __forceinline__ void fp16_load(float (&o)[VEC], const uint16_t *p)
-{
-    if constexpr (VEC == 4) {
-        const uint2 v = *reinterpret_cast<const uint2 *>(p);
-        o[0] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.x & 0xffffu)));
-        o[1] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.x >> 16)));
-        o[2] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.y & 0xffffu)));
-        o[3] = static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(v.y >> 16)));
-    } else {
-        o[0] = static_cast<float>(__builtin_bit_cast(_Float16, *p));
-    }
-}
-
-template <int VEC>
 __global__ __launch_bounds__(kBbWavesPerBlock *kWave) void recover_fp16_fwd_kernel(
     const uint16_t *__restrict__ wire, int64_t n_rows, int d, float *__restrict__ dst, int64_t ld,
     int64_t row_offset)

@@ -113,7 +113,7 @@ class LayerLoop:
         # fused: the forward aggregation reads halo rows straight from the packed wire
         # (no dequantize pass, no float halo block)
         # (the wider codes of the bit-width study too, when every width is a multiple of 4)
-        fusable = wire == "1bit" or (wire in ("2bit", "4bit", "8bit") and all(d % 4 == 0 for d in dims))
+        fusable = wire == "1bit" or (wire in ("2bit", "4bit", "8bit", "fp16") and all(d % 4 == 0 for d in dims))
         self.fused = fused and fusable
         # fused_bwd: the transposed aggregation quantizes the halo gradients on the spot
         # and adds the received ones in its epilogue (no float halo-gradient block, no

@@ -307,3 +307,76 @@ def test_full_precision_wire(d):
     ref = J.copy()
     np.add.at(ref[:, :d], dst, x[idx][:, :d])
     assert np.array_equal(bits32(Jg.cpu().numpy()), bits32(ref))
+
+
+@pytest.mark.parametrize("d", [4, 64, 100, 256, 600])
+@pytest.mark.parametrize("cfg,n_nodes,model", [("stress", 30_000, "gcn"), ("co_purchase", 20_000, "sage")])
+def test_fused_half_precision_wire(oracle, d, cfg, n_nodes, model):
+    """bits = 16 of the three fused aggregation calls (the bit-width study's half-precision point):
+    the forward aggregation that reads binary16 halo rows against the oracle's recover + aggregate
+    and the GPU's two-step path; the backward epilogues against aggregate_csr_bwd + the stand-alone
+    conversion / accumulate bit for bit, the wire also against the oracle's conversion."""
+    from paper_2303_01277_amd import binding as B
+    from paper_2303_01277_amd import graph_engine as GE
+    from test_gpu_ops import _operator, close
+    p, (rp, cl, w) = _operator(oracle, cfg, n_nodes, model)
+    n_loc = p.n_in + p.n_halo
+    rng = np.random.default_rng(d + 16)
+    X = make_rows(rng, n_loc, d, "heavy")
+    Wh = (d + 3) // 4
+    half = oracle.convert_fp16(X, d, p.n_halo, row_offset=p.n_in)
+    Xo = X.copy()
+    oracle.recover_fp16_fwd(half, d, Xo, p.n_in)
+    Z, S = oracle.aggregate_fwd(rp, cl, w, Xo, d, want_S=True)
+    rpd, cld, wd, Xfull = dev(rp), dev(cl), dev(w), dev(X)
+    wired = torch.full((p.n_halo * Wh,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_bbit_fwd(Xfull, d, d, None, p.n_in, p.n_halo, 16, 0, 0, wired)
+    for chunk in (0, 128):
+        kw = {}
+        if chunk:
+            lr, lp, nt = GE.long_row_plan(rpd, chunk)
+            kw = dict(chunk=chunk, long_rows=lr, long_ptr=lp, n_long=int(lr.numel()), n_tasks=nt,
+                      workspace=torch.empty(max(1, nt) * d, device=DEV))
+        Y = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd_wire_bbit(rpd, cld, wd, None, None, p.n_in, Xfull, d, d, 16, p.n_in, wired,
+                                             p.n_halo, Y, d, **kw)
+        X2 = Xfull.clone()
+        B.sylvie_dequantize_bbit_fwd(wired, p.n_halo, d, 16, X2, d, p.n_in)
+        Y2 = torch.full((p.n_in, d), float("nan"), device=DEV)
+        B.sylvie_aggregate_csr_fwd(rpd, cld, wd, None, None, p.n_in, X2, d, d, Y2, d, **kw)
+        torch.cuda.synchronize()
+        close(Y.cpu().numpy(), Z, S, ("half wire", chunk))
+        close(Y.cpu().numpy(), Y2.cpu().numpy().astype(np.float64), S, ("half wire vs two-step", chunk))
+    # backward epilogues
+    dZ = dev(make_rows(rng, p.n_in, d, "heavy"))
+    add = dev(make_rows(rng, p.n_in, d, "normal"))
+    mirror = dev(rng.integers(0, p.n_in, p.n_halo).astype(np.int32))
+    rpT, clT, wT = GE.transpose_csr(rpd, cld, wd, n_loc)
+    chunk = 128
+    lr, lp, nt = GE.long_row_plan(rpT, chunk)
+    ws = torch.empty(max(1, nt) * d, device=DEV)
+    G = torch.full((n_loc, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd(rpT, clT, wT, None, None, n_loc, dZ, d, d, G, d, addend=add, ld_addend=d,
+                               addend_rows=p.n_in, chunk=chunk, long_rows=lr, long_ptr=lp,
+                               n_long=int(lr.numel()), n_tasks=nt, workspace=ws)
+    wire_ref = torch.full((p.n_halo * Wh,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_quantize_bbit_bwd(G, d, d, None, p.n_in, p.n_halo, 16, 0, 0, wire_ref)
+    sp_, sr, di = GE.scatter_segments(mirror)
+    Gpre = G.clone()
+    B.sylvie_dequantize_bbit_bwd(wire_ref, p.n_halo, d, 16, G, d, sp_, sr, int(di.numel()), di)
+    lrh, lph, nth = GE.long_row_plan(rpT, chunk, p.n_in, n_loc)
+    wire = torch.full((p.n_halo * Wh,), -1, dtype=torch.int64, device=DEV)
+    B.sylvie_aggregate_csr_bwd_quantize_bbit(rpT, clT, wT, None, None, p.n_in, p.n_halo, dZ, d, d, 16, 0, 0, wire,
+                                             chunk=chunk, long_rows=lrh, long_ptr=lph, n_long=int(lrh.numel()),
+                                             n_tasks=nth, workspace=ws)
+    lri, lpi, nti = GE.long_row_plan(rpT, chunk, 0, p.n_in)
+    sp2, sr2 = GE.scatter_segments_dense(mirror, p.n_in)
+    J = torch.full((p.n_in, d), float("nan"), device=DEV)
+    B.sylvie_aggregate_csr_bwd_integrate_bbit(rpT, clT, wT, None, None, 0, p.n_in, dZ, d, d, 16, J, d, add, d,
+                                              p.n_in, wire, p.n_halo, sp2, sr2, chunk=chunk, long_rows=lri,
+                                              long_ptr=lpi, n_long=int(lri.numel()), n_tasks=nti, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(wire, wire_ref)
+    assert np.array_equal(bits32(J.cpu().numpy()), bits32(G[: p.n_in].cpu().numpy()))
+    ref = oracle.convert_fp16(Gpre.cpu().numpy(), d, p.n_halo, row_offset=p.n_in)
+    assert np.array_equal(wire.cpu().numpy().view(np.uint16).reshape(p.n_halo, 4 * Wh), ref)

@@ -278,7 +278,7 @@ def test_layer_loop_bit_widths(oracle, cfg, n_nodes, wire, fused):
     wl = build_workload(spec)
     pdata = to_partdata(wl)
     loop = build_loop(wl, wire=wire, fused=fused)
-    fusable = wire != "fp16" and all(d % 4 == 0 for d in spec.dims)
+    fusable = all(d % 4 == 0 for d in spec.dims)
     if fused and not fusable:
         pytest.skip("this wire / width runs the two-step exchange either way")
     assert loop.fused == fused and not loop.fused_bwd
@@ -314,7 +314,7 @@ def test_layer_loop_end_to_end_fp32_wire(oracle, cfg, n_nodes):
             assert np.abs(g - pd.G[l]).max() <= 2e-5 * np.abs(pd.G[l]).max()
 
 
-@pytest.mark.parametrize("wire", ["1bit", "2bit", "4bit", "8bit"])
+@pytest.mark.parametrize("wire", ["1bit", "2bit", "4bit", "8bit", "fp16"])
 @pytest.mark.parametrize("cfg,n_nodes", CASES)
 def test_fused_backward_equals_two_step_backward(cfg, n_nodes, wire):
     """The transposed aggregation with the quantize / integrate epilogues must give, bit
