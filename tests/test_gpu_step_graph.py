@@ -93,3 +93,24 @@ def test_recorded_step_replays_equal_eager_steps(cfg, n_nodes, wire, fused_bwd):
     graph.replay()
     torch.cuda.synchronize()
     assert same(outputs(loop)[-1:], first_wire)
+
+
+def test_recorded_attention_step_replays_equal_eager_steps():
+    """The attention model's step records and replays the same way (one stream: its partitions'
+    launches are not forked)."""
+    from paper_2303_01277_amd.trainer import StepGraph
+    from test_gpu_gat_layers import build_attention_loop, make_att, workload
+    wl = workload("tiny", None)
+    loop = build_attention_loop(wl, make_att(wl, 3), 4, "1bit")
+    seed = 0xA77
+    graph = StepGraph(loop, seed, OL.pair_seed)
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        got = outputs(loop) + [g.clone() for st in loop.parts for g in st.Ga[1]]
+        for st in loop.parts:
+            st.out.fill_(float("nan"))
+        loop.step(seed, lambda s, a, b, k=k: OL.pair_seed(s, a, b) + k)
+        torch.cuda.synchronize()
+        want = outputs(loop) + [g.clone() for st in loop.parts for g in st.Ga[1]]
+        assert same(got, want), ("attention replay", k)
