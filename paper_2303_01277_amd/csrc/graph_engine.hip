@@ -146,18 +146,49 @@ __global__ __launch_bounds__(kBlock) void radix_count_kernel(const uint32_t *key
         for (int d = lane; d < 256; d += kWave) hist[static_cast<int64_t>(d) * tiles + tile] = cnt[wave][d];
 }
 
-__global__ __launch_bounds__(kBlock) void radix_scatter_kernel(const uint32_t *keys_in, const uint32_t *vals_in,
-                                                              uint32_t *keys_out, uint32_t *vals_out, int64_t n,
-                                                              int shift, const uint32_t *offs, int64_t tiles)
+// Scatter pass.  A wavefront first sorts its tile by the digit inside LDS (positions from the tile's
+// own digit counts, which are the differences of consecutive scanned offsets), then writes the
+// tile out in that order: the items of one digit are adjacent lanes writing adjacent addresses,
+// runs of eight items on average instead of 64 separate 4-byte writes per instruction.
+constexpr int kScatterWaves = 2;        // 2 x (16 KB of staged pairs + 3 KB of tables) of LDS per workgroup
+
+__global__ __launch_bounds__(kScatterWaves *kWave) void radix_scatter_kernel(
+    const uint32_t *keys_in, const uint32_t *vals_in, uint32_t *keys_out, uint32_t *vals_out, int64_t n, int shift,
+    const uint32_t *offs, int64_t tiles)
 {
-    __shared__ uint32_t run[kWavesPerBlock][256];
+    __shared__ uint32_t goff[kScatterWaves][256];      // where the tile's items of a digit go
+    __shared__ uint32_t lstart[kScatterWaves][256];    // where they start inside the sorted tile
+    __shared__ uint32_t lrun[kScatterWaves][256];      // next free place inside the sorted tile
+    __shared__ uint32_t skey[kScatterWaves][kSortTile];
+    __shared__ uint32_t sval[kScatterWaves][kSortTile];
     const int wave = static_cast<int>(threadIdx.x) / kWave, lane = lane_id();
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wave;
-    if (tile < tiles)
-        for (int d = lane; d < 256; d += kWave) run[wave][d] = offs[static_cast<int64_t>(d) * tiles + tile];
-    __syncthreads();
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kScatterWaves + wave;
     if (tile >= tiles) return;
     const int64_t base = tile * kSortTile;
+    const int count = static_cast<int>(n - base < kSortTile ? n - base : kSortTile);
+    // lane l owns digits 4 l .. 4 l + 3: global offsets, counts, local starts
+    {
+        uint32_t c[4], total = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int d = 4 * lane + q;
+            const int64_t at = static_cast<int64_t>(d) * tiles + tile;        // digit-major scan order
+            const uint32_t here = offs[at];
+            const uint32_t next = at + 1 < 256 * tiles ? offs[at + 1] : static_cast<uint32_t>(n);
+            goff[wave][d] = here;
+            c[q] = next - here;
+            total += c[q];
+        }
+        uint32_t start = wave_inclusive_scan(total) - total;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            lstart[wave][4 * lane + q] = start;
+            lrun[wave][4 * lane + q] = start;
+            start += c[q];
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     const uint64_t below = (uint64_t(1) << lane) - 1;
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * kWave + lane;
@@ -173,17 +204,27 @@ __global__ __launch_bounds__(kBlock) void radix_scatter_kernel(const uint32_t *k
             same &= bit ? m : ~m;
         }
         if (valid) {
-            const uint32_t first = run[wave][digit];
+            const uint32_t first = lrun[wave][digit];
             const uint32_t rank = static_cast<uint32_t>(__popcll(same & below));
             __builtin_amdgcn_wave_barrier();
-            if (rank == 0) run[wave][digit] = first + static_cast<uint32_t>(__popcll(same));
+            if (rank == 0) lrun[wave][digit] = first + static_cast<uint32_t>(__popcll(same));
             const uint32_t pos = first + rank;
-            if (pos < n) {                     // always true for a histogram of these keys
-                keys_out[pos] = key;
-                vals_out[pos] = val;
+            if (pos < static_cast<uint32_t>(kSortTile)) {       // always true for a histogram of these keys
+                skey[wave][pos] = key;
+                sval[wave][pos] = val;
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+    }
+    for (int j = lane; j < count; j += kWave) {
+        const uint32_t key = skey[wave][j];
+        const uint32_t digit = (key >> shift) & 255u;
+        const uint32_t pos = goff[wave][digit] + (static_cast<uint32_t>(j) - lstart[wave][digit]);
+        if (pos < n) {                         // always true for a histogram of these keys
+            keys_out[pos] = key;
+            vals_out[pos] = sval[wave][j];
+        }
     }
 }
 
@@ -207,8 +248,9 @@ int radix_sort_pairs(const SortBuffers &b, int64_t n, int key_bits, hipStream_t 
     for (int shift = 0; shift < key_bits; shift += 8) {
         hipLaunchKernelGGL(radix_count_kernel, dim3(blocks), dim3(kBlock), 0, st, b.keys[cur], n, shift, b.hist, tiles);
         exclusive_scan<uint32_t>(b.hist, b.hist, 256 * tiles, b.scan_scratch, st);
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kBlock), 0, st, b.keys[cur], b.vals[cur],
-                           b.keys[cur ^ 1], b.vals[cur ^ 1], n, shift, b.hist, tiles);
+        const unsigned sblocks = static_cast<unsigned>((tiles + kScatterWaves - 1) / kScatterWaves);
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(sblocks), dim3(kScatterWaves * kWave), 0, st, b.keys[cur],
+                           b.vals[cur], b.keys[cur ^ 1], b.vals[cur ^ 1], n, shift, b.hist, tiles);
         cur ^= 1;
     }
     return cur;
