@@ -327,9 +327,11 @@ __global__ __launch_bounds__(kBlock) void keys_from_i32_kernel(const int32_t *sr
     vals[i] = static_cast<uint32_t>(i);
 }
 
-// Row of every entry: the r with rowptr[r] <= e < rowptr[r + 1].
+// Row of every entry (the r with rowptr[r] <= e < rowptr[r + 1]) and the entry's weight side by
+// side, so that the transposition's last step gathers one 8-byte record per entry, not two words
+// from two arrays.
 __global__ __launch_bounds__(kBlock) void expand_rows_kernel(const int64_t *rowptr, int64_t n_rows, int64_t nnz,
-                                                            int32_t *row_ids, int32_t *status)
+                                                            const float *w, uint2 *row_w, int32_t *status)
 {
     const int64_t e = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (e == 0 && (rowptr[0] != 0 || rowptr[n_rows] != nnz)) status[0] = 2;
@@ -340,17 +342,18 @@ __global__ __launch_bounds__(kBlock) void expand_rows_kernel(const int64_t *rowp
         if (rowptr[mid] <= e) lo = mid; else hi = mid;
     }
     if (!(rowptr[lo] <= e && e < rowptr[lo + 1])) status[0] = 2;      // row pointer not ascending
-    row_ids[e] = static_cast<int32_t>(lo);
+    row_w[e] = make_uint2(static_cast<uint32_t>(lo), w ? __float_as_uint(w[e]) : 0u);
 }
 
-__global__ __launch_bounds__(kBlock) void transpose_gather_kernel(const uint32_t *order, int64_t n, const int32_t *row_ids,
-                                                                 const float *w, int32_t *colT, float *wT, int64_t *perm)
+__global__ __launch_bounds__(kBlock) void transpose_gather_kernel(const uint32_t *order, int64_t n, const uint2 *row_w,
+                                                                 int32_t *colT, float *wT, int64_t *perm)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (i >= n) return;
     const uint32_t e = order[i];
-    colT[i] = row_ids[e];
-    if (wT) wT[i] = w[e];
+    const uint2 rw = row_w[e];
+    colT[i] = static_cast<int32_t>(rw.x);
+    if (wT) wT[i] = __uint_as_float(rw.y);
     if (perm) perm[i] = static_cast<int64_t>(e);
 }
 
@@ -758,17 +761,17 @@ extern "C" int32_t sylvie_graph_transpose_csr(const int64_t *rowptr, const int32
     Arena a{static_cast<char *>(workspace), 0, workspace_bytes};
     int32_t *status = a.take<int32_t>(1);
     SortBuffers b = take_sort(a, nnz);
-    int32_t *row_ids = a.take<int32_t>(nnz + 1);
+    uint2 *row_w = a.take<uint2>(nnz + 1);
     hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, st, status);
     hipLaunchKernelGGL(expand_rows_kernel, dim3(blocks_for(nnz > 0 ? nnz : 1)), dim3(kBlock), 0, st, rowptr, n_rows, nnz,
-                       row_ids, status);
+                       wT ? w : nullptr, row_w, status);
     if (nnz > 0)
         hipLaunchKernelGGL(keys_from_i32_kernel, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, col, nnz, n_cols, b.keys[0],
                            b.vals[0], status);
     const int cur = radix_sort_pairs(b, nnz, bits_for(n_cols), st);
     hipLaunchKernelGGL(boundaries_kernel, dim3(blocks_for(nnz + 1)), dim3(kBlock), 0, st, b.keys[cur], nnz, n_cols, rowptrT);
     if (nnz > 0)
-        hipLaunchKernelGGL(transpose_gather_kernel, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, b.vals[cur], nnz, row_ids, w,
+        hipLaunchKernelGGL(transpose_gather_kernel, dim3(blocks_for(nnz)), dim3(kBlock), 0, st, b.vals[cur], nnz, row_w,
                            colT, wT, perm);
     return finish(name, status, st, "column outside [0, n_cols)", "row pointer does not ascend from 0 to nnz");
 }
