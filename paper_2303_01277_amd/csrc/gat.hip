@@ -991,13 +991,14 @@ extern "C" int32_t sylvie_rank1_add_heads(float *X, int64_t ld_x, int32_t F, int
     if (!X || (s1 && !a1) || (s2 && !a2)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
     const int Fh = F / heads;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (rows * static_cast<int64_t>(F) >= (int64_t(1) << 39))
+        return fail(SYLVIE_ERR_INVALID_ARG, "%s: too many elements", name);
     if (Fh % 4 == 0 && ld_x % 4 == 0 && aligned(X, 16)) {
         const int64_t total = rows * (F / 4);
         hipLaunchKernelGGL(rank1_pair_kernel<4>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
                            X, ld_x, rows, F, Fh, heads, s1, a1, n1, s2, a2, n2);
     } else {
         const int64_t total = rows * F;
-        if (total >= (int64_t(1) << 39)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: too many elements", name);
         hipLaunchKernelGGL(rank1_pair_kernel<1>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, st,
                            X, ld_x, rows, F, Fh, heads, s1, a1, n1, s2, a2, n2);
     }
