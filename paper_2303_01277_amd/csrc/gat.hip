@@ -582,18 +582,29 @@ __global__ void rank1_pair_kernel(float *__restrict__ X, int64_t ld, int64_t row
     stream_store<VEC>(X + i * ld + c, x);
 }
 
-// FWD: out = max(in, 0); otherwise out = gate > 0 ? in : 0.
-template <bool FWD>
+// FWD: out = max(in, 0); otherwise out = gate > 0 ? in : 0.  One thread per VEC adjacent columns;
+// every operand is read or written once, with the streaming hint.
+template <bool FWD, int VEC>
 __global__ void relu_kernel(const float *__restrict__ in, int64_t ld_in, const float *__restrict__ gate,
                             int64_t ld_gate, int64_t n, int F, float *__restrict__ out, int64_t ld_out)
 {
+    const int per_row = F / VEC;
     const int64_t t = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (t >= n * F) return;
-    const int64_t i = t / F;
-    const int c = static_cast<int>(t - i * F);
-    const float x = in[i * ld_in + c];
-    if constexpr (FWD) out[i * ld_out + c] = x > 0.0f ? x : 0.0f;
-    else out[i * ld_out + c] = gate[i * ld_gate + c] > 0.0f ? x : 0.0f;
+    if (t >= n * per_row) return;
+    const int64_t i = t / per_row;
+    const int c = static_cast<int>(t - i * per_row) * VEC;
+    float x[VEC];
+    stream_load<VEC>(x, in + i * ld_in + c);
+    if constexpr (FWD) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) x[q] = x[q] > 0.0f ? x[q] : 0.0f;
+    } else {
+        float g[VEC];
+        stream_load<VEC>(g, gate + i * ld_gate + c);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) x[q] = g[q] > 0.0f ? x[q] : 0.0f;
+    }
+    stream_store<VEC>(out + i * ld_out + c, x);
 }
 
 // ---- host side ----------------------------------------------------------------------------
@@ -1015,11 +1026,18 @@ static int32_t relu_common(const char *name, bool fwd, const float *in, int64_t 
         return fail(SYLVIE_ERR_INVALID_ARG, "%s: bad sizes", name);
     if (n == 0) return SYLVIE_OK;
     if (!in || !out || (!fwd && !gate)) return fail(SYLVIE_ERR_INVALID_ARG, "%s: null pointer", name);
-    const int64_t total = n * F;
-    const dim3 grid(static_cast<unsigned>((total + 255) / 256));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (fwd) hipLaunchKernelGGL(relu_kernel<true>, grid, dim3(256), 0, st, in, ld_in, gate, ld_gate, n, F, out, ld_out);
-    else hipLaunchKernelGGL(relu_kernel<false>, grid, dim3(256), 0, st, in, ld_in, gate, ld_gate, n, F, out, ld_out);
+    const bool v4 = F % 4 == 0 && ld_in % 4 == 0 && ld_out % 4 == 0 && aligned(in, 16) && aligned(out, 16) &&
+                    (fwd || (ld_gate % 4 == 0 && aligned(gate, 16)));
+    const int64_t total = n * (v4 ? F / 4 : F);
+    const dim3 grid(static_cast<unsigned>((total + 255) / 256));
+#define SYLVIE_RELU(FWDV, V) \
+    hipLaunchKernelGGL((relu_kernel<FWDV, V>), grid, dim3(256), 0, st, in, ld_in, gate, ld_gate, n, F, out, ld_out)
+    if (fwd && v4) SYLVIE_RELU(true, 4);
+    else if (fwd) SYLVIE_RELU(true, 1);
+    else if (v4) SYLVIE_RELU(false, 4);
+    else SYLVIE_RELU(false, 1);
+#undef SYLVIE_RELU
     SYLVIE_HIP_LAUNCH_CHECK(name);
     return SYLVIE_OK;
 }
